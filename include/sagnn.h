@@ -1,0 +1,204 @@
+/*
+ * sagnn -- one GPU's share of the sparsity-aware block-row SpMM of full-graph GCN
+ * training, for AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * Paper: "Sparsity-Aware Communication for Distributed Graph Neural Network Training"
+ * (ICPP'24).  A process P(i) that owns row block A_i of the (transposed) adjacency matrix
+ *   1. finds NnzCols(i,q), the nonzero column indices of each block A_iq, i.e. the rows of
+ *      H_q it needs                                   (Sec. 4.1, paragraph defining NnzCols)
+ *   2. obtains exactly those rows, packed one block after the other
+ *                                                     (Alg. 1, statement "T <- [H[NnzCols..]]")
+ *   3. multiplies: Z_i = sum_q A_iq H_q               (Sec. 4.1 block-sum equation; Alg. 1/2
+ *                                                      "Z <- Z + SpMM(A_iq, H^)")
+ *   4. applies the dense layer: H' = sigma(Z W)       (Sec. 2.1 forward equations; Alg. 1
+ *                                                      "GEMM(Z, W)")
+ *   5. and in the backward pass computes G' = (A G W^T) .* sigma'(Z') and Y = H'^T (A G)
+ *                                                     (Sec. 2.1 backward equations)
+ * The exchange between steps 2 and 3 (all-to-allv / isend-recv) is not part of this
+ * library: the remote H is any device-resident matrix that is read only through the
+ * packed row set.
+ *
+ * Conventions for every entry point
+ *   - d_* pointers are device memory owned by the caller, h_* pointers are host memory
+ *     owned by the caller.  The library allocates no device memory and keeps no state
+ *     besides the last HIP error code.
+ *   - Matrices are row-major; ld* are leading dimensions in elements.
+ *   - CSR: rowptr has m+1 int32 entries with rowptr[0] = 0 and rowptr[m] = nnz; colidx and
+ *     val have nnz entries.  Entries of a row may be unsorted and may repeat: the planner
+ *     treats them as a set, the products sum them.
+ *   - Dense float pointers must be 16-byte aligned and ld* / f multiples of 4, otherwise
+ *     SAGNN_EINVAL.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously unless stated otherwise.
+ *   - Return value: SAGNN_OK or a negative error code.  Arguments are validated on the host
+ *     before anything is launched; no entry point throws or aborts.  Kernels bounds-check
+ *     every index they read from device memory (an out-of-range column index is clamped
+ *     or skipped), so malformed device data cannot fault the GPU.
+ */
+#ifndef SAGNN_H
+#define SAGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SAGNN_OK = 0,
+  SAGNN_EINVAL = -1,    /* null pointer, negative size, misaligned pointer, unsupported f */
+  SAGNN_ECAPACITY = -2, /* an output buffer or the workspace is too small                 */
+  SAGNN_EFORMAT = -3,   /* validation requested and the CSR / block offsets are malformed  */
+  SAGNN_EHIP = -4       /* a HIP runtime call failed; see sagnn_last_hip_error()            */
+};
+
+#define SAGNN_PLAN_VALIDATE 1u /* flags bit 0 of spmm_plan_needed_rows */
+
+#define SAGNN_ACT_IDENTITY 0
+#define SAGNN_ACT_RELU 1
+
+#define SAGNN_GEMM_FP32 0 /* fp32 operands, fp32 MFMA                          */
+#define SAGNN_GEMM_BF16 1 /* operands rounded to bfloat16 (RNE), fp32 accumulate */
+
+/* Text for an error code (static string). */
+const char* sagnn_strerror(int code);
+/* hipError_t of the most recent failing HIP call made by this library (0 if none). */
+int sagnn_last_hip_error(void);
+/* Library version: major*10000 + minor*100 + patch. */
+int sagnn_version(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Step 1: needed rows (NnzCols; Sec. 4.1).
+ *
+ * For the row block given as CSR (m rows, n columns) and nb contiguous column blocks
+ * [h_colblk[q], h_colblk[q+1]) with h_colblk[0] = 0 and h_colblk[nb] = n (ascending),
+ * computes
+ *   d_needed[0..N)        global column ids that hold at least one stored entry, ascending;
+ *                         block q owns positions [h_blk_off[q], h_blk_off[q+1]); this is the
+ *                         order in which Alg. 1 concatenates the packed rows
+ *   h_blk_off[0..nb]      host output, h_blk_off[nb] = N
+ *   d_colidx_compact[nnz] for every entry e the position p with d_needed[p] == d_colidx[e]
+ *                         (column index into the packed buffer); may be NULL to skip.
+ *                         An entry whose column is outside [0,n) gets -1.
+ * All integer work; the result is unique, so it is bit-exact by construction.
+ *
+ * Synchronises the stream once (N has to reach the host).  If N > needed_cap returns
+ * SAGNN_ECAPACITY with h_blk_off filled in (so the caller knows the size to allocate) and
+ * d_needed / d_colidx_compact untouched.  With SAGNN_PLAN_VALIDATE the CSR is checked on
+ * the device first (rowptr monotone from 0 to nnz, every column in [0,n)) and
+ * SAGNN_EFORMAT is returned on failure.
+ *
+ * Workspace: spmm_plan_workspace_bytes(); contents are scratch.
+ */
+int spmm_plan_workspace_bytes(int64_t m, int64_t n, int64_t nnz, int32_t nb, size_t* bytes);
+int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m,
+                          int64_t n, int64_t nnz, const int64_t* h_colblk, int32_t nb,
+                          int32_t* d_needed, int64_t needed_cap, int64_t* h_blk_off,
+                          int32_t* d_colidx_compact, void* d_ws, size_t ws_bytes,
+                          uint32_t flags, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Step 2: pack / gather (Alg. 1 first statement; Alg. 2 "H[srows,:]").
+ *
+ *   d_out[r, 0:f) = d_H[d_rows[r], 0:f)   for r in [0,N)
+ *
+ * d_H is n x f (leading dimension ldh), d_out is N x f (leading dimension ldo).  A row id
+ * outside [0,n) produces a row of zeros.  Pure copy: bit-exact.  Element offsets are 64-bit
+ * (n*ldh may exceed 2^32).
+ */
+int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const int32_t* d_rows,
+                   int64_t N, float* d_out, int64_t ldo, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Step 3: local SpMM (Alg. 1/2 "Z <- Z + SpMM(A_iq, H^)").
+ *
+ *   C[r, 0:f) (+)= sum_e val[e] * B[colidx[e], 0:f)   over the stored entries of row r
+ *
+ * A is m x k CSR, B is k x f (ldb), C is m x f (ldc); accumulate = 0 overwrites C,
+ * accumulate = 1 adds to it (the per-block accumulation of the algorithms).  fp32 FMA.
+ * The summation order is fixed for a given (m, nnz, f, workspace), so results are
+ * reproducible run to run; it differs from the stored order, so they agree with a
+ * sequential sum up to rounding (|err| <= ~1e-6 * sum |val||B|).
+ * A column index outside [0,k) is clamped into range (never read out of bounds).
+ *
+ * Load balancing: the pattern of A is fixed during training, so a one-time
+ * spmm_csr_prepare() cuts the entries into equal chunks (nonzero splitting) and records
+ * where each chunk starts.  d_ws must then be passed unchanged to every
+ * spmm_csr_tallskinny() call with the same (rowptr, m, nnz, f); part of it is scratch for
+ * partial row sums, so two calls that share a workspace must not overlap in time.
+ * With d_ws == NULL a simple one-wavefront-per-row kernel is used (no preparation, no
+ * balancing).  Passing a workspace that was not prepared for these arguments leaves C
+ * unspecified but does not fault.
+ */
+int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
+int spmm_csr_prepare(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t f, void* d_ws,
+                     size_t ws_bytes, void* stream);
+int spmm_csr_tallskinny(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                        int64_t m, int64_t k, int64_t nnz, const float* d_B, int64_t ldb,
+                        int32_t f, float* d_C, int64_t ldc, int32_t accumulate, void* d_ws,
+                        size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Dense transform on the matrix cores:  Z = op(X) * op(W), optional epilogue.
+ *
+ *   transW = 0: W is kdim x nout (ldw);  transW = 1: W is nout x kdim (ldw), used as W^T
+ *   X is m x kdim (ldx), Z is m x nout (ldz)
+ *   prec: SAGNN_GEMM_FP32 or SAGNN_GEMM_BF16
+ *   d_Z   (may be NULL) receives the product
+ *   d_act (may be NULL) receives ReLU(product) when act = SAGNN_ACT_RELU, else the product
+ *   d_mask (may be NULL, m x nout, ldmask): the product is zeroed where d_mask <= 0
+ *         (the ".* sigma'(Z)" factor of the backward equation) before it is stored
+ * kdim and nout: multiples of 32, at most 256 (W stays resident in LDS).
+ */
+int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw, int32_t transW,
+                   int64_t m, int32_t kdim, int32_t nout, int32_t prec, int32_t act,
+                   const float* d_mask, int64_t ldmask, float* d_Z, int64_t ldz, float* d_act,
+                   int64_t ldact, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Step 4: one GCN layer forward (Sec. 2.1 forward equations in the order of Alg. 1):
+ *
+ *   T = A * H            (m x f_in; kept because the backward pass needs it)
+ *   Z = T * W            (m x f_out, W is f_in x f_out row-major, ld = f_out)
+ *   Hout = sigma(Z)      sigma = ReLU or identity
+ *
+ * A, H as in spmm_csr_tallskinny (H is k x f_in, ldh).  d_T is required; d_Z or d_Hout may
+ * be NULL (not stored).  d_T, d_Z, d_Hout are dense with ld = f_in / f_out / f_out.
+ * d_ws: SpMM workspace prepared for (rowptr, m, nnz, f_in), or NULL.
+ */
+int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                  int64_t m, int64_t k, int64_t nnz, const float* d_H, int64_t ldh,
+                  int32_t f_in, const float* d_W, int32_t f_out, int32_t act,
+                  int32_t gemm_prec, float* d_T, float* d_Z, float* d_Hout, void* d_ws,
+                  size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Step 5: one GCN layer backward (Sec. 2.1 backward equations; Sec. 4.1 paragraphs on the
+ * two gradient equations).  For the layer whose forward was Z = (A Hprev) W and incoming
+ * gradient G = dLoss/dZ (m x f_out):
+ *
+ *   S     = A_bwd * G                        (m x f_out)  the CSR passed here is the
+ *                                             orientation the backward equation multiplies
+ *                                             by; for a symmetric graph it is the same CSR
+ *   Gprev = (S * W^T) .* [Zprev > 0]          (m x f_in)   skipped if d_Gprev == NULL;
+ *                                             mask skipped if d_Zprev == NULL.  Any array
+ *                                             that is positive exactly where Z^{l-1} is
+ *                                             (e.g. ReLU(Z^{l-1})) serves as d_Zprev
+ *   Y     = Hprev^T * S                       (f_in x f_out, fp32) skipped if d_Y == NULL
+ *
+ * The cross-process sum of Y is not part of this library.  d_ws: SpMM workspace prepared for
+ * (rowptr, m, nnz, f_out) or NULL.  d_yws: scratch of gcn_bwd_workspace_bytes() bytes for
+ * the partial sums of Y (required if d_Y != NULL).
+ */
+int gcn_bwd_workspace_bytes(int64_t m, int32_t f_in, int32_t f_out, size_t* bytes);
+int gcn_layer_bwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                  int64_t m, int64_t nnz, const float* d_G, int32_t f_out, const float* d_W,
+                  int32_t f_in, const float* d_Zprev, const float* d_Hprev, int32_t gemm_prec,
+                  float* d_S, float* d_Gprev, float* d_Y, void* d_ws, size_t ws_bytes,
+                  void* d_yws, size_t yws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGNN_H */

@@ -1,0 +1,13 @@
+"""MI355X-native hot path of sparsity-aware block-row SpMM for full-graph GCN training.
+
+The compute lives in libsagnn.so (hand-written HIP for gfx950, C ABI declared in
+include/sagnn.h).  This package is a thin marshalling layer: torch supplies device memory
+and the stream, every step runs in the library's kernels.  There is no CPU fallback: if the
+library is missing or no GPU is present, calls raise.
+"""
+from .binding import (  # noqa: F401
+    SagnnError, lib, lib_path, Plan, SpmmWorkspace,
+    spmm_plan_needed_rows, spmm_pack_rows, spmm_csr_prepare, spmm_csr_tallskinny,
+    dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd,
+    ACT_IDENTITY, ACT_RELU, GEMM_FP32, GEMM_BF16, PLAN_VALIDATE,
+)

@@ -1,0 +1,258 @@
+"""ctypes binding of libsagnn.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+ACT_IDENTITY, ACT_RELU = 0, 1
+GEMM_FP32, GEMM_BF16 = 0, 1
+PLAN_VALIDATE = 1
+
+EXPORTS = [
+    "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
+    "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_pack_rows",
+    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_tallskinny",
+    "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
+]
+
+
+class SagnnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().sagnn_strerror(code).decode()
+        extra = f" (hipError {lib().sagnn_last_hip_error()})" if code == -4 else ""
+        super().__init__(f"{where}: {msg}{extra} [{code}]")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def lib():
+    """Load libsagnn.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build_hip()
+        L = ctypes.CDLL(_build.LIB)
+        i64, i32, u32, vp, sz = (ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p,
+                                 ctypes.c_size_t)
+        psz = ctypes.POINTER(ctypes.c_size_t)
+        L.sagnn_strerror.restype = ctypes.c_char_p
+        L.sagnn_strerror.argtypes = [ctypes.c_int]
+        L.sagnn_last_hip_error.restype = ctypes.c_int
+        L.sagnn_version.restype = ctypes.c_int
+        L.spmm_plan_workspace_bytes.argtypes = [i64, i64, i64, i32, psz]
+        L.spmm_plan_needed_rows.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64, vp, vp, vp, sz,
+                                            u32, vp]
+        L.spmm_pack_rows.argtypes = [vp, i64, i64, i32, vp, i64, vp, i64, vp]
+        L.spmm_csr_workspace_bytes.argtypes = [i64, i64, i32, psz]
+        L.spmm_csr_prepare.argtypes = [vp, i64, i64, i32, vp, sz, vp]
+        L.spmm_csr_tallskinny.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i64, i32, vp,
+                                          sz, vp]
+        L.dense_gemm_act.argtypes = [vp, i64, vp, i64, i32, i64, i32, i32, i32, i32, vp, i64, vp, i64,
+                                     vp, i64, vp]
+        L.gcn_layer_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i32, i32, i32, vp,
+                                    vp, vp, vp, sz, vp]
+        L.gcn_bwd_workspace_bytes.argtypes = [i64, i32, i32, psz]
+        L.gcn_layer_bwd.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i32, vp, vp, i32, vp, vp, vp,
+                                    vp, sz, vp, sz, vp]
+        for name in EXPORTS[3:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise SagnnError(rc, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a CUDA/HIP tensor (there is no CPU path)")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name}: expected contiguous {dtype}")
+    return t
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    # torch's caching allocator returns 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class Plan:
+    needed: torch.Tensor          # int32 [N], ascending global column ids
+    blk_off: np.ndarray           # int64 [nb+1] (host)
+    colidx_compact: torch.Tensor  # int32 [nnz] or None
+
+    @property
+    def N(self) -> int:
+        return int(self.blk_off[-1])
+
+
+def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, validate=False,
+                          needed_cap=None) -> Plan:
+    """NnzCols of every column block (Sec. 4.1).  Allocates outputs with torch; the first call
+    sizes `needed` at min(n, nnz) unless needed_cap is given."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    colblk = np.ascontiguousarray(colblk, dtype=np.int64)
+    nb = colblk.size - 1
+    L = lib()
+    wsb = ctypes.c_size_t(0)
+    _check(L.spmm_plan_workspace_bytes(m, n, nnz, nb, ctypes.byref(wsb)), "spmm_plan_workspace_bytes")
+    ws = _ws(wsb.value, rowptr.device)
+    cap = int(min(n, nnz) if needed_cap is None else needed_cap)
+    needed = torch.empty(max(cap, 1), dtype=torch.int32, device=rowptr.device)
+    compact = torch.empty(max(nnz, 1), dtype=torch.int32, device=rowptr.device) if want_compact else None
+    blk_off = np.zeros(nb + 1, dtype=np.int64)
+    rc = L.spmm_plan_needed_rows(_ptr(rowptr), _ptr(colidx), m, n, nnz,
+                                 colblk.ctypes.data_as(ctypes.c_void_p), nb, _ptr(needed), cap,
+                                 blk_off.ctypes.data_as(ctypes.c_void_p), _ptr(compact), _ptr(ws),
+                                 ws.numel(), PLAN_VALIDATE if validate else 0, _stream())
+    _check(rc, "spmm_plan_needed_rows")
+    N = int(blk_off[-1])
+    return Plan(needed[:N], blk_off, compact[:nnz] if want_compact else None)
+
+
+def spmm_pack_rows(H, rows, out=None):
+    """out[r,:] = H[rows[r],:] (Alg. 1, packed buffer)."""
+    H = _dev(H, torch.float32, "H")
+    rows = _dev(rows, torch.int32, "rows")
+    n, f = H.shape
+    N = rows.numel()
+    if out is None:
+        out = torch.empty((N, f), dtype=torch.float32, device=H.device)
+    _dev(out, torch.float32, "out")
+    _check(lib().spmm_pack_rows(_ptr(H), n, H.stride(0), f, _ptr(rows), N, _ptr(out), out.stride(0),
+                                _stream()), "spmm_pack_rows")
+    return out
+
+
+@dataclass
+class SpmmWorkspace:
+    buf: torch.Tensor
+    m: int
+    nnz: int
+    f: int
+
+
+def spmm_csr_prepare(rowptr, nnz: int, f: int) -> SpmmWorkspace:
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    m = rowptr.numel() - 1
+    L = lib()
+    wsb = ctypes.c_size_t(0)
+    _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
+    buf = _ws(wsb.value, rowptr.device)
+    _check(L.spmm_csr_prepare(_ptr(rowptr), m, nnz, f, _ptr(buf), buf.numel(), _stream()),
+           "spmm_csr_prepare")
+    return SpmmWorkspace(buf, m, nnz, f)
+
+
+def spmm_csr_tallskinny(rowptr, colidx, val, B, C=None, accumulate=False, ws: SpmmWorkspace = None):
+    """C (+)= A * B (Alg. 1/2 local SpMM)."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    B = _dev(B, torch.float32, "B")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    k, f = B.shape
+    if C is None:
+        if accumulate:
+            raise ValueError("accumulate needs C")
+        C = torch.empty((m, f), dtype=torch.float32, device=B.device)
+    _dev(C, torch.float32, "C")
+    if ws is not None and (ws.m != m or ws.nnz != nnz or ws.f < f):
+        raise ValueError("workspace was prepared for another matrix")
+    rc = lib().spmm_csr_tallskinny(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(B),
+                                   B.stride(0), f, _ptr(C), C.stride(0), int(accumulate),
+                                   _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0,
+                                   _stream())
+    _check(rc, "spmm_csr_tallskinny")
+    return C
+
+
+def dense_gemm_act(X, W, transW=False, prec=GEMM_FP32, act=ACT_IDENTITY, mask=None, want_z=True,
+                   want_act=False):
+    X = _dev(X, torch.float32, "X")
+    W = _dev(W, torch.float32, "W")
+    m, kdim = X.shape
+    nout = W.shape[0] if transW else W.shape[1]
+    Z = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_z else None
+    A = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_act else None
+    rc = lib().dense_gemm_act(_ptr(X), X.stride(0), _ptr(W), W.stride(0), int(transW), m, kdim, nout,
+                              prec, act, _ptr(mask), mask.stride(0) if mask is not None else 0,
+                              _ptr(Z), nout, _ptr(A), nout, _stream())
+    _check(rc, "dense_gemm_act")
+    return Z, A
+
+
+def gcn_layer_fwd(rowptr, colidx, val, H, W, act=ACT_RELU, prec=GEMM_FP32, ws: SpmmWorkspace = None,
+                  want_z=True, want_h=True, out=None):
+    """T = A H, Z = T W, Hout = sigma(Z).  Returns (T, Z, Hout)."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    H = _dev(H, torch.float32, "H")
+    W = _dev(W, torch.float32, "W")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    k, f_in = H.shape
+    f_out = W.shape[1]
+    if out is None:
+        T = torch.empty((m, f_in), dtype=torch.float32, device=H.device)
+        Z = torch.empty((m, f_out), dtype=torch.float32, device=H.device) if want_z else None
+        Ho = torch.empty((m, f_out), dtype=torch.float32, device=H.device) if want_h else None
+    else:
+        T, Z, Ho = out
+    rc = lib().gcn_layer_fwd(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(H), H.stride(0),
+                             f_in, _ptr(W), f_out, act, prec, _ptr(T), _ptr(Z), _ptr(Ho),
+                             _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0, _stream())
+    _check(rc, "gcn_layer_fwd")
+    return T, Z, Ho
+
+
+def gcn_layer_bwd(rowptr, colidx, val, G, W, Zprev, Hprev, prec=GEMM_FP32, ws: SpmmWorkspace = None,
+                  want_gprev=True, want_y=True):
+    """S = A G, Gprev = (S W^T) .* [Zprev > 0], Y = Hprev^T S.  Returns (S, Gprev, Y)."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    G = _dev(G, torch.float32, "G")
+    W = _dev(W, torch.float32, "W")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    f_in, f_out = W.shape
+    dev = G.device
+    S = torch.empty((m, f_out), dtype=torch.float32, device=dev)
+    Gp = torch.empty((m, f_in), dtype=torch.float32, device=dev) if want_gprev else None
+    Y = torch.empty((f_in, f_out), dtype=torch.float32, device=dev) if want_y else None
+    yws = None
+    if want_y:
+        b = ctypes.c_size_t(0)
+        _check(lib().gcn_bwd_workspace_bytes(m, f_in, f_out, ctypes.byref(b)), "gcn_bwd_workspace_bytes")
+        yws = _ws(b.value, dev)
+    rc = lib().gcn_layer_bwd(_ptr(rowptr), _ptr(colidx), _ptr(val), m, nnz, _ptr(G), f_out, _ptr(W),
+                             f_in, _ptr(Zprev), _ptr(Hprev), prec, _ptr(S), _ptr(Gp), _ptr(Y),
+                             _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0,
+                             _ptr(yws), yws.numel() if yws is not None else 0, _stream())
+    _check(rc, "gcn_layer_bwd")
+    return S, Gp, Y

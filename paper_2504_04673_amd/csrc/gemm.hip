@@ -1,0 +1,404 @@
+// Dense transforms of the GCN layer on the matrix cores (MFMA), gfx950.
+//   forward   Z = T W, H' = sigma(Z)                     (Sec. 2.1 forward equations; Alg. 1
+//                                                          "H <- GEMM(Z, W)")
+//   backward  G' = (S W^T) .* sigma'(Z')                  (Sec. 2.1 backward equation for G)
+//             Y  = H'^T S                                  (Sec. 4.1, weight-gradient paragraph)
+//
+// Tall-skinny shapes: m is 10^5..10^7 rows, the feature widths are <= 256, so W fits in LDS
+// and every kernel streams the tall operand from HBM exactly once.
+//
+// gemm_nn_kernel (Z = X op(W)): a workgroup stages its slab of W in LDS once and then walks
+// row tiles persistently; each wavefront owns a 32-row tile and keeps NT 32x32 accumulator
+// tiles in registers.  The A operand of the MFMA is read straight from global memory in
+// operand layout: the k order inside an MFMA does not matter as long as both operands agree,
+// so lane (row r, half h) takes the 16 (fp32) or 32 (bf16) contiguous bytes
+// X[r][8j+4h..] / X[r][16j+8h..] and the matching rows of W are picked from LDS.
+//   fp32: v_mfma_f32_32x32x2_f32;  bf16: operands rounded RNE, v_mfma_f32_32x32x16_bf16.
+// The epilogue applies the optional mask and activation and stores from the accumulator
+// layout (row = 8*(v/4) + 4*(lane/32) + v%4, col = lane%32 of each 32x32 tile).
+//
+// gemm_tn_kernel (Y = X^T S): the reduction runs over the m rows.  Each workgroup takes a
+// contiguous slab of rows, stages 32 rows of X and S at a time in LDS transposed (k
+// contiguous per column, so an operand is one LDS read), accumulates a full f_in x f_out
+// partial in registers (8 wavefronts x 2x4 tiles) and writes it to scratch; a second kernel
+// sums the partials in a fixed order (reproducible, no atomics).
+#include <type_traits>
+
+#include "common.h"
+
+namespace sagnn {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct GemmArgs {
+  const float* X; int64_t ldx;
+  const float* W; int64_t ldw; int32_t transW;
+  int64_t m; int32_t kdim, nout;
+  int32_t act;
+  const float* mask; int64_t ldmask;
+  float* Z; int64_t ldz;
+  float* A; int64_t lda;
+  int32_t n0;  // first output column of this launch's slab
+};
+
+// ------------------------------------------------------------------------------------------
+template <int NT, bool BF16, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int NB = NT * 32;
+  const int tid = threadIdx.x;
+  const int kdim = g.kdim;
+
+  // stage the W slab: fp32 as Ws[k][n]; bf16 packed as Ws[k/8][n][k%8]
+  for (int idx = tid; idx < kdim * NB; idx += WAVES * 64) {
+    const int k = idx / NB, n = idx - k * NB;
+    const int col = g.n0 + n;
+    float w = 0.f;
+    if (col < g.nout) w = g.transW ? g.W[(int64_t)col * g.ldw + k] : g.W[(int64_t)k * g.ldw + col];
+    if (BF16)
+      reinterpret_cast<__bf16*>(smem)[((k >> 3) * NB + n) * 8 + (k & 7)] = (__bf16)w;
+    else
+      reinterpret_cast<float*>(smem)[k * NB + n] = w;
+  }
+  __syncthreads();
+
+  const int lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 31, h = lane >> 5;
+  const int64_t ntiles = (g.m + 31) >> 5;
+  for (int64_t t = (int64_t)blockIdx.x * WAVES + wave; t < ntiles; t += (int64_t)gridDim.x * WAVES) {
+    int64_t row = t * 32 + r;
+    if (row >= g.m) row = g.m - 1;  // clamped read, result discarded at the store
+    const float* __restrict__ xrow = g.X + row * g.ldx;
+    floatx16 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
+
+    if (BF16) {
+      const bf16x8* __restrict__ Ws = reinterpret_cast<const bf16x8*>(smem);
+#pragma unroll 2
+      for (int j = 0; j < kdim / 16; ++j) {
+        const float4 x0 = *reinterpret_cast<const float4*>(xrow + 16 * j + 8 * h);
+        const float4 x1 = *reinterpret_cast<const float4*>(xrow + 16 * j + 8 * h + 4);
+        bf16x8 a;
+        a[0] = (__bf16)x0.x; a[1] = (__bf16)x0.y; a[2] = (__bf16)x0.z; a[3] = (__bf16)x0.w;
+        a[4] = (__bf16)x1.x; a[5] = (__bf16)x1.y; a[6] = (__bf16)x1.z; a[7] = (__bf16)x1.w;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const bf16x8 b = Ws[(2 * j + h) * NB + nt * 32 + r];
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+        }
+      }
+    } else {
+      const float* __restrict__ Ws = reinterpret_cast<const float*>(smem);
+#pragma unroll 2
+      for (int j = 0; j < kdim / 8; ++j) {
+        const float4 x = *reinterpret_cast<const float4*>(xrow + 8 * j + 4 * h);
+        const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float* wrow = Ws + (8 * j + 4 * h + i) * NB + r;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[i], wrow[nt * 32], acc[nt], 0, 0, 0);
+        }
+      }
+    }
+
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int col = g.n0 + nt * 32 + r;
+      if (col >= g.nout) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t ro = t * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+        if (ro >= g.m) continue;
+        float z = acc[nt][v];
+        if (g.mask && !(g.mask[ro * g.ldmask + col] > 0.f)) z = 0.f;
+        if (g.Z) g.Z[ro * g.ldz + col] = z;
+        if (g.A) g.A[ro * g.lda + col] = (g.act == SAGNN_ACT_RELU) ? (z > 0.f ? z : 0.f) : z;
+      }
+    }
+  }
+}
+
+template <int NT, bool BF16>
+int launch_nn(const GemmArgs& g, hipStream_t s) {
+  constexpr int WAVES = BF16 ? 8 : 4;
+  auto kern = gemm_nn_kernel<NT, BF16, WAVES>;
+  const size_t lds = (size_t)g.kdim * NT * 32 * (BF16 ? 2 : 4);
+  if (lds > 160 * 1024) return SAGNN_EINVAL;
+  SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  const int64_t ntiles = (g.m + 31) / 32;
+  int64_t blocks = ceil_div(ntiles, WAVES);
+  const int64_t per_cu = lds > 80 * 1024 ? 1 : (lds > 40 * 1024 ? 2 : 4);
+  if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), lds, s, g);
+  SAGNN_LAUNCH_CHECK();
+  return SAGNN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Y = X^T S.  KB rows per stage; LDS rows padded to KP elements (16-byte multiple).
+constexpr int kTnWaves = 8;
+constexpr int kTnThreads = kTnWaves * 64;
+constexpr int KB = 32, KP = 40;
+
+struct TnArgs {
+  const float* X; int64_t ldx;
+  const float* S; int64_t lds_;
+  int64_t m; int32_t fi, fo;
+  int64_t rows_per_wg;
+  float* partial;  // [gridDim.x][fi][fo]
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
+  using lds_t = typename std::conditional<BF16, __bf16, float>::type;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  lds_t* Xs = reinterpret_cast<lds_t*>(smem);                    // [fi][KP]
+  lds_t* Ss = Xs + (size_t)g.fi * KP;                            // [fo][KP]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i = lane & 31, h = lane >> 5;
+  const int wa = wave >> 1, wb = wave & 1;  // wave tile: a-tiles {2wa,2wa+1}, b-tiles {4wb..4wb+3}
+  const int TA = g.fi / 32, TB = g.fo / 32;
+
+  const int64_t r_begin = (int64_t)blockIdx.x * g.rows_per_wg;
+  int64_t r_end = r_begin + g.rows_per_wg;
+  if (r_end > g.m) r_end = g.m;
+
+  floatx16 acc[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  // staging map: thread -> (column group cg of 4 columns, row pair kp); 64 groups x 8 pairs
+  // per pass, two passes cover the KB = 32 rows of a stage
+  const int cg = tid & 63, kp = tid >> 6;
+  float4 xr[2][2], sr[2][2];
+  auto load_stage = [&](int64_t r0) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int64_t row = r0 + (kp + 8 * p) * 2 + q;
+        const bool ok = row < r_end;
+        xr[p][q] = (ok && cg * 4 < g.fi) ? *reinterpret_cast<const float4*>(g.X + row * g.ldx + cg * 4)
+                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+        sr[p][q] = (ok && cg * 4 < g.fo) ? *reinterpret_cast<const float4*>(g.S + row * g.lds_ + cg * 4)
+                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+  };
+  auto store_stage = [&]() {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int kk = (kp + 8 * p) * 2;
+      const float xa[4] = {xr[p][0].x, xr[p][0].y, xr[p][0].z, xr[p][0].w};
+      const float xb[4] = {xr[p][1].x, xr[p][1].y, xr[p][1].z, xr[p][1].w};
+      const float sa[4] = {sr[p][0].x, sr[p][0].y, sr[p][0].z, sr[p][0].w};
+      const float sb[4] = {sr[p][1].x, sr[p][1].y, sr[p][1].z, sr[p][1].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int col = cg * 4 + c;
+        if (col < g.fi) {
+          Xs[col * KP + kk] = (lds_t)xa[c];
+          Xs[col * KP + kk + 1] = (lds_t)xb[c];
+        }
+        if (col < g.fo) {
+          Ss[col * KP + kk] = (lds_t)sa[c];
+          Ss[col * KP + kk + 1] = (lds_t)sb[c];
+        }
+      }
+    }
+  };
+
+  if (r_begin < r_end) load_stage(r_begin);
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += KB) {
+    __syncthreads();  // previous stage fully consumed
+    store_stage();
+    __syncthreads();
+    if (r0 + KB < r_end) load_stage(r0 + KB);  // prefetch the next stage into registers
+    if (BF16) {
+#pragma unroll
+      for (int ks = 0; ks < KB / 16; ++ks) {
+        bf16x8 av[2], bv[4];
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          const int ta = 2 * wa + a;
+          av[a] = *reinterpret_cast<const bf16x8*>(
+              reinterpret_cast<const __bf16*>(Xs) + ((ta < TA ? ta : 0) * 32 + i) * KP + ks * 16 + 8 * h);
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int tb = 4 * wb + b;
+          bv[b] = *reinterpret_cast<const bf16x8*>(
+              reinterpret_cast<const __bf16*>(Ss) + ((tb < TB ? tb : 0) * 32 + i) * KP + ks * 16 + 8 * h);
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (2 * wa + a < TA && 4 * wb + b < TB)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
+      }
+    } else {
+#pragma unroll 4
+      for (int ks = 0; ks < KB / 2; ++ks) {
+        float av[2], bv[4];
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          const int ta = 2 * wa + a;
+          av[a] = reinterpret_cast<const float*>(Xs)[((ta < TA ? ta : 0) * 32 + i) * KP + ks * 2 + h];
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int tb = 4 * wb + b;
+          bv[b] = reinterpret_cast<const float*>(Ss)[((tb < TB ? tb : 0) * 32 + i) * KP + ks * 2 + h];
+        }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (2 * wa + a < TA && 4 * wb + b < TB)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+      }
+    }
+  }
+
+  float* __restrict__ P = g.partial + (int64_t)blockIdx.x * g.fi * g.fo;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int ta = 2 * wa + a, tb = 4 * wb + b;
+      if (ta >= TA || tb >= TB) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ro = ta * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+        P[(int64_t)ro * g.fo + tb * 32 + i] = acc[a][b][v];
+      }
+    }
+}
+
+__global__ __launch_bounds__(256) void tn_reduce_kernel(const float* __restrict__ partial,
+                                                        int32_t nparts, int64_t elems,
+                                                        float* __restrict__ Y) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= elems) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int p = 0;
+  for (; p + 4 <= nparts; p += 4) {
+    s0 += partial[(int64_t)(p + 0) * elems + idx];
+    s1 += partial[(int64_t)(p + 1) * elems + idx];
+    s2 += partial[(int64_t)(p + 2) * elems + idx];
+    s3 += partial[(int64_t)(p + 3) * elems + idx];
+  }
+  for (; p < nparts; ++p) s0 += partial[(int64_t)p * elems + idx];
+  Y[idx] = (s0 + s1) + (s2 + s3);
+}
+
+inline int32_t tn_parts(int64_t m) {
+  int64_t p = ceil_div(m, 4 * KB);  // at least 4 stages of work per workgroup
+  if (p > 256) p = 256;
+  if (p < 1) p = 1;
+  return (int32_t)p;
+}
+
+}  // namespace
+
+size_t gemm_tn_ws_bytes(int64_t m, int32_t fi, int32_t fo) {
+  return round_up(sizeof(float) * (size_t)tn_parts(m) * (size_t)fi * (size_t)fo, 256);
+}
+
+int launch_gemm_tn(const float* X, int64_t ldx, const float* S, int64_t lds_, int64_t m,
+                   int32_t fi, int32_t fo, int32_t prec, float* Y, void* yws, size_t yws_bytes,
+                   hipStream_t s) {
+  if (m < 0 || fi <= 0 || fo <= 0 || (fi & 31) || (fo & 31) || fi > 256 || fo > 256 ||
+      ldx < fi || lds_ < fo || (ldx & 3) || (lds_ & 3))
+    return SAGNN_EINVAL;
+  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
+  if (!Y || !yws || !aligned16(yws)) return SAGNN_EINVAL;
+  if (m > 0 && (!X || !S || !aligned16(X) || !aligned16(S))) return SAGNN_EINVAL;
+  if (yws_bytes < gemm_tn_ws_bytes(m, fi, fo)) return SAGNN_ECAPACITY;
+  const int32_t parts = tn_parts(m);
+  TnArgs g{};
+  g.X = X; g.ldx = ldx; g.S = S; g.lds_ = lds_; g.m = m; g.fi = fi; g.fo = fo;
+  g.rows_per_wg = ceil_div(ceil_div(m > 0 ? m : 1, parts), KB) * KB;
+  g.partial = reinterpret_cast<float*>(yws);
+  const bool bf16 = prec == SAGNN_GEMM_BF16;
+  const size_t lds = (size_t)(fi + fo) * KP * (bf16 ? 2 : 4);
+  if (bf16) {
+    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_kernel<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(gemm_tn_kernel<true>, dim3(parts), dim3(kTnThreads), lds, s, g);
+  } else {
+    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_kernel<false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(gemm_tn_kernel<false>, dim3(parts), dim3(kTnThreads), lds, s, g);
+  }
+  SAGNN_LAUNCH_CHECK();
+  const int64_t elems = (int64_t)fi * fo;
+  hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)ceil_div(elems, 256)), dim3(256), 0, s,
+                     g.partial, parts, elems, Y);
+  SAGNN_LAUNCH_CHECK();
+  return SAGNN_OK;
+}
+
+int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_t transW,
+                int64_t m, int32_t kdim, int32_t nout, int32_t prec, int32_t act,
+                const float* mask, int64_t ldmask, float* Z, int64_t ldz, float* A, int64_t lda,
+                hipStream_t s) {
+  if (m < 0 || kdim <= 0 || nout <= 0 || (kdim & 31) || (nout & 31) || kdim > 256 || nout > 256)
+    return SAGNN_EINVAL;
+  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
+  if (act != SAGNN_ACT_IDENTITY && act != SAGNN_ACT_RELU) return SAGNN_EINVAL;
+  if (transW != 0 && transW != 1) return SAGNN_EINVAL;
+  if (ldx < kdim || (ldx & 3) || ldw < (transW ? kdim : nout)) return SAGNN_EINVAL;
+  if ((Z && ldz < nout) || (A && lda < nout) || (mask && ldmask < nout)) return SAGNN_EINVAL;
+  if (!Z && !A) return SAGNN_EINVAL;
+  if (!W) return SAGNN_EINVAL;
+  if (m == 0) return SAGNN_OK;
+  if (!X || !aligned16(X)) return SAGNN_EINVAL;
+
+  GemmArgs g{};
+  g.X = X; g.ldx = ldx; g.W = W; g.ldw = ldw; g.transW = transW; g.m = m; g.kdim = kdim;
+  g.nout = nout; g.act = act; g.mask = mask; g.ldmask = ldmask; g.Z = Z; g.ldz = ldz; g.A = A;
+  g.lda = lda;
+  if (prec == SAGNN_GEMM_BF16) {
+    g.n0 = 0;
+    const int tiles = nout / 32;
+    if (tiles <= 1) return launch_nn<1, true>(g, s);
+    if (tiles <= 2) return launch_nn<2, true>(g, s);
+    if (tiles <= 4) return launch_nn<4, true>(g, s);
+    return launch_nn<8, true>(g, s);
+  }
+  for (int32_t n0 = 0; n0 < nout; n0 += 128) {
+    g.n0 = n0;
+    const int tiles = (nout - n0 < 128 ? nout - n0 : 128) / 32;
+    int rc;
+    if (tiles <= 1) rc = launch_nn<1, false>(g, s);
+    else if (tiles <= 2) rc = launch_nn<2, false>(g, s);
+    else rc = launch_nn<4, false>(g, s);
+    if (rc != SAGNN_OK) return rc;
+  }
+  return SAGNN_OK;
+}
+
+}  // namespace sagnn
+
+SAGNN_EXPORT int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw,
+                                int32_t transW, int64_t m, int32_t kdim, int32_t nout,
+                                int32_t prec, int32_t act, const float* d_mask, int64_t ldmask,
+                                float* d_Z, int64_t ldz, float* d_act, int64_t ldact,
+                                void* stream) {
+  return sagnn::launch_gemm(d_X, ldx, d_W, ldw, transW, m, kdim, nout, prec, act, d_mask, ldmask,
+                            d_Z, ldz, d_act, ldact, (hipStream_t)stream);
+}

@@ -1,0 +1,306 @@
+// Needed-row planning: NnzCols of every column block of a CSR row block (Sec. 4.1, the
+// paragraph that defines NnzCols(i,j) as the nonzero column indices of block A_ij, i.e. the
+// rows of H_j that P(i) has to receive).
+//
+// Integer only, result unique.  Pipeline (all kernels on the caller's stream):
+//   clear    bitmap of n bits (64 columns per word)
+//   mark     one pass over colidx: set bit c.  Test-before-set keeps hub columns from
+//            hammering one word with atomics.
+//   count    per-word popcount, block sums                      \  three-kernel exclusive
+//   scan     exclusive scan of the block sums (one workgroup)    > scan of the popcounts
+//   prefix   per-word exclusive prefix = rank of the word's       /  (wavefront shuffles)
+//            first column among the needed columns
+//   blkoff   rank of every column-block boundary -> blk_off, N   (then one D2H copy + sync)
+//   emit     one wavefront per 64-column word: lane l tests column 64w+l, the ballot of the
+//            test is the wavefront's 64-bit mask and mbcnt gives each set lane its slot
+//            (ballot / prefix-count stream compaction); needed[] comes out ascending
+//   remap    compact[e] = prefix[c>>6] + popcount(word & bits below c): position of column
+//            c in needed[]; monotone in c, so sorted rows stay sorted
+// Traffic: nnz*4 (mark) + nnz*8 (remap read+write) + N*4 + a few passes over n/8 bytes.
+#include "common.h"
+
+namespace sagnn {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWordsPerBlock = 2048;  // scan tile: 256 threads x 8 words
+
+struct PlanWs {
+  uint64_t* bitmap;   // W words
+  int32_t* prefix;    // W + 1
+  int32_t* blocksum;  // nblk + 1
+  int64_t* colblk;    // nb + 1 (device copy of the block boundaries)
+  int64_t* blkoff;    // nb + 1
+  int32_t* err;       // 4 counters
+  int64_t W, nblk;
+  size_t bytes;
+};
+
+PlanWs carve(void* base, int64_t n, int32_t nb) {
+  PlanWs w;
+  w.W = ceil_div(n > 0 ? n : 1, 64);
+  w.nblk = ceil_div(w.W, kWordsPerBlock);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += round_up(bytes, 256);
+    return reinterpret_cast<char*>(base) + o;
+  };
+  w.bitmap = reinterpret_cast<uint64_t*>(take(sizeof(uint64_t) * (size_t)w.W));
+  w.prefix = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(w.W + 1)));
+  w.blocksum = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(w.nblk + 1)));
+  w.colblk = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
+  w.blkoff = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
+  w.err = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 4));
+  w.bytes = off;
+  return w;
+}
+
+__global__ __launch_bounds__(kThreads) void clear_kernel(uint64_t* __restrict__ bm, int64_t W,
+                                                         int32_t* __restrict__ err) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < W; i += stride) bm[i] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < 4) err[threadIdx.x] = 0;
+}
+
+// err[0]: rowptr malformed, err[1]: column out of range
+__global__ __launch_bounds__(kThreads) void validate_rowptr_kernel(
+    const int32_t* __restrict__ rowptr, int64_t m, int64_t nnz, int32_t* __restrict__ err) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r < m; r += stride)
+    if (rowptr[r] > rowptr[r + 1]) err[0] = 1;
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    if (rowptr[0] != 0 || (int64_t)rowptr[m] != nnz) err[0] = 1;
+}
+
+__global__ __launch_bounds__(kThreads) void mark_kernel(const int32_t* __restrict__ colidx,
+                                                        int64_t nnz, int64_t n,
+                                                        uint32_t* __restrict__ bm32,
+                                                        int32_t* __restrict__ err) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride) {
+    const int64_t c = colidx[e];
+    if (c < 0 || c >= n) {
+      err[1] = 1;
+      continue;
+    }
+    const uint32_t bit = 1u << (c & 31);
+    uint32_t* w = bm32 + (c >> 5);
+    if (!(__builtin_nontemporal_load(w) & bit)) atomicOr(w, bit);
+  }
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(v, d, 64);
+    if (lane >= d) v += t;
+  }
+  return v;
+}
+
+// exclusive scan over the kThreads threads of a block; returns the exclusive prefix of v and
+// the block total through *total
+__device__ __forceinline__ int block_exclusive_scan(int v, int* total) {
+  __shared__ int wsum[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int inc = wave_inclusive_scan(v);
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) {
+    const int s = wsum[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  __syncthreads();
+  *total = tot;
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(kThreads) void count_kernel(const uint64_t* __restrict__ bm,
+                                                         int64_t W, int32_t* __restrict__ blocksum) {
+  const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + (int64_t)threadIdx.x * 8;
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    if (w0 + i < W) s += __popcll(bm[w0 + i]);
+  int total;
+  (void)block_exclusive_scan(s, &total);
+  if (threadIdx.x == 0) blocksum[blockIdx.x] = total;
+}
+
+// one workgroup: in-place exclusive scan of blocksum[0..nblk), blocksum[nblk] = grand total
+__global__ __launch_bounds__(kThreads) void scan_blocks_kernel(int32_t* __restrict__ blocksum,
+                                                               int64_t nblk) {
+  int carry = 0;
+  for (int64_t base = 0; base < nblk; base += kThreads) {
+    const int64_t i = base + threadIdx.x;
+    const int v = (i < nblk) ? blocksum[i] : 0;
+    int total;
+    const int ex = block_exclusive_scan(v, &total);
+    if (i < nblk) blocksum[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) blocksum[nblk] = carry;
+}
+
+__global__ __launch_bounds__(kThreads) void prefix_kernel(const uint64_t* __restrict__ bm,
+                                                          int64_t W,
+                                                          const int32_t* __restrict__ blocksum,
+                                                          int64_t nblk, int32_t* __restrict__ prefix) {
+  const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + (int64_t)threadIdx.x * 8;
+  int c[8];
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    c[i] = (w0 + i < W) ? __popcll(bm[w0 + i]) : 0;
+    s += c[i];
+  }
+  int total;
+  int run = blocksum[blockIdx.x] + block_exclusive_scan(s, &total);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (w0 + i < W) prefix[w0 + i] = run;
+    run += c[i];
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) prefix[W] = blocksum[nblk];
+}
+
+__device__ __forceinline__ int rank_of(const uint64_t* __restrict__ bm,
+                                       const int32_t* __restrict__ prefix, int64_t c) {
+  const int64_t w = c >> 6;
+  const uint64_t below = bm[w] & ((1ull << (c & 63)) - 1ull);
+  return prefix[w] + __popcll(below);
+}
+
+__global__ void blkoff_kernel(const uint64_t* __restrict__ bm, const int32_t* __restrict__ prefix,
+                              int64_t W, int64_t n, const int64_t* __restrict__ colblk, int32_t nb,
+                              int64_t* __restrict__ blkoff) {
+  for (int q = threadIdx.x; q <= nb; q += blockDim.x) {
+    const int64_t c = colblk[q];
+    blkoff[q] = (c >= n || (c >> 6) >= W) ? (int64_t)prefix[W] : (int64_t)rank_of(bm, prefix, c);
+  }
+}
+
+// one wavefront per bitmap word
+__global__ __launch_bounds__(kThreads) void emit_kernel(const uint64_t* __restrict__ bm,
+                                                        const int32_t* __restrict__ prefix,
+                                                        int64_t W, int64_t n,
+                                                        int32_t* __restrict__ needed) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * kThreads) >> 6;
+  for (int64_t w = wave0; w < W; w += nwaves) {
+    const uint64_t word = bm[w];
+    const int64_t c = w * 64 + lane;
+    const bool set = ((word >> lane) & 1ull) != 0 && c < n;
+    const uint64_t mask = __ballot(set);
+    const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                               __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+    if (set) needed[(int64_t)prefix[w] + slot] = (int32_t)c;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void remap_kernel(const int32_t* __restrict__ colidx,
+                                                         int64_t nnz, int64_t n,
+                                                         const uint64_t* __restrict__ bm,
+                                                         const int32_t* __restrict__ prefix,
+                                                         int32_t* __restrict__ compact) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride) {
+    const int64_t c = colidx[e];
+    compact[e] = (c < 0 || c >= n) ? -1 : rank_of(bm, prefix, c);
+  }
+}
+
+inline unsigned grid_for(int64_t items, int64_t per_thread = 1) {
+  int64_t b = ceil_div(ceil_div(items, per_thread), kThreads);
+  const int64_t cap = 256 * 32;  // enough workgroups to fill 256 CUs several times over
+  if (b > cap) b = cap;
+  if (b < 1) b = 1;
+  return (unsigned)b;
+}
+
+}  // namespace
+}  // namespace sagnn
+
+SAGNN_EXPORT int spmm_plan_workspace_bytes(int64_t m, int64_t n, int64_t nnz, int32_t nb,
+                                           size_t* bytes) {
+  using namespace sagnn;
+  if (!bytes || m < 0 || n < 0 || nnz < 0 || nb < 1 || n > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  *bytes = carve(nullptr, n, nb).bytes;
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                       int64_t m, int64_t n, int64_t nnz,
+                                       const int64_t* h_colblk, int32_t nb, int32_t* d_needed,
+                                       int64_t needed_cap, int64_t* h_blk_off,
+                                       int32_t* d_colidx_compact, void* d_ws, size_t ws_bytes,
+                                       uint32_t flags, void* stream) {
+  using namespace sagnn;
+  if (m < 0 || n < 0 || nnz < 0 || nb < 1 || needed_cap < 0 || n > 0x7FFFFFFFll ||
+      nnz > 0x7FFFFFFFll || m > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  if (!h_colblk || !h_blk_off || !d_ws || !d_rowptr) return SAGNN_EINVAL;
+  if (nnz > 0 && !d_colidx) return SAGNN_EINVAL;
+  if (needed_cap > 0 && !d_needed) return SAGNN_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return SAGNN_EINVAL;
+  if (h_colblk[0] != 0 || h_colblk[nb] != n) return SAGNN_EFORMAT;
+  for (int32_t q = 0; q < nb; ++q)
+    if (h_colblk[q] > h_colblk[q + 1]) return SAGNN_EFORMAT;
+  const PlanWs w = carve(d_ws, n, nb);
+  if (ws_bytes < w.bytes) return SAGNN_ECAPACITY;
+  hipStream_t s = (hipStream_t)stream;
+
+  SAGNN_HIP(hipMemcpyAsync(w.colblk, h_colblk, sizeof(int64_t) * (size_t)(nb + 1),
+                           hipMemcpyHostToDevice, s));
+  hipLaunchKernelGGL(clear_kernel, dim3(grid_for(w.W)), dim3(kThreads), 0, s, w.bitmap, w.W, w.err);
+  SAGNN_LAUNCH_CHECK();
+  if (flags & SAGNN_PLAN_VALIDATE) {
+    hipLaunchKernelGGL(validate_rowptr_kernel, dim3(grid_for(m)), dim3(kThreads), 0, s, d_rowptr,
+                       m, nnz, w.err);
+    SAGNN_LAUNCH_CHECK();
+  }
+  if (nnz > 0) {
+    hipLaunchKernelGGL(mark_kernel, dim3(grid_for(nnz, 4)), dim3(kThreads), 0, s, d_colidx, nnz,
+                       n, reinterpret_cast<uint32_t*>(w.bitmap), w.err);
+    SAGNN_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(count_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.bitmap, w.W,
+                     w.blocksum);
+  SAGNN_LAUNCH_CHECK();
+  hipLaunchKernelGGL(scan_blocks_kernel, dim3(1), dim3(kThreads), 0, s, w.blocksum, w.nblk);
+  SAGNN_LAUNCH_CHECK();
+  hipLaunchKernelGGL(prefix_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.bitmap, w.W,
+                     w.blocksum, w.nblk, w.prefix);
+  SAGNN_LAUNCH_CHECK();
+  hipLaunchKernelGGL(blkoff_kernel, dim3(1), dim3(kThreads), 0, s, w.bitmap, w.prefix, w.W, n,
+                     w.colblk, nb, w.blkoff);
+  SAGNN_LAUNCH_CHECK();
+
+  int32_t h_err[4] = {0, 0, 0, 0};
+  SAGNN_HIP(hipMemcpyAsync(h_blk_off, w.blkoff, sizeof(int64_t) * (size_t)(nb + 1),
+                           hipMemcpyDeviceToHost, s));
+  SAGNN_HIP(hipMemcpyAsync(h_err, w.err, sizeof(h_err), hipMemcpyDeviceToHost, s));
+  SAGNN_HIP(hipStreamSynchronize(s));
+  if ((flags & SAGNN_PLAN_VALIDATE) && (h_err[0] || h_err[1])) return SAGNN_EFORMAT;
+  const int64_t N = h_blk_off[nb];
+  if (N > needed_cap) return SAGNN_ECAPACITY;
+
+  if (N > 0) {
+    hipLaunchKernelGGL(emit_kernel, dim3(grid_for(w.W * 64)), dim3(kThreads), 0, s, w.bitmap,
+                       w.prefix, w.W, n, d_needed);
+    SAGNN_LAUNCH_CHECK();
+  }
+  if (d_colidx_compact && nnz > 0) {
+    hipLaunchKernelGGL(remap_kernel, dim3(grid_for(nnz, 4)), dim3(kThreads), 0, s, d_colidx, nnz,
+                       n, w.bitmap, w.prefix, d_colidx_compact);
+    SAGNN_LAUNCH_CHECK();
+  }
+  return SAGNN_OK;
+}

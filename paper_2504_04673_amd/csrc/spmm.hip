@@ -1,0 +1,531 @@
+// Local CSR x tall-skinny dense product  C (+)= A * B  (Alg. 1 / Alg. 2, the statement
+// "Z <- Z + SpMM(A_iq, H^)"; Sec. 4.1 block-sum equation).  fp32 FMA on the vector ALUs.
+//
+// Schedule: nonzero splitting.  The nnz stored entries are cut into chunks of kSpmmChunk
+// consecutive entries; one wavefront owns one chunk, whatever rows it covers, so a hub row of
+// a power-law graph is spread over many wavefronts and a run of short rows shares one.
+// Because the sparsity pattern is fixed for the whole training run, spmm_csr_prepare() records
+// once (a) the row in which each chunk starts and (b) one bit per entry telling whether the
+// entry is the last of its row.  The product kernel then walks its chunk as a flat stream:
+// the column indices and values of a batch are wavefront-uniform (scalar loads), the 64
+// lanes split the f columns of the dense row (coalesced 64*FPL*4-byte reads along f), all
+// loads of a batch are issued before the first FMA, and a set "row end" bit flushes the
+// accumulator to C.  A row that started in an earlier chunk is flushed to a per-chunk carry
+// slot instead; a second small kernel adds the carries to C in chunk order, so the result is
+// reproducible (no floating-point atomics).
+//
+// Narrow matrices (f < 64) use sub-wavefront groups: G = f/4 lanes (rounded up to a power of
+// two) read one dense row as float4 pieces, and 64/G entries are processed per step; a row
+// end inside a step triggers a cross-group butterfly reduction.
+//
+// Widths other than 64/128/256 are processed as column slabs of those widths plus a narrow
+// remainder.
+#include "common.h"
+
+namespace sagnn {
+namespace {
+
+constexpr int kT = kSpmmChunk;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWavesPerBlock * 64;
+
+template <int N> struct Vec { typedef float T __attribute__((ext_vector_type(N))); };
+template <> struct Vec<1> { typedef float T; };
+
+// Scalars of a launch.  Pointers are passed as separate __restrict__ kernel parameters: that
+// is what lets the compiler prove the index/value streams are never written by the kernel and
+// fetch them with scalar loads.
+struct SpmmDims {
+  int64_t m, nnz, nchunks, ldb, ldc, carry_ld;
+  uint32_t kmax;  // k - 1: largest valid column index
+  int32_t f;      // columns handled by this launch (slab width)
+  int32_t accumulate;
+};
+
+__device__ __forceinline__ bool ws_matches(const SpmmWsHeader* __restrict__ hdr, const SpmmDims& d) {
+  return hdr->magic == kSpmmMagic && hdr->m == d.m && hdr->nnz == d.nnz && hdr->nchunks == d.nchunks;
+}
+
+__device__ __forceinline__ int next_row(int r, bool has_empty, const int32_t* __restrict__ rowptr,
+                                        int64_t m) {
+  ++r;
+  if (has_empty)
+    while (r < m - 1 && rowptr[r + 1] == rowptr[r]) ++r;
+  return r;
+}
+
+#define SPMM_PTR_PARAMS                                                                     \
+  const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,                   \
+      const float *__restrict__ val, const float *__restrict__ B, float *__restrict__ C,    \
+      const SpmmWsHeader *__restrict__ hdr, const int32_t *__restrict__ chunk_row,          \
+      const uint32_t *__restrict__ flags, float *__restrict__ carry_base
+
+// ------------------------------------------------------------------------------------------
+// wide kernel: f == 64 * FPL, one entry per wavefront load.
+// Per batch of U entries: U dense-row loads are issued back to back (their column indices and
+// values are already in scalar registers), then the scalar loads of the NEXT batch, then the
+// FMAs with a uniform branch at every row end.
+template <int FPL, int U>
+__global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, const SpmmDims d) {
+  using vec = typename Vec<FPL>::T;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t loff = lane * (FPL * 4);  // byte offset of this lane's columns inside a row
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t k = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (k >= d.nchunks) return;
+  if (!ws_matches(hdr, d)) return;
+  const bool has_empty = hdr->has_empty_rows != 0;
+  const int32_t e0 = (int32_t)(k * kT);
+  const int32_t e1 = (int32_t)((d.nnz - e0 < kT) ? d.nnz : e0 + kT);
+  int r = chunk_row[k];
+  r = r < 0 ? 0 : (r > d.m - 1 ? (int)(d.m - 1) : r);
+  bool head = rowptr[r] < e0;  // first row began in an earlier chunk -> carry slot
+  const uint32_t* __restrict__ fl = flags + (e0 >> 5);
+  char* __restrict__ carry = reinterpret_cast<char*>(carry_base + k * d.carry_ld) + loff;
+
+  vec acc = 0.f;
+  auto flush = [&]() {
+    if (r >= d.m) return;  // cannot happen with a consistent rowptr; keeps stores in bounds
+    if (head) {
+      *reinterpret_cast<vec*>(carry) = acc;
+      head = false;
+    } else {
+      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)r * d.ldc) + loff);
+      if (d.accumulate) acc += *p;
+      *p = acc;
+    }
+    acc = 0.f;
+    r = next_row(r, has_empty, rowptr, d.m);
+  };
+
+  // entry e of the chunk, clamped so that the (only) partial chunk never reads past nnz
+  auto fetch = [&](int32_t e, int32_t (&c)[U], float (&v)[U]) {
+    if (e + U <= e1) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        c[u] = colidx[e + u];
+        v[u] = val[e + u];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int32_t ee = (e + u < e1) ? e + u : e1 - 1;
+        c[u] = colidx[ee];
+        v[u] = (e + u < e1) ? val[ee] : 0.f;
+      }
+    }
+  };
+
+  int32_t c[U];
+  float v[U];
+  fetch(e0, c, v);
+  for (int b = 0; b < kT / U; ++b) {
+    const int32_t e = e0 + b * U;
+    if (e >= e1) break;
+    const uint32_t fbits = (fl[(b * U) >> 5] >> ((b * U) & 31)) & (uint32_t)((1ull << U) - 1ull);
+    vec h[U];
+    float vc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t cc = (uint32_t)c[u] > d.kmax ? d.kmax : (uint32_t)c[u];
+      const char* rowbase = reinterpret_cast<const char*>(B + (int64_t)cc * d.ldb);
+      h[u] = *reinterpret_cast<const vec*>(rowbase + loff);
+      vc[u] = v[u];
+    }
+    if (e + U < e1) fetch(e + U, c, v);
+    // keep the U loads above together (the compiler would otherwise sink each one next to its use)
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc += vc[u] * h[u];
+      if ((fbits >> u) & 1u) flush();
+    }
+  }
+  const int32_t last = e1 - 1;
+  const bool closed = (flags[last >> 5] >> (last & 31)) & 1u;
+  if (!closed) flush();  // the row continues in the next chunk: store the partial sum
+}
+
+// ------------------------------------------------------------------------------------------
+// narrow kernel: f <= 64 (G lanes x float4 per entry, P = 64/G entries per step)
+typedef float vec4 __attribute__((ext_vector_type(4)));
+
+template <int G>
+__device__ __forceinline__ vec4 group_sum(vec4 t) {
+#pragma unroll
+  for (int dlt = G; dlt < 64; dlt <<= 1) {
+    t.x += __shfl_xor(t.x, dlt, 64);
+    t.y += __shfl_xor(t.y, dlt, 64);
+    t.z += __shfl_xor(t.z, dlt, 64);
+    t.w += __shfl_xor(t.w, dlt, 64);
+  }
+  return t;
+}
+
+template <int G, int U>
+__global__ __launch_bounds__(kBlock) void spmm_narrow_kernel(SPMM_PTR_PARAMS, const SpmmDims d) {
+  constexpr int P = 64 / G;
+  static_assert(P <= 32 && P >= 1, "group size");
+  const int lane = threadIdx.x & 63;
+  const int g = lane / G, li = lane % G;
+  const bool active = li * 4 < d.f;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t k = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (k >= d.nchunks) return;
+  if (!ws_matches(hdr, d)) return;
+  const bool has_empty = hdr->has_empty_rows != 0;
+  const int32_t e0 = (int32_t)(k * kT);
+  const int32_t e1 = (int32_t)((d.nnz - e0 < kT) ? d.nnz : e0 + kT);
+  int r = chunk_row[k];
+  r = r < 0 ? 0 : (r > d.m - 1 ? (int)(d.m - 1) : r);
+  bool head = rowptr[r] < e0;
+  const float* __restrict__ Bl = B + li * 4;
+  float* __restrict__ Cl = C + li * 4;
+  float* __restrict__ carry = carry_base + k * d.carry_ld + li * 4;
+  vec4 acc = 0.f;
+
+  auto emit = [&](vec4 t) {  // t: this lane's contribution to the row that ends / is cut here
+    t = group_sum<G>(t);
+    if (r >= d.m) return;  // cannot happen with a consistent rowptr; keeps stores in bounds
+    if (head) {
+      if (g == 0 && active) *reinterpret_cast<vec4*>(carry) = t;
+      head = false;
+    } else if (g == 0 && active) {
+      vec4* p = reinterpret_cast<vec4*>(Cl + (int64_t)r * d.ldc);
+      if (d.accumulate) t += *p;
+      *p = t;
+    }
+    r = next_row(r, has_empty, rowptr, d.m);
+  };
+
+  constexpr int kSteps = kT / P;
+  for (int s0 = 0; s0 < kSteps; s0 += U) {
+    if (e0 + s0 * P >= e1) break;
+    int32_t c[U];
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int32_t me = e0 + (s0 + u) * P + g;
+      const bool valid = me < e1;
+      c[u] = valid ? colidx[me] : 0;
+      v[u] = valid ? val[me] : 0.f;
+    }
+    vec4 h[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t cc = (uint32_t)c[u] > d.kmax ? d.kmax : (uint32_t)c[u];
+      h[u] = 0.f;
+      if (active) h[u] = *reinterpret_cast<const vec4*>(Bl + (int64_t)cc * d.ldb);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int32_t es = e0 + (s0 + u) * P;  // uniform
+      if (es < e1) {
+        uint32_t fm = (flags[es >> 5] >> (es & 31)) & (uint32_t)((1ull << P) - 1ull);
+        const vec4 prod = v[u] * h[u];
+        if (fm == 0) {
+          acc += prod;
+        } else {
+          int lo = 0;
+          while (fm) {
+            const int j = __builtin_ctz(fm);
+            fm &= fm - 1;
+            vec4 t = acc;
+            if (g >= lo && g <= j) t += prod;
+            emit(t);
+            acc = 0.f;
+            lo = j + 1;
+          }
+          if (g >= lo) acc = prod;
+        }
+      }
+    }
+  }
+  const int32_t last = e1 - 1;
+  const bool closed = (flags[last >> 5] >> (last & 31)) & 1u;
+  if (!closed) emit(acc);
+}
+
+// ------------------------------------------------------------------------------------------
+// carries: chunk k holds a carry iff its first row began before the chunk.  The first such
+// chunk of a row ("leader") sums the carries of all following chunks of the same row in a
+// fixed order and adds them to C.
+__global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(SPMM_PTR_PARAMS, const SpmmDims d,
+                                                            int32_t f_total) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t k = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (k >= d.nchunks || k == 0) return;
+  if (!ws_matches(hdr, d)) return;
+  int R = chunk_row[k];
+  if (R < 0 || R >= d.m) return;
+  const int64_t begin = rowptr[R];
+  if (begin >= k * kT) return;               // no carry in this chunk
+  if (begin < (k - 1) * kT) return;          // an earlier chunk leads this row
+  int64_t kend = k + 1;
+  while (kend < d.nchunks && chunk_row[kend] == R) ++kend;
+  for (int c4 = lane; c4 * 4 < f_total; c4 += 64) {
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0, s2 = s0, s3 = s0;
+    int64_t j = k;
+    for (; j + 4 <= kend; j += 4) {
+      const float4 t0 = *reinterpret_cast<const float4*>(carry_base + (j + 0) * d.carry_ld + c4 * 4);
+      const float4 t1 = *reinterpret_cast<const float4*>(carry_base + (j + 1) * d.carry_ld + c4 * 4);
+      const float4 t2 = *reinterpret_cast<const float4*>(carry_base + (j + 2) * d.carry_ld + c4 * 4);
+      const float4 t3 = *reinterpret_cast<const float4*>(carry_base + (j + 3) * d.carry_ld + c4 * 4);
+      s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
+      s1.x += t1.x; s1.y += t1.y; s1.z += t1.z; s1.w += t1.w;
+      s2.x += t2.x; s2.y += t2.y; s2.z += t2.z; s2.w += t2.w;
+      s3.x += t3.x; s3.y += t3.y; s3.z += t3.z; s3.w += t3.w;
+    }
+    for (; j < kend; ++j) {
+      const float4 t0 = *reinterpret_cast<const float4*>(carry_base + j * d.carry_ld + c4 * 4);
+      s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
+    }
+    float4* p = reinterpret_cast<float4*>(C + (int64_t)R * d.ldc + c4 * 4);
+    float4 o = *p;
+    o.x += (s0.x + s1.x) + (s2.x + s3.x);
+    o.y += (s0.y + s1.y) + (s2.y + s3.y);
+    o.z += (s0.z + s1.z) + (s2.z + s3.z);
+    o.w += (s0.w + s1.w) + (s2.w + s3.w);
+    *p = o;
+  }
+}
+
+// rows without entries: C[r,:] = 0 when overwriting (no chunk ever visits them)
+__global__ __launch_bounds__(kBlock) void spmm_zero_empty_kernel(SPMM_PTR_PARAMS, const SpmmDims d,
+                                                                 int32_t f_total) {
+  if (!ws_matches(hdr, d) || hdr->has_empty_rows == 0) return;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+  for (int64_t r = wave0; r < d.m; r += nwaves) {
+    if (rowptr[r + 1] != rowptr[r]) continue;
+    for (int c4 = lane; c4 * 4 < f_total; c4 += 64)
+      *reinterpret_cast<float4*>(C + r * d.ldc + c4 * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// fallback without a prepared workspace: one wavefront per row, float4 pieces along f
+__global__ __launch_bounds__(kBlock) void spmm_row_kernel(SPMM_PTR_PARAMS, const SpmmDims d,
+                                                          int32_t f_total) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+  for (int64_t r = wave0; r < d.m; r += nwaves) {
+    int32_t lo = rowptr[r], hi = rowptr[r + 1];
+    lo = lo < 0 ? 0 : lo;
+    hi = hi > d.nnz ? (int32_t)d.nnz : hi;
+    for (int c4 = lane; c4 * 4 < f_total; c4 += 64) {
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int32_t e = lo; e < hi; ++e) {
+        const uint32_t c = (uint32_t)colidx[e];
+        const uint32_t cc = c > d.kmax ? d.kmax : c;
+        const float v = val[e];
+        const float4 h = *reinterpret_cast<const float4*>(B + (int64_t)cc * d.ldb + c4 * 4);
+        acc.x += v * h.x; acc.y += v * h.y; acc.z += v * h.z; acc.w += v * h.w;
+      }
+      float4* p = reinterpret_cast<float4*>(C + r * d.ldc + c4 * 4);
+      if (d.accumulate) {
+        const float4 o = *p;
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+      }
+      *p = acc;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// preparation
+__global__ void prep_header_kernel(SpmmWsHeader* hdr, int64_t m, int64_t nnz, int64_t nchunks,
+                                   int32_t f) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    hdr->magic = kSpmmMagic;
+    hdr->has_empty_rows = 0;
+    hdr->m = m;
+    hdr->nnz = nnz;
+    hdr->nchunks = nchunks;
+    hdr->f = f;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void prep_clear_flags_kernel(uint32_t* flags, int64_t words) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < words; i += stride) flags[i] = 0;
+}
+
+// chunk_row[k] = last row r with rowptr[r] <= k*kT (the non-empty row that holds entry k*kT)
+__global__ __launch_bounds__(kBlock) void prep_chunks_kernel(const int32_t* __restrict__ rowptr,
+                                                             int64_t m, int64_t nchunks,
+                                                             int32_t* __restrict__ chunk_row) {
+  const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (k > nchunks) return;
+  if (k == nchunks) {
+    chunk_row[k] = (int32_t)m;
+    return;
+  }
+  const int64_t target = k * kT;
+  int64_t lo = 0, hi = m;  // invariant: rowptr[lo] <= target; answer in [lo, hi)
+  while (hi - lo > 1) {
+    const int64_t mid = (lo + hi) >> 1;
+    if ((int64_t)rowptr[mid] <= target) lo = mid; else hi = mid;
+  }
+  chunk_row[k] = (int32_t)lo;
+}
+
+__global__ __launch_bounds__(kBlock) void prep_rowend_kernel(const int32_t* __restrict__ rowptr,
+                                                             int64_t m, int64_t nnz,
+                                                             uint32_t* __restrict__ flags,
+                                                             SpmmWsHeader* hdr) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x; r < m; r += stride) {
+    const int64_t b = rowptr[r], e = rowptr[r + 1];
+    if (e > b && e <= nnz && e >= 1) {
+      atomicOr(&flags[(e - 1) >> 5], 1u << ((e - 1) & 31));
+    } else if (e == b) {
+      hdr->has_empty_rows = 1;
+    }
+  }
+}
+
+inline unsigned capped_grid(int64_t blocks) {
+  const int64_t cap = 256 * 64;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (unsigned)blocks;
+}
+
+struct SpmmPtrs {
+  const int32_t* rowptr; const int32_t* colidx; const float* val; const float* B; float* C;
+  const SpmmWsHeader* hdr; const int32_t* chunk_row; const uint32_t* flags; float* carry;
+};
+
+template <typename Kern, typename... Extra>
+inline void launch_waves(Kern kern, int64_t blocks, const SpmmPtrs& p, const SpmmDims& d,
+                         hipStream_t s, Extra... extra) {
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kBlock), 0, s, p.rowptr, p.colidx, p.val,
+                     p.B, p.C, p.hdr, p.chunk_row, p.flags, p.carry, d, extra...);
+}
+
+}  // namespace
+
+int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
+                int64_t k, int64_t nnz, const float* B, int64_t ldb, int32_t f, float* C,
+                int64_t ldc, int32_t accumulate, void* ws, size_t ws_bytes, hipStream_t s) {
+  if (m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || ldb < f || ldc < f || (ldb & 3) ||
+      (ldc & 3) || m > 0x7FFFFFFFll || k > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  if (accumulate != 0 && accumulate != 1) return SAGNN_EINVAL;
+  if (m == 0) return SAGNN_OK;
+  if (!rowptr || !C || !aligned16(C)) return SAGNN_EINVAL;
+  if (nnz > 0 && (!colidx || !val || !B || !aligned16(B) || k == 0)) return SAGNN_EINVAL;
+  if (ws && (reinterpret_cast<uintptr_t>(ws) & 255u)) return SAGNN_EINVAL;
+  if (ws && ws_bytes < spmm_ws_bytes(nnz, f)) return SAGNN_ECAPACITY;
+
+  SpmmPtrs p{};
+  p.rowptr = rowptr; p.colidx = colidx; p.val = val; p.B = B; p.C = C;
+  SpmmDims d{};
+  d.m = m; d.nnz = nnz; d.ldb = ldb; d.ldc = ldc;
+  d.kmax = k > 0 ? (uint32_t)(k - 1) : 0u;
+  d.f = f; d.accumulate = accumulate;
+  d.nchunks = spmm_nchunks(nnz);
+  d.carry_ld = f;
+
+  if (!ws) {
+    launch_waves(spmm_row_kernel, capped_grid(ceil_div(m, kWavesPerBlock)), p, d, s, f);
+    SAGNN_LAUNCH_CHECK();
+    return SAGNN_OK;
+  }
+
+  char* base = reinterpret_cast<char*>(ws);
+  p.hdr = reinterpret_cast<const SpmmWsHeader*>(base);
+  p.chunk_row = reinterpret_cast<const int32_t*>(base + spmm_ws_table_off());
+  p.flags = reinterpret_cast<const uint32_t*>(base + spmm_ws_flags_off(nnz));
+  p.carry = reinterpret_cast<float*>(base + spmm_ws_carry_off(nnz));
+
+  if (d.nchunks > 0) {
+    const int64_t blocks = ceil_div(d.nchunks, kWavesPerBlock);
+    // column slabs: 256 / 128 / 64 wide through the wide kernel, the rest through the narrow one
+    int32_t col0 = 0;
+    while (col0 < f) {
+      const int32_t rest = f - col0;
+      SpmmPtrs sp = p;
+      SpmmDims sd = d;
+      sp.B = B + col0; sp.C = C + col0; sp.carry = p.carry + col0;
+      if (rest >= 256) { sd.f = 256; launch_waves(spmm_wide_kernel<4, 8>, blocks, sp, sd, s); }
+      else if (rest >= 128) { sd.f = 128; launch_waves(spmm_wide_kernel<2, 8>, blocks, sp, sd, s); }
+      else if (rest >= 64) { sd.f = 64; launch_waves(spmm_wide_kernel<1, 8>, blocks, sp, sd, s); }
+      else {
+        sd.f = rest;
+        if (rest > 32) launch_waves(spmm_narrow_kernel<16, 4>, blocks, sp, sd, s);
+        else if (rest > 16) launch_waves(spmm_narrow_kernel<8, 4>, blocks, sp, sd, s);
+        else if (rest > 8) launch_waves(spmm_narrow_kernel<4, 4>, blocks, sp, sd, s);
+        else launch_waves(spmm_narrow_kernel<2, 4>, blocks, sp, sd, s);
+      }
+      SAGNN_LAUNCH_CHECK();
+      col0 += sd.f;
+    }
+    if (d.nchunks > 1) {
+      launch_waves(spmm_fixup_kernel, blocks, p, d, s, f);
+      SAGNN_LAUNCH_CHECK();
+    }
+  }
+  if (!accumulate) {
+    launch_waves(spmm_zero_empty_kernel, capped_grid(ceil_div(m, kWavesPerBlock)), p, d, s, f);
+    SAGNN_LAUNCH_CHECK();
+  }
+  return SAGNN_OK;
+}
+
+}  // namespace sagnn
+
+SAGNN_EXPORT int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes) {
+  using namespace sagnn;
+  if (!bytes || m < 0 || nnz < 0 || f <= 0 || (f & 3) || nnz > 0x7FFFFFFFll) return SAGNN_EINVAL;
+  *bytes = spmm_ws_bytes(nnz, f);
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t f,
+                                  void* d_ws, size_t ws_bytes, void* stream) {
+  using namespace sagnn;
+  if (m < 0 || nnz < 0 || f <= 0 || (f & 3) || m > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  if (!d_rowptr || !d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return SAGNN_EINVAL;
+  if (ws_bytes < spmm_ws_bytes(nnz, f)) return SAGNN_ECAPACITY;
+  hipStream_t s = (hipStream_t)stream;
+  char* base = reinterpret_cast<char*>(d_ws);
+  auto* hdr = reinterpret_cast<SpmmWsHeader*>(base);
+  auto* chunk_row = reinterpret_cast<int32_t*>(base + spmm_ws_table_off());
+  auto* flags = reinterpret_cast<uint32_t*>(base + spmm_ws_flags_off(nnz));
+  const int64_t nchunks = spmm_nchunks(nnz);
+  const int64_t words = nchunks * (kSpmmChunk / 32);
+  hipLaunchKernelGGL(prep_header_kernel, dim3(1), dim3(64), 0, s, hdr, m, nnz, nchunks, f);
+  SAGNN_LAUNCH_CHECK();
+  if (words > 0) {
+    hipLaunchKernelGGL(prep_clear_flags_kernel, dim3(capped_grid(ceil_div(words, kBlock))),
+                       dim3(kBlock), 0, s, flags, words);
+    SAGNN_LAUNCH_CHECK();
+  }
+  if (m > 0) {
+    hipLaunchKernelGGL(prep_chunks_kernel, dim3((unsigned)ceil_div(nchunks + 1, kBlock)),
+                       dim3(kBlock), 0, s, d_rowptr, m, nchunks, chunk_row);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(prep_rowend_kernel, dim3(capped_grid(ceil_div(m, kBlock))), dim3(kBlock), 0,
+                       s, d_rowptr, m, nnz, flags, hdr);
+    SAGNN_LAUNCH_CHECK();
+  }
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_csr_tallskinny(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                     const float* d_val, int64_t m, int64_t k, int64_t nnz,
+                                     const float* d_B, int64_t ldb, int32_t f, float* d_C,
+                                     int64_t ldc, int32_t accumulate, void* d_ws, size_t ws_bytes,
+                                     void* stream) {
+  return sagnn::launch_spmm(d_rowptr, d_colidx, d_val, m, k, nnz, d_B, ldb, f, d_C, ldc,
+                            accumulate, d_ws, ws_bytes, (hipStream_t)stream);
+}

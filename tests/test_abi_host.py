@@ -1,0 +1,72 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and argument validation rejects bad calls before any HIP call is made."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2504_04673_amd as sagnn
+from paper_2504_04673_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sagnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(?:int|const char\*)\s+([a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    L = sagnn.lib()
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_strerror():
+    L = sagnn.lib()
+    assert L.sagnn_version() >= 100
+    for code in (0, -1, -2, -3, -4, -99):
+        assert len(L.sagnn_strerror(code)) > 0
+
+
+def test_workspace_queries():
+    L = sagnn.lib()
+    b = ctypes.c_size_t(0)
+    assert L.spmm_plan_workspace_bytes(10, 1000, 50, 4, ctypes.byref(b)) == 0 and b.value >= 1000 // 8
+    assert L.spmm_plan_workspace_bytes(10, 1000, 50, 0, ctypes.byref(b)) == -1
+    assert L.spmm_plan_workspace_bytes(10, 1 << 33, 50, 1, ctypes.byref(b)) == -1
+    assert L.spmm_csr_workspace_bytes(10, 1000, 128, ctypes.byref(b)) == 0
+    assert b.value >= 4 * 128 * 4
+    assert L.spmm_csr_workspace_bytes(10, 1000, 6, ctypes.byref(b)) == -1
+    assert L.gcn_bwd_workspace_bytes(1000, 256, 256, ctypes.byref(b)) == 0 and b.value >= 256 * 256 * 4
+    assert L.gcn_bwd_workspace_bytes(1000, 100, 256, ctypes.byref(b)) == -1
+
+
+def test_argument_validation_before_launch():
+    L = sagnn.lib()
+    # pack: bad f, null pointers, bad leading dimension
+    assert L.spmm_pack_rows(None, 10, 16, 16, None, 5, None, 16, None) == -1
+    assert L.spmm_pack_rows(None, 10, 16, 6, None, 0, None, 16, None) == -1
+    assert L.spmm_pack_rows(None, 10, 8, 16, None, 0, None, 16, None) == -1
+    assert L.spmm_pack_rows(None, 10, 16, 16, None, 0, None, 16, None) == 0     # N = 0: nothing to do
+    # SpMM: null pointers with work to do, bad f
+    assert L.spmm_csr_tallskinny(None, None, None, 4, 4, 4, None, 16, 16, None, 16, 0, None, 0, None) == -1
+    assert L.spmm_csr_tallskinny(None, None, None, 0, 4, 0, None, 16, 16, None, 16, 0, None, 0, None) == 0
+    assert L.spmm_csr_tallskinny(None, None, None, 4, 4, 4, None, 16, 18, None, 16, 0, None, 0, None) == -1
+    assert L.spmm_csr_prepare(None, 4, 4, 16, None, 0, None) == -1
+    # plan: missing host arrays
+    assert L.spmm_plan_needed_rows(None, None, 4, 4, 0, None, 1, None, 0, None, None, None, 0, 0, None) == -1
+    # GEMM: unsupported sizes
+    assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 100, 128, 0, 0, None, 0, None, 0, None, 0, None) == -1
+    assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 128, 512, 0, 0, None, 0, None, 0, None, 0, None) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        sagnn.spmm_pack_rows(torch.zeros(4, 4), torch.zeros(2, dtype=torch.int32))

@@ -1,0 +1,315 @@
+"""GPU parity: every step of the hot path, called through the C ABI, element by element against
+the CPU oracle on the same seeded inputs.  Integer results bit-exact; fp32 SpMM within
+1e-5 * sum|terms|; bf16 GEMM within 1e-2 * sum|terms|."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_04673_amd as sagnn
+from paper_2504_04673_amd import synth
+from tests.util import assert_close, csr_dev, dev
+
+pytestmark = pytest.mark.gpu
+
+RTOL_SPMM = 1e-5
+RTOL_GEMM_FP32 = 1e-5
+RTOL_BF16 = 1e-2
+
+
+def random_csr(m, n, avg, rng, empty_frac=0.0, hubs=(), dup=False):
+    deg = rng.poisson(avg, size=m)
+    if empty_frac:
+        deg[rng.random(m) < empty_frac] = 0
+    for r, d in hubs:
+        deg[r] = d
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    nnz = int(rowptr[-1])
+    colidx = rng.integers(0, n, size=nnz).astype(np.int32)
+    if not dup:
+        # sort inside rows (duplicates may remain; both sides sum them)
+        for r in range(m):
+            colidx[rowptr[r]:rowptr[r + 1]].sort()
+    val = rng.standard_normal(nnz).astype(np.float32)
+    return rowptr, colidx, val
+
+
+# ------------------------------------------------------------------------------------ pack
+
+@pytest.mark.parametrize("n,f,N,ld", [(4096, 16, 3700, 16), (1000, 4, 1, 4), (1000, 20, 333, 24),
+                                      (5000, 128, 4097, 128), (3000, 256, 1025, 260), (2000, 300, 777, 300),
+                                      (10, 64, 0, 64)])
+def test_pack_rows(n, f, N, ld):
+    rng = np.random.default_rng(n + f)
+    Hfull = synth.normal((n, ld), 1, synth.STREAM_H)
+    rows = np.sort(rng.choice(n, size=N, replace=False)).astype(np.int32)
+    Hd = dev(Hfull)[:, :f]          # strided view: leading dimension ld
+    got = torch.empty((N, f), device="cuda")
+    L = sagnn.lib()
+    import ctypes
+    rc = L.spmm_pack_rows(ctypes.c_void_p(Hd.data_ptr()), n, ld, f, ctypes.c_void_p(dev(rows).data_ptr()) if N else None,
+                          N, ctypes.c_void_p(got.data_ptr()) if N else None, f,
+                          ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0
+    torch.cuda.synchronize()
+    ref = oracle.pack_rows(np.ascontiguousarray(Hfull[:, :f]), rows)
+    assert got.cpu().numpy().tobytes() == ref.tobytes()
+
+
+def test_pack_rows_out_of_range_ids_give_zero_rows():
+    H = dev(synth.normal((100, 32), 2, synth.STREAM_H))
+    rows = dev(np.array([5, -1, 100, 99, 2 ** 31 - 1], np.int32))
+    out = sagnn.spmm_pack_rows(H, rows).cpu().numpy()
+    Hh = H.cpu().numpy()
+    assert np.array_equal(out[0], Hh[5]) and np.array_equal(out[3], Hh[99])
+    assert not out[1].any() and not out[2].any() and not out[4].any()
+
+
+def test_pack_rows_offsets_beyond_4gib():
+    """H larger than 2^32 bytes: element offsets must be 64-bit."""
+    n, f = 9_000_000, 128                       # 4.6 GB
+    H = torch.empty((n, f), device="cuda")
+    rows_h = np.array([0, 1, 4_194_304, 8_388_607, 8_388_608, 8_999_999], np.int32)
+    vals = synth.normal_rows(rows_h, f, 3, synth.STREAM_H)
+    H[torch.from_numpy(rows_h.astype(np.int64)).cuda()] = dev(vals)
+    out = sagnn.spmm_pack_rows(H, dev(rows_h)).cpu().numpy()
+    assert out.tobytes() == vals.tobytes()
+    del H
+
+
+# ------------------------------------------------------------------------------------ plan
+
+def check_plan(rowptr, colidx, n, colblk):
+    plan = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), n, colblk)
+    torch.cuda.synchronize()
+    needed, blk_off, compact = oracle.needed_rows(rowptr, colidx, n, colblk)
+    assert np.array_equal(plan.blk_off, blk_off)
+    assert np.array_equal(plan.needed.cpu().numpy(), needed)
+    if colidx.size:
+        assert np.array_equal(plan.colidx_compact.cpu().numpy(), compact)
+    return plan
+
+
+def test_plan_cfg1_all_blocks(cfg1):
+    g, _ = cfg1
+    off = synth.block_offsets(g.n, 4)
+    for i in range(4):
+        blk = g.row_block(int(off[i]), int(off[i + 1]))
+        check_plan(blk.rowptr, blk.colidx, g.n, off)
+    check_plan(g.rowptr, g.colidx, g.n, np.array([0, g.n]))
+
+
+@pytest.mark.parametrize("m,n,nb,avg,seed", [(1, 1, 1, 1, 0), (50, 63, 3, 2, 1), (64, 64, 1, 3, 2),
+                                             (1000, 65, 5, 1, 3), (3000, 100_003, 16, 9, 4),
+                                             (20000, 5_000_001, 7, 4, 5), (10, 1_000_000, 64, 0.3, 6)])
+def test_plan_random_ragged(m, n, nb, avg, seed):
+    rng = np.random.default_rng(seed)
+    rowptr, colidx, _ = random_csr(m, n, avg, rng, dup=True)
+    cuts = np.sort(rng.integers(0, n + 1, size=nb - 1))       # ragged, possibly empty blocks
+    colblk = np.array([0, *cuts, n], dtype=np.int64)
+    check_plan(rowptr, colidx, n, colblk)
+
+
+def test_plan_empty_matrix_and_capacity_and_validate():
+    rp = np.zeros(6, np.int32)
+    plan = sagnn.spmm_plan_needed_rows(dev(rp), torch.empty(0, dtype=torch.int32, device="cuda"), 100,
+                                       np.array([0, 50, 100]))
+    assert plan.N == 0 and list(plan.blk_off) == [0, 0, 0]
+    rng = np.random.default_rng(0)
+    rowptr, colidx, _ = random_csr(100, 1000, 5, rng)
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), 1000, np.array([0, 1000]), needed_cap=3)
+    assert ei.value.code == -2
+    bad = colidx.copy()
+    bad[7] = 1000
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_plan_needed_rows(dev(rowptr), dev(bad), 1000, np.array([0, 1000]), validate=True)
+    assert ei.value.code == -3
+    badrp = rowptr.copy()
+    badrp[10] = badrp[11] + 1
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_plan_needed_rows(dev(badrp), dev(colidx), 1000, np.array([0, 1000]), validate=True)
+    assert ei.value.code == -3
+    # without validation the bad column is skipped and flagged -1 in the remap
+    plan = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(bad), 1000, np.array([0, 1000]))
+    assert int(plan.colidx_compact[7]) == -1
+    sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), 1000, np.array([0, 1000]), validate=True)
+
+
+# ------------------------------------------------------------------------------------ SpMM
+
+def run_spmm(rowptr, colidx, val, B, use_ws, C0=None):
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    ws = sagnn.spmm_csr_prepare(rp, colidx.size, B.shape[1]) if use_ws else None
+    C = None if C0 is None else dev(C0)
+    out = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), C=C, accumulate=C0 is not None, ws=ws)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("f", [4, 16, 20, 32, 48, 64, 100, 128, 192, 256, 320])
+@pytest.mark.parametrize("use_ws", [True, False])
+def test_spmm_random_widths(f, use_ws):
+    rng = np.random.default_rng(f)
+    m, n = 3001, 2500
+    rowptr, colidx, val = random_csr(m, n, 12, rng, empty_frac=0.15, hubs=[(7, 3000), (1500, 777), (3000, 300)],
+                                     dup=True)
+    B = synth.normal((n, f), f, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    got = run_spmm(rowptr, colidx, val, B, use_ws)
+    assert_close(got, ref, zabs, RTOL_SPMM, f"spmm f={f} ws={use_ws}")
+    C0 = synth.normal((m, f), f + 1, synth.STREAM_G)
+    ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
+    got2 = run_spmm(rowptr, colidx, val, B, use_ws, C0=C0)
+    assert_close(got2, ref2, zabs2, RTOL_SPMM, f"spmm accumulate f={f} ws={use_ws}")
+
+
+@pytest.mark.parametrize("case", ["all_empty", "single_entry", "one_long_row", "exact_chunk", "tail_empty"])
+def test_spmm_degenerate(case):
+    f, n = 128, 700
+    rng = np.random.default_rng(1)
+    if case == "all_empty":
+        rowptr = np.zeros(11, np.int32); colidx = np.empty(0, np.int32); val = np.empty(0, np.float32)
+    elif case == "single_entry":
+        rowptr = np.array([0, 0, 1, 1], np.int32); colidx = np.array([699], np.int32); val = np.array([2.5], np.float32)
+    elif case == "one_long_row":
+        rowptr = np.array([0, 2000], np.int32); colidx = rng.integers(0, n, 2000).astype(np.int32)
+        val = rng.standard_normal(2000).astype(np.float32)
+    elif case == "exact_chunk":     # rows end exactly on chunk boundaries
+        rowptr = np.array([0, 256, 512, 512, 1024], np.int32); colidx = rng.integers(0, n, 1024).astype(np.int32)
+        val = rng.standard_normal(1024).astype(np.float32)
+    else:
+        rowptr = np.array([0, 300, 300, 300], np.int32); colidx = rng.integers(0, n, 300).astype(np.int32)
+        val = rng.standard_normal(300).astype(np.float32)
+    B = synth.normal((n, f), 9, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    for use_ws in (True, False):
+        got = torch.full((rowptr.size - 1, f), 7.0, device="cuda")     # stale contents must be overwritten
+        rp = dev(rowptr)
+        ws = sagnn.spmm_csr_prepare(rp, colidx.size, f) if use_ws else None
+        sagnn.spmm_csr_tallskinny(rp, dev(colidx) if colidx.size else torch.empty(0, dtype=torch.int32, device="cuda"),
+                                  dev(val) if val.size else torch.empty(0, device="cuda"), dev(B), C=got, ws=ws)
+        torch.cuda.synchronize()
+        assert_close(got, ref, zabs, RTOL_SPMM, f"{case} ws={use_ws}")
+
+
+def test_spmm_identity_and_ring_closed_forms():
+    n, f = 1000, 128
+    H = synth.normal((n, f), 4, synth.STREAM_H)
+    rp = np.arange(n + 1, dtype=np.int32); ci = np.arange(n, dtype=np.int32); v = np.ones(n, np.float32)
+    got = run_spmm(rp, ci, v, H, True)
+    assert got.cpu().numpy().tobytes() == H.tobytes()
+    g = synth.ring_graph(4096, 8)
+    ones = np.ones((4096, 64), np.float32)
+    got = run_spmm(g.rowptr, g.colidx, g.val, ones, True).cpu().numpy()
+    assert np.all(got == 8.0)
+
+
+def test_spmm_cfg1_blocks_through_packed_buffer(cfg1):
+    """Configuration 1 end to end: plan -> pack -> SpMM with compact indices, per row block,
+    equals the oracle's A_i * H; also the whole matrix as one block."""
+    g, H = cfg1
+    off = synth.block_offsets(g.n, 4)
+    Hd = dev(H)
+    for i in range(4):
+        blk = g.row_block(int(off[i]), int(off[i + 1]))
+        rp, ci, v = csr_dev(blk)
+        plan = sagnn.spmm_plan_needed_rows(rp, ci, g.n, off)
+        Hn = sagnn.spmm_pack_rows(Hd, plan.needed)
+        ws = sagnn.spmm_csr_prepare(rp, blk.nnz, 16)
+        Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
+        torch.cuda.synchronize()
+        ref, zabs = oracle.spmm(blk.rowptr, blk.colidx, blk.val, H, want_abs=True)
+        assert_close(Z, ref, zabs, RTOL_SPMM, f"cfg1 block {i}")
+        # block-by-block accumulation (Alg. 1 inner loop): Z += A_iq * H[NnzCols(i,q)]
+        Zacc = torch.zeros_like(Z)
+        comp = plan.colidx_compact.cpu().numpy()
+        for q in range(4):
+            keep = (blk.colidx >= off[q]) & (blk.colidx < off[q + 1])
+            cnt = np.add.reduceat(keep.astype(np.int64), blk.rowptr[:-1]) * (np.diff(blk.rowptr) > 0)
+            rpq = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
+            ciq = (comp[keep] - plan.blk_off[q]).astype(np.int32)
+            Hq = Hn[int(plan.blk_off[q]):int(plan.blk_off[q + 1])].contiguous()
+            wsq = sagnn.spmm_csr_prepare(dev(rpq), int(rpq[-1]), 16)
+            sagnn.spmm_csr_tallskinny(dev(rpq), dev(ciq), dev(blk.val[keep]), Hq, C=Zacc, accumulate=True, ws=wsq)
+        torch.cuda.synchronize()
+        assert_close(Zacc, ref, zabs, RTOL_SPMM, f"cfg1 block {i} accumulated")
+    rp, ci, v = csr_dev(g)
+    ws = sagnn.spmm_csr_prepare(rp, g.nnz, 16)
+    Z = sagnn.spmm_csr_tallskinny(rp, ci, v, Hd, ws=ws)
+    ref, zabs = oracle.spmm(g.rowptr, g.colidx, g.val, H, want_abs=True)
+    assert_close(Z, ref, zabs, RTOL_SPMM, "cfg1 whole")
+
+
+@pytest.mark.parametrize("f", [16, 64, 128, 256])
+def test_spmm_small_rmat(f):
+    g = synth.rmat_graph(40_000, 2_000_000, 5)
+    H = synth.normal((g.n, f), 5, synth.STREAM_H)
+    ref, zabs = oracle.spmm(g.rowptr, g.colidx, g.val, H, want_abs=True)
+    got = run_spmm(g.rowptr, g.colidx, g.val, H, True)
+    assert_close(got, ref, zabs, RTOL_SPMM, f"rmat f={f}")
+    # sqrt(d) is an eigenvector of the normalised adjacency matrix (closed form at any size)
+    x = np.sqrt(np.diff(g.rowptr).astype(np.float64)).astype(np.float32)
+    X = np.repeat(x[:, None], f, axis=1).copy()
+    got = run_spmm(g.rowptr, g.colidx, g.val, X, True).cpu().numpy()
+    assert np.allclose(got, X, rtol=2e-5, atol=0)
+
+
+# ------------------------------------------------------------------------------------ GEMM / layer
+
+@pytest.mark.parametrize("m,k,n", [(1, 32, 32), (31, 64, 96), (33, 128, 128), (1000, 160, 256), (4097, 256, 64)])
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("transW", [False, True])
+def test_dense_gemm(m, k, n, prec, transW):
+    X = synth.normal((m, k), m, synth.STREAM_H)
+    W = synth.normal((n, k) if transW else (k, n), k, synth.STREAM_W, scale=1 / np.sqrt(k))
+    if prec == 1:
+        X.reshape(-1)[:4] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 2.0 ** -8 + 2.0 ** -20][:min(4, X.size)]
+    mask = synth.normal((m, n), n, synth.STREAM_G)
+    ref, zabs = oracle.gemm(X, W, bf16=bool(prec), transW=transW, want_abs=True)
+    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+    Z, A = sagnn.dense_gemm_act(dev(X), dev(W), transW=transW, prec=prec, act=sagnn.ACT_RELU, want_z=True, want_act=True)
+    torch.cuda.synchronize()
+    assert_close(Z, ref, zabs, rtol, "gemm Z")
+    assert torch.equal(A, torch.clamp_min(Z, 0))
+    Zm, _ = sagnn.dense_gemm_act(dev(X), dev(W), transW=transW, prec=prec, mask=dev(mask))
+    torch.cuda.synchronize()
+    assert_close(Zm, np.where(mask > 0, ref, 0), zabs, rtol, "gemm masked")
+    assert torch.equal(Zm == 0, (dev(mask) <= 0) | (Z == 0))
+
+
+def test_bf16_gemm_is_tight_against_bf16_rounded_oracle():
+    """With operands rounded the same way the only difference left is fp32 vs fp64 accumulation,
+    so the result must sit far inside the 1e-2 budget; a wrong rounding mode would not."""
+    X = synth.normal((512, 256), 1, synth.STREAM_H)
+    W = synth.normal((256, 256), 1, synth.STREAM_W, scale=1 / 16)
+    ref, zabs = oracle.gemm(X, W, bf16=True, want_abs=True)
+    Z, _ = sagnn.dense_gemm_act(dev(X), dev(W), prec=1)
+    torch.cuda.synchronize()
+    assert_close(Z, ref, zabs, 2e-5, "bf16 gemm vs bf16-rounded oracle")
+
+
+@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 32)])
+def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
+    g = synth.sbm_graph(6000, 16, 40, 2, 3)
+    H = synth.normal((g.n, fin), 1, synth.STREAM_H)
+    W = synth.normal((fin, fout), 1, synth.STREAM_W, scale=1 / np.sqrt(fin))
+    G = synth.normal((g.n, fout), 1, synth.STREAM_G)
+    rp, ci, v = csr_dev(g)
+    ws_in = sagnn.spmm_csr_prepare(rp, g.nnz, fin)
+    ws_out = sagnn.spmm_csr_prepare(rp, g.nnz, fout)
+    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+    o = oracle.gcn_layer_fwd(g.rowptr, g.colidx, g.val, H, W, act=1, bf16=bool(prec))
+    T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws_in)
+    torch.cuda.synchronize()
+    assert_close(T, o["T"], o["Tabs"], RTOL_SPMM, "layer T")
+    assert_close(Z, o["Z"], o["Zabs"], rtol, "layer Z")
+    assert_close(Ho, o["H"], o["Zabs"], rtol, "layer H")
+    # backward of this layer with the oracle's own Z / inputs as given data
+    Zprev = synth.normal((g.n, fin), 2, synth.STREAM_G)
+    ob = oracle.gcn_layer_bwd(g.rowptr, g.colidx, g.val, G, W, Zprev, H, bf16=bool(prec))
+    S, Gp, Y = sagnn.gcn_layer_bwd(rp, ci, v, dev(G), dev(W), dev(Zprev), dev(H), prec=prec, ws=ws_out)
+    torch.cuda.synchronize()
+    assert_close(S, ob["S"], ob["Sabs"], RTOL_SPMM, "bwd S")
+    assert_close(Gp, ob["Gprev"], ob["Gabs"], rtol, "bwd Gprev")
+    assert_close(Y, ob["Y"], ob["Yabs"], rtol, "bwd Y")
