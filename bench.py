@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch, every stage through the C ABI:
+    spmm_plan_needed_rows -> spmm_pack_rows -> spmm_csr_tallskinny -> dense_gemm_act (ReLU)
+(the last two are exactly what gcn_layer_fwd chains; they are called separately here so that
+HIP events can bracket the SpMM inside the timed region).
+
+Prints ONE JSON line (see README / DESIGN for the fields).  Default workload: configuration 3
+(R-MAT, 2.45 M vertices, ~124 M stored entries) at f = 128, the headline case of the metric.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+METRIC = "CSR SpMM GB/s & GFLOP/s at f=128 (fraction of HBM peak); needed-row gather GB/s"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse_traffic(workload: str, f: int):
+    """HBM bytes per SpMM launch from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"spmm_{workload}_f{f}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except (ValueError, IndexError):
+                pass
+    if "hbm_bytes_per_launch" in vals:
+        return vals["hbm_bytes_per_launch"]
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg5_random"])
+    ap.add_argument("--f", type=int, default=None, help="feature width (default: the workload's)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-plan", action="store_true", help="leave the plan out of the timed step")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU's share of the path; --gpus must be 1 "
+              "(inter-GPU communication is out of scope).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2504_04673_amd as sagnn
+    from paper_2504_04673_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    kw = {"scale": args.scale}
+    if args.f:
+        kw["f"] = args.f
+    if args.workload == "cfg1":
+        wl = workloads.cfg1()
+    elif args.workload == "cfg5_random":
+        wl = workloads.cfg5(order="random", **kw)
+    else:
+        wl = getattr(workloads, args.workload)(**kw)
+    g, f = wl.g, wl.f
+    if args.workload.startswith("cfg5"):
+        g = g.row_block(0, g.n // 16)          # rank 0's row block
+    if wl.W is None:
+        from paper_2504_04673_amd import synth
+        wl.W = synth.normal((f, f), 0, synth.STREAM_W, scale=1 / np.sqrt(f))
+    f_out = wl.W.shape[1]
+    m, n, nnz = g.m, g.n, g.nnz
+    nb = wl.colblk.size - 1
+    log(f"[bench] {wl.name}: m={m} n={n} nnz={nnz} f={f} nb={nb} generated in {time.time() - t0:.1f}s")
+
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    rp, ci, va = d(g.rowptr), d(g.colidx), d(g.val)
+    W = d(wl.W)
+
+    # --- one untimed plan to size the buffers and (for a virtual H) to materialise the rows
+    pbufs = sagnn.plan_buffers(m, n, nnz, nb, dev)
+    plan = sagnn.spmm_plan_needed_rows(rp, ci, n, wl.colblk, bufs=pbufs)
+    N = plan.N
+    if wl.H is not None:
+        Hd = d(wl.H)
+    else:
+        # virtual H: allocate all n rows, fill only the referenced ones
+        Hd = torch.empty((n, f), dtype=torch.float32, device=dev)
+        rows_h = plan.needed.cpu().numpy()
+        step_rows = 1 << 20
+        for s in range(0, N, step_rows):
+            idx = rows_h[s:s + step_rows]
+            Hd[torch.from_numpy(idx.astype(np.int64)).to(dev)] = d(wl.H_rows(idx))
+    Hn = torch.empty((N, f), dtype=torch.float32, device=dev)
+    T = torch.empty((m, f), dtype=torch.float32, device=dev)
+    Ho = torch.empty((m, f_out), dtype=torch.float32, device=dev)
+    ws = sagnn.spmm_csr_prepare(rp, nnz, f)
+    torch.cuda.synchronize()
+    models = workloads.byte_models(m, n, nnz, N, f, f_out, nb)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        e = [ev() for _ in range(5)] if record else None
+        if record:
+            e[0].record()
+        p = plan if args.no_plan else sagnn.spmm_plan_needed_rows(rp, ci, n, wl.colblk, bufs=pbufs)
+        if record:
+            e[1].record()
+        sagnn.spmm_pack_rows(Hd, p.needed, out=Hn)
+        if record:
+            e[2].record()
+        sagnn.spmm_csr_tallskinny(rp, p.colidx_compact, va, Hn, C=T, ws=ws)
+        if record:
+            e[3].record()
+        sagnn.dense_gemm_act(T, W, act=sagnn.ACT_RELU, want_z=False, want_act=True, out=(None, Ho))
+        if record:
+            e[4].record()
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    # the fused layer entry point must give the same bits as the split calls
+    T2, _, Ho2 = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, va, Hn, W, act=sagnn.ACT_RELU, ws=ws, want_z=False)
+    torch.cuda.synchronize()
+    if args.warmup > 0:
+        assert torch.equal(T2, T) and torch.equal(Ho2, Ho), "gcn_layer_fwd differs from split calls"
+    del T2, Ho2
+
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    phase = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])  # ms
+    avg = phase.mean(axis=0)
+    plan_ms, pack_ms, spmm_ms, gemm_ms = [float(x) for x in avg]
+    step_bytes = models["pack_bytes"] + models["spmm_bytes"] + models["gemm_bytes"] + \
+        (0 if args.no_plan else models["plan_bytes"])
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    spmm_gbps = models["spmm_bytes"] / (spmm_ms * 1e-3) / 1e9
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: " + {
+            "cfg1": "ER n=4096 deg 8, f=16",
+            "cfg2": "R-MAT 233k vertices",
+            "cfg3": "R-MAT 2.45M vertices",
+            "cfg4": "rank 0 of P=64 of an R-MAT graph with 111M vertices, 16 column blocks",
+            "cfg5": "SBM 2M vertices, rank-0 block of 16, ordered by community",
+        }[wl.name] + f", m={m} n={n} nnz={nnz} N_needed={N} f={f} f_out={f_out} nb={nb}",
+            "step": ("" if args.no_plan else "plan+") + "pack+spmm+gemm_relu", "seed": 0,
+            "scale": args.scale},
+        "roofline": {
+            "kernel": "spmm_csr_tallskinny (spmm_wide/narrow_kernel + carry fix-up)",
+            "bound": "hbm", "achieved": round(spmm_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(spmm_gbps / HBM_PEAK_GBPS, 4), "traffic": parse_traffic(wl.name, f),
+            "algorithmic_bytes": models["spmm_bytes"], "avg_ms": round(spmm_ms, 4),
+            "min_ms": round(float(phase[:, 2].min()), 4),
+            "gflops": round(models["spmm_flops"] / (spmm_ms * 1e-3) / 1e9, 1),
+            "gather_delivery_GBps": round(models["spmm_gather_bytes"] / (spmm_ms * 1e-3) / 1e9, 1),
+        },
+        "stages": {
+            "plan_ms": round(plan_ms, 4), "pack_ms": round(pack_ms, 4), "spmm_ms": round(spmm_ms, 4),
+            "gemm_ms": round(gemm_ms, 4),
+            "pack_GBps": round(models["pack_bytes"] / (pack_ms * 1e-3) / 1e9, 1),
+            "plan_GBps": round(models["plan_bytes"] / (plan_ms * 1e-3) / 1e9, 1) if not args.no_plan else None,
+            "gemm_GBps": round(models["gemm_bytes"] / (gemm_ms * 1e-3) / 1e9, 1),
+            "gemm_TFLOPs": round(models["gemm_flops"] / (gemm_ms * 1e-3) / 1e12, 2),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, g, args)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(wl, g, args):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the first rows of
+    the row block (about 1/16 of its stored entries), all four stages.  Same unit as `value`:
+    algorithmic bytes of the sample per second."""
+    import numpy as np
+    import oracle
+    from paper_2504_04673_amd import workloads
+    target = max(1, g.nnz // 16)
+    rows = int(np.searchsorted(g.rowptr, target))
+    rows = max(1, min(rows, g.m))
+    blk = g.row_block(0, rows)
+    f = wl.f
+    t0 = time.perf_counter()
+    needed, blk_off, compact = oracle.needed_rows(blk.rowptr, blk.colidx, g.n, wl.colblk)
+    if wl.H is not None:
+        Hn = oracle.pack_rows(wl.H, needed)
+        t_gen = 0.0
+    else:
+        tg = time.perf_counter()
+        Hfull_rows = wl.H_rows(needed)          # generating virtual rows is not oracle work
+        t_gen = time.perf_counter() - tg
+        Hn = oracle.pack_rows(Hfull_rows, np.arange(needed.size, dtype=np.int32))
+    T = oracle.spmm(blk.rowptr, compact, blk.val, Hn)
+    Z = oracle.gemm(T, wl.W)
+    Ho = np.maximum(Z, 0)
+    dt = time.perf_counter() - t0 - t_gen
+    mdl = workloads.byte_models(blk.m, g.n, blk.nnz, needed.size, f, wl.W.shape[1])
+    nbytes = mdl["plan_bytes"] + mdl["pack_bytes"] + mdl["spmm_bytes"] + mdl["gemm_bytes"]
+    _ = Ho
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"rows [0,{rows}) of the row block ({blk.nnz} stored entries, N_needed={needed.size}); "
+                      f"plan+pack+spmm+gemm_relu in fp64-accumulating C, {dt:.2f}s"}
+
+
+if __name__ == "__main__":
+    main()

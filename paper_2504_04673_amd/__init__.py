@@ -6,7 +6,7 @@ and the stream, every step runs in the library's kernels.  There is no CPU fallb
 library is missing or no GPU is present, calls raise.
 """
 from .binding import (  # noqa: F401
-    SagnnError, lib, lib_path, Plan, SpmmWorkspace,
+    SagnnError, lib, lib_path, Plan, SpmmWorkspace, plan_buffers,
     spmm_plan_needed_rows, spmm_pack_rows, spmm_csr_prepare, spmm_csr_tallskinny,
     dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd,
     ACT_IDENTITY, ACT_RELU, GEMM_FP32, GEMM_BF16, PLAN_VALIDATE,

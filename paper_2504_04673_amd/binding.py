@@ -110,21 +110,20 @@ class Plan:
 
 
 def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, validate=False,
-                          needed_cap=None) -> Plan:
-    """NnzCols of every column block (Sec. 4.1).  Allocates outputs with torch; the first call
-    sizes `needed` at min(n, nnz) unless needed_cap is given."""
+                          needed_cap=None, bufs=None) -> Plan:
+    """NnzCols of every column block (Sec. 4.1).  Outputs are torch tensors; `needed` is sized
+    min(n, nnz) unless needed_cap is given.  `bufs` = (ws, needed, compact) reuses buffers of an
+    earlier call (see plan_buffers) so that a repeated call allocates nothing."""
     rowptr = _dev(rowptr, torch.int32, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     m, nnz = rowptr.numel() - 1, colidx.numel()
     colblk = np.ascontiguousarray(colblk, dtype=np.int64)
     nb = colblk.size - 1
     L = lib()
-    wsb = ctypes.c_size_t(0)
-    _check(L.spmm_plan_workspace_bytes(m, n, nnz, nb, ctypes.byref(wsb)), "spmm_plan_workspace_bytes")
-    ws = _ws(wsb.value, rowptr.device)
     cap = int(min(n, nnz) if needed_cap is None else needed_cap)
-    needed = torch.empty(max(cap, 1), dtype=torch.int32, device=rowptr.device)
-    compact = torch.empty(max(nnz, 1), dtype=torch.int32, device=rowptr.device) if want_compact else None
+    if bufs is None:
+        bufs = plan_buffers(m, n, nnz, nb, rowptr.device, cap, want_compact)
+    ws, needed, compact = bufs
     blk_off = np.zeros(nb + 1, dtype=np.int64)
     rc = L.spmm_plan_needed_rows(_ptr(rowptr), _ptr(colidx), m, n, nnz,
                                  colblk.ctypes.data_as(ctypes.c_void_p), nb, _ptr(needed), cap,
@@ -132,7 +131,18 @@ def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, val
                                  ws.numel(), PLAN_VALIDATE if validate else 0, _stream())
     _check(rc, "spmm_plan_needed_rows")
     N = int(blk_off[-1])
-    return Plan(needed[:N], blk_off, compact[:nnz] if want_compact else None)
+    return Plan(needed[:N], blk_off, compact[:nnz] if compact is not None else None)
+
+
+def plan_buffers(m, n, nnz, nb, device, cap=None, want_compact=True):
+    """Workspace and output buffers of spmm_plan_needed_rows."""
+    wsb = ctypes.c_size_t(0)
+    _check(lib().spmm_plan_workspace_bytes(m, n, nnz, nb, ctypes.byref(wsb)), "spmm_plan_workspace_bytes")
+    cap = int(min(n, nnz) if cap is None else cap)
+    ws = _ws(wsb.value, device)
+    needed = torch.empty(max(cap, 1), dtype=torch.int32, device=device)
+    compact = torch.empty(max(nnz, 1), dtype=torch.int32, device=device) if want_compact else None
+    return ws, needed, compact
 
 
 def spmm_pack_rows(H, rows, out=None):
@@ -193,13 +203,16 @@ def spmm_csr_tallskinny(rowptr, colidx, val, B, C=None, accumulate=False, ws: Sp
 
 
 def dense_gemm_act(X, W, transW=False, prec=GEMM_FP32, act=ACT_IDENTITY, mask=None, want_z=True,
-                   want_act=False):
+                   want_act=False, out=None):
     X = _dev(X, torch.float32, "X")
     W = _dev(W, torch.float32, "W")
     m, kdim = X.shape
     nout = W.shape[0] if transW else W.shape[1]
-    Z = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_z else None
-    A = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_act else None
+    if out is not None:
+        Z, A = out
+    else:
+        Z = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_z else None
+        A = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_act else None
     rc = lib().dense_gemm_act(_ptr(X), X.stride(0), _ptr(W), W.stride(0), int(transW), m, kdim, nout,
                               prec, act, _ptr(mask), mask.stride(0) if mask is not None else 0,
                               _ptr(Z), nout, _ptr(A), nout, _stream())

@@ -77,34 +77,72 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
 
+    // The k loop runs in groups of JB steps; the A-operand loads of the next group are issued
+    // before the MFMAs of the current one, so HBM latency hides behind matrix-core work.
     if (BF16) {
       const bf16x8* __restrict__ Ws = reinterpret_cast<const bf16x8*>(smem);
-#pragma unroll 2
-      for (int j = 0; j < kdim / 16; ++j) {
-        const float4 x0 = *reinterpret_cast<const float4*>(xrow + 16 * j + 8 * h);
-        const float4 x1 = *reinterpret_cast<const float4*>(xrow + 16 * j + 8 * h + 4);
-        bf16x8 a;
-        a[0] = (__bf16)x0.x; a[1] = (__bf16)x0.y; a[2] = (__bf16)x0.z; a[3] = (__bf16)x0.w;
-        a[4] = (__bf16)x1.x; a[5] = (__bf16)x1.y; a[6] = (__bf16)x1.z; a[7] = (__bf16)x1.w;
+      constexpr int JB = 2;
+      const int ngroups = kdim / (16 * JB);
+      float4 cur[JB][2], nxt[JB][2];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const bf16x8 b = Ws[(2 * j + h) * NB + nt * 32 + r];
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+      for (int q = 0; q < JB; ++q) {
+        cur[q][0] = *reinterpret_cast<const float4*>(xrow + 16 * q + 8 * h);
+        cur[q][1] = *reinterpret_cast<const float4*>(xrow + 16 * q + 8 * h + 4);
+      }
+      for (int gi = 0; gi < ngroups; ++gi) {
+        if (gi + 1 < ngroups) {
+#pragma unroll
+          for (int q = 0; q < JB; ++q) {
+            nxt[q][0] = *reinterpret_cast<const float4*>(xrow + 16 * ((gi + 1) * JB + q) + 8 * h);
+            nxt[q][1] = *reinterpret_cast<const float4*>(xrow + 16 * ((gi + 1) * JB + q) + 8 * h + 4);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < JB; ++q) {
+          const int j = gi * JB + q;
+          const float4 x0 = cur[q][0], x1 = cur[q][1];
+          bf16x8 a;
+          a[0] = (__bf16)x0.x; a[1] = (__bf16)x0.y; a[2] = (__bf16)x0.z; a[3] = (__bf16)x0.w;
+          a[4] = (__bf16)x1.x; a[5] = (__bf16)x1.y; a[6] = (__bf16)x1.z; a[7] = (__bf16)x1.w;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const bf16x8 b = Ws[(2 * j + h) * NB + nt * 32 + r];
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nt], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < JB; ++q) {
+          cur[q][0] = nxt[q][0];
+          cur[q][1] = nxt[q][1];
         }
       }
     } else {
       const float* __restrict__ Ws = reinterpret_cast<const float*>(smem);
-#pragma unroll 2
-      for (int j = 0; j < kdim / 8; ++j) {
-        const float4 x = *reinterpret_cast<const float4*>(xrow + 8 * j + 4 * h);
-        const float xs[4] = {x.x, x.y, x.z, x.w};
+      constexpr int JB = 4;
+      const int ngroups = kdim / (8 * JB);
+      float4 cur[JB], nxt[JB];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float* wrow = Ws + (8 * j + 4 * h + i) * NB + r;
+      for (int q = 0; q < JB; ++q) cur[q] = *reinterpret_cast<const float4*>(xrow + 8 * q + 4 * h);
+      for (int gi = 0; gi < ngroups; ++gi) {
+        if (gi + 1 < ngroups) {
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[i], wrow[nt * 32], acc[nt], 0, 0, 0);
+          for (int q = 0; q < JB; ++q)
+            nxt[q] = *reinterpret_cast<const float4*>(xrow + 8 * ((gi + 1) * JB + q) + 4 * h);
         }
+#pragma unroll
+        for (int q = 0; q < JB; ++q) {
+          const int j = gi * JB + q;
+          const float xs[4] = {cur[q].x, cur[q].y, cur[q].z, cur[q].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float* wrow = Ws + (8 * j + 4 * h + i) * NB + r;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[i], wrow[nt * 32], acc[nt], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < JB; ++q) cur[q] = nxt[q];
       }
     }
 

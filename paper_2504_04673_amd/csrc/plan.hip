@@ -3,20 +3,21 @@
 // rows of H_j that P(i) has to receive).
 //
 // Integer only, result unique.  Pipeline (all kernels on the caller's stream):
-//   clear    bitmap of n bits (64 columns per word)
-//   mark     one pass over colidx: set bit c.  Test-before-set keeps hub columns from
-//            hammering one word with atomics.
-//   count    per-word popcount, block sums                      \  three-kernel exclusive
-//   scan     exclusive scan of the block sums (one workgroup)    > scan of the popcounts
-//   prefix   per-word exclusive prefix = rank of the word's       /  (wavefront shuffles)
-//            first column among the needed columns
+//   clear    one flag byte per column
+//   mark     one pass over colidx: flag[c] = 1.  Plain byte stores: every writer stores the
+//            same value, so no atomics are needed, and a test before the store keeps hub
+//            columns from producing write traffic at all
+//   words    one wavefront per 64 columns: lane l tests flag[64w+l]; the ballot of the test IS
+//            the 64-bit membership word of those columns; its popcount feeds the scan
+//   scan     exclusive scan of the per-block popcounts (one workgroup)       \  three-kernel
+//   prefix   per-word exclusive prefix = rank of the word's first column       /  scan
 //   blkoff   rank of every column-block boundary -> blk_off, N   (then one D2H copy + sync)
-//   emit     one wavefront per 64-column word: lane l tests column 64w+l, the ballot of the
-//            test is the wavefront's 64-bit mask and mbcnt gives each set lane its slot
-//            (ballot / prefix-count stream compaction); needed[] comes out ascending
+//   emit     one wavefront per word: lane l owns column 64w+l, the ballot mask and mbcnt give
+//            each set lane its slot (ballot / prefix-count stream compaction); needed[] comes
+//            out ascending
 //   remap    compact[e] = prefix[c>>6] + popcount(word & bits below c): position of column
 //            c in needed[]; monotone in c, so sorted rows stay sorted
-// Traffic: nnz*4 (mark) + nnz*8 (remap read+write) + N*4 + a few passes over n/8 bytes.
+// Traffic: nnz*4 (mark) + nnz*8 (remap read+write) + N*4 + a few passes over n bytes.
 #include "common.h"
 
 namespace sagnn {
@@ -26,6 +27,7 @@ constexpr int kThreads = 256;
 constexpr int kWordsPerBlock = 2048;  // scan tile: 256 threads x 8 words
 
 struct PlanWs {
+  uint8_t* flag;      // n bytes (rounded up to 64W)
   uint64_t* bitmap;   // W words
   int32_t* prefix;    // W + 1
   int32_t* blocksum;  // nblk + 1
@@ -46,6 +48,7 @@ PlanWs carve(void* base, int64_t n, int32_t nb) {
     off += round_up(bytes, 256);
     return reinterpret_cast<char*>(base) + o;
   };
+  w.flag = reinterpret_cast<uint8_t*>(take((size_t)w.W * 64));
   w.bitmap = reinterpret_cast<uint64_t*>(take(sizeof(uint64_t) * (size_t)w.W));
   w.prefix = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(w.W + 1)));
   w.blocksum = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(w.nblk + 1)));
@@ -56,10 +59,11 @@ PlanWs carve(void* base, int64_t n, int32_t nb) {
   return w;
 }
 
-__global__ __launch_bounds__(kThreads) void clear_kernel(uint64_t* __restrict__ bm, int64_t W,
+__global__ __launch_bounds__(kThreads) void clear_kernel(uint4* __restrict__ flag16, int64_t n16,
                                                          int32_t* __restrict__ err) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
-  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < W; i += stride) bm[i] = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride)
+    flag16[i] = make_uint4(0u, 0u, 0u, 0u);
   if (blockIdx.x == 0 && threadIdx.x < 4) err[threadIdx.x] = 0;
 }
 
@@ -73,20 +77,36 @@ __global__ __launch_bounds__(kThreads) void validate_rowptr_kernel(
     if (rowptr[0] != 0 || (int64_t)rowptr[m] != nnz) err[0] = 1;
 }
 
+__device__ __forceinline__ void mark_one(int32_t c, int64_t n, uint8_t* __restrict__ flag,
+                                         int32_t* __restrict__ err) {
+  if (c < 0 || c >= n) {
+    err[1] = 1;
+    return;
+  }
+  if (flag[c] == 0) flag[c] = 1;  // benign race: all writers store 1
+}
+
+// 4 entries per thread per iteration (16-byte loads when the index array is aligned)
 __global__ __launch_bounds__(kThreads) void mark_kernel(const int32_t* __restrict__ colidx,
                                                         int64_t nnz, int64_t n,
-                                                        uint32_t* __restrict__ bm32,
-                                                        int32_t* __restrict__ err) {
+                                                        uint8_t* __restrict__ flag,
+                                                        int32_t* __restrict__ err, int aligned) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
-  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride) {
-    const int64_t c = colidx[e];
-    if (c < 0 || c >= n) {
-      err[1] = 1;
-      continue;
+  const int64_t quads = nnz >> 2;
+  if (aligned) {
+    const int4* __restrict__ c4 = reinterpret_cast<const int4*>(colidx);
+    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < quads; q += stride) {
+      const int4 c = c4[q];
+      mark_one(c.x, n, flag, err);
+      mark_one(c.y, n, flag, err);
+      mark_one(c.z, n, flag, err);
+      mark_one(c.w, n, flag, err);
     }
-    const uint32_t bit = 1u << (c & 31);
-    uint32_t* w = bm32 + (c >> 5);
-    if (!(__builtin_nontemporal_load(w) & bit)) atomicOr(w, bit);
+    for (int64_t e = (quads << 2) + (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride)
+      mark_one(colidx[e], n, flag, err);
+  } else {
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride)
+      mark_one(colidx[e], n, flag, err);
   }
 }
 
@@ -120,16 +140,37 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* total) {
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(kThreads) void count_kernel(const uint64_t* __restrict__ bm,
-                                                         int64_t W, int32_t* __restrict__ blocksum) {
-  const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + (int64_t)threadIdx.x * 8;
-  int s = 0;
+// Membership words by ballot.  A block owns kWordsPerBlock consecutive words; each of its
+// wavefronts walks its share, one word (64 columns) per step.
+__global__ __launch_bounds__(kThreads) void words_kernel(const uint8_t* __restrict__ flag, int64_t W,
+                                                         uint64_t* __restrict__ bm,
+                                                         int32_t* __restrict__ blocksum) {
+  __shared__ int wsum[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int kPerWave = kWordsPerBlock / (kThreads / 64);
+  const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + (int64_t)wave * kPerWave;
+  int cnt = 0;
+  for (int i = 0; i < kPerWave; i += 4) {
+    uint8_t b[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
-    if (w0 + i < W) s += __popcll(bm[w0 + i]);
-  int total;
-  (void)block_exclusive_scan(s, &total);
-  if (threadIdx.x == 0) blocksum[blockIdx.x] = total;
+    for (int j = 0; j < 4; ++j) b[j] = (w0 + i + j < W) ? flag[(w0 + i + j) * 64 + lane] : (uint8_t)0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint64_t word = __ballot(b[j] != 0);
+      if (w0 + i + j < W) {
+        cnt += __popcll(word);
+        if (lane == 0) bm[w0 + i + j] = word;
+      }
+    }
+  }
+  if (lane == 0) wsum[wave] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) t += wsum[w];
+    blocksum[blockIdx.x] = t;
+  }
 }
 
 // one workgroup: in-place exclusive scan of blocksum[0..nblk), blocksum[nblk] = grand total
@@ -204,16 +245,31 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const uint64_t* __restri
   }
 }
 
+__device__ __forceinline__ int32_t remap_one(int32_t c, int64_t n, const uint64_t* __restrict__ bm,
+                                             const int32_t* __restrict__ prefix) {
+  return (c < 0 || c >= n) ? -1 : rank_of(bm, prefix, c);
+}
+
 __global__ __launch_bounds__(kThreads) void remap_kernel(const int32_t* __restrict__ colidx,
                                                          int64_t nnz, int64_t n,
                                                          const uint64_t* __restrict__ bm,
                                                          const int32_t* __restrict__ prefix,
-                                                         int32_t* __restrict__ compact) {
+                                                         int32_t* __restrict__ compact, int aligned) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
-  for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride) {
-    const int64_t c = colidx[e];
-    compact[e] = (c < 0 || c >= n) ? -1 : rank_of(bm, prefix, c);
+  const int64_t quads = aligned ? (nnz >> 2) : 0;
+  const int4* __restrict__ c4 = reinterpret_cast<const int4*>(colidx);
+  int4* __restrict__ o4 = reinterpret_cast<int4*>(compact);
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < quads; q += stride) {
+    const int4 c = c4[q];
+    int4 o;
+    o.x = remap_one(c.x, n, bm, prefix);
+    o.y = remap_one(c.y, n, bm, prefix);
+    o.z = remap_one(c.z, n, bm, prefix);
+    o.w = remap_one(c.w, n, bm, prefix);
+    o4[q] = o;
   }
+  for (int64_t e = (quads << 2) + (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride)
+    compact[e] = remap_one(colidx[e], n, bm, prefix);
 }
 
 inline unsigned grid_for(int64_t items, int64_t per_thread = 1) {
@@ -259,7 +315,8 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
 
   SAGNN_HIP(hipMemcpyAsync(w.colblk, h_colblk, sizeof(int64_t) * (size_t)(nb + 1),
                            hipMemcpyHostToDevice, s));
-  hipLaunchKernelGGL(clear_kernel, dim3(grid_for(w.W)), dim3(kThreads), 0, s, w.bitmap, w.W, w.err);
+  hipLaunchKernelGGL(clear_kernel, dim3(grid_for(w.W * 4)), dim3(kThreads), 0, s,
+                     reinterpret_cast<uint4*>(w.flag), w.W * 4, w.err);
   SAGNN_LAUNCH_CHECK();
   if (flags & SAGNN_PLAN_VALIDATE) {
     hipLaunchKernelGGL(validate_rowptr_kernel, dim3(grid_for(m)), dim3(kThreads), 0, s, d_rowptr,
@@ -267,12 +324,12 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
     SAGNN_LAUNCH_CHECK();
   }
   if (nnz > 0) {
-    hipLaunchKernelGGL(mark_kernel, dim3(grid_for(nnz, 4)), dim3(kThreads), 0, s, d_colidx, nnz,
-                       n, reinterpret_cast<uint32_t*>(w.bitmap), w.err);
+    hipLaunchKernelGGL(mark_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz,
+                       n, w.flag, w.err, aligned16(d_colidx) ? 1 : 0);
     SAGNN_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(count_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.bitmap, w.W,
-                     w.blocksum);
+  hipLaunchKernelGGL(words_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.flag, w.W,
+                     w.bitmap, w.blocksum);
   SAGNN_LAUNCH_CHECK();
   hipLaunchKernelGGL(scan_blocks_kernel, dim3(1), dim3(kThreads), 0, s, w.blocksum, w.nblk);
   SAGNN_LAUNCH_CHECK();
@@ -298,8 +355,9 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
     SAGNN_LAUNCH_CHECK();
   }
   if (d_colidx_compact && nnz > 0) {
-    hipLaunchKernelGGL(remap_kernel, dim3(grid_for(nnz, 4)), dim3(kThreads), 0, s, d_colidx, nnz,
-                       n, w.bitmap, w.prefix, d_colidx_compact);
+    hipLaunchKernelGGL(remap_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz,
+                       n, w.bitmap, w.prefix, d_colidx_compact,
+                       (aligned16(d_colidx) && aligned16(d_colidx_compact)) ? 1 : 0);
     SAGNN_LAUNCH_CHECK();
   }
   return SAGNN_OK;

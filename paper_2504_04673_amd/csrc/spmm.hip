@@ -20,6 +20,8 @@
 //
 // Widths other than 64/128/256 are processed as column slabs of those widths plus a narrow
 // remainder.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace sagnn {
@@ -456,7 +458,12 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
       SpmmDims sd = d;
       sp.B = B + col0; sp.C = C + col0; sp.carry = p.carry + col0;
       if (rest >= 256) { sd.f = 256; launch_waves(spmm_wide_kernel<4, 8>, blocks, sp, sd, s); }
-      else if (rest >= 128) { sd.f = 128; launch_waves(spmm_wide_kernel<2, 8>, blocks, sp, sd, s); }
+      else if (rest >= 128) {
+        sd.f = 128;
+        static const int u16 = getenv("SAGNN_EXP_U16") ? 1 : 0;  // EXPERIMENT knob
+        if (u16) launch_waves(spmm_wide_kernel<2, 16>, blocks, sp, sd, s);
+        else launch_waves(spmm_wide_kernel<2, 8>, blocks, sp, sd, s);
+      }
       else if (rest >= 64) { sd.f = 64; launch_waves(spmm_wide_kernel<1, 8>, blocks, sp, sd, s); }
       else {
         sd.f = rest;
