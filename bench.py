@@ -116,8 +116,9 @@ def main():
     Hn = torch.empty((N, f), dtype=torch.float32, device=dev)
     T = torch.empty((m, f), dtype=torch.float32, device=dev)
     Ho = torch.empty((m, f_out), dtype=torch.float32, device=dev)
-    ws = sagnn.spmm_csr_prepare(rp, nnz, f)
+    ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, va, N, f)
     torch.cuda.synchronize()
+    log(f"[bench] spmm schedule: {ws.info()}")
     models = workloads.byte_models(m, n, nnz, N, f, f_out, nb)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -178,6 +179,7 @@ def main():
             "cfg5": "SBM 2M vertices, rank-0 block of 16, ordered by community",
         }[wl.name] + f", m={m} n={n} nnz={nnz} N_needed={N} f={f} f_out={f_out} nb={nb}",
             "step": ("" if args.no_plan else "plan+") + "pack+spmm+gemm_relu", "seed": 0,
+            "spmm_schedule": ws.info(),
             "scale": args.scale},
         "roofline": {
             "kernel": "spmm_csr_tallskinny (spmm_wide/narrow_kernel + carry fix-up)",

@@ -21,7 +21,7 @@
  * Conventions for every entry point
  *   - d_* pointers are device memory owned by the caller, h_* pointers are host memory
  *     owned by the caller.  The library allocates no device memory and keeps no state
- *     besides the last HIP error code.
+ *     besides the last HIP error code and the descriptors of prepared SpMM workspaces.
  *   - Matrices are row-major; ld* are leading dimensions in elements.
  *   - CSR: rowptr has m+1 int32 entries with rowptr[0] = 0 and rowptr[m] = nnz; colidx and
  *     val have nnz entries.  Entries of a row may be unsorted and may repeat: the planner
@@ -117,23 +117,42 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  *
  * A is m x k CSR, B is k x f (ldb), C is m x f (ldc); accumulate = 0 overwrites C,
  * accumulate = 1 adds to it (the per-block accumulation of the algorithms).  fp32 FMA.
- * The summation order is fixed for a given (m, nnz, f, workspace), so results are
- * reproducible run to run; it differs from the stored order, so they agree with a
- * sequential sum up to rounding (|err| <= ~1e-6 * sum |val||B|).
+ * The summation order is a fixed function of (rowptr, colidx, m, k, nnz, f), so results are
+ * reproducible run to run and across preparations (no floating-point atomics); it differs
+ * from the stored order, so they agree with a sequential sum up to rounding
+ * (|err| <= ~1e-6 * sum |val||B|).
  * A column index outside [0,k) is clamped into range (never read out of bounds).
  *
- * Load balancing: the pattern of A is fixed during training, so a one-time
- * spmm_csr_prepare() cuts the entries into equal chunks (nonzero splitting) and records
- * where each chunk starts.  d_ws must then be passed unchanged to every
- * spmm_csr_tallskinny() call with the same (rowptr, m, nnz, f); part of it is scratch for
+ * Scheduling: the pattern (and here also the values) of A is fixed during training, so a
+ * one-time spmm_csr_prepare() builds a schedule in the workspace:
+ *   - always: the entries are cut into equal chunks (nonzero splitting) and the row in which
+ *     each chunk starts is recorded, so hub rows and runs of short rows are balanced;
+ *   - for large power-law matrices with f a multiple of 64: the entries of long rows are copied
+ *     into the workspace re-ordered by column slab ("slab sweep"), so that all wavefronts of an
+ *     XCD touch the same small part of B at the same time (L2 reuse).  Requires ascending
+ *     column indices inside long rows and k < 2^27; otherwise the first schedule is used.
+ * The workspace then holds a private copy of colidx/val: call spmm_csr_prepare() again if
+ * they change.  d_ws must be passed unchanged to every spmm_csr_tallskinny() call with the
+ * same (rowptr, colidx, val, m, k, nnz) and f <= the prepared f; part of it is scratch for
  * partial row sums, so two calls that share a workspace must not overlap in time.
- * With d_ws == NULL a simple one-wavefront-per-row kernel is used (no preparation, no
- * balancing).  Passing a workspace that was not prepared for these arguments leaves C
- * unspecified but does not fault.
+ * spmm_csr_prepare() synchronises the stream (it plans on the host from a copy of rowptr) and
+ * the library remembers a small host descriptor per prepared workspace address; passing a
+ * workspace that was not prepared in this process returns SAGNN_EINVAL.  If the workspace
+ * memory was overwritten after preparation, C is unspecified (the kernels check a generation
+ * tag and exit), but nothing faults.
+ * With d_ws == NULL a simple one-wavefront-per-row kernel is used (no preparation).
+ * B and C must not overlap.
  */
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
-int spmm_csr_prepare(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t f, void* d_ws,
-                     size_t ws_bytes, void* stream);
+int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                     int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws, size_t ws_bytes,
+                     void* stream);
+/* What spmm_csr_prepare() decided for a workspace (host query, no GPU work).  h_info[8]:
+ * [0] schedule (0 nonzero splitting, 1 slab sweep + nonzero splitting for short rows),
+ * [1] wavefront streams of the sweep, [2] entries in them, [3] rows, [4] entries and
+ * [5] chunks of the nonzero-splitting part, [6] rows cut into several pieces,
+ * [7] 1 if the matrix has empty rows.  SAGNN_EINVAL if the workspace is unknown. */
+int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info);
 int spmm_csr_tallskinny(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                         int64_t m, int64_t k, int64_t nnz, const float* d_B, int64_t ldb,
                         int32_t f, float* d_C, int64_t ldc, int32_t accumulate, void* d_ws,

@@ -17,7 +17,7 @@ PLAN_VALIDATE = 1
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_pack_rows",
-    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_tallskinny",
+    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_schedule_info", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
 ]
 
@@ -56,7 +56,8 @@ def lib():
                                             u32, vp]
         L.spmm_pack_rows.argtypes = [vp, i64, i64, i32, vp, i64, vp, i64, vp]
         L.spmm_csr_workspace_bytes.argtypes = [i64, i64, i32, psz]
-        L.spmm_csr_prepare.argtypes = [vp, i64, i64, i32, vp, sz, vp]
+        L.spmm_csr_prepare.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
+        L.spmm_csr_schedule_info.argtypes = [vp, vp]
         L.spmm_csr_tallskinny.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i64, i32, vp,
                                           sz, vp]
         L.dense_gemm_act.argtypes = [vp, i64, vp, i64, i32, i64, i32, i32, i32, i32, vp, i64, vp, i64,
@@ -166,16 +167,28 @@ class SpmmWorkspace:
     nnz: int
     f: int
 
+    def info(self) -> dict:
+        """Schedule chosen by spmm_csr_prepare (see spmm_csr_schedule_info)."""
+        a = np.zeros(8, dtype=np.int64)
+        _check(lib().spmm_csr_schedule_info(_ptr(self.buf), a.ctypes.data_as(ctypes.c_void_p)),
+               "spmm_csr_schedule_info")
+        keys = ("mode", "sweep_waves", "sweep_entries", "chunk_rows", "chunk_entries", "chunks",
+                "split_rows", "has_empty_rows")
+        return dict(zip(keys, (int(x) for x in a)))
 
-def spmm_csr_prepare(rowptr, nnz: int, f: int) -> SpmmWorkspace:
+
+def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int) -> SpmmWorkspace:
+    """One-time schedule for C = A*B with A = (rowptr, colidx, val), B of k rows and width f."""
     rowptr = _dev(rowptr, torch.int32, "rowptr")
-    m = rowptr.numel() - 1
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
     L = lib()
     wsb = ctypes.c_size_t(0)
     _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
     buf = _ws(wsb.value, rowptr.device)
-    _check(L.spmm_csr_prepare(_ptr(rowptr), m, nnz, f, _ptr(buf), buf.numel(), _stream()),
-           "spmm_csr_prepare")
+    _check(L.spmm_csr_prepare(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
+                              buf.numel(), _stream()), "spmm_csr_prepare")
     return SpmmWorkspace(buf, m, nnz, f)
 
 

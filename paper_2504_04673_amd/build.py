@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB = os.path.join(_HERE, "libsagnn.so")
-SOURCES = ["api.hip", "pack.hip", "plan.hip", "spmm.hip", "gemm.hip"]
+SOURCES = ["api.hip", "pack.hip", "plan.hip", "spmm.hip", "spmm_sweep.hip", "gemm.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
@@ -26,7 +26,8 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "common.h"), os.path.join(INCLUDE, "sagnn.h")]
+    deps = sources() + [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "rowload.h"),
+                        os.path.join(INCLUDE, "sagnn.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -2,14 +2,30 @@
 // spmm.hip and gemm.hip on one stream (Sec. 2.1 forward / backward equations, in the order
 // of Alg. 1: sparse product first, dense transform second).
 #include <atomic>
+#include <mutex>
+#include <unordered_map>
 
 #include "common.h"
 
 namespace sagnn {
 namespace {
 std::atomic<int> g_last_hip_error{0};
-}
+// host descriptors of prepared SpMM workspaces, keyed by the workspace address
+std::mutex g_desc_mutex;
+std::unordered_map<const void*, SpmmHostDesc> g_desc;
+}  // namespace
 void set_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
+void spmm_desc_put(const void* ws, const SpmmHostDesc& d) {
+  std::lock_guard<std::mutex> lock(g_desc_mutex);
+  g_desc[ws] = d;
+}
+bool spmm_desc_get(const void* ws, SpmmHostDesc* d) {
+  std::lock_guard<std::mutex> lock(g_desc_mutex);
+  auto it = g_desc.find(ws);
+  if (it == g_desc.end()) return false;
+  *d = it->second;
+  return true;
+}
 }  // namespace sagnn
 
 SAGNN_EXPORT const char* sagnn_strerror(int code) {

@@ -23,6 +23,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "rowload.h"
 
 namespace sagnn {
 namespace {
@@ -31,21 +32,22 @@ constexpr int kT = kSpmmChunk;
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = kWavesPerBlock * 64;
 
-template <int N> struct Vec { typedef float T __attribute__((ext_vector_type(N))); };
-template <> struct Vec<1> { typedef float T; };
-
 // Scalars of a launch.  Pointers are passed as separate __restrict__ kernel parameters: that
 // is what lets the compiler prove the index/value streams are never written by the kernel and
 // fetch them with scalar loads.
 struct SpmmDims {
-  int64_t m, nnz, nchunks, ldb, ldc, carry_ld;
+  int64_t m, nnz, nchunks, ldb, ldc, carry_ld;  // m, nnz, nchunks: of the CSR being walked
+  uint64_t generation;
+  uint32_t b_bytes;    // bytes addressable from B (buffer-load variant)
+  uint32_t row_bytes;  // ldb * 4
   uint32_t kmax;  // k - 1: largest valid column index
   int32_t f;      // columns handled by this launch (slab width)
   int32_t accumulate;
 };
 
 __device__ __forceinline__ bool ws_matches(const SpmmWsHeader* __restrict__ hdr, const SpmmDims& d) {
-  return hdr->magic == kSpmmMagic && hdr->m == d.m && hdr->nnz == d.nnz && hdr->nchunks == d.nchunks;
+  return hdr->magic == kSpmmMagic && hdr->generation == d.generation && hdr->c_rows == d.m &&
+         hdr->c_nnz == d.nnz && hdr->c_nchunks == d.nchunks;
 }
 
 __device__ __forceinline__ int next_row(int r, bool has_empty, const int32_t* __restrict__ rowptr,
@@ -60,14 +62,15 @@ __device__ __forceinline__ int next_row(int r, bool has_empty, const int32_t* __
   const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,                   \
       const float *__restrict__ val, const float *__restrict__ B, float *__restrict__ C,    \
       const SpmmWsHeader *__restrict__ hdr, const int32_t *__restrict__ chunk_row,          \
-      const uint32_t *__restrict__ flags, float *__restrict__ carry_base
+      const uint32_t *__restrict__ flags, float *__restrict__ carry_base,                   \
+      const int32_t *__restrict__ rowmap
 
 // ------------------------------------------------------------------------------------------
 // wide kernel: f == 64 * FPL, one entry per wavefront load.
 // Per batch of U entries: U dense-row loads are issued back to back (their column indices and
 // values are already in scalar registers), then the scalar loads of the NEXT batch, then the
 // FMAs with a uniform branch at every row end.
-template <int FPL, int U>
+template <int FPL, int U, bool BUF>
 __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, const SpmmDims d) {
   using vec = typename Vec<FPL>::T;
   const uint32_t lane = threadIdx.x & 63;
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
   const int64_t k = (int64_t)blockIdx.x * kWavesPerBlock + wave;
   if (k >= d.nchunks) return;
   if (!ws_matches(hdr, d)) return;
-  const bool has_empty = hdr->has_empty_rows != 0;
+  const bool has_empty = hdr->has_empty_rows != 0 && rowmap == nullptr;
   const int32_t e0 = (int32_t)(k * kT);
   const int32_t e1 = (int32_t)((d.nnz - e0 < kT) ? d.nnz : e0 + kT);
   int r = chunk_row[k];
@@ -84,6 +87,7 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
   bool head = rowptr[r] < e0;  // first row began in an earlier chunk -> carry slot
   const uint32_t* __restrict__ fl = flags + (e0 >> 5);
   char* __restrict__ carry = reinterpret_cast<char*>(carry_base + k * d.carry_ld) + loff;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
 
   vec acc = 0.f;
   auto flush = [&]() {
@@ -92,7 +96,8 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
       *reinterpret_cast<vec*>(carry) = acc;
       head = false;
     } else {
-      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)r * d.ldc) + loff);
+      const int64_t ro = rowmap ? rowmap[r] : r;
+      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + ro * d.ldc) + loff);
       if (d.accumulate) acc += *p;
       *p = acc;
     }
@@ -130,8 +135,7 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t cc = (uint32_t)c[u] > d.kmax ? d.kmax : (uint32_t)c[u];
-      const char* rowbase = reinterpret_cast<const char*>(B + (int64_t)cc * d.ldb);
-      h[u] = *reinterpret_cast<const vec*>(rowbase + loff);
+      h[u] = load_row<FPL, BUF>(rs, B, cc, loff, d.row_bytes, d.ldb);
       vc[u] = v[u];
     }
     if (e + U < e1) fetch(e + U, c, v);
@@ -176,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void spmm_narrow_kernel(SPMM_PTR_PARAMS, co
   const int64_t k = (int64_t)blockIdx.x * kWavesPerBlock + wave;
   if (k >= d.nchunks) return;
   if (!ws_matches(hdr, d)) return;
-  const bool has_empty = hdr->has_empty_rows != 0;
+  const bool has_empty = hdr->has_empty_rows != 0 && rowmap == nullptr;
   const int32_t e0 = (int32_t)(k * kT);
   const int32_t e1 = (int32_t)((d.nnz - e0 < kT) ? d.nnz : e0 + kT);
   int r = chunk_row[k];
@@ -194,7 +198,8 @@ __global__ __launch_bounds__(kBlock) void spmm_narrow_kernel(SPMM_PTR_PARAMS, co
       if (g == 0 && active) *reinterpret_cast<vec4*>(carry) = t;
       head = false;
     } else if (g == 0 && active) {
-      vec4* p = reinterpret_cast<vec4*>(Cl + (int64_t)r * d.ldc);
+      const int64_t ro = rowmap ? rowmap[r] : r;
+      vec4* p = reinterpret_cast<vec4*>(Cl + ro * d.ldc);
       if (d.accumulate) t += *p;
       *p = t;
     }
@@ -286,7 +291,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(SPMM_PTR_PARAMS, con
       const float4 t0 = *reinterpret_cast<const float4*>(carry_base + j * d.carry_ld + c4 * 4);
       s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
     }
-    float4* p = reinterpret_cast<float4*>(C + (int64_t)R * d.ldc + c4 * 4);
+    const int64_t ro = rowmap ? rowmap[R] : R;
+    float4* p = reinterpret_cast<float4*>(C + ro * d.ldc + c4 * 4);
     float4 o = *p;
     o.x += (s0.x + s1.x) + (s2.x + s3.x);
     o.y += (s0.y + s1.y) + (s2.y + s3.y);
@@ -299,7 +305,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(SPMM_PTR_PARAMS, con
 // rows without entries: C[r,:] = 0 when overwriting (no chunk ever visits them)
 __global__ __launch_bounds__(kBlock) void spmm_zero_empty_kernel(SPMM_PTR_PARAMS, const SpmmDims d,
                                                                  int32_t f_total) {
-  if (!ws_matches(hdr, d) || hdr->has_empty_rows == 0) return;
+  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->has_empty_rows == 0) return;
   const int lane = threadIdx.x & 63;
   const int64_t wave0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
   const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
@@ -342,18 +348,6 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SPMM_PTR_PARAMS, const
 
 // ------------------------------------------------------------------------------------------
 // preparation
-__global__ void prep_header_kernel(SpmmWsHeader* hdr, int64_t m, int64_t nnz, int64_t nchunks,
-                                   int32_t f) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    hdr->magic = kSpmmMagic;
-    hdr->has_empty_rows = 0;
-    hdr->m = m;
-    hdr->nnz = nnz;
-    hdr->nchunks = nchunks;
-    hdr->f = f;
-  }
-}
-
 __global__ __launch_bounds__(kBlock) void prep_clear_flags_kernel(uint32_t* flags, int64_t words) {
   const int64_t stride = (int64_t)gridDim.x * kBlock;
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < words; i += stride) flags[i] = 0;
@@ -381,14 +375,14 @@ __global__ __launch_bounds__(kBlock) void prep_chunks_kernel(const int32_t* __re
 __global__ __launch_bounds__(kBlock) void prep_rowend_kernel(const int32_t* __restrict__ rowptr,
                                                              int64_t m, int64_t nnz,
                                                              uint32_t* __restrict__ flags,
-                                                             SpmmWsHeader* hdr) {
+                                                             int32_t* __restrict__ has_empty) {
   const int64_t stride = (int64_t)gridDim.x * kBlock;
   for (int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x; r < m; r += stride) {
     const int64_t b = rowptr[r], e = rowptr[r + 1];
     if (e > b && e <= nnz && e >= 1) {
       atomicOr(&flags[(e - 1) >> 5], 1u << ((e - 1) & 31));
     } else if (e == b) {
-      hdr->has_empty_rows = 1;
+      *has_empty = 1;
     }
   }
 }
@@ -403,16 +397,42 @@ inline unsigned capped_grid(int64_t blocks) {
 struct SpmmPtrs {
   const int32_t* rowptr; const int32_t* colidx; const float* val; const float* B; float* C;
   const SpmmWsHeader* hdr; const int32_t* chunk_row; const uint32_t* flags; float* carry;
+  const int32_t* rowmap;
 };
 
 template <typename Kern, typename... Extra>
 inline void launch_waves(Kern kern, int64_t blocks, const SpmmPtrs& p, const SpmmDims& d,
                          hipStream_t s, Extra... extra) {
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kBlock), 0, s, p.rowptr, p.colidx, p.val,
-                     p.B, p.C, p.hdr, p.chunk_row, p.flags, p.carry, d, extra...);
+                     p.B, p.C, p.hdr, p.chunk_row, p.flags, p.carry, p.rowmap, d, extra...);
+}
+
+// chunk-table construction for a CSR (rowptr of `rows` rows, `nnz` entries)
+int build_chunk_tables(const int32_t* d_rowptr, int64_t rows, int64_t nnz, int32_t* chunk_row,
+                       uint32_t* flags, int32_t* d_has_empty, hipStream_t s) {
+  const int64_t nchunks = spmm_nchunks(nnz);
+  const int64_t words = nchunks * (kSpmmChunk / 32);
+  if (words > 0) {
+    hipLaunchKernelGGL(prep_clear_flags_kernel, dim3(capped_grid(ceil_div(words, kBlock))), dim3(kBlock),
+                       0, s, flags, words);
+    SAGNN_LAUNCH_CHECK();
+  }
+  if (rows > 0) {
+    hipLaunchKernelGGL(prep_chunks_kernel, dim3((unsigned)ceil_div(nchunks + 1, kBlock)), dim3(kBlock), 0,
+                       s, d_rowptr, rows, nchunks, chunk_row);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(prep_rowend_kernel, dim3(capped_grid(ceil_div(rows, kBlock))), dim3(kBlock), 0, s,
+                       d_rowptr, rows, nnz, flags, d_has_empty);
+    SAGNN_LAUNCH_CHECK();
+  }
+  return SAGNN_OK;
 }
 
 }  // namespace
+
+uint64_t spmm_next_generation();
+int sweep_combine(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, float* C, int64_t ldc,
+                  int32_t f_total, int32_t accumulate, hipStream_t s);
 
 int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
                 int64_t k, int64_t nnz, const float* B, int64_t ldb, int32_t f, float* C,
@@ -425,7 +445,6 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
   if (!rowptr || !C || !aligned16(C)) return SAGNN_EINVAL;
   if (nnz > 0 && (!colidx || !val || !B || !aligned16(B) || k == 0)) return SAGNN_EINVAL;
   if (ws && (reinterpret_cast<uintptr_t>(ws) & 255u)) return SAGNN_EINVAL;
-  if (ws && ws_bytes < spmm_ws_bytes(nnz, f)) return SAGNN_ECAPACITY;
 
   SpmmPtrs p{};
   p.rowptr = rowptr; p.colidx = colidx; p.val = val; p.B = B; p.C = C;
@@ -442,47 +461,70 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
     return SAGNN_OK;
   }
 
+  SpmmHostDesc desc{};
+  if (!spmm_desc_get(ws, &desc)) return SAGNN_EINVAL;        // never prepared in this process
+  if (desc.m != m || desc.nnz != nnz || desc.f < f) return SAGNN_EINVAL;
+  const SpmmWsLayout L = spmm_ws_layout(m, nnz, desc.f);
+  if (ws_bytes < L.total) return SAGNN_ECAPACITY;
   char* base = reinterpret_cast<char*>(ws);
-  p.hdr = reinterpret_cast<const SpmmWsHeader*>(base);
-  p.chunk_row = reinterpret_cast<const int32_t*>(base + spmm_ws_table_off());
-  p.flags = reinterpret_cast<const uint32_t*>(base + spmm_ws_flags_off(nnz));
-  p.carry = reinterpret_cast<float*>(base + spmm_ws_carry_off(nnz));
+  p.hdr = reinterpret_cast<const SpmmWsHeader*>(base + L.header);
+  p.chunk_row = reinterpret_cast<const int32_t*>(base + L.chunk_row);
+  p.flags = reinterpret_cast<const uint32_t*>(base + L.flags);
+  p.carry = reinterpret_cast<float*>(base + L.carry);
+  d.generation = desc.generation;
 
-  if (d.nchunks > 0) {
-    const int64_t blocks = ceil_div(d.nchunks, kWavesPerBlock);
-    // column slabs: 256 / 128 / 64 wide through the wide kernel, the rest through the narrow one
-    int32_t col0 = 0;
-    while (col0 < f) {
-      const int32_t rest = f - col0;
-      SpmmPtrs sp = p;
-      SpmmDims sd = d;
-      sp.B = B + col0; sp.C = C + col0; sp.carry = p.carry + col0;
-      if (rest >= 256) { sd.f = 256; launch_waves(spmm_wide_kernel<4, 8>, blocks, sp, sd, s); }
-      else if (rest >= 128) {
-        sd.f = 128;
-        static const int u16 = getenv("SAGNN_EXP_U16") ? 1 : 0;  // EXPERIMENT knob
-        if (u16) launch_waves(spmm_wide_kernel<2, 16>, blocks, sp, sd, s);
-        else launch_waves(spmm_wide_kernel<2, 8>, blocks, sp, sd, s);
-      }
-      else if (rest >= 64) { sd.f = 64; launch_waves(spmm_wide_kernel<1, 8>, blocks, sp, sd, s); }
-      else {
-        sd.f = rest;
-        if (rest > 32) launch_waves(spmm_narrow_kernel<16, 4>, blocks, sp, sd, s);
-        else if (rest > 16) launch_waves(spmm_narrow_kernel<8, 4>, blocks, sp, sd, s);
-        else if (rest > 8) launch_waves(spmm_narrow_kernel<4, 4>, blocks, sp, sd, s);
-        else launch_waves(spmm_narrow_kernel<2, 4>, blocks, sp, sd, s);
-      }
-      SAGNN_LAUNCH_CHECK();
-      col0 += sd.f;
-    }
-    if (d.nchunks > 1) {
-      launch_waves(spmm_fixup_kernel, blocks, p, d, s, f);
-      SAGNN_LAUNCH_CHECK();
-    }
-  }
-  if (!accumulate) {
+  if (!accumulate && desc.has_empty_rows) {
     launch_waves(spmm_zero_empty_kernel, capped_grid(ceil_div(m, kWavesPerBlock)), p, d, s, f);
     SAGNN_LAUNCH_CHECK();
+  }
+  if (desc.mode == 1) {
+    if (f & 63) return SAGNN_EINVAL;  // the sweep schedule was prepared for 64-multiples only
+    // the chunk kernels walk the compacted short-row CSR stored in the workspace
+    const int64_t short_base = (int64_t)round_up((size_t)desc.sweep_stream_len + 64, 256);
+    p.rowptr = reinterpret_cast<const int32_t*>(base + L.rowptr_s);
+    p.rowmap = reinterpret_cast<const int32_t*>(base + L.rowmap_s);
+    p.colidx = reinterpret_cast<const int32_t*>(base + L.code) + short_base;
+    p.val = reinterpret_cast<const float*>(base + L.vals) + short_base;
+    d.m = desc.c_rows; d.nnz = desc.c_nnz; d.nchunks = desc.c_nchunks;
+  }
+
+  const int64_t blocks = ceil_div(d.nchunks, kWavesPerBlock);
+  // column slabs: 256 / 128 / 64 wide through the wide kernels, the rest through the narrow one
+  int32_t col0 = 0;
+  while (col0 < f) {
+    const int32_t rest = f - col0;
+    SpmmPtrs sp = p;
+    SpmmDims sd = d;
+    sp.B = B + col0; sp.C = C + col0; sp.carry = p.carry + col0;
+    sd.f = rest >= 256 ? 256 : (rest >= 128 ? 128 : (rest >= 64 ? 64 : rest));
+    const bool buf = buffer_addressable(d.kmax, ldb, sd.f, &sd.b_bytes);
+    sd.row_bytes = (uint32_t)(ldb * 4);
+    if (desc.mode == 1) {
+      int rc = sweep_launch(desc, L, base, B, ldb, col0, sd.f, d.kmax, C, ldc, accumulate, f, s);
+      if (rc != SAGNN_OK) return rc;
+    }
+    if (d.nchunks > 0) {
+      if (sd.f == 256 && buf) launch_waves(spmm_wide_kernel<4, 8, true>, blocks, sp, sd, s);
+      else if (sd.f == 256) launch_waves(spmm_wide_kernel<4, 8, false>, blocks, sp, sd, s);
+      else if (sd.f == 128 && buf) launch_waves(spmm_wide_kernel<2, 8, true>, blocks, sp, sd, s);
+      else if (sd.f == 128) launch_waves(spmm_wide_kernel<2, 8, false>, blocks, sp, sd, s);
+      else if (sd.f == 64 && buf) launch_waves(spmm_wide_kernel<1, 8, true>, blocks, sp, sd, s);
+      else if (sd.f == 64) launch_waves(spmm_wide_kernel<1, 8, false>, blocks, sp, sd, s);
+      else if (rest > 32) launch_waves(spmm_narrow_kernel<16, 4>, blocks, sp, sd, s);
+      else if (rest > 16) launch_waves(spmm_narrow_kernel<8, 4>, blocks, sp, sd, s);
+      else if (rest > 8) launch_waves(spmm_narrow_kernel<4, 4>, blocks, sp, sd, s);
+      else launch_waves(spmm_narrow_kernel<2, 4>, blocks, sp, sd, s);
+      SAGNN_LAUNCH_CHECK();
+    }
+    col0 += sd.f;
+  }
+  if (d.nchunks > 1) {
+    launch_waves(spmm_fixup_kernel, blocks, p, d, s, f);
+    SAGNN_LAUNCH_CHECK();
+  }
+  if (desc.mode == 1) {
+    int rc = sweep_combine(desc, L, base, C, ldc, f, accumulate, s);
+    if (rc != SAGNN_OK) return rc;
   }
   return SAGNN_OK;
 }
@@ -491,40 +533,77 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
 
 SAGNN_EXPORT int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes) {
   using namespace sagnn;
-  if (!bytes || m < 0 || nnz < 0 || f <= 0 || (f & 3) || nnz > 0x7FFFFFFFll) return SAGNN_EINVAL;
-  *bytes = spmm_ws_bytes(nnz, f);
+  if (!bytes || m < 0 || nnz < 0 || f <= 0 || (f & 3) || nnz > 0x7FFFFFFFll || m > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  *bytes = spmm_ws_bytes(m, nnz, f);
   return SAGNN_OK;
 }
 
-SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t f,
+SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                  const float* d_val, int64_t m, int64_t k, int64_t nnz, int32_t f,
                                   void* d_ws, size_t ws_bytes, void* stream) {
   using namespace sagnn;
-  if (m < 0 || nnz < 0 || f <= 0 || (f & 3) || m > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
+  if (m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || m > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll ||
+      k > 0x7FFFFFFFll)
     return SAGNN_EINVAL;
   if (!d_rowptr || !d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return SAGNN_EINVAL;
-  if (ws_bytes < spmm_ws_bytes(nnz, f)) return SAGNN_ECAPACITY;
+  if (nnz > 0 && (!d_colidx || !d_val)) return SAGNN_EINVAL;
+  const SpmmWsLayout L = spmm_ws_layout(m, nnz, f);
+  if (ws_bytes < L.total) return SAGNN_ECAPACITY;
   hipStream_t s = (hipStream_t)stream;
   char* base = reinterpret_cast<char*>(d_ws);
-  auto* hdr = reinterpret_cast<SpmmWsHeader*>(base);
-  auto* chunk_row = reinterpret_cast<int32_t*>(base + spmm_ws_table_off());
-  auto* flags = reinterpret_cast<uint32_t*>(base + spmm_ws_flags_off(nnz));
-  const int64_t nchunks = spmm_nchunks(nnz);
-  const int64_t words = nchunks * (kSpmmChunk / 32);
-  hipLaunchKernelGGL(prep_header_kernel, dim3(1), dim3(64), 0, s, hdr, m, nnz, nchunks, f);
-  SAGNN_LAUNCH_CHECK();
-  if (words > 0) {
-    hipLaunchKernelGGL(prep_clear_flags_kernel, dim3(capped_grid(ceil_div(words, kBlock))),
-                       dim3(kBlock), 0, s, flags, words);
-    SAGNN_LAUNCH_CHECK();
+  int32_t* d_has_empty = reinterpret_cast<int32_t*>(base + L.carry);  // scratch until the first product
+
+  SweepPlanResult plan{};
+  if ((f & 63) == 0) {
+    int rc = sweep_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, base, L, s, &plan);
+    if (rc != SAGNN_OK) return rc;
   }
-  if (m > 0) {
-    hipLaunchKernelGGL(prep_chunks_kernel, dim3((unsigned)ceil_div(nchunks + 1, kBlock)),
-                       dim3(kBlock), 0, s, d_rowptr, m, nchunks, chunk_row);
-    SAGNN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(prep_rowend_kernel, dim3(capped_grid(ceil_div(m, kBlock))), dim3(kBlock), 0,
-                       s, d_rowptr, m, nnz, flags, hdr);
-    SAGNN_LAUNCH_CHECK();
+  SpmmWsHeader h{};
+  SAGNN_HIP(hipMemsetAsync(d_has_empty, 0, 4, s));
+  if (plan.use_sweep) {
+    h = plan.hdr;
+    int rc = build_chunk_tables(reinterpret_cast<const int32_t*>(base + L.rowptr_s), h.c_rows, h.c_nnz,
+                                reinterpret_cast<int32_t*>(base + L.chunk_row),
+                                reinterpret_cast<uint32_t*>(base + L.flags), d_has_empty, s);
+    if (rc != SAGNN_OK) return rc;
+  } else {
+    h.magic = kSpmmMagic;
+    h.m = m; h.nnz = nnz; h.f = f; h.mode = 0;
+    h.generation = spmm_next_generation();
+    h.c_rows = m; h.c_nnz = nnz; h.c_nchunks = spmm_nchunks(nnz);
+    int rc = build_chunk_tables(d_rowptr, m, nnz, reinterpret_cast<int32_t*>(base + L.chunk_row),
+                                reinterpret_cast<uint32_t*>(base + L.flags), d_has_empty, s);
+    if (rc != SAGNN_OK) return rc;
+    int32_t he = 0;
+    SAGNN_HIP(hipMemcpyAsync(&he, d_has_empty, 4, hipMemcpyDeviceToHost, s));
+    SAGNN_HIP(hipStreamSynchronize(s));
+    h.has_empty_rows = he;
   }
+  SAGNN_HIP(hipMemcpyAsync(base + L.header, &h, sizeof(h), hipMemcpyHostToDevice, s));
+  SAGNN_HIP(hipStreamSynchronize(s));
+  SpmmHostDesc desc{};
+  desc.generation = h.generation; desc.m = m; desc.nnz = nnz; desc.f = f; desc.mode = h.mode;
+  desc.c_rows = h.c_rows; desc.c_nnz = h.c_nnz; desc.c_nchunks = h.c_nchunks;
+  desc.n_waves = h.n_waves; desc.n_multi_rows = h.n_multi_rows; desc.has_empty_rows = h.has_empty_rows;
+  desc.sweep_stream_len = h.n_long_entries;
+  spmm_desc_put(d_ws, desc);
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info) {
+  using namespace sagnn;
+  if (!d_ws || !h_info) return SAGNN_EINVAL;
+  SpmmHostDesc d{};
+  if (!spmm_desc_get(d_ws, &d)) return SAGNN_EINVAL;
+  h_info[0] = d.mode;
+  h_info[1] = d.n_waves;
+  h_info[2] = d.nnz - (d.mode == 1 ? d.c_nnz : d.nnz);   // entries in the slab-sweep streams
+  h_info[3] = d.c_rows;
+  h_info[4] = d.c_nnz;
+  h_info[5] = d.c_nchunks;
+  h_info[6] = d.n_multi_rows;
+  h_info[7] = d.has_empty_rows;
   return SAGNN_OK;
 }
 

@@ -1,0 +1,515 @@
+// Locality-aware schedule for the local SpMM of power-law graphs: the "slab sweep".
+//
+// Why: in C = A * B (Alg. 1 / Alg. 2, "Z <- Z + SpMM(A_iq, H^)") every stored entry pulls one
+// f-wide row of B through the memory system.  With a randomly ordered power-law graph a row of
+// B is almost never still in a 4 MB per-XCD L2 when it is needed again, so the plain schedule
+// moves ~15x the compulsory bytes over the fabric (measured).  The paper fixes the sparsity
+// pattern for the whole training run (it partitions once and reuses the plan every epoch), so
+// a one-time re-ordering of the entry stream is free to choose WHEN each row of B is touched.
+//
+// What: the rows of B are cut into S contiguous slabs.  Rows of A with at least `min_long`
+// entries ("long" rows; they hold most entries of a power-law graph) are cut into pieces of at
+// most `piece_max` entries, and every wavefront is given kSweepSlots pieces whose entries it
+// walks slab by slab: all entries that reference slab 0, then slab 1, ...  Because every
+// wavefront of an XCD walks the slabs in the same order at the same pace, the XCD's L2 only has
+// to hold the hot rows of ONE slab at a time; workgroup b starts at slab (b mod 8) * S/8, so the
+// eight XCDs (workgroups are dispatched to XCDs round-robin) work on eight different slabs.
+// Per-piece accumulators live in LDS (a wavefront adds its register accumulator to the piece's
+// LDS row whenever a (piece, slab) segment ends), so nothing is spilled to HBM between slabs.
+// Pieces of a split row are summed in a fixed order by a small second kernel.  Short rows go
+// through the nonzero-splitting kernels of spmm.hip on a compacted CSR.
+//
+// The entry stream of a wavefront is stored in the workspace as (code, value) pairs sorted by
+// (slab, piece): code = column | piece_slot << 27 | segment_end << 31.
+#include <stdlib.h>
+
+#include <algorithm>
+#include <atomic>
+#include <vector>
+
+#include "common.h"
+#include "rowload.h"
+
+namespace sagnn {
+namespace {
+
+constexpr int kBuildThreads = 256;
+constexpr uint32_t kColMask = (1u << kSweepColBits) - 1u;
+
+// ---------------------------------------------------------------------------------------
+// preparation kernels
+
+// piece_info[2*g] = row (or -1), piece_info[2*g+1] = (j << 16) | p.  One wavefront per piece
+// slot with j == 0 checks that its row's column indices are ascending and inside [0, k).
+__global__ __launch_bounds__(256) void sweep_check_sorted_kernel(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+    const int32_t* __restrict__ piece_info, int64_t n_slots, uint32_t kmax,
+    int32_t* __restrict__ unsorted) {
+  const int lane = threadIdx.x & 63;
+  const int64_t g = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+  if (g >= n_slots) return;
+  const int32_t row = piece_info[2 * g];
+  if (row < 0 || (piece_info[2 * g + 1] >> 16) != 0) return;
+  const int32_t b = rowptr[row], e = rowptr[row + 1];
+  bool bad = false;
+  for (int32_t i = b + lane; i < e; i += 64) {
+    bad |= (uint32_t)colidx[i] > kmax;                       // negative or >= k
+    if (i + 1 < e) bad |= colidx[i] > colidx[i + 1];
+  }
+  if (bad) *unsorted = 1;
+}
+
+__device__ __forceinline__ int32_t count_upto(int32_t x, int32_t j, int32_t p) {
+  // number of i in [0, x) with i % p == j
+  return x > j ? (x - j + p - 1) / p : 0;
+}
+
+// One workgroup per wavefront stream: segment the 16 pieces by slab, lay the entries out in
+// (slab, piece) order and encode them.
+__global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+    const float* __restrict__ val, const int32_t* __restrict__ piece_info,
+    const int32_t* __restrict__ wave_base, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
+    uint32_t* __restrict__ code, float* __restrict__ vals) {
+  __shared__ int32_t lo[kSweepSlots][kSweepMaxSlabs + 1];   // first entry (index in row) of slab s
+  __shared__ int32_t off[kSweepMaxSlabs][kSweepSlots];      // stream offset of segment (s, slot)
+  __shared__ int32_t p_row[kSweepSlots], p_j[kSweepSlots], p_p[kSweepSlots], p_beg[kSweepSlots],
+      p_deg[kSweepSlots];
+  const int64_t w = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int S = n_slabs;
+  if (tid < kSweepSlots) {
+    const int32_t row = piece_info[2 * (w * kSweepSlots + tid)];
+    const int32_t jp = piece_info[2 * (w * kSweepSlots + tid) + 1];
+    p_row[tid] = row;
+    p_j[tid] = jp >> 16;
+    p_p[tid] = jp & 0xFFFF;
+    p_beg[tid] = row >= 0 ? rowptr[row] : 0;
+    p_deg[tid] = row >= 0 ? rowptr[row + 1] - rowptr[row] : 0;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kSweepSlots * (S + 1); idx += kBuildThreads) {
+    const int slot = idx / (S + 1), s = idx - slot * (S + 1);
+    int32_t res = 0;
+    if (p_row[slot] >= 0) {
+      const int32_t d = p_deg[slot];
+      if (s == S) {
+        res = d;
+      } else {
+        // lower bound of column s*slab_width in the (ascending) row
+        const int64_t target = (int64_t)s * slab_width;
+        const int32_t* __restrict__ c = colidx + p_beg[slot];
+        int32_t a = 0, b = d;
+        while (a < b) {
+          const int32_t mid = (a + b) >> 1;
+          const uint32_t cv = (uint32_t)c[mid] > kmax ? kmax : (uint32_t)c[mid];
+          if ((int64_t)cv < target) a = mid + 1; else b = mid;
+        }
+        res = a;
+      }
+    }
+    lo[slot][s] = res;
+  }
+  __syncthreads();
+  // The stream is laid out in the order the wavefront will walk the slabs: it starts at slab
+  // s0 = xcd * S/8 (xcd = workgroup index mod 8, four wavefronts per workgroup) and wraps.
+  const int s0 = (int)(((w >> 2) & 7) * S / 8);
+  __shared__ int32_t total;
+  if (tid == 0) {
+    int32_t run = 0;
+    for (int t = 0; t < S; ++t) {
+      const int s = (s0 + t) % S;
+      for (int slot = 0; slot < kSweepSlots; ++slot) {
+        off[s][slot] = run;
+        if (p_row[slot] >= 0)
+          run += count_upto(lo[slot][s + 1], p_j[slot], p_p[slot]) -
+                 count_upto(lo[slot][s], p_j[slot], p_p[slot]);
+      }
+    }
+    total = run;
+  }
+  __syncthreads();
+  const int64_t base = wave_base[w];
+  // padding up to the next stream: entries that multiply row 0 of B by zero
+  for (int64_t e = base + total + tid; e < wave_base[w + 1]; e += kBuildThreads) {
+    code[e] = 0u;
+    vals[e] = 0.f;
+  }
+  for (int slot = 0; slot < kSweepSlots; ++slot) {
+    if (p_row[slot] < 0) continue;
+    const int32_t j = p_j[slot], p = p_p[slot], d = p_deg[slot], beg = p_beg[slot];
+    const int32_t size = count_upto(d, j, p);
+    for (int32_t t = tid; t < size; t += kBuildThreads) {
+      const int32_t i = j + t * p;
+      const uint32_t craw = (uint32_t)colidx[beg + i];
+      const uint32_t c = craw > kmax ? kmax : craw;
+      int s = (int)(c / (uint32_t)slab_width);
+      if (s > S - 1) s = S - 1;
+      // the row is ascending, but clamped / equal columns may sit on a slab boundary: trust lo[]
+      while (s > 0 && i < lo[slot][s]) --s;
+      while (s < S - 1 && i >= lo[slot][s + 1]) ++s;
+      const int32_t rank = t - count_upto(lo[slot][s], j, p);
+      const bool last = i + p >= lo[slot][s + 1];
+      code[base + off[s][slot] + rank] = c | ((uint32_t)slot << kSweepColBits) | (last ? 0x80000000u : 0u);
+      vals[base + off[s][slot] + rank] = val[beg + i];
+    }
+  }
+}
+
+// compacted CSR of the short rows: copy entries
+__global__ __launch_bounds__(256) void sweep_short_copy_kernel(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+    const float* __restrict__ val, const int32_t* __restrict__ rowptr_s,
+    const int32_t* __restrict__ rowmap_s, int64_t rows_s, int32_t* __restrict__ colidx_s,
+    float* __restrict__ val_s) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows_s) return;
+  const int32_t r = rowmap_s[i];
+  const int32_t b = rowptr[r], n = rowptr[r + 1] - b, o = rowptr_s[i];
+  for (int32_t t = 0; t < n; ++t) {
+    colidx_s[o + t] = colidx[b + t];
+    val_s[o + t] = val[b + t];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// product kernel
+struct SweepDims {
+  int64_t n_waves, ldb, ldc, f_total;
+  uint64_t generation;
+  uint32_t b_bytes;     // bytes addressable from B + col0 (buffer-load variant)
+  uint32_t row_bytes;   // ldb * 4
+  int32_t col0, accumulate;
+};
+
+template <int FPL, int U, bool BUF>
+__global__ __launch_bounds__(256) void spmm_sweep_kernel(
+    const uint32_t* __restrict__ code, const float* __restrict__ vals,
+    const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
+    const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ partial, const SweepDims d) {
+  using vec = typename Vec<FPL>::T;
+  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][16 slots][64*FPL]
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t loff = lane * (FPL * 4);
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+  if (w >= d.n_waves) return;
+  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves) return;
+  constexpr int kRow = 64 * FPL;  // floats per accumulator row
+  float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lane * FPL;
+#pragma unroll
+  for (int s = 0; s < kSweepSlots; ++s) *reinterpret_cast<vec*>(my + s * kRow) = vec(0.f);
+
+  const int32_t base = wave_base[w];
+  const int32_t len = wave_base[w + 1] - base;  // a multiple of U (padded when built)
+  const uint32_t* __restrict__ cw = code + base;
+  const float* __restrict__ vw = vals + base;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
+
+  vec acc = 0.f;
+  for (int32_t e = 0; e < len; e += U) {
+    uint32_t c[U];
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      c[u] = cw[e + u];
+      v[u] = vw[e + u];
+    }
+    vec h[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) h[u] = load_row<FPL, BUF>(rs, B, c[u] & kColMask, loff, d.row_bytes, d.ldb);
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc += v[u] * h[u];
+      if (c[u] >> 31) {   // last entry of a (piece, slab) segment: fold into the piece's LDS row
+        vec* p = reinterpret_cast<vec*>(my + ((c[u] >> kSweepColBits) & (kSweepSlots - 1)) * kRow);
+        *p += acc;
+        acc = 0.f;
+      }
+    }
+  }
+
+#pragma unroll 1
+  for (int s = 0; s < kSweepSlots; ++s) {
+    const int32_t tgt = piece_target[w * kSweepSlots + s];
+    if (tgt == INT32_MIN) continue;
+    vec r = *reinterpret_cast<const vec*>(my + s * kRow);
+    if (tgt >= 0) {
+      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)tgt * d.ldc) + loff);
+      if (d.accumulate) r += *p;
+      *p = r;
+    } else {
+      const int64_t pi = -(int64_t)tgt - 1;
+      *reinterpret_cast<vec*>(reinterpret_cast<char*>(partial + pi * d.f_total + d.col0) + loff) = r;
+    }
+  }
+}
+
+// rows cut into several pieces: C[row] (+)= sum of the pieces' partial rows, fixed order
+__global__ __launch_bounds__(256) void sweep_combine_kernel(
+    const int32_t* __restrict__ multi_row, const int32_t* __restrict__ multi_first,
+    const float* __restrict__ partial, const SpmmWsHeader* __restrict__ hdr, uint64_t generation,
+    int64_t n_multi, float* __restrict__ C, int64_t ldc, int32_t f_total, int32_t accumulate) {
+  const int lane = threadIdx.x & 63;
+  const int64_t q = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+  if (q >= n_multi) return;
+  if (hdr->magic != kSpmmMagic || hdr->generation != generation) return;
+  const int32_t row = multi_row[q];
+  const int32_t a = multi_first[q], b = multi_first[q + 1];
+  for (int c4 = lane; c4 * 4 < f_total; c4 += 64) {
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
+    int32_t j = a;
+    for (; j + 2 <= b; j += 2) {
+      const float4 t0 = *reinterpret_cast<const float4*>(partial + (int64_t)j * f_total + c4 * 4);
+      const float4 t1 = *reinterpret_cast<const float4*>(partial + (int64_t)(j + 1) * f_total + c4 * 4);
+      s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
+      s1.x += t1.x; s1.y += t1.y; s1.z += t1.z; s1.w += t1.w;
+    }
+    if (j < b) {
+      const float4 t0 = *reinterpret_cast<const float4*>(partial + (int64_t)j * f_total + c4 * 4);
+      s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
+    }
+    float4* p = reinterpret_cast<float4*>(C + (int64_t)row * ldc + c4 * 4);
+    float4 o = accumulate ? *p : make_float4(0.f, 0.f, 0.f, 0.f);
+    o.x += s0.x + s1.x; o.y += s0.y + s1.y; o.z += s0.z + s1.z; o.w += s0.w + s1.w;
+    *p = o;
+  }
+}
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : dflt;
+}
+
+struct Piece {
+  int32_t size, row, j, p;
+};
+
+std::atomic<uint64_t> g_generation{1};
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+// host side of the preparation: classify rows, cut long rows into pieces, deal pieces to
+// wavefronts (sorted by size, snake order: every wavefront gets one piece per round, so the
+// streams have nearly equal lengths), build the compacted short-row CSR.
+int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
+                  int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
+                  hipStream_t s, SweepPlanResult* out) {
+  out->use_sweep = false;
+  const int force = env_int("SAGNN_SWEEP", -1);  // 0: never, 1: whenever possible, -1: heuristic
+  if (force == 0 || nnz < 4096 || k <= 0 || k >= (1ll << kSweepColBits) || m <= 0) return SAGNN_OK;
+  const int64_t b_bytes = k * (int64_t)f * 4;
+  if (force != 1 && (nnz < (1 << 20) || b_bytes <= (8ll << 20))) return SAGNN_OK;
+
+  std::vector<int32_t> rp((size_t)m + 1);
+  SAGNN_HIP(hipMemcpyAsync(rp.data(), d_rowptr, sizeof(int32_t) * (size_t)(m + 1),
+                           hipMemcpyDeviceToHost, s));
+  SAGNN_HIP(hipStreamSynchronize(s));
+  if (rp[0] != 0 || rp[m] != nnz) return SAGNN_OK;  // inconsistent: keep the plain schedule
+
+  int min_long = env_int("SAGNN_SWEEP_MINDEG", 32);
+  if (min_long < kSweepMinLong) min_long = kSweepMinLong;
+  int piece_max = env_int("SAGNN_SWEEP_PIECE", 4096);
+  if (piece_max < 1024) piece_max = 1024;
+  if (piece_max > 32768) piece_max = 32768;
+  const int64_t slab_bytes = (int64_t)env_int("SAGNN_SWEEP_SLAB_MB", 16) << 20;
+  int64_t S = slab_bytes >= (1 << 16) ? 8 * ceil_div(b_bytes, 8 * slab_bytes) : kSweepMaxSlabs;
+  if (S < 8) S = 8;
+  if (S > kSweepMaxSlabs) S = kSweepMaxSlabs;
+  const int64_t width = ceil_div(k, S);
+
+  std::vector<Piece> pieces;
+  int64_t long_entries = 0, short_rows = 0, short_entries = 0;
+  bool has_empty = false;
+  for (int64_t r = 0; r < m; ++r) {
+    const int64_t d = (int64_t)rp[r + 1] - rp[r];
+    if (d < 0) return SAGNN_OK;
+    if (d == 0) { has_empty = true; continue; }
+    if (d >= min_long) {
+      const int32_t p = (int32_t)ceil_div(d, piece_max);
+      if (p > 0x7FFF) return SAGNN_OK;
+      for (int32_t j = 0; j < p; ++j)
+        pieces.push_back({(int32_t)((d - j + p - 1) / p), (int32_t)r, j, p});
+      long_entries += d;
+    } else {
+      ++short_rows;
+      short_entries += d;
+    }
+  }
+  if (force != 1 && long_entries * 10 < nnz * 3) return SAGNN_OK;   // < 30 % of the entries
+  if (pieces.empty() || (int64_t)pieces.size() > L.max_pieces) return SAGNN_OK;
+
+  std::sort(pieces.begin(), pieces.end(), [](const Piece& a, const Piece& b) {
+    if (a.size != b.size) return a.size > b.size;
+    if (a.row != b.row) return a.row < b.row;
+    return a.j < b.j;
+  });
+  const int64_t P = (int64_t)pieces.size();
+  const int64_t NW = ceil_div(P, kSweepSlots);
+  std::vector<int32_t> info((size_t)NW * kSweepSlots * 2, -1), target((size_t)NW * kSweepSlots, INT32_MIN);
+  std::vector<int64_t> wsize((size_t)NW, 0);
+  // multi-piece rows: partial slots in row order
+  std::vector<int32_t> multi_row, multi_first;
+  {
+    std::vector<std::pair<int32_t, int32_t>> mr;  // (row, p)
+    for (const Piece& pc : pieces)
+      if (pc.p > 1 && pc.j == 0) mr.push_back({pc.row, pc.p});
+    std::sort(mr.begin(), mr.end());
+    multi_first.push_back(0);
+    for (auto& e : mr) {
+      multi_row.push_back(e.first);
+      multi_first.push_back(multi_first.back() + e.second);
+    }
+  }
+  if ((int64_t)multi_row.size() > L.max_multi_rows || (int64_t)multi_first.back() > L.max_multi_pieces)
+    return SAGNN_OK;
+  for (int64_t t = 0; t < P; ++t) {
+    const int64_t round = t / NW, pos = t % NW;
+    const int64_t wv = (round & 1) ? NW - 1 - pos : pos;
+    const size_t g = (size_t)(wv * kSweepSlots + round);
+    const Piece& pc = pieces[(size_t)t];
+    info[2 * g] = pc.row;
+    info[2 * g + 1] = (pc.j << 16) | pc.p;
+    wsize[(size_t)wv] += pc.size;
+    if (pc.p == 1) {
+      target[g] = pc.row;
+    } else {
+      const size_t q = (size_t)(std::lower_bound(multi_row.begin(), multi_row.end(), pc.row) - multi_row.begin());
+      target[g] = -(multi_first[q] + pc.j) - 1;
+    }
+  }
+  // every stream is padded to a multiple of the kernel's batch (8 entries)
+  std::vector<int32_t> wbase((size_t)NW + 1);
+  int64_t run = 0, unpadded = 0;
+  for (int64_t wv = 0; wv < NW; ++wv) {
+    wbase[(size_t)wv] = (int32_t)run;
+    run += (wsize[(size_t)wv] + 7) / 8 * 8;
+    unpadded += wsize[(size_t)wv];
+  }
+  wbase[(size_t)NW] = (int32_t)run;
+  if (unpadded != long_entries) return SAGNN_EINVAL;
+  const int64_t stream_len = run;
+  const int64_t short_base = round_up((size_t)stream_len + 64, 256);
+  if (short_base + short_entries + kSpmmChunk > L.stream_cap) return SAGNN_OK;
+
+  // short-row CSR
+  std::vector<int32_t> rps((size_t)short_rows + 1), rmap((size_t)short_rows + 1);
+  {
+    int64_t i = 0, acc = 0;
+    for (int64_t r = 0; r < m; ++r) {
+      const int64_t d = (int64_t)rp[r + 1] - rp[r];
+      if (d > 0 && d < min_long) { rps[(size_t)i] = (int32_t)acc; rmap[(size_t)i] = (int32_t)r; acc += d; ++i; }
+    }
+    rps[(size_t)short_rows] = (int32_t)acc;
+  }
+
+  auto up = [&](size_t off, const void* src, size_t bytes) {
+    return bytes ? hipMemcpyAsync(ws + off, src, bytes, hipMemcpyHostToDevice, s) : hipSuccess;
+  };
+  SAGNN_HIP(up(L.piece_info, info.data(), info.size() * 4));
+  SAGNN_HIP(up(L.piece_target, target.data(), target.size() * 4));
+  SAGNN_HIP(up(L.wave_base, wbase.data(), wbase.size() * 4));
+  SAGNN_HIP(up(L.multi_row, multi_row.data(), multi_row.size() * 4));
+  SAGNN_HIP(up(L.multi_first, multi_first.data(), multi_first.size() * 4));
+  SAGNN_HIP(up(L.rowptr_s, rps.data(), rps.size() * 4));
+  SAGNN_HIP(up(L.rowmap_s, rmap.data(), rmap.size() * 4));
+
+  // long rows must be column-sorted for the slab segmentation
+  int32_t* d_flag = reinterpret_cast<int32_t*>(ws + L.carry);  // scratch until the first product
+  SAGNN_HIP(hipMemsetAsync(d_flag, 0, 4, s));
+  hipLaunchKernelGGL(sweep_check_sorted_kernel, dim3((unsigned)ceil_div(NW * kSweepSlots, 4)), dim3(256),
+                     0, s, d_rowptr, d_colidx, reinterpret_cast<const int32_t*>(ws + L.piece_info),
+                     NW * kSweepSlots, (uint32_t)(k - 1), d_flag);
+  SAGNN_LAUNCH_CHECK();
+  int32_t unsorted = 0;
+  SAGNN_HIP(hipMemcpyAsync(&unsorted, d_flag, 4, hipMemcpyDeviceToHost, s));
+  SAGNN_HIP(hipStreamSynchronize(s));
+  if (unsorted) return SAGNN_OK;
+
+  const uint32_t kmax = (uint32_t)(k - 1);
+  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW), dim3(kBuildThreads), 0, s, d_rowptr, d_colidx,
+                     d_val, reinterpret_cast<const int32_t*>(ws + L.piece_info),
+                     reinterpret_cast<const int32_t*>(ws + L.wave_base), (int32_t)S, (int32_t)width, kmax,
+                     reinterpret_cast<uint32_t*>(ws + L.code), reinterpret_cast<float*>(ws + L.vals));
+  SAGNN_LAUNCH_CHECK();
+  // zero the gap between the long stream and the short entries (tail batches read into it)
+  SAGNN_HIP(hipMemsetAsync(ws + L.code + 4 * (size_t)stream_len, 0, 4 * (size_t)(short_base - stream_len), s));
+  SAGNN_HIP(hipMemsetAsync(ws + L.vals + 4 * (size_t)stream_len, 0, 4 * (size_t)(short_base - stream_len), s));
+  if (short_rows > 0) {
+    hipLaunchKernelGGL(sweep_short_copy_kernel, dim3((unsigned)ceil_div(short_rows, 256)), dim3(256), 0, s,
+                       d_rowptr, d_colidx, d_val, reinterpret_cast<const int32_t*>(ws + L.rowptr_s),
+                       reinterpret_cast<const int32_t*>(ws + L.rowmap_s), short_rows,
+                       reinterpret_cast<int32_t*>(ws + L.code) + short_base,
+                       reinterpret_cast<float*>(ws + L.vals) + short_base);
+    SAGNN_LAUNCH_CHECK();
+  }
+  SAGNN_HIP(hipStreamSynchronize(s));  // host vectors are read by the copies above
+
+  SpmmWsHeader& h = out->hdr;
+  h = SpmmWsHeader{};
+  h.magic = kSpmmMagic;
+  h.has_empty_rows = has_empty ? 1 : 0;
+  h.m = m; h.nnz = nnz; h.f = f; h.mode = 1;
+  h.generation = g_generation.fetch_add(1);
+  h.c_rows = short_rows; h.c_nnz = short_entries; h.c_nchunks = spmm_nchunks(short_entries);
+  h.n_waves = NW; h.n_long_entries = stream_len;   // padded length of the sweep streams
+  h.n_multi_rows = (int64_t)multi_row.size(); h.n_multi_pieces = multi_first.back();
+  h.n_slabs = (int32_t)S; h.slab_width = (int32_t)width;
+  out->use_sweep = true;
+  return SAGNN_OK;
+}
+
+uint64_t spmm_next_generation() { return g_generation.fetch_add(1); }
+
+int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
+                 int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
+                 int32_t accumulate, int32_t f_total, hipStream_t s) {
+  if (d.n_waves <= 0) return SAGNN_OK;
+  SweepDims sd{};
+  sd.n_waves = d.n_waves; sd.ldb = ldb; sd.ldc = ldc; sd.f_total = f_total;
+  sd.generation = d.generation; sd.col0 = col0; sd.accumulate = accumulate;
+  // bytes of B reachable from B + col0: rows 0..kmax, fw columns each (columns were clamped to
+  // kmax when the stream was built)
+  sd.b_bytes = 0;
+  const bool buf = buffer_addressable(kmax, ldb, fw, &sd.b_bytes);
+  sd.row_bytes = (uint32_t)(ldb * 4);
+  const unsigned blocks = (unsigned)ceil_div(d.n_waves, 4);
+  const size_t lds = (size_t)4 * kSweepSlots * fw * sizeof(float);
+  auto go = [&](auto kern) -> int {
+    if (lds > 48 * 1024)
+      SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s,
+                       reinterpret_cast<const uint32_t*>(ws + L.code),
+                       reinterpret_cast<const float*>(ws + L.vals),
+                       reinterpret_cast<const int32_t*>(ws + L.wave_base),
+                       reinterpret_cast<const int32_t*>(ws + L.piece_target),
+                       reinterpret_cast<const SpmmWsHeader*>(ws + L.header), B + col0, C + col0,
+                       reinterpret_cast<float*>(ws + L.partial), sd);
+    SAGNN_LAUNCH_CHECK();
+    return SAGNN_OK;
+  };
+  if (fw == 256) return buf ? go(spmm_sweep_kernel<4, 8, true>) : go(spmm_sweep_kernel<4, 8, false>);
+  if (fw == 128) return buf ? go(spmm_sweep_kernel<2, 8, true>) : go(spmm_sweep_kernel<2, 8, false>);
+  if (fw == 64) return buf ? go(spmm_sweep_kernel<1, 8, true>) : go(spmm_sweep_kernel<1, 8, false>);
+  return SAGNN_EINVAL;
+}
+
+int sweep_combine(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, float* C, int64_t ldc,
+                  int32_t f_total, int32_t accumulate, hipStream_t s) {
+  if (d.n_multi_rows <= 0) return SAGNN_OK;
+  hipLaunchKernelGGL(sweep_combine_kernel, dim3((unsigned)ceil_div(d.n_multi_rows, 4)), dim3(256), 0, s,
+                     reinterpret_cast<const int32_t*>(ws + L.multi_row),
+                     reinterpret_cast<const int32_t*>(ws + L.multi_first),
+                     reinterpret_cast<const float*>(ws + L.partial),
+                     reinterpret_cast<const SpmmWsHeader*>(ws + L.header), d.generation, d.n_multi_rows,
+                     C, ldc, f_total, accumulate);
+  SAGNN_LAUNCH_CHECK();
+  return SAGNN_OK;
+}
+
+}  // namespace sagnn

@@ -74,7 +74,7 @@ def test_cfg2_full_path():
     Hd = dev(H)
     Hn = sagnn.spmm_pack_rows(Hd, plan.needed)
     assert torch.equal(Hn, Hd)                             # needed = all rows, ascending
-    ws = sagnn.spmm_csr_prepare(rp, g.nnz, f)
+    ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, v, plan.N, f)
     T, Z, Ho = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, dev(W), act=sagnn.ACT_RELU, ws=ws)
     torch.cuda.synchronize()
     rows = pick_rows(g, 1500, 2)
@@ -83,7 +83,7 @@ def test_cfg2_full_path():
     sel = torch.from_numpy(rows).cuda()
     assert_close(Z[sel], zref, zabs, RTOL_GEMM, "cfg2 Z")
     assert_close(Ho[sel], np.maximum(zref, 0), zabs, RTOL_GEMM, "cfg2 H'")
-    check_eigenvector(g, f, ws, rp, ci, v)
+    check_eigenvector(g, f, ws, rp, plan.colidx_compact, v)
 
 
 # ------------------------------------------------------------------------------------------ cfg3
@@ -96,12 +96,12 @@ def test_cfg3_width_sweep():
     rows = pick_rows(g, 1500, 3)
     for f in (16, 64, 128, 256):
         H = np.ascontiguousarray(wl.H[:, :f])
-        ws = sagnn.spmm_csr_prepare(rp, g.nnz, f)
+        ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, v, plan.N, f)
         Hn = sagnn.spmm_pack_rows(dev(H), plan.needed)
         Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
         torch.cuda.synchronize()
         check_spmm_rows(g, Z, H, rows, f"cfg3 f={f}")
-        check_eigenvector(g, f, ws, rp, ci, v)
+        check_eigenvector(g, f, ws, rp, plan.colidx_compact, v)
         del Hn, Z, ws
 
 
@@ -129,7 +129,7 @@ def test_cfg4_rank_share():
     assert Hn[torch.from_numpy(pos).cuda()].cpu().numpy().tobytes() == ref.tobytes()
     # local SpMM on the packed buffer; oracle on sampled rows with their own tiny packed buffer
     rp, ci, v = csr_dev(g)
-    ws = sagnn.spmm_csr_prepare(rp, g.nnz, f)
+    ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, v, N, f)
     Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
     torch.cuda.synchronize()
     rows = pick_rows(g, 1500, 4)
@@ -160,7 +160,7 @@ def test_cfg5_reordering_and_two_layer_training_step():
         torch.cuda.synchronize()
         assert Hn.cpu().numpy().tobytes() == oracle.pack_rows(wl.H, needed).tobytes()
         rp, ci, v = csr_dev(gb)
-        ws = sagnn.spmm_csr_prepare(rp, gb.nnz, f)
+        ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, v, plan.N, f)
         Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
         torch.cuda.synchronize()
         rows = pick_rows(gb, 800, 5)
@@ -178,7 +178,7 @@ def test_cfg5_reordering_and_two_layer_training_step():
     wl = after
     g, W1, W2, G2 = wl.g, wl.W, wl.extra["W2"], wl.extra["G2"]
     rp, ci, v = csr_dev(g)
-    ws = sagnn.spmm_csr_prepare(rp, g.nnz, f)
+    ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f)
     rows = pick_rows(g, 600, 6)
     sel = torch.from_numpy(rows).cuda()
     H0d, W1d, W2d = dev(wl.H), dev(W1), dev(W2)

@@ -138,9 +138,11 @@ def test_plan_empty_matrix_and_capacity_and_validate():
 
 # ------------------------------------------------------------------------------------ SpMM
 
-def run_spmm(rowptr, colidx, val, B, use_ws, C0=None):
+def run_spmm(rowptr, colidx, val, B, use_ws, C0=None, expect_mode=None):
     rp, ci, v = dev(rowptr), dev(colidx), dev(val)
-    ws = sagnn.spmm_csr_prepare(rp, colidx.size, B.shape[1]) if use_ws else None
+    ws = sagnn.spmm_csr_prepare(rp, ci, v, B.shape[0], B.shape[1]) if use_ws else None
+    if expect_mode is not None:
+        assert ws.info()["mode"] == expect_mode, ws.info()
     C = None if C0 is None else dev(C0)
     out = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), C=C, accumulate=C0 is not None, ws=ws)
     torch.cuda.synchronize()
@@ -162,6 +164,60 @@ def test_spmm_random_widths(f, use_ws):
     ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
     got2 = run_spmm(rowptr, colidx, val, B, use_ws, C0=C0)
     assert_close(got2, ref2, zabs2, RTOL_SPMM, f"spmm accumulate f={f} ws={use_ws}")
+
+
+@pytest.fixture
+def force_sweep(monkeypatch):
+    """Force the slab-sweep schedule on small matrices (the heuristic reserves it for big ones)
+    with tiny pieces and many slabs, so that split rows, staggered starts and the short-row
+    path are all exercised."""
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
+    monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+    monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "0")
+
+
+@pytest.mark.parametrize("f", [64, 128, 192, 256, 320])
+def test_spmm_slab_sweep_schedule(f, force_sweep):
+    rng = np.random.default_rng(100 + f)
+    m, n = 5003, 40_000
+    rowptr, colidx, val = random_csr(m, n, 20, rng, empty_frac=0.1,
+                                     hubs=[(3, 9000), (7, 3000), (2500, 1024), (2501, 1025), (5002, 17), (11, 16)])
+    B = synth.normal((n, f), f, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    got = run_spmm(rowptr, colidx, val, B, True, expect_mode=1)
+    assert_close(got, ref, zabs, RTOL_SPMM, f"sweep f={f}")
+    got_again = run_spmm(rowptr, colidx, val, B, True)
+    assert torch.equal(got, got_again)                       # reproducible across preparations
+    C0 = synth.normal((m, f), f + 1, synth.STREAM_G)
+    ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
+    got2 = run_spmm(rowptr, colidx, val, B, True, C0=C0)
+    assert_close(got2, ref2, zabs2, RTOL_SPMM, f"sweep accumulate f={f}")
+
+
+def test_spmm_slab_sweep_falls_back_on_unsorted_rows(force_sweep):
+    rng = np.random.default_rng(5)
+    m, n, f = 2000, 30_000, 128
+    rowptr, colidx, val = random_csr(m, n, 40, rng, hubs=[(5, 5000)], dup=True)   # unsorted rows
+    B = synth.normal((n, f), 1, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    assert_close(run_spmm(rowptr, colidx, val, B, True, expect_mode=0), ref, zabs, RTOL_SPMM, "unsorted fallback")
+    bad = colidx.copy()
+    rowptr2, colidx2, val2 = random_csr(m, n, 40, rng, hubs=[(5, 5000)])
+    colidx2[rowptr2[5] + 4999] = n + 7                        # out-of-range column in a long row
+    ref, zabs = oracle.spmm(rowptr2, np.minimum(colidx2, n - 1), val2, B, want_abs=True)
+    assert_close(run_spmm(rowptr2, colidx2, val2, B, True, expect_mode=0), ref, zabs, RTOL_SPMM, "clamped column")
+    _ = bad
+
+
+def test_spmm_rmat_with_and_without_sweep(monkeypatch):
+    g = synth.rmat_graph(60_000, 4_000_000, 9)
+    H = synth.normal((g.n, 128), 9, synth.STREAM_H)
+    ref, zabs = oracle.spmm(g.rowptr, g.colidx, g.val, H, want_abs=True)
+    for mode in ("0", "1"):
+        monkeypatch.setenv("SAGNN_SWEEP", mode)
+        got = run_spmm(g.rowptr, g.colidx, g.val, H, True, expect_mode=int(mode))
+        assert_close(got, ref, zabs, RTOL_SPMM, f"rmat sweep={mode}")
 
 
 @pytest.mark.parametrize("case", ["all_empty", "single_entry", "one_long_row", "exact_chunk", "tail_empty"])
@@ -186,9 +242,10 @@ def test_spmm_degenerate(case):
     for use_ws in (True, False):
         got = torch.full((rowptr.size - 1, f), 7.0, device="cuda")     # stale contents must be overwritten
         rp = dev(rowptr)
-        ws = sagnn.spmm_csr_prepare(rp, colidx.size, f) if use_ws else None
-        sagnn.spmm_csr_tallskinny(rp, dev(colidx) if colidx.size else torch.empty(0, dtype=torch.int32, device="cuda"),
-                                  dev(val) if val.size else torch.empty(0, device="cuda"), dev(B), C=got, ws=ws)
+        ci = dev(colidx) if colidx.size else torch.empty(0, dtype=torch.int32, device="cuda")
+        va = dev(val) if val.size else torch.empty(0, device="cuda")
+        ws = sagnn.spmm_csr_prepare(rp, ci, va, n, f) if use_ws else None
+        sagnn.spmm_csr_tallskinny(rp, ci, va, dev(B), C=got, ws=ws)
         torch.cuda.synchronize()
         assert_close(got, ref, zabs, RTOL_SPMM, f"{case} ws={use_ws}")
 
@@ -216,7 +273,7 @@ def test_spmm_cfg1_blocks_through_packed_buffer(cfg1):
         rp, ci, v = csr_dev(blk)
         plan = sagnn.spmm_plan_needed_rows(rp, ci, g.n, off)
         Hn = sagnn.spmm_pack_rows(Hd, plan.needed)
-        ws = sagnn.spmm_csr_prepare(rp, blk.nnz, 16)
+        ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, v, plan.N, 16)
         Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
         torch.cuda.synchronize()
         ref, zabs = oracle.spmm(blk.rowptr, blk.colidx, blk.val, H, want_abs=True)
@@ -230,12 +287,13 @@ def test_spmm_cfg1_blocks_through_packed_buffer(cfg1):
             rpq = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
             ciq = (comp[keep] - plan.blk_off[q]).astype(np.int32)
             Hq = Hn[int(plan.blk_off[q]):int(plan.blk_off[q + 1])].contiguous()
-            wsq = sagnn.spmm_csr_prepare(dev(rpq), int(rpq[-1]), 16)
-            sagnn.spmm_csr_tallskinny(dev(rpq), dev(ciq), dev(blk.val[keep]), Hq, C=Zacc, accumulate=True, ws=wsq)
+            drp, dci, dva = dev(rpq), dev(ciq), dev(blk.val[keep])
+            wsq = sagnn.spmm_csr_prepare(drp, dci, dva, Hq.shape[0], 16)
+            sagnn.spmm_csr_tallskinny(drp, dci, dva, Hq, C=Zacc, accumulate=True, ws=wsq)
         torch.cuda.synchronize()
         assert_close(Zacc, ref, zabs, RTOL_SPMM, f"cfg1 block {i} accumulated")
     rp, ci, v = csr_dev(g)
-    ws = sagnn.spmm_csr_prepare(rp, g.nnz, 16)
+    ws = sagnn.spmm_csr_prepare(rp, ci, v, g.n, 16)
     Z = sagnn.spmm_csr_tallskinny(rp, ci, v, Hd, ws=ws)
     ref, zabs = oracle.spmm(g.rowptr, g.colidx, g.val, H, want_abs=True)
     assert_close(Z, ref, zabs, RTOL_SPMM, "cfg1 whole")
@@ -296,8 +354,8 @@ def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     W = synth.normal((fin, fout), 1, synth.STREAM_W, scale=1 / np.sqrt(fin))
     G = synth.normal((g.n, fout), 1, synth.STREAM_G)
     rp, ci, v = csr_dev(g)
-    ws_in = sagnn.spmm_csr_prepare(rp, g.nnz, fin)
-    ws_out = sagnn.spmm_csr_prepare(rp, g.nnz, fout)
+    ws_in = sagnn.spmm_csr_prepare(rp, ci, v, g.n, fin)
+    ws_out = sagnn.spmm_csr_prepare(rp, ci, v, g.n, fout)
     rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
     o = oracle.gcn_layer_fwd(g.rowptr, g.colidx, g.val, H, W, act=1, bf16=bool(prec))
     T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws_in)
