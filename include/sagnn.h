@@ -168,7 +168,8 @@ int spmm_csr_tallskinny(const int32_t* d_rowptr, const int32_t* d_colidx, const 
  *   d_act (may be NULL) receives ReLU(product) when act = SAGNN_ACT_RELU, else the product
  *   d_mask (may be NULL, m x nout, ldmask): the product is zeroed where d_mask <= 0
  *         (the ".* sigma'(Z)" factor of the backward equation) before it is stored
- * kdim and nout: multiples of 32, at most 256 (W stays resident in LDS).
+ * kdim and nout: multiples of 4, at most 256 (W stays resident in LDS; the matrix-core tiles
+ * are zero-padded to multiples of 32).
  */
 int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw, int32_t transW,
                    int64_t m, int32_t kdim, int32_t nout, int32_t prec, int32_t act,

@@ -61,7 +61,7 @@ SAGNN_EXPORT int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx,
 
 SAGNN_EXPORT int gcn_bwd_workspace_bytes(int64_t m, int32_t f_in, int32_t f_out, size_t* bytes) {
   using namespace sagnn;
-  if (!bytes || m < 0 || f_in <= 0 || f_out <= 0 || (f_in & 31) || (f_out & 31) || f_in > 256 ||
+  if (!bytes || m < 0 || f_in <= 0 || f_out <= 0 || (f_in & 3) || (f_out & 3) || f_in > 256 ||
       f_out > 256)
     return SAGNN_EINVAL;
   *bytes = gemm_tn_ws_bytes(m, f_in, f_out);

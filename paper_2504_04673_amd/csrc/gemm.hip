@@ -49,14 +49,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int NB = NT * 32;
   const int tid = threadIdx.x;
-  const int kdim = g.kdim;
+  const int kreal = g.kdim;                  // any multiple of 4
+  const int kdim = (kreal + 31) & ~31;       // the k loop runs over the zero-padded extent
 
-  // stage the W slab: fp32 as Ws[k][n]; bf16 packed as Ws[k/8][n][k%8]
+  // stage the W slab: fp32 as Ws[k][n]; bf16 packed as Ws[k/8][n][k%8]; zero outside W
   for (int idx = tid; idx < kdim * NB; idx += WAVES * 64) {
     const int k = idx / NB, n = idx - k * NB;
     const int col = g.n0 + n;
     float w = 0.f;
-    if (col < g.nout) w = g.transW ? g.W[(int64_t)col * g.ldw + k] : g.W[(int64_t)k * g.ldw + col];
+    if (col < g.nout && k < kreal)
+      w = g.transW ? g.W[(int64_t)col * g.ldw + k] : g.W[(int64_t)k * g.ldw + col];
     if (BF16)
       reinterpret_cast<__bf16*>(smem)[((k >> 3) * NB + n) * 8 + (k & 7)] = (__bf16)w;
     else
@@ -71,6 +73,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
     int64_t row = t * 32 + r;
     if (row >= g.m) row = g.m - 1;  // clamped read, result discarded at the store
     const float* __restrict__ xrow = g.X + row * g.ldx;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto ldx4 = [&](int col) {   // X[row][col..col+3], zero beyond the real k extent
+      return col < kreal ? *reinterpret_cast<const float4*>(xrow + col) : zero4;
+    };
     floatx16 acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -86,15 +92,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
       float4 cur[JB][2], nxt[JB][2];
 #pragma unroll
       for (int q = 0; q < JB; ++q) {
-        cur[q][0] = *reinterpret_cast<const float4*>(xrow + 16 * q + 8 * h);
-        cur[q][1] = *reinterpret_cast<const float4*>(xrow + 16 * q + 8 * h + 4);
+        cur[q][0] = ldx4(16 * q + 8 * h);
+        cur[q][1] = ldx4(16 * q + 8 * h + 4);
       }
       for (int gi = 0; gi < ngroups; ++gi) {
         if (gi + 1 < ngroups) {
 #pragma unroll
           for (int q = 0; q < JB; ++q) {
-            nxt[q][0] = *reinterpret_cast<const float4*>(xrow + 16 * ((gi + 1) * JB + q) + 8 * h);
-            nxt[q][1] = *reinterpret_cast<const float4*>(xrow + 16 * ((gi + 1) * JB + q) + 8 * h + 4);
+            nxt[q][0] = ldx4(16 * ((gi + 1) * JB + q) + 8 * h);
+            nxt[q][1] = ldx4(16 * ((gi + 1) * JB + q) + 8 * h + 4);
           }
         }
 #pragma unroll
@@ -122,12 +128,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
       const int ngroups = kdim / (8 * JB);
       float4 cur[JB], nxt[JB];
 #pragma unroll
-      for (int q = 0; q < JB; ++q) cur[q] = *reinterpret_cast<const float4*>(xrow + 8 * q + 4 * h);
+      for (int q = 0; q < JB; ++q) cur[q] = ldx4(8 * q + 4 * h);
       for (int gi = 0; gi < ngroups; ++gi) {
         if (gi + 1 < ngroups) {
 #pragma unroll
           for (int q = 0; q < JB; ++q)
-            nxt[q] = *reinterpret_cast<const float4*>(xrow + 8 * ((gi + 1) * JB + q) + 4 * h);
+            nxt[q] = ldx4(8 * ((gi + 1) * JB + q) + 4 * h);
         }
 #pragma unroll
         for (int q = 0; q < JB; ++q) {
@@ -167,7 +173,7 @@ template <int NT, bool BF16>
 int launch_nn(const GemmArgs& g, hipStream_t s) {
   constexpr int WAVES = BF16 ? 8 : 4;
   auto kern = gemm_nn_kernel<NT, BF16, WAVES>;
-  const size_t lds = (size_t)g.kdim * NT * 32 * (BF16 ? 2 : 4);
+  const size_t lds = (size_t)((g.kdim + 31) & ~31) * NT * 32 * (BF16 ? 2 : 4);
   if (lds > 160 * 1024) return SAGNN_EINVAL;
   SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -200,11 +206,17 @@ __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
   using lds_t = typename std::conditional<BF16, __bf16, float>::type;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   lds_t* Xs = reinterpret_cast<lds_t*>(smem);                    // [fi][KP]
-  lds_t* Ss = Xs + (size_t)g.fi * KP;                            // [fo][KP]
+  lds_t* Ss = Xs + (size_t)((g.fi + 31) / 32) * 32 * KP;         // [fo][KP], after the padded X part
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i = lane & 31, h = lane >> 5;
   const int wa = wave >> 1, wb = wave & 1;  // wave tile: a-tiles {2wa,2wa+1}, b-tiles {4wb..4wb+3}
-  const int TA = g.fi / 32, TB = g.fo / 32;
+  const int TA = (g.fi + 31) / 32, TB = (g.fo + 31) / 32;
+  // columns of the last tile that lie beyond fi / fo are never staged: keep them zero
+  for (int idx = tid; idx < (TA + TB) * 32 * KP; idx += kTnThreads) {
+    if (idx < TA * 32 * KP) Xs[idx] = (lds_t)0.f;
+    else (Xs + (size_t)TA * 32 * KP)[idx - TA * 32 * KP] = (lds_t)0.f;
+  }
+  __syncthreads();
 
   const int64_t r_begin = (int64_t)blockIdx.x * g.rows_per_wg;
   int64_t r_end = r_begin + g.rows_per_wg;
@@ -321,7 +333,7 @@ __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int ro = ta * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-        P[(int64_t)ro * g.fo + tb * 32 + i] = acc[a][b][v];
+        if (ro < g.fi && tb * 32 + i < g.fo) P[(int64_t)ro * g.fo + tb * 32 + i] = acc[a][b][v];
       }
     }
 }
@@ -359,7 +371,7 @@ size_t gemm_tn_ws_bytes(int64_t m, int32_t fi, int32_t fo) {
 int launch_gemm_tn(const float* X, int64_t ldx, const float* S, int64_t lds_, int64_t m,
                    int32_t fi, int32_t fo, int32_t prec, float* Y, void* yws, size_t yws_bytes,
                    hipStream_t s) {
-  if (m < 0 || fi <= 0 || fo <= 0 || (fi & 31) || (fo & 31) || fi > 256 || fo > 256 ||
+  if (m < 0 || fi <= 0 || fo <= 0 || (fi & 3) || (fo & 3) || fi > 256 || fo > 256 ||
       ldx < fi || lds_ < fo || (ldx & 3) || (lds_ & 3))
     return SAGNN_EINVAL;
   if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
@@ -372,7 +384,7 @@ int launch_gemm_tn(const float* X, int64_t ldx, const float* S, int64_t lds_, in
   g.rows_per_wg = ceil_div(ceil_div(m > 0 ? m : 1, parts), KB) * KB;
   g.partial = reinterpret_cast<float*>(yws);
   const bool bf16 = prec == SAGNN_GEMM_BF16;
-  const size_t lds = (size_t)(fi + fo) * KP * (bf16 ? 2 : 4);
+  const size_t lds = (size_t)(((fi + 31) / 32 + (fo + 31) / 32) * 32) * KP * (bf16 ? 2 : 4);
   if (bf16) {
     SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_kernel<true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -394,7 +406,7 @@ int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_
                 int64_t m, int32_t kdim, int32_t nout, int32_t prec, int32_t act,
                 const float* mask, int64_t ldmask, float* Z, int64_t ldz, float* A, int64_t lda,
                 hipStream_t s) {
-  if (m < 0 || kdim <= 0 || nout <= 0 || (kdim & 31) || (nout & 31) || kdim > 256 || nout > 256)
+  if (m < 0 || kdim <= 0 || nout <= 0 || (kdim & 3) || (nout & 3) || kdim > 256 || nout > 256)
     return SAGNN_EINVAL;
   if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
   if (act != SAGNN_ACT_IDENTITY && act != SAGNN_ACT_RELU) return SAGNN_EINVAL;
@@ -412,7 +424,7 @@ int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_
   g.lda = lda;
   if (prec == SAGNN_GEMM_BF16) {
     g.n0 = 0;
-    const int tiles = nout / 32;
+    const int tiles = (nout + 31) / 32;
     if (tiles <= 1) return launch_nn<1, true>(g, s);
     if (tiles <= 2) return launch_nn<2, true>(g, s);
     if (tiles <= 4) return launch_nn<4, true>(g, s);
@@ -420,7 +432,7 @@ int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_
   }
   for (int32_t n0 = 0; n0 < nout; n0 += 128) {
     g.n0 = n0;
-    const int tiles = (nout - n0 < 128 ? nout - n0 : 128) / 32;
+    const int tiles = ((nout - n0 < 128 ? nout - n0 : 128) + 31) / 32;
     int rc;
     if (tiles <= 1) rc = launch_nn<1, false>(g, s);
     else if (tiles <= 2) rc = launch_nn<2, false>(g, s);

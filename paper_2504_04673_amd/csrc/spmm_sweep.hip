@@ -10,10 +10,11 @@
 // What: the rows of B are cut into S contiguous slabs.  Rows of A with at least `min_long`
 // entries ("long" rows; they hold most entries of a power-law graph) are cut into pieces of at
 // most `piece_max` entries, and every wavefront is given kSweepSlots pieces whose entries it
-// walks slab by slab: all entries that reference slab 0, then slab 1, ...  Because every
-// wavefront of an XCD walks the slabs in the same order at the same pace, the XCD's L2 only has
-// to hold the hot rows of ONE slab at a time; workgroup b starts at slab (b mod 8) * S/8, so the
-// eight XCDs (workgroups are dispatched to XCDs round-robin) work on eight different slabs.
+// walks slab by slab: all entries that reference slab 0, then slab 1, ...  Because all resident
+// wavefronts walk the slabs in the same order at about the same pace (their streams have nearly
+// equal lengths), each XCD's L2 only has to hold the hot rows of ONE slab at a time, and a slab
+// that one XCD has pulled from HBM is served to the other seven from the memory-side cache.
+// (Starting the XCDs at different slabs was measured to be slower: it defeats that sharing.)
 // Per-piece accumulators live in LDS (a wavefront adds its register accumulator to the piece's
 // LDS row whenever a (piece, slab) segment ends), so nothing is spilled to HBM between slabs.
 // Pieces of a split row are summed in a fixed order by a small second kernel.  Short rows go
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
     const float* __restrict__ val, const int32_t* __restrict__ piece_info,
     const int32_t* __restrict__ wave_base, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
-    uint32_t* __restrict__ code, float* __restrict__ vals) {
+    int32_t stagger, uint32_t* __restrict__ code, float* __restrict__ vals) {
   __shared__ int32_t lo[kSweepSlots][kSweepMaxSlabs + 1];   // first entry (index in row) of slab s
   __shared__ int32_t off[kSweepMaxSlabs][kSweepSlots];      // stream offset of segment (s, slot)
   __shared__ int32_t p_row[kSweepSlots], p_j[kSweepSlots], p_p[kSweepSlots], p_beg[kSweepSlots],
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
   __syncthreads();
   // The stream is laid out in the order the wavefront will walk the slabs: it starts at slab
   // s0 = xcd * S/8 (xcd = workgroup index mod 8, four wavefronts per workgroup) and wraps.
-  const int s0 = (int)(((w >> 2) & 7) * S / 8);
+  const int s0 = stagger ? (int)(((w >> 2) & 7) * S / 8) : 0;
   __shared__ int32_t total;
   if (tid == 0) {
     int32_t run = 0;
@@ -303,6 +304,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   const int force = env_int("SAGNN_SWEEP", -1);  // 0: never, 1: whenever possible, -1: heuristic
   if (force == 0 || nnz < 4096 || k <= 0 || k >= (1ll << kSweepColBits) || m <= 0) return SAGNN_OK;
   const int64_t b_bytes = k * (int64_t)f * 4;
+  // worth it only if B is much larger than an L2 (the long-row share is checked below)
   if (force != 1 && (nnz < (1 << 20) || b_bytes <= (8ll << 20))) return SAGNN_OK;
 
   std::vector<int32_t> rp((size_t)m + 1);
@@ -311,7 +313,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   SAGNN_HIP(hipStreamSynchronize(s));
   if (rp[0] != 0 || rp[m] != nnz) return SAGNN_OK;  // inconsistent: keep the plain schedule
 
-  int min_long = env_int("SAGNN_SWEEP_MINDEG", 32);
+  int min_long = env_int("SAGNN_SWEEP_MINDEG", 64);
   if (min_long < kSweepMinLong) min_long = kSweepMinLong;
   int piece_max = env_int("SAGNN_SWEEP_PIECE", 4096);
   if (piece_max < 1024) piece_max = 1024;
@@ -348,6 +350,8 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     if (a.row != b.row) return a.row < b.row;
     return a.j < b.j;
   });
+  std::vector<char> is_long((size_t)m, 0);
+  for (const Piece& pc : pieces) is_long[(size_t)pc.row] = 1;
   const int64_t P = (int64_t)pieces.size();
   const int64_t NW = ceil_div(P, kSweepSlots);
   std::vector<int32_t> info((size_t)NW * kSweepSlots * 2, -1), target((size_t)NW * kSweepSlots, INT32_MIN);
@@ -402,7 +406,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     int64_t i = 0, acc = 0;
     for (int64_t r = 0; r < m; ++r) {
       const int64_t d = (int64_t)rp[r + 1] - rp[r];
-      if (d > 0 && d < min_long) { rps[(size_t)i] = (int32_t)acc; rmap[(size_t)i] = (int32_t)r; acc += d; ++i; }
+      if (d > 0 && !is_long[(size_t)r]) { rps[(size_t)i] = (int32_t)acc; rmap[(size_t)i] = (int32_t)r; acc += d; ++i; }
     }
     rps[(size_t)short_rows] = (int32_t)acc;
   }
@@ -434,6 +438,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW), dim3(kBuildThreads), 0, s, d_rowptr, d_colidx,
                      d_val, reinterpret_cast<const int32_t*>(ws + L.piece_info),
                      reinterpret_cast<const int32_t*>(ws + L.wave_base), (int32_t)S, (int32_t)width, kmax,
+                     (int32_t)env_int("SAGNN_SWEEP_STAGGER", 0),
                      reinterpret_cast<uint32_t*>(ws + L.code), reinterpret_cast<float*>(ws + L.vals));
   SAGNN_LAUNCH_CHECK();
   // zero the gap between the long stream and the short entries (tail batches read into it)

@@ -44,7 +44,8 @@ def test_workspace_queries():
     assert b.value >= 4 * 128 * 4
     assert L.spmm_csr_workspace_bytes(10, 1000, 6, ctypes.byref(b)) == -1
     assert L.gcn_bwd_workspace_bytes(1000, 256, 256, ctypes.byref(b)) == 0 and b.value >= 256 * 256 * 4
-    assert L.gcn_bwd_workspace_bytes(1000, 100, 256, ctypes.byref(b)) == -1
+    assert L.gcn_bwd_workspace_bytes(1000, 102, 256, ctypes.byref(b)) == -1
+    assert L.gcn_bwd_workspace_bytes(1000, 16, 260, ctypes.byref(b)) == -1
 
 
 def test_argument_validation_before_launch():
@@ -62,7 +63,7 @@ def test_argument_validation_before_launch():
     # plan: missing host arrays
     assert L.spmm_plan_needed_rows(None, None, 4, 4, 0, None, 1, None, 0, None, None, None, 0, 0, None) == -1
     # GEMM: unsupported sizes
-    assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 100, 128, 0, 0, None, 0, None, 0, None, 0, None) == -1
+    assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 102, 128, 0, 0, None, 0, None, 0, None, 0, None) == -1
     assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 128, 512, 0, 0, None, 0, None, 0, None, 0, None) == -1
 
 

@@ -315,7 +315,8 @@ def test_spmm_small_rmat(f):
 
 # ------------------------------------------------------------------------------------ GEMM / layer
 
-@pytest.mark.parametrize("m,k,n", [(1, 32, 32), (31, 64, 96), (33, 128, 128), (1000, 160, 256), (4097, 256, 64)])
+@pytest.mark.parametrize("m,k,n", [(1, 32, 32), (31, 64, 96), (33, 128, 128), (1000, 160, 256), (4097, 256, 64),
+                                   (77, 16, 16), (500, 20, 100), (129, 100, 44), (64, 4, 4)])
 @pytest.mark.parametrize("prec", [0, 1])
 @pytest.mark.parametrize("transW", [False, True])
 def test_dense_gemm(m, k, n, prec, transW):
@@ -347,7 +348,7 @@ def test_bf16_gemm_is_tight_against_bf16_rounded_oracle():
     assert_close(Z, ref, zabs, 2e-5, "bf16 gemm vs bf16-rounded oracle")
 
 
-@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 32)])
+@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 32), (0, 16, 16), (1, 48, 20)])
 def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     g = synth.sbm_graph(6000, 16, 40, 2, 3)
     H = synth.normal((g.n, fin), 1, synth.STREAM_H)
