@@ -44,7 +44,8 @@ struct GemmArgs {
 };
 
 // ------------------------------------------------------------------------------------------
-template <int NT, bool BF16, int WAVES>
+// KPAD: kdim is not a multiple of 32, loads of X are guarded against the real k extent
+template <int NT, bool BF16, int WAVES, bool KPAD>
 __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int NB = NT * 32;
@@ -75,7 +76,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
     const float* __restrict__ xrow = g.X + row * g.ldx;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     auto ldx4 = [&](int col) {   // X[row][col..col+3], zero beyond the real k extent
-      return col < kreal ? *reinterpret_cast<const float4*>(xrow + col) : zero4;
+      if constexpr (KPAD) return col < kreal ? *reinterpret_cast<const float4*>(xrow + col) : zero4;
+      else return *reinterpret_cast<const float4*>(xrow + col);
     };
     floatx16 acc[NT];
 #pragma unroll
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
 template <int NT, bool BF16>
 int launch_nn(const GemmArgs& g, hipStream_t s) {
   constexpr int WAVES = BF16 ? 8 : 4;
-  auto kern = gemm_nn_kernel<NT, BF16, WAVES>;
+  auto kern = (g.kdim & 31) ? gemm_nn_kernel<NT, BF16, WAVES, true> : gemm_nn_kernel<NT, BF16, WAVES, false>;
   const size_t lds = (size_t)((g.kdim + 31) & ~31) * NT * 32 * (BF16 ? 2 : 4);
   if (lds > 160 * 1024) return SAGNN_EINVAL;
   SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
