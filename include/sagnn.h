@@ -53,7 +53,8 @@ enum {
   SAGNN_EHIP = -4       /* a HIP runtime call failed; see sagnn_last_hip_error()            */
 };
 
-#define SAGNN_PLAN_VALIDATE 1u /* flags bit 0 of spmm_plan_needed_rows */
+#define SAGNN_PLAN_VALIDATE 1u  /* flags bit 0 of spmm_plan_needed_rows */
+#define SAGNN_PLAN_OBLIVIOUS 2u /* flags bit 1: plan of the sparsity-oblivious algorithm   */
 
 #define SAGNN_ACT_IDENTITY 0
 #define SAGNN_ACT_RELU 1
@@ -88,6 +89,12 @@ int sagnn_version(void);
  * d_needed / d_colidx_compact untouched.  With SAGNN_PLAN_VALIDATE the CSR is checked on
  * the device first (rowptr monotone from 0 to nnz, every column in [0,n)) and
  * SAGNN_EFORMAT is returned on failure.
+ *
+ * With SAGNN_PLAN_OBLIVIOUS the sparsity of the block is ignored, as in the
+ * sparsity-oblivious algorithm the paper compares against (Sec. 4.1: every process transfers
+ * its whole block row of H): every column of [0,n) is "needed", so d_needed = 0..n-1,
+ * h_blk_off = h_colblk and d_colidx_compact = d_colidx.  Same kernels downstream; it exists so
+ * that both algorithms can be measured on one harness.
  *
  * Workspace: spmm_plan_workspace_bytes(); contents are scratch.
  */
@@ -217,6 +224,80 @@ int gcn_layer_bwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
                   int32_t f_in, const float* d_Zprev, const float* d_Hprev, int32_t gemm_prec,
                   float* d_S, float* d_Gprev, float* d_Y, void* d_ws, size_t ws_bytes,
                   void* d_yws, size_t yws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Column-block split (Sec. 4.2: every row block A_i "is further partitioned in p/c block
+ * columns"; Alg. 2 multiplies one block A_iq per stage).
+ *
+ * Splits the CSR row block (m rows) into nb CSR matrices, one per contiguous range
+ * [h_bounds[q], h_bounds[q+1]) of the index space d_colidx lives in: global column ids with
+ * the h_colblk of the plan, or packed positions with its h_blk_off (then block q's column ids
+ * index that block's part of the packed buffer).  h_bounds is ascending, nb <= 256.
+ *   d_rowptr_blk  nb*(m+1) int32: block q's row pointer is d_rowptr_blk + q*(m+1), starts at 0
+ *   d_colidx_blk, d_val_blk   nnz entries each: block q's entries are
+ *                 [h_nnz_off[q], h_nnz_off[q+1]), column ids relative to h_bounds[q]; inside a
+ *                 row the stored order is kept (stable), so a block product sums in the same
+ *                 order as the unsplit product restricted to that block
+ *   h_nnz_off     nb+1 int64, host output
+ * Entries whose column is outside [h_bounds[0], h_bounds[nb]) are dropped.  Integer work with
+ * a unique result: bit-exact.  Synchronises the stream once.  d_ws: scratch of
+ * spmm_split_workspace_bytes() bytes.
+ */
+int spmm_split_workspace_bytes(int64_t m, int32_t nb, size_t* bytes);
+int spmm_split_colblocks(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                         int64_t m, int64_t nnz, const int64_t* h_bounds, int32_t nb,
+                         int32_t* d_rowptr_blk, int32_t* d_colidx_blk, float* d_val_blk,
+                         int64_t* h_nnz_off, void* d_ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Stage loop of one rank of the 1.5D algorithm (Alg. 2, the loop over k = 0..s-1 with
+ * q = j*s + k: obtain the rows NnzCols(i,q) of H, then Z^ <- Z^ + SpMM(A_iq, H^)).
+ *
+ * The receive of Alg. 2 is replaced by a pack out of the device-resident d_H (n x f, ldh):
+ * the exchange itself is not part of this library.  For stage k
+ *   T_k = d_H[stage.d_rows[0..N), :]                    on stream_pack
+ *   d_Z (+)= A_k * T_k                                  on stream_spmm
+ * with two packed buffers d_T0 / d_T1 (each t_cap_rows x f, ld = f) used alternately, so the
+ * pack of stage k+1 overlaps the product of stage k when the two streams differ (they may be
+ * the same stream: then the stages run back to back).  accumulate_first = 0 makes the first
+ * stage overwrite d_Z (m x f, ldz), 1 adds to its current contents; later stages always add.
+ * The all-reduce over the replicas that follows in Alg. 2 is outside this library.
+ * Ordering: work already queued on stream_spmm is waited for by stream_pack; on return all
+ * of the loop's work is ordered before later work on stream_spmm.  Returns SAGNN_ECAPACITY if
+ * some stage has N > t_cap_rows.
+ */
+typedef struct sagnn_stage {
+  const int32_t* d_rowptr; /* A_iq as CSR, m+1 entries                                      */
+  const int32_t* d_colidx; /* column ids = positions in this stage's packed buffer, [0,N)   */
+  const float* d_val;
+  int64_t nnz;
+  const int32_t* d_rows;   /* NnzCols(i,q): N global row ids of d_H, in packed order        */
+  int64_t N;
+  void* d_ws;              /* SpMM workspace prepared for this block, or NULL               */
+  size_t ws_bytes;
+} sagnn_stage;
+int spmm_stage_loop(const sagnn_stage* h_stages, int32_t n_stages, int64_t m, const float* d_H,
+                    int64_t n, int64_t ldh, int32_t f, float* d_T0, float* d_T1,
+                    int64_t t_cap_rows, float* d_Z, int64_t ldz, int32_t accumulate_first,
+                    void* stream_spmm, void* stream_pack);
+
+/* ---------------------------------------------------------------------------------------
+ * Communication-volume statistics of one SpMM (Sec. 4.1 cost paragraph: cut_P(G), the largest
+ * |NnzCols(i,j)| over i != j; Sec. 5, Table 2: average and maximum data per process and the
+ * load imbalance, which for every row of that table equals (max / average - 1) * 100).
+ *
+ * h_counts is P x P row-major, h_counts[i*P + q] = |NnzCols(i,q)| = rows of H_q that P(i)
+ * needs (diff of the plan's h_blk_off for row block i); the diagonal is ignored (local rows).
+ * Host arithmetic only.  h_out[8]:
+ *   0 total bytes moved        = sum_{i != q} counts * f * elem_bytes
+ *   1 average bytes per process (total / P)
+ *   2 maximum bytes received by one process   3 its imbalance % = (max / avg - 1) * 100
+ *   4 maximum bytes sent by one process       5 its imbalance %
+ *   6 cut_P (rows)                            7 cut_P * f * elem_bytes
+ * Imbalances are 0 when nothing is moved.
+ */
+int spmm_volume_stats(const int64_t* h_counts, int32_t P, int32_t f, int32_t elem_bytes,
+                      double* h_out);
 
 #ifdef __cplusplus
 }

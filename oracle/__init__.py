@@ -162,3 +162,73 @@ def bf16_round(x):
     for i in range(flat_in.size):
         flat_out[i] = L.oracle_bf16_round(float(flat_in[i]))
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# 1.5D stage loop, sparsity-oblivious plan and volume statistics (plain numpy / Python)
+
+def needed_rows_oblivious(colidx, n, colblk):
+    """Plan of the sparsity-oblivious algorithm (Sec. 4.1: a process transfers its whole block
+    row of H): every column is needed.  Returns (needed, blk_off, compact) like needed_rows."""
+    colblk = np.asarray(colblk, dtype=np.int64)
+    return (np.arange(n, dtype=np.int32), colblk.copy(),
+            np.array(colidx, dtype=np.int32, copy=True))
+
+
+def split_colblocks(rowptr, colidx, val, bounds):
+    """The column blocks A_iq of a row block (Sec. 4.2): for every q the CSR of the entries
+    with bounds[q] <= column < bounds[q+1], columns made relative to bounds[q], stored order
+    kept.  Returns a list of (rowptr_q, colidx_q, val_q)."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    colidx = np.asarray(colidx, dtype=np.int64)
+    val = np.asarray(val, dtype=np.float32)
+    bounds = np.asarray(bounds, dtype=np.int64)
+    m = rowptr.size - 1
+    row_of = np.repeat(np.arange(m, dtype=np.int64), np.diff(rowptr))
+    out = []
+    for q in range(bounds.size - 1):
+        sel = (colidx >= bounds[q]) & (colidx < bounds[q + 1])     # boolean mask keeps order
+        cnt = np.bincount(row_of[sel], minlength=m)
+        rp = np.zeros(m + 1, dtype=np.int32)
+        rp[1:] = np.cumsum(cnt)
+        out.append((rp, (colidx[sel] - bounds[q]).astype(np.int32), val[sel].copy()))
+    return out
+
+
+def stage_loop(blocks, rows_per_stage, H, m, want_abs=False):
+    """Alg. 2, loop over the stages of one rank: for each stage take the rows NnzCols(i,q) of
+    H (here: pack them), then Z^ <- Z^ + SpMM(A_iq, H^).  `blocks[k]` = (rowptr, colidx, val)
+    with column ids = positions in stage k's packed rows; `rows_per_stage[k]` = those rows.
+    Returns Z (float32) or (Z, Zabs) with Zabs = sum over stages of |A_iq| |H^|."""
+    f = np.asarray(H).shape[1]
+    Z = np.zeros((m, f), dtype=np.float32)
+    Zabs = np.zeros((m, f), dtype=np.float64)
+    for (rp, ci, va), rows in zip(blocks, rows_per_stage):
+        T = pack_rows(H, rows)
+        if want_abs:
+            Z, ab = spmm(rp, ci, va, T, C=Z, want_abs=True)
+            Zabs += ab
+        else:
+            Z = spmm(rp, ci, va, T, C=Z)
+    return (Z, Zabs) if want_abs else Z
+
+
+def volume_stats(counts, f, elem_bytes=4):
+    """Data moved by one SpMM (Sec. 4.1 cost paragraph, Sec. 5 / Table 2).  counts[i][q] =
+    |NnzCols(i,q)|: rows of H_q that P(i) receives; the diagonal is local.  A process's volume
+    is what it receives (or sends) from all others; imbalance % = (max / average - 1) * 100;
+    cut_P = largest off-diagonal count."""
+    c = np.array(counts, dtype=np.float64)
+    P = c.shape[0]
+    off = c.copy()
+    np.fill_diagonal(off, 0.0)
+    row_bytes = float(f) * float(elem_bytes)
+    recv = off.sum(axis=1) * row_bytes
+    send = off.sum(axis=0) * row_bytes
+    total = recv.sum()
+    avg = total / P
+    imb = lambda mx: (mx / avg - 1.0) * 100.0 if avg > 0 else 0.0
+    return {"total_bytes": total, "avg_bytes": avg, "max_recv_bytes": recv.max(),
+            "recv_imbalance_pct": imb(recv.max()), "max_send_bytes": send.max(),
+            "send_imbalance_pct": imb(send.max()), "cut_rows": off.max(),
+            "cut_bytes": off.max() * row_bytes}

@@ -12,14 +12,22 @@ from . import build as _build
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 GEMM_FP32, GEMM_BF16 = 0, 1
-PLAN_VALIDATE = 1
+PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
 
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_pack_rows",
     "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_schedule_info", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
+    "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
 ]
+
+
+class _Stage(ctypes.Structure):
+    """struct sagnn_stage of the C header."""
+    _fields_ = [("d_rowptr", ctypes.c_void_p), ("d_colidx", ctypes.c_void_p),
+                ("d_val", ctypes.c_void_p), ("nnz", ctypes.c_int64), ("d_rows", ctypes.c_void_p),
+                ("N", ctypes.c_int64), ("d_ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 class SagnnError(RuntimeError):
@@ -67,6 +75,11 @@ def lib():
         L.gcn_bwd_workspace_bytes.argtypes = [i64, i32, i32, psz]
         L.gcn_layer_bwd.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i32, vp, vp, i32, vp, vp, vp,
                                     vp, sz, vp, sz, vp]
+        L.spmm_split_workspace_bytes.argtypes = [i64, i32, psz]
+        L.spmm_split_colblocks.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.spmm_stage_loop.argtypes = [vp, i32, i64, vp, i64, i64, i32, vp, vp, i64, vp, i64, i32, vp,
+                                      vp]
+        L.spmm_volume_stats.argtypes = [vp, i32, i32, i32, vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -111,7 +124,7 @@ class Plan:
 
 
 def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, validate=False,
-                          needed_cap=None, bufs=None) -> Plan:
+                          needed_cap=None, bufs=None, oblivious=False) -> Plan:
     """NnzCols of every column block (Sec. 4.1).  Outputs are torch tensors; `needed` is sized
     min(n, nnz) unless needed_cap is given.  `bufs` = (ws, needed, compact) reuses buffers of an
     earlier call (see plan_buffers) so that a repeated call allocates nothing."""
@@ -121,7 +134,7 @@ def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, val
     colblk = np.ascontiguousarray(colblk, dtype=np.int64)
     nb = colblk.size - 1
     L = lib()
-    cap = int(min(n, nnz) if needed_cap is None else needed_cap)
+    cap = int((n if oblivious else min(n, nnz)) if needed_cap is None else needed_cap)
     if bufs is None:
         bufs = plan_buffers(m, n, nnz, nb, rowptr.device, cap, want_compact)
     ws, needed, compact = bufs
@@ -129,7 +142,9 @@ def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, val
     rc = L.spmm_plan_needed_rows(_ptr(rowptr), _ptr(colidx), m, n, nnz,
                                  colblk.ctypes.data_as(ctypes.c_void_p), nb, _ptr(needed), cap,
                                  blk_off.ctypes.data_as(ctypes.c_void_p), _ptr(compact), _ptr(ws),
-                                 ws.numel(), PLAN_VALIDATE if validate else 0, _stream())
+                                 ws.numel(),
+                                 (PLAN_VALIDATE if validate else 0) | (PLAN_OBLIVIOUS if oblivious else 0),
+                                 _stream())
     _check(rc, "spmm_plan_needed_rows")
     N = int(blk_off[-1])
     return Plan(needed[:N], blk_off, compact[:nnz] if compact is not None else None)
@@ -282,3 +297,86 @@ def gcn_layer_bwd(rowptr, colidx, val, G, W, Zprev, Hprev, prec=GEMM_FP32, ws: S
                              _ptr(yws), yws.numel() if yws is not None else 0, _stream())
     _check(rc, "gcn_layer_bwd")
     return S, Gp, Y
+
+
+@dataclass
+class ColBlocks:
+    """Result of spmm_split_colblocks: nb CSR matrices sharing three buffers."""
+    rowptr_blk: torch.Tensor      # int32 [nb, m+1]
+    colidx_blk: torch.Tensor      # int32 [nnz]
+    val_blk: torch.Tensor         # float32 [nnz]
+    nnz_off: np.ndarray           # int64 [nb+1] (host)
+
+    def block(self, q: int):
+        a, b = int(self.nnz_off[q]), int(self.nnz_off[q + 1])
+        return self.rowptr_blk[q], self.colidx_blk[a:b], self.val_blk[a:b]
+
+
+def spmm_split_colblocks(rowptr, colidx, val, bounds) -> ColBlocks:
+    """Split a CSR row block into one CSR per column range (Sec. 4.2; the A_iq of Alg. 2)."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    bounds = np.ascontiguousarray(bounds, dtype=np.int64)
+    nb = bounds.size - 1
+    dev = rowptr.device
+    L = lib()
+    wsb = ctypes.c_size_t(0)
+    _check(L.spmm_split_workspace_bytes(m, nb, ctypes.byref(wsb)), "spmm_split_workspace_bytes")
+    ws = _ws(wsb.value, dev)
+    rp = torch.empty((nb, m + 1), dtype=torch.int32, device=dev)
+    ci = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    va = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)
+    off = np.zeros(nb + 1, dtype=np.int64)
+    rc = L.spmm_split_colblocks(_ptr(rowptr), _ptr(colidx), _ptr(val), m, nnz,
+                                bounds.ctypes.data_as(ctypes.c_void_p), nb, _ptr(rp), _ptr(ci), _ptr(va),
+                                off.ctypes.data_as(ctypes.c_void_p), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "spmm_split_colblocks")
+    return ColBlocks(rp, ci[:nnz], va[:nnz], off)
+
+
+def spmm_stage_loop(stages, m: int, H, T0, T1, Z, accumulate_first=False, pack_stream=None):
+    """Stage loop of Alg. 2 on one rank.  `stages` is a list of dicts with keys rowptr, colidx,
+    val, rows and optionally ws (SpmmWorkspace).  Products run on the current stream, packs on
+    `pack_stream` (a torch.cuda.Stream; None = the current stream)."""
+    H = _dev(H, torch.float32, "H")
+    Z = _dev(Z, torch.float32, "Z")
+    T0 = _dev(T0, torch.float32, "T0")
+    T1 = _dev(T1, torch.float32, "T1")
+    n, f = H.shape
+    arr = (_Stage * max(len(stages), 1))()
+    for k, st in enumerate(stages):
+        rp = _dev(st["rowptr"], torch.int32, "stage rowptr")
+        ci = _dev(st["colidx"], torch.int32, "stage colidx")
+        va = _dev(st["val"], torch.float32, "stage val")
+        rows = _dev(st["rows"], torch.int32, "stage rows")
+        if rp.numel() != m + 1:
+            raise ValueError("stage rowptr must have m+1 entries")
+        ws = st.get("ws")
+        arr[k] = _Stage(rp.data_ptr(), ci.data_ptr() if ci.numel() else None,
+                        va.data_ptr() if va.numel() else None, ci.numel(),
+                        rows.data_ptr() if rows.numel() else None, rows.numel(),
+                        ws.buf.data_ptr() if ws else None, ws.buf.numel() if ws else 0)
+    cap = min(T0.shape[0], T1.shape[0])
+    if T0.shape[1] != f or T1.shape[1] != f:
+        raise ValueError("packed buffers must have H's width")
+    ps = _stream() if pack_stream is None else ctypes.c_void_p(pack_stream.cuda_stream)
+    rc = lib().spmm_stage_loop(ctypes.cast(arr, ctypes.c_void_p), len(stages), m, _ptr(H), n,
+                               H.stride(0), f, _ptr(T0), _ptr(T1), cap, _ptr(Z), Z.stride(0),
+                               int(accumulate_first), _stream(), ps)
+    _check(rc, "spmm_stage_loop")
+    return Z
+
+
+def spmm_volume_stats(counts, f: int, elem_bytes: int = 4) -> dict:
+    """Volume statistics of one SpMM from the P x P matrix of |NnzCols(i,q)| (host arithmetic)."""
+    c = np.ascontiguousarray(counts, dtype=np.int64)
+    if c.ndim != 2 or c.shape[0] != c.shape[1]:
+        raise ValueError("counts must be P x P")
+    out = np.zeros(8, dtype=np.float64)
+    _check(lib().spmm_volume_stats(c.ctypes.data_as(ctypes.c_void_p), c.shape[0], f, elem_bytes,
+                                   out.ctypes.data_as(ctypes.c_void_p)), "spmm_volume_stats")
+    keys = ("total_bytes", "avg_bytes", "max_recv_bytes", "recv_imbalance_pct", "max_send_bytes",
+            "send_imbalance_pct", "cut_rows", "cut_bytes")
+    return dict(zip(keys, (float(x) for x in out)))

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB = os.path.join(_HERE, "libsagnn.so")
-SOURCES = ["api.hip", "pack.hip", "plan.hip", "spmm.hip", "spmm_sweep.hip", "gemm.hip"]
+SOURCES = ["api.hip", "pack.hip", "plan.hip", "spmm.hip", "spmm_sweep.hip", "gemm.hip", "stages.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

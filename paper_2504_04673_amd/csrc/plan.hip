@@ -69,6 +69,13 @@ __global__ __launch_bounds__(kThreads) void clear_kernel(uint4* __restrict__ fla
   if (blockIdx.x == 0 && threadIdx.x < 4) err[threadIdx.x] = 0;
 }
 
+// Sparsity-oblivious plan: every column of [0, n) counts as needed (the whole block row of H
+// is transferred, Sec. 4.1 "sparsity-oblivious algorithm"); bytes past n stay clear.
+__global__ __launch_bounds__(kThreads) void fill_all_kernel(uint8_t* __restrict__ flag, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c < n; c += stride) flag[c] = 1;
+}
+
 // err[0]: rowptr malformed, err[1]: column out of range
 __global__ __launch_bounds__(kThreads) void validate_rowptr_kernel(
     const int32_t* __restrict__ rowptr, int64_t m, int64_t nnz, int32_t* __restrict__ err) {
@@ -333,9 +340,14 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
                        m, nnz, w.err);
     SAGNN_LAUNCH_CHECK();
   }
-  if (nnz > 0) {
+  const bool oblivious = (flags & SAGNN_PLAN_OBLIVIOUS) != 0;
+  if (nnz > 0 && (!oblivious || (flags & SAGNN_PLAN_VALIDATE))) {
     hipLaunchKernelGGL(mark_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz,
                        n, w.flag, w.err, aligned16(d_colidx) ? 1 : 0);
+    SAGNN_LAUNCH_CHECK();
+  }
+  if (oblivious && n > 0) {
+    hipLaunchKernelGGL(fill_all_kernel, dim3(grid_for(n)), dim3(kThreads), 0, s, w.flag, n);
     SAGNN_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(words_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.flag, w.W,

@@ -65,6 +65,21 @@ def test_argument_validation_before_launch():
     # GEMM: unsupported sizes
     assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 102, 128, 0, 0, None, 0, None, 0, None, 0, None) == -1
     assert L.dense_gemm_act(None, 128, None, 128, 0, 10, 128, 512, 0, 0, None, 0, None, 0, None, 0, None) == -1
+    # split / stage loop: bad block count, missing arrays, too many blocks
+    b = ctypes.c_size_t(0)
+    assert L.spmm_split_workspace_bytes(100, 4, ctypes.byref(b)) == 0 and b.value > 0
+    assert L.spmm_split_workspace_bytes(100, 257, ctypes.byref(b)) == -1
+    assert L.spmm_split_colblocks(None, None, None, 4, 0, None, 2, None, None, None, None, None, 0, None) == -1
+    assert L.spmm_stage_loop(None, 1, 4, None, 4, 16, 16, None, None, 4, None, 16, 0, None, None) == -1
+
+
+def test_volume_stats_host_only():
+    """spmm_volume_stats is host arithmetic: it runs without a GPU.  Hand-counted 3 x 3 case."""
+    st = sagnn.spmm_volume_stats([[9, 1, 2], [4, 9, 0], [5, 6, 9]], 2, 4)
+    assert st["total_bytes"] == 144 and st["avg_bytes"] == 48 and st["max_recv_bytes"] == 88
+    assert st["max_send_bytes"] == 72 and st["cut_rows"] == 6 and st["cut_bytes"] == 48
+    assert st["send_imbalance_pct"] == pytest.approx(50.0)
+    assert sagnn.lib().spmm_volume_stats(None, 3, 2, 4, None) == -1
 
 
 def test_binding_refuses_cpu_tensors():

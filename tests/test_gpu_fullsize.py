@@ -120,7 +120,6 @@ def test_cfg4_rank_share():
         Hd[torch.from_numpy(idx.astype(np.int64)).cuda()] = dev(wl.H_rows(idx))
     Hn = sagnn.spmm_pack_rows(Hd, plan.needed)
     torch.cuda.synchronize()
-    del Hd
     rng = np.random.default_rng(4)
     pos = np.unique(np.concatenate([rng.integers(0, N, size=50_000), [0, N - 1], plan.blk_off[1:-1] - 1,
                                     plan.blk_off[1:-1]])).astype(np.int64)
@@ -140,6 +139,34 @@ def test_cfg4_rank_share():
     # per-pair volumes (what the all-to-allv of the 1D algorithm would carry) are consistent
     counts = np.diff(plan.blk_off)
     assert counts.sum() == N and counts[0] >= g.m       # the diagonal block holds the self loops
+
+    # Stage loop of Alg. 2 at the paper's P = 64, c = 4 shape: 16 column blocks, a rank owns
+    # s = P/c^2 = 4 of them.  Rank j = 0's partial sum (stages q = 0..3), then all 16 stages,
+    # packing each stage's rows straight out of the full H on a second stream.
+    cb = sagnn.spmm_split_colblocks(rp, plan.colidx_compact, v, plan.blk_off)
+    assert cb.nnz_off[-1] == g.nnz
+    stages = []
+    for q in range(16):
+        brp, bci, bva = cb.block(q)
+        stages.append({"rowptr": brp, "colidx": bci, "val": bva,
+                       "rows": plan.needed[int(plan.blk_off[q]):int(plan.blk_off[q + 1])]})
+    cap = int(counts.max())
+    T0 = torch.empty((cap, f), dtype=torch.float32, device="cuda")
+    T1 = torch.empty((cap, f), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    Zs = torch.empty((g.m, f), dtype=torch.float32, device="cuda")
+    sagnn.spmm_stage_loop(stages, g.m, Hd, T0, T1, Zs, pack_stream=side)
+    torch.cuda.synchronize()
+    assert_close(Zs[torch.from_numpy(rows).cuda()], ref, zabs, RTOL_SPMM, "cfg4 stage loop, 16 stages")
+    sagnn.spmm_stage_loop(stages[:4], g.m, Hd, T0, T1, Zs, pack_stream=side)
+    torch.cuda.synchronize()
+    keep = sci < wl.colblk[4]                             # entries of column blocks 0..3
+    row_of = np.repeat(np.arange(rows.size), np.diff(srp))
+    krp = np.concatenate([[0], np.cumsum(np.bincount(row_of[keep], minlength=rows.size))]).astype(np.int32)
+    pref, pabs = oracle.spmm(krp, inv[keep].astype(np.int32), sv[keep], wl.H_rows(ucols.astype(np.int32)),
+                             want_abs=True)
+    assert_close(Zs[torch.from_numpy(rows).cuda()], pref, pabs, RTOL_SPMM, "cfg4 stage loop, rank 0's 4 stages")
+    del Hd
 
 
 # ------------------------------------------------------------------------------------------ cfg5

@@ -1,0 +1,131 @@
+"""Pins of the oracle's 1.5D stage loop, column-block split, sparsity-oblivious plan and volume
+statistics (CPU only): the figures printed in the paper's Table 2, hand-computed tiny cases,
+pure-Python brute force and the dense product."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from tests.test_oracle_pins import dense_of, random_csr
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def table2_rows():
+    rows = []
+    for line in open(os.path.join(GOLDEN, "table2_amazon_metis.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            p, avg, mx, imb = line.split()
+            rows.append((int(p), float(avg), float(mx), float(imb)))
+    return rows
+
+
+@pytest.mark.parametrize("p,avg_mb,max_mb,imb", table2_rows())
+def test_volume_imbalance_matches_table2(p, avg_mb, max_mb, imb):
+    """Table 2 prints average MB, max MB and imbalance % for f = 300.  Build a count matrix
+    whose per-process received volumes have exactly that average and maximum (process 0 gets
+    the maximum, the others share the rest) and check that the oracle reports the printed
+    imbalance (within the rounding of the printed one-decimal figures)."""
+    f, eb = 300, 4
+    row_b = f * eb
+    max_rows = int(round(max_mb * 1e6 / row_b))
+    rest_rows = int(round((avg_mb * p - max_mb) * 1e6 / row_b / (p - 1)))
+    counts = np.zeros((p, p), dtype=np.int64)
+    counts[0, 1] = max_rows                       # everything process 0 receives comes from P(1)
+    for i in range(1, p):
+        counts[i, (i + 1) % p if (i + 1) % p != i else 0] = rest_rows
+    counts[np.arange(p), np.arange(p)] = 123456   # diagonal must not count
+    st = oracle.volume_stats(counts, f, eb)
+    assert abs(st["avg_bytes"] / 1e6 - avg_mb) < 0.06
+    assert abs(st["max_recv_bytes"] / 1e6 - max_mb) < 0.06
+    # one-decimal rounding of avg and max moves the ratio by up to ~0.05/avg + 0.05/max relative
+    slack = 100.0 * (max_mb / avg_mb) * (0.05 / avg_mb + 0.05 / max_mb) + 0.06
+    assert abs(st["recv_imbalance_pct"] - imb) <= slack
+
+
+def test_volume_stats_hand_case():
+    """3 processes, f = 2, 4-byte elements (8 bytes per row), counted by hand:
+    received rows: P0 = 1+2 = 3, P1 = 4+0 = 4, P2 = 5+6 = 11; sent rows: P0 = 4+5 = 9,
+    P1 = 1+6 = 7, P2 = 2+0 = 2; total 18 rows = 144 B; average 48 B; cut = 6 rows."""
+    counts = [[9, 1, 2], [4, 9, 0], [5, 6, 9]]
+    st = oracle.volume_stats(counts, 2, 4)
+    assert st["total_bytes"] == 144 and st["avg_bytes"] == 48
+    assert st["max_recv_bytes"] == 88 and st["max_send_bytes"] == 72
+    assert st["recv_imbalance_pct"] == pytest.approx((88 / 48 - 1) * 100)
+    assert st["send_imbalance_pct"] == pytest.approx(50.0)
+    assert st["cut_rows"] == 6 and st["cut_bytes"] == 48
+    z = oracle.volume_stats(np.diag([5, 5]), 16)
+    assert z["total_bytes"] == 0 and z["recv_imbalance_pct"] == 0 and z["cut_rows"] == 0
+
+
+def test_volume_counts_from_plan_equal_bruteforce_sets():
+    """counts[i][q] taken from the plan's block offsets equal the sizes of brute-force sets."""
+    rng = np.random.default_rng(5)
+    n, P = 60, 4
+    rowptr, colidx, val = random_csr(n, n, 0.05, rng)
+    blk = np.array([0, 13, 13, 40, 60], dtype=np.int64)   # ragged, one empty block
+    counts = np.zeros((P, P), dtype=np.int64)
+    for i in range(P):
+        a, b = rowptr[blk[i]], rowptr[blk[i + 1]]
+        rp = (rowptr[blk[i]:blk[i + 1] + 1] - a).astype(np.int32)
+        _, off, _ = oracle.needed_rows(rp, colidx[a:b], n, blk)
+        counts[i] = np.diff(off)
+        for q in range(P):
+            brute = {int(c) for c in colidx[a:b] if blk[q] <= c < blk[q + 1]}
+            assert counts[i, q] == len(brute)
+    ob = oracle.volume_stats(np.tile(np.diff(blk), (P, 1)), 8)   # oblivious: whole blocks
+    aw = oracle.volume_stats(counts, 8)
+    assert aw["total_bytes"] <= ob["total_bytes"]
+
+
+def test_oblivious_plan_is_identity():
+    colidx = np.array([3, 0, 3, 5], dtype=np.int32)
+    needed, off, compact = oracle.needed_rows_oblivious(colidx, 7, [0, 2, 7])
+    assert needed.tolist() == list(range(7)) and off.tolist() == [0, 2, 7]
+    assert compact.tolist() == colidx.tolist()
+
+
+@pytest.mark.parametrize("seed,sort", [(0, True), (1, False)])
+def test_split_colblocks_bruteforce(seed, sort):
+    """Pure-Python scan of every entry: block membership, relative column, stable order."""
+    rng = np.random.default_rng(seed)
+    m, n = 23, 50
+    rowptr, colidx, val = random_csr(m, n, 0.3, rng, sort=sort, dup=True)
+    bounds = [5, 5, 17, 30, 44]          # drops columns < 5 and >= 44; one empty block
+    blocks = oracle.split_colblocks(rowptr, colidx, val, bounds)
+    assert len(blocks) == 4
+    for q, (rp, ci, va) in enumerate(blocks):
+        exp_rp, exp_ci, exp_va = [0], [], []
+        for r in range(m):
+            for e in range(rowptr[r], rowptr[r + 1]):
+                if bounds[q] <= colidx[e] < bounds[q + 1]:
+                    exp_ci.append(int(colidx[e]) - bounds[q])
+                    exp_va.append(val[e])
+            exp_rp.append(len(exp_ci))
+        assert rp.tolist() == exp_rp and ci.tolist() == exp_ci
+        assert np.array_equal(va, np.array(exp_va, dtype=np.float32))
+
+
+def test_stage_loop_equals_dense_product_of_selected_blocks():
+    """Alg. 2's partial sum over the stages q of A_iq H_q equals the dense product with the
+    columns of the other blocks zeroed (Eq. for the 1.5D partial sum)."""
+    rng = np.random.default_rng(11)
+    m, n, f = 19, 64, 5
+    rowptr, colidx, val = random_csr(m, n, 0.2, rng, sort=True)
+    H = rng.standard_normal((n, f)).astype(np.float32)
+    colblk = np.array([0, 16, 30, 30, 51, 64], dtype=np.int64)
+    needed, off, compact = oracle.needed_rows(rowptr, colidx, n, colblk)
+    blocks = oracle.split_colblocks(rowptr, compact, val, off)
+    stages = [1, 3, 4]                                   # a rank's share of the column blocks
+    rows = [needed[off[q]:off[q + 1]] for q in stages]
+    Z, Zabs = oracle.stage_loop([blocks[q] for q in stages], rows, H, m, want_abs=True)
+    D = np.array(dense_of(rowptr, colidx, val, n))
+    keep = np.zeros(n, dtype=bool)
+    for q in stages:
+        keep[colblk[q]:colblk[q + 1]] = True
+    ref = (D * keep[None, :]) @ H.astype(np.float64)
+    assert np.all(np.abs(Z - ref) <= 1e-6 * Zabs + 1e-30)
+    full = oracle.stage_loop(blocks, [needed[off[q]:off[q + 1]] for q in range(5)], H, m)
+    assert np.allclose(full, D @ H.astype(np.float64), rtol=0, atol=1e-5)
