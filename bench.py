@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plan", action="store_true", help="leave the plan out of the timed step")
+    ap.add_argument("--stage-loop", action="store_true",
+                    help="also time the 1.5D stage loop (Alg. 2) over the workload's column blocks, with one "
+                         "and with two streams; reported under \"stage_loop\" (not part of `value`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
                          "known traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -170,6 +173,7 @@ def main():
 
     phase = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])  # ms
     avg = phase.mean(axis=0)
+    med = np.median(phase, axis=0)
     plan_ms, pack_ms, spmm_ms, gemm_ms = [float(x) for x in avg]
     step_bytes = models["pack_bytes"] + models["spmm_bytes"] + models["gemm_bytes"] + \
         (0 if args.no_plan else models["plan_bytes"])
@@ -191,17 +195,21 @@ def main():
             "spmm_schedule": ws.info(),
             "scale": args.scale},
         "roofline": {
-            "kernel": "spmm_csr_tallskinny (spmm_wide/narrow_kernel + carry fix-up)",
+            "kernel": "spmm_csr_tallskinny (all kernels of one call: slab-sweep + nonzero-splitting "
+                      "product kernels, carry fix-up, piece combine)",
             "bound": "hbm", "achieved": round(spmm_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(spmm_gbps / HBM_PEAK_GBPS, 4), "traffic": parse_traffic(wl.name, f),
             "algorithmic_bytes": models["spmm_bytes"], "avg_ms": round(spmm_ms, 4),
-            "min_ms": round(float(phase[:, 2].min()), 4),
+            "median_ms": round(float(med[2]), 4), "min_ms": round(float(phase[:, 2].min()), 4),
+            "no_reuse_model_bytes": models["spmm_bytes"] - N * f * 4 + models["spmm_gather_bytes"],
             "gflops": round(models["spmm_flops"] / (spmm_ms * 1e-3) / 1e9, 1),
             "gather_delivery_GBps": round(models["spmm_gather_bytes"] / (spmm_ms * 1e-3) / 1e9, 1),
         },
         "stages": {
             "plan_ms": round(plan_ms, 4), "pack_ms": round(pack_ms, 4), "spmm_ms": round(spmm_ms, 4),
             "gemm_ms": round(gemm_ms, 4),
+            "median_ms": {k: round(float(v), 4) for k, v in zip(("plan", "pack", "spmm", "gemm"), med)},
+            "min_ms": {k: round(float(v), 4) for k, v in zip(("plan", "pack", "spmm", "gemm"), phase.min(axis=0))},
             "pack_GBps": round(models["pack_bytes"] / (pack_ms * 1e-3) / 1e9, 1),
             "plan_GBps": round(models["plan_bytes"] / (plan_ms * 1e-3) / 1e9, 1) if not args.no_plan else None,
             "gemm_GBps": round(models["gemm_bytes"] / (gemm_ms * 1e-3) / 1e9, 1),
@@ -209,9 +217,49 @@ def main():
         },
     }
 
+    if args.stage_loop:
+        out["stage_loop"] = stage_loop_timing(sagnn, torch, wl, plan, rp, va, Hd, m, f, max(args.steps // 2, 3))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, g, args)
     print(json.dumps(out), flush=True)
+
+
+def stage_loop_timing(sagnn, torch, wl, plan, rp, va, Hd, m, f, reps):
+    """Alg. 2's loop over a rank's stages: pack(q) then accumulate A_iq * packed rows, for the
+    first s column blocks (s = P/c^2 when the workload names P and c, else all blocks) and for all
+    blocks; one stream versus two (pack of stage k+1 overlapping the product of stage k)."""
+    import numpy as np
+    nb = wl.colblk.size - 1
+    cb = sagnn.spmm_split_colblocks(rp, plan.colidx_compact, va, plan.blk_off)
+    stages = []
+    for q in range(nb):
+        brp, bci, bva = cb.block(q)
+        rows = plan.needed[int(plan.blk_off[q]):int(plan.blk_off[q + 1])]
+        st = {"rowptr": brp, "colidx": bci, "val": bva, "rows": rows}
+        if bci.numel():
+            st["ws"] = sagnn.spmm_csr_prepare(brp, bci, bva, rows.numel(), f)
+        stages.append(st)
+    cap = max(int(np.diff(plan.blk_off).max()), 1)
+    T0 = torch.empty((cap, f), dtype=torch.float32, device=Hd.device)
+    T1 = torch.empty((cap, f), dtype=torch.float32, device=Hd.device)
+    Z = torch.empty((m, f), dtype=torch.float32, device=Hd.device)
+    side = torch.cuda.Stream()
+    s_rank = nb
+    if "P" in wl.extra and "c" in wl.extra:
+        s_rank = max(1, wl.extra["P"] // wl.extra["c"] ** 2)
+    res = {"column_blocks": nb, "rank_stages": s_rank}
+    for label, sub in (("rank_stages", stages[:s_rank]), ("all_blocks", stages)):
+        for name, ps in (("one_stream", None), ("two_streams", side)):
+            best = 1e30
+            for _ in range(reps + 1):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                sagnn.spmm_stage_loop(sub, m, Hd, T0, T1, Z, pack_stream=ps)
+                b.record()
+                torch.cuda.synchronize()
+                best = min(best, a.elapsed_time(b))
+            res[f"{label}_{name}_ms"] = round(best, 4)
+    return res
 
 
 def cpu_baseline(wl, g, args):

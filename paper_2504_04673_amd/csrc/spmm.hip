@@ -22,6 +22,8 @@
 // remainder.
 #include <stdlib.h>
 
+#include <vector>
+
 #include "common.h"
 #include "rowload.h"
 
@@ -70,7 +72,7 @@ __device__ __forceinline__ int next_row(int r, bool has_empty, const int32_t* __
 // Per batch of U entries: U dense-row loads are issued back to back (their column indices and
 // values are already in scalar registers), then the scalar loads of the NEXT batch, then the
 // FMAs with a uniform branch at every row end.
-template <int FPL, int U, bool BUF>
+template <int FPL, int U, bool BUF, bool AHEAD>
 __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, const SpmmDims d) {
   using vec = typename Vec<FPL>::T;
   const uint32_t lane = threadIdx.x & 63;
@@ -90,7 +92,9 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
   const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
 
   vec acc = 0.f;
-  auto flush = [&]() {
+  // `old` = the current contents of the row of C when they were fetched ahead (accumulating
+  // calls), otherwise they are read here
+  auto flush = [&](const vec old, const bool have_old) {
     if (r >= d.m) return;  // cannot happen with a consistent rowptr; keeps stores in bounds
     if (head) {
       *reinterpret_cast<vec*>(carry) = acc;
@@ -98,12 +102,18 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
     } else {
       const int64_t ro = rowmap ? rowmap[r] : r;
       vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + ro * d.ldc) + loff);
-      if (d.accumulate) acc += *p;
+      if (d.accumulate) acc += have_old ? old : *p;
       *p = acc;
     }
     acc = 0.f;
     r = next_row(r, has_empty, rowptr, d.m);
   };
+  // Accumulating calls (the per-stage sums of Alg. 2) read the old row of C at every row end.
+  // With short rows that read would sit on the critical path once per row, so the rows that
+  // end inside a batch are fetched together with the batch's rows of B.  (Rows are consecutive
+  // in the row list unless empty rows are being stepped over.)
+  // (AHEAD is chosen by the launcher for accumulating calls that walk a row list without empty rows.)
+  const bool ahead = AHEAD && d.accumulate != 0 && !has_empty;
 
   // entry e of the chunk, clamped so that the (only) partial chunk never reads past nnz
   auto fetch = [&](int32_t e, int32_t (&c)[U], float (&v)[U]) {
@@ -138,6 +148,22 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
       h[u] = load_row<FPL, BUF>(rs, B, cc, loff, d.row_bytes, d.ldb);
       vc[u] = v[u];
     }
+    vec cold[AHEAD ? U : 1];
+#pragma unroll
+    for (int u = 0; u < (AHEAD ? U : 1); ++u) cold[u] = 0.f;
+    if (AHEAD && ahead && fbits) {
+      int rr = r;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if ((fbits >> u) & 1u) {
+          const int rc = rr < d.m ? rr : (int)(d.m - 1);
+          const int64_t ro = rowmap ? rowmap[rc] : rc;
+          cold[AHEAD ? u : 0] =
+              *reinterpret_cast<const vec*>(reinterpret_cast<const char*>(C + ro * d.ldc) + loff);
+          ++rr;
+        }
+      }
+    }
     if (e + U < e1) fetch(e + U, c, v);
     // keep the U loads above together (the compiler would otherwise sink each one next to its use)
 #pragma unroll
@@ -145,12 +171,12 @@ __global__ __launch_bounds__(kBlock) void spmm_wide_kernel(SPMM_PTR_PARAMS, cons
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       acc += vc[u] * h[u];
-      if ((fbits >> u) & 1u) flush();
+      if ((fbits >> u) & 1u) flush(cold[AHEAD ? u : 0], ahead);
     }
   }
   const int32_t last = e1 - 1;
   const bool closed = (flags[last >> 5] >> (last & 31)) & 1u;
-  if (!closed) flush();  // the row continues in the next chunk: store the partial sum
+  if (!closed) flush(vec(0.f), false);  // the row continues in the next chunk: store the partial sum
 }
 
 // ------------------------------------------------------------------------------------------
@@ -486,6 +512,11 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
     p.colidx = reinterpret_cast<const int32_t*>(base + L.code) + short_base;
     p.val = reinterpret_cast<const float*>(base + L.vals) + short_base;
     d.m = desc.c_rows; d.nnz = desc.c_nnz; d.nchunks = desc.c_nchunks;
+  } else if (desc.c_rows != m) {
+    // empty rows were taken out of the row list when the workspace was prepared
+    p.rowptr = reinterpret_cast<const int32_t*>(base + L.rowptr_s);
+    p.rowmap = reinterpret_cast<const int32_t*>(base + L.rowmap_s);
+    d.m = desc.c_rows;
   }
 
   const int64_t blocks = ceil_div(d.nchunks, kWavesPerBlock);
@@ -504,12 +535,18 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
       if (rc != SAGNN_OK) return rc;
     }
     if (d.nchunks > 0) {
-      if (sd.f == 256 && buf) launch_waves(spmm_wide_kernel<4, 8, true>, blocks, sp, sd, s);
-      else if (sd.f == 256) launch_waves(spmm_wide_kernel<4, 8, false>, blocks, sp, sd, s);
-      else if (sd.f == 128 && buf) launch_waves(spmm_wide_kernel<2, 8, true>, blocks, sp, sd, s);
-      else if (sd.f == 128) launch_waves(spmm_wide_kernel<2, 8, false>, blocks, sp, sd, s);
-      else if (sd.f == 64 && buf) launch_waves(spmm_wide_kernel<1, 8, true>, blocks, sp, sd, s);
-      else if (sd.f == 64) launch_waves(spmm_wide_kernel<1, 8, false>, blocks, sp, sd, s);
+      // accumulating calls over a row list without empty rows fetch the old rows of C ahead
+      const bool ahead = accumulate != 0 && !(desc.has_empty_rows && sp.rowmap == nullptr);
+#define SAGNN_WIDE(FPL_, BUF_)                                                              \
+  (ahead ? launch_waves(spmm_wide_kernel<FPL_, 8, BUF_, true>, blocks, sp, sd, s)           \
+         : launch_waves(spmm_wide_kernel<FPL_, 8, BUF_, false>, blocks, sp, sd, s))
+      if (sd.f == 256 && buf) SAGNN_WIDE(4, true);
+      else if (sd.f == 256) SAGNN_WIDE(4, false);
+      else if (sd.f == 128 && buf) SAGNN_WIDE(2, true);
+      else if (sd.f == 128) SAGNN_WIDE(2, false);
+      else if (sd.f == 64 && buf) SAGNN_WIDE(1, true);
+      else if (sd.f == 64) SAGNN_WIDE(1, false);
+#undef SAGNN_WIDE
       else if (rest > 32) launch_waves(spmm_narrow_kernel<16, 4>, blocks, sp, sd, s);
       else if (rest > 16) launch_waves(spmm_narrow_kernel<8, 4>, blocks, sp, sd, s);
       else if (rest > 8) launch_waves(spmm_narrow_kernel<4, 4>, blocks, sp, sd, s);
@@ -579,6 +616,35 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
     SAGNN_HIP(hipMemcpyAsync(&he, d_has_empty, 4, hipMemcpyDeviceToHost, s));
     SAGNN_HIP(hipStreamSynchronize(s));
     h.has_empty_rows = he;
+    if (he && nnz > 0) {
+      // Rows without entries (e.g. one column block of a row block, Alg. 2) would make a chunk's
+      // wavefront step over them one dependent load at a time.  Walk a row list without them
+      // instead: the same compacted-CSR form the short rows of the sweep schedule use.
+      std::vector<int32_t> rp((size_t)m + 1);
+      SAGNN_HIP(hipMemcpyAsync(rp.data(), d_rowptr, sizeof(int32_t) * (size_t)(m + 1),
+                               hipMemcpyDeviceToHost, s));
+      SAGNN_HIP(hipStreamSynchronize(s));
+      std::vector<int32_t> rps, rmap;
+      bool ok = rp[0] == 0 && rp[(size_t)m] == nnz;
+      for (int64_t r = 0; ok && r < m; ++r) {
+        if (rp[(size_t)r + 1] < rp[(size_t)r]) ok = false;
+        else if (rp[(size_t)r + 1] > rp[(size_t)r]) { rps.push_back(rp[(size_t)r]); rmap.push_back((int32_t)r); }
+      }
+      if (ok) {   // (a malformed row pointer keeps the plain walk, which clamps everything)
+        rps.push_back((int32_t)nnz);
+        const int64_t rows_c = (int64_t)rmap.size();
+        SAGNN_HIP(hipMemcpyAsync(base + L.rowptr_s, rps.data(), sizeof(int32_t) * rps.size(),
+                                 hipMemcpyHostToDevice, s));
+        SAGNN_HIP(hipMemcpyAsync(base + L.rowmap_s, rmap.data(), sizeof(int32_t) * rmap.size(),
+                                 hipMemcpyHostToDevice, s));
+        rc = build_chunk_tables(reinterpret_cast<const int32_t*>(base + L.rowptr_s), rows_c, nnz,
+                                reinterpret_cast<int32_t*>(base + L.chunk_row),
+                                reinterpret_cast<uint32_t*>(base + L.flags), d_has_empty, s);
+        if (rc != SAGNN_OK) return rc;
+        SAGNN_HIP(hipStreamSynchronize(s));   // the host vectors are read by the copies above
+        h.c_rows = rows_c;
+      }
+    }
   }
   SAGNN_HIP(hipMemcpyAsync(base + L.header, &h, sizeof(h), hipMemcpyHostToDevice, s));
   SAGNN_HIP(hipStreamSynchronize(s));

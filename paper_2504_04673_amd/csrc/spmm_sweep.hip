@@ -353,7 +353,13 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   std::vector<char> is_long((size_t)m, 0);
   for (const Piece& pc : pieces) is_long[(size_t)pc.row] = 1;
   const int64_t P = (int64_t)pieces.size();
-  const int64_t NW = ceil_div(P, kSweepSlots);
+  // Pieces per wavefront: all kSweepSlots when there are plenty of pieces; fewer when that would
+  // leave the chip short of wavefronts (a row block of a partitioned graph has few long rows).
+  int64_t slots_used = ceil_div(P, (int64_t)env_int("SAGNN_SWEEP_MIN_WAVES", 8192));
+  if (slots_used < 1) slots_used = 1;
+  if (slots_used > kSweepSlots) slots_used = kSweepSlots;
+  int64_t NW = ceil_div(P, slots_used);
+  if (NW > L.max_waves - 1) NW = ceil_div(P, kSweepSlots);
   std::vector<int32_t> info((size_t)NW * kSweepSlots * 2, -1), target((size_t)NW * kSweepSlots, INT32_MIN);
   std::vector<int64_t> wsize((size_t)NW, 0);
   // multi-piece rows: partial slots in row order
