@@ -52,7 +52,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg5_random"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg5_random", "cfg5_train"],
+                    help="cfg5_train: 2-layer GCN forward + backward on the whole 2 M-vertex graph of "
+                         "configuration 5 (bf16 MFMA GEMMs) instead of the plan+pack+spmm+gemm step")
     ap.add_argument("--f", type=int, default=None, help="feature width (default: the workload's)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -84,6 +86,9 @@ def main():
     kw = {"scale": args.scale}
     if args.f:
         kw["f"] = args.f
+    if args.workload == "cfg5_train":
+        print(json.dumps(train_step_bench(args, sagnn, workloads, torch, np, dev, kw)), flush=True)
+        return
     if args.workload == "cfg1":
         wl = workloads.cfg1()
     elif args.workload == "cfg5_random":
@@ -222,6 +227,83 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, g, args)
     print(json.dumps(out), flush=True)
+
+
+def train_step_bench(args, sagnn, workloads, torch, np, dev, kw):
+    """Configuration 5's training step: two GCN layers forward, then backward (Sec. 2.1 forward
+    and backward equations), on the whole community-ordered graph, f = 256 everywhere, GEMMs
+    with bf16 operands.  The forward is issued as separate SpMM / GEMM calls so that the SpMM
+    can be bracketed by events; the backward goes through gcn_layer_bwd."""
+    t0 = time.time()
+    wl = workloads.cfg5(**kw)
+    g, f = wl.g, wl.f
+    m, nnz = g.m, g.nnz
+    log(f"[bench] cfg5_train: n={m} nnz={nnz} f={f} generated in {time.time() - t0:.1f}s")
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    rp, ci, va = d(g.rowptr), d(g.colidx), d(g.val)
+    H0, W1, W2, G2 = d(wl.H), d(wl.W), d(wl.extra["W2"]), d(wl.extra["G2"])
+    ws = sagnn.spmm_csr_prepare(rp, ci, va, m, f)
+    log(f"[bench] spmm schedule: {ws.info()}")
+    T1 = torch.empty((m, f), dtype=torch.float32, device=dev)
+    Z1, H1, T2, Z2 = (torch.empty_like(T1) for _ in range(4))
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+    BF = sagnn.GEMM_BF16
+
+    def step(record):
+        e = [ev() for _ in range(7)]
+        e[0].record()
+        sagnn.spmm_csr_tallskinny(rp, ci, va, H0, C=T1, ws=ws)
+        e[1].record()
+        sagnn.dense_gemm_act(T1, W1, prec=BF, act=sagnn.ACT_RELU, want_z=True, want_act=True, out=(Z1, H1))
+        e[2].record()
+        sagnn.spmm_csr_tallskinny(rp, ci, va, H1, C=T2, ws=ws)
+        e[3].record()
+        sagnn.dense_gemm_act(T2, W2, prec=BF, act=sagnn.ACT_IDENTITY, want_z=True, out=(Z2, None))
+        e[4].record()
+        S2, G1, Y2 = sagnn.gcn_layer_bwd(rp, ci, va, G2, W2, Z1, H1, prec=BF, ws=ws)
+        e[5].record()
+        S1, _, Y1 = sagnn.gcn_layer_bwd(rp, ci, va, G1, W1, None, H0, prec=BF, ws=ws, want_gprev=False)
+        e[6].record()
+        if record:
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
+    ph = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(6)] for e in marks])
+    med = np.median(ph, axis=0)
+    mdl = workloads.byte_models(m, m, nnz, m, f, f)
+    tn_bytes = 2 * m * f * 4 + f * f * 4
+    step_bytes = 4 * mdl["spmm_bytes"] + 3 * mdl["gemm_bytes"] + 2 * tn_bytes
+    step_flops = 4 * mdl["spmm_flops"] + 5 * mdl["gemm_flops"]
+    spmm_ms = float((ph[:, 0].mean() + ph[:, 2].mean()) / 2)
+    spmm_gbps = mdl["spmm_bytes"] / (spmm_ms * 1e-3) / 1e9
+    return {
+        "metric": METRIC, "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"cfg5_train: SBM 2M vertices ordered by community, whole graph, m=n={m} nnz={nnz} "
+                               f"f={f}, 2-layer GCN forward + backward, GEMM operands bf16 (fp32 accumulate)",
+                   "step": "spmm+gemm_relu, spmm+gemm, bwd layer 2 (spmm, S W^T .* mask, H^T S), bwd layer 1 (spmm, H^T S)",
+                   "seed": 0, "spmm_schedule": ws.info(), "scale": args.scale},
+        "roofline": {"kernel": "spmm_csr_tallskinny (the two forward calls, bracketed by events)", "bound": "hbm",
+                     "achieved": round(spmm_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(spmm_gbps / HBM_PEAK_GBPS, 4), "traffic": parse_traffic("cfg5_train", f),
+                     "algorithmic_bytes": mdl["spmm_bytes"], "avg_ms": round(spmm_ms, 4),
+                     "gflops": round(mdl["spmm_flops"] / (spmm_ms * 1e-3) / 1e9, 1),
+                     "gather_delivery_GBps": round(mdl["spmm_gather_bytes"] / (spmm_ms * 1e-3) / 1e9, 1)},
+        "stages": {"median_ms": {k: round(float(v), 4) for k, v in zip(
+            ("fwd1_spmm", "fwd1_gemm_relu", "fwd2_spmm", "fwd2_gemm", "bwd2_layer", "bwd1_layer"), med)},
+            "step_TFLOPs": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
+            "fwd_gemm_TFLOPs": round(mdl["gemm_flops"] / (float(med[1]) * 1e-3) / 1e12, 2)},
+    }
 
 
 def stage_loop_timing(sagnn, torch, wl, plan, rp, va, Hd, m, f, reps):
