@@ -40,7 +40,7 @@ constexpr uint32_t kSpmmMagic = 0x53A66E02u;
 
 // Slab-sweep schedule (long rows): a wavefront owns kSweepSlots row pieces.
 constexpr int kSweepSlots = 16;
-constexpr int kSweepMaxSlabs = 128;
+constexpr int kSweepMaxSlabs = 384;
 constexpr int kSweepColBits = 27;           // column id bits in an encoded entry
 constexpr int kSweepMinLong = 16;           // smallest degree a "long" row can be given
 

@@ -26,6 +26,8 @@
 
 #include <algorithm>
 #include <atomic>
+#include <functional>
+#include <queue>
 #include <vector>
 
 #include "common.h"
@@ -425,11 +427,34 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   }
   if ((int64_t)multi_row.size() > L.max_multi_rows || (int64_t)multi_first.back() > L.max_multi_pieces)
     return SAGNN_OK;
+  // Inside a window: largest piece first, each to the wavefront with the shortest stream so far
+  // that still has a free slot (ties: lowest wavefront).  Streams come out equal to within a
+  // piece of the smallest size class, which keeps the wavefronts in step from slab to slab.
+  std::vector<int32_t> used((size_t)NW, 0);
+  using Load = std::pair<int64_t, int64_t>;   // (stream length, wavefront)
+  std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
+  int64_t cur_win = -1;
+  const bool lpt = env_int("SAGNN_SWEEP_LPT", 1) != 0;
   for (int64_t t = 0; t < P; ++t) {
     const int64_t win = t / window, tw = t - win * window;
     const int64_t nw = win_wave0[(size_t)win + 1] - win_wave0[(size_t)win];
-    const int64_t round = tw / nw, pos = tw % nw;
-    const int64_t wv = win_wave0[(size_t)win] + ((round & 1) ? nw - 1 - pos : pos);
+    int64_t wv, round;
+    if (lpt) {
+      if (win != cur_win) {
+        cur_win = win;
+        heap = decltype(heap)();
+        for (int64_t w = 0; w < nw; ++w) heap.push({0, win_wave0[(size_t)win] + w});
+      }
+      if (heap.empty()) return SAGNN_EINVAL;   // nw * kSweepSlots >= pieces of the window
+      wv = heap.top().second;
+      heap.pop();
+      round = used[(size_t)wv]++;
+      if (used[(size_t)wv] < kSweepSlots) heap.push({wsize[(size_t)wv] + pieces[(size_t)t].size, wv});
+    } else {
+      round = tw / nw;
+      const int64_t pos = tw % nw;
+      wv = win_wave0[(size_t)win] + ((round & 1) ? nw - 1 - pos : pos);
+    }
     const size_t g = (size_t)(wv * kSweepSlots + round);
     const Piece& pc = pieces[(size_t)t];
     info[2 * g] = pc.row;
