@@ -26,6 +26,19 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWordsPerBlock = 2048;  // scan tile: 256 threads x 8 words
 
+// LDS marking (column ranges small enough to be covered by a few LDS-resident bitmaps):
+// a workgroup owns a private bitmap of kLdsCols columns in LDS and a share of the entries.
+constexpr int kLdsThreads = 1024;
+constexpr int kLdsWords = 38912;                    // 32-bit words: 152 KB of the CU's 160 KB
+constexpr int64_t kLdsCols = (int64_t)kLdsWords * 32;
+constexpr int kLdsMaxPasses = 4;
+constexpr int kLdsGroups = 256;                     // workgroups in total (one per CU)
+constexpr int64_t kLdsMinNnz = 1ll << 22;
+
+inline bool lds_mark_eligible(int64_t n, int64_t nnz) {
+  return nnz >= kLdsMinNnz && n > 0 && n <= kLdsMaxPasses * kLdsCols;
+}
+
 struct PlanWs {
   uint8_t* flag;      // n bytes (rounded up to 64W)
   uint64_t* bitmap;   // W words
@@ -35,11 +48,12 @@ struct PlanWs {
   int64_t* colblk;    // nb + 1 (device copy of the block boundaries)
   int64_t* blkoff;    // nb + 1
   int32_t* err;       // 4 counters
+  uint32_t* part;     // LDS marking only: kLdsGroups private bitmaps of kLdsWords words
   int64_t W, nblk;
   size_t bytes;
 };
 
-PlanWs carve(void* base, int64_t n, int32_t nb) {
+PlanWs carve(void* base, int64_t n, int32_t nb, int64_t nnz) {
   PlanWs w;
   w.W = ceil_div(n > 0 ? n : 1, 64);
   w.nblk = ceil_div(w.W, kWordsPerBlock);
@@ -57,9 +71,14 @@ PlanWs carve(void* base, int64_t n, int32_t nb) {
   w.colblk = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
   w.blkoff = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
   w.err = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 4));
+  w.part = lds_mark_eligible(n, nnz)
+               ? reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)kLdsGroups * kLdsWords))
+               : nullptr;
   w.bytes = off;
   return w;
 }
+
+__device__ __forceinline__ int64_t ceil_div_dev(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 __global__ __launch_bounds__(kThreads) void clear_kernel(uint4* __restrict__ flag16, int64_t n16,
                                                          int32_t* __restrict__ err) {
@@ -118,6 +137,124 @@ __global__ __launch_bounds__(kThreads) void mark_kernel(const int32_t* __restric
   } else {
     for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride)
       mark_one(colidx[e], n, flag, err);
+  }
+}
+
+// --- LDS marking ---------------------------------------------------------------------------
+// Byte probes into a flag array cost one cache-line fill each (the array is far larger than
+// a CU's L1), which is what bounds mark_kernel.  When a few LDS-sized bitmaps cover all
+// columns, a workgroup instead ORs the bits of its share of the entries into a private LDS
+// bitmap of one column range (pass), reading colidx once per pass as a stream, and writes
+// the bitmap out; merge_kernel ORs the private bitmaps into the membership words.
+__device__ __forceinline__ void lds_mark_one(int32_t c, int64_t n, int64_t c0, uint32_t* bits,
+                                             int32_t* __restrict__ err) {
+  if (c < 0 || c >= n) {
+    err[1] = 1;
+    return;
+  }
+  const int64_t rel = (int64_t)c - c0;
+  if (rel >= 0 && rel < kLdsCols) {
+    // test first: lanes that read one address are served by a broadcast, lanes that update one
+    // address are serialised, and hub columns come up thousands of times
+    const uint32_t bit = 1u << (rel & 31);
+    if ((__hip_atomic_load(&bits[rel >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) & bit) == 0)
+      __hip_atomic_fetch_or(&bits[rel >> 5], bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+}
+
+__global__ __launch_bounds__(kLdsThreads) void mark_lds_kernel(const int32_t* __restrict__ colidx,
+                                                               int64_t nnz, int64_t n,
+                                                               int32_t groups_per_pass,
+                                                               uint32_t* __restrict__ part,
+                                                               int32_t* __restrict__ err, int aligned) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t bits[];
+  const int pass = blockIdx.x / groups_per_pass, share = blockIdx.x % groups_per_pass;
+  const int64_t c0 = (int64_t)pass * kLdsCols;
+  uint4* b4 = reinterpret_cast<uint4*>(bits);
+  for (int i = threadIdx.x; i < kLdsWords / 4; i += kLdsThreads) b4[i] = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();
+  if (aligned) {
+    const int64_t quads = nnz >> 2;
+    const int64_t per = ceil_div_dev(quads, groups_per_pass);
+    const int64_t q0 = (int64_t)share * per;
+    const int64_t q1 = q0 + per < quads ? q0 + per : quads;
+    const int4* __restrict__ c4 = reinterpret_cast<const int4*>(colidx);
+    for (int64_t q = q0 + threadIdx.x; q < q1; q += kLdsThreads) {
+      const int4 c = c4[q];
+      lds_mark_one(c.x, n, c0, bits, err);
+      lds_mark_one(c.y, n, c0, bits, err);
+      lds_mark_one(c.z, n, c0, bits, err);
+      lds_mark_one(c.w, n, c0, bits, err);
+    }
+    if (share == 0)
+      for (int64_t e = (quads << 2) + threadIdx.x; e < nnz; e += kLdsThreads)
+        lds_mark_one(colidx[e], n, c0, bits, err);
+  } else {
+    const int64_t per = ceil_div_dev(nnz, groups_per_pass);
+    const int64_t e0 = (int64_t)share * per;
+    const int64_t e1 = e0 + per < nnz ? e0 + per : nnz;
+    for (int64_t e = e0 + threadIdx.x; e < e1; e += kLdsThreads) lds_mark_one(colidx[e], n, c0, bits, err);
+  }
+  __syncthreads();
+  // only the words that cover columns below n are ever read back
+  const int64_t cols_here = n - c0 < kLdsCols ? n - c0 : kLdsCols;
+  const int used4 = cols_here > 0 ? (int)((cols_here + 127) >> 7) : 0;
+  uint4* __restrict__ out = reinterpret_cast<uint4*>(part + (size_t)blockIdx.x * kLdsWords);
+  for (int i = threadIdx.x; i < used4; i += kLdsThreads) out[i] = b4[i];
+}
+
+// Membership words from the private bitmaps.  A workgroup owns 16 consecutive 64-bit words;
+// thread (wi, sl) ORs the bitmaps of groups sl, sl+16, ... for word wi, LDS combines the 16
+// slices.
+__global__ __launch_bounds__(kThreads) void merge_kernel(const uint32_t* __restrict__ part,
+                                                         int32_t groups_per_pass, int64_t W, int64_t n,
+                                                         uint64_t* __restrict__ bm) {
+  __shared__ uint64_t red[16][17];
+  const int wi = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int64_t w = (int64_t)blockIdx.x * 16 + wi;
+  uint64_t word = 0;
+  if (w < W) {
+    const int64_t col = w * 64;
+    const int pass = (int)(col / kLdsCols);          // kLdsCols is a multiple of 64
+    const int64_t idx = (col - (int64_t)pass * kLdsCols) >> 5;
+    const uint32_t* __restrict__ p = part + ((size_t)pass * groups_per_pass) * kLdsWords + idx;
+#pragma unroll 4
+    for (int g = sl; g < groups_per_pass; g += 16) {
+      const uint2 t = *reinterpret_cast<const uint2*>(p + (size_t)g * kLdsWords);
+      word |= (uint64_t)t.x | ((uint64_t)t.y << 32);
+    }
+  }
+  red[sl][wi] = word;
+  __syncthreads();
+  if (sl == 0 && w < W) {
+#pragma unroll
+    for (int j = 1; j < 16; ++j) word |= red[j][wi];
+    const int64_t col = w * 64;
+    if (n - col < 64) word &= (1ull << (n - col)) - 1ull;
+    bm[w] = word;
+  }
+}
+
+// blocksum[b] = number of set bits in the b-th tile of kWordsPerBlock words (what words_kernel
+// produces on the byte-flag path)
+__global__ __launch_bounds__(kThreads) void count_kernel(const uint64_t* __restrict__ bm, int64_t W,
+                                                         int32_t* __restrict__ blocksum) {
+  __shared__ int wsum[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int cnt = 0;
+  for (int i = threadIdx.x; i < kWordsPerBlock; i += kThreads) {
+    const int64_t w = (int64_t)blockIdx.x * kWordsPerBlock + i;
+    if (w < W) cnt += __popcll(bm[w]);
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+  if (lane == 0) wsum[wave] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) t += wsum[w];
+    blocksum[blockIdx.x] = t;
   }
 }
 
@@ -305,7 +442,7 @@ SAGNN_EXPORT int spmm_plan_workspace_bytes(int64_t m, int64_t n, int64_t nnz, in
   using namespace sagnn;
   if (!bytes || m < 0 || n < 0 || nnz < 0 || nb < 1 || n > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
     return SAGNN_EINVAL;
-  *bytes = carve(nullptr, n, nb).bytes;
+  *bytes = carve(nullptr, n, nb, nnz).bytes;
   return SAGNN_OK;
 }
 
@@ -326,7 +463,7 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
   if (h_colblk[0] != 0 || h_colblk[nb] != n) return SAGNN_EFORMAT;
   for (int32_t q = 0; q < nb; ++q)
     if (h_colblk[q] > h_colblk[q + 1]) return SAGNN_EFORMAT;
-  const PlanWs w = carve(d_ws, n, nb);
+  const PlanWs w = carve(d_ws, n, nb, nnz);
   if (ws_bytes < w.bytes) return SAGNN_ECAPACITY;
   hipStream_t s = (hipStream_t)stream;
 
@@ -341,18 +478,37 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
     SAGNN_LAUNCH_CHECK();
   }
   const bool oblivious = (flags & SAGNN_PLAN_OBLIVIOUS) != 0;
-  if (nnz > 0 && (!oblivious || (flags & SAGNN_PLAN_VALIDATE))) {
-    hipLaunchKernelGGL(mark_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz,
-                       n, w.flag, w.err, aligned16(d_colidx) ? 1 : 0);
+  const bool lds_mark = !oblivious && w.part != nullptr;
+  if (lds_mark) {
+    const int passes = (int)ceil_div(n, kLdsCols);
+    const int groups_per_pass = kLdsGroups / passes;
+    const size_t lds = sizeof(uint32_t) * (size_t)kLdsWords;
+    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mark_lds_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(mark_lds_kernel, dim3((unsigned)(passes * groups_per_pass)), dim3(kLdsThreads),
+                       lds, s, d_colidx, nnz, n, (int32_t)groups_per_pass, w.part, w.err,
+                       aligned16(d_colidx) ? 1 : 0);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)ceil_div(w.W, 16)), dim3(kThreads), 0, s, w.part,
+                       (int32_t)groups_per_pass, w.W, n, w.bitmap);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(count_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.bitmap, w.W,
+                       w.blocksum);
+    SAGNN_LAUNCH_CHECK();
+  } else {
+    if (nnz > 0 && (!oblivious || (flags & SAGNN_PLAN_VALIDATE))) {
+      hipLaunchKernelGGL(mark_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz,
+                         n, w.flag, w.err, aligned16(d_colidx) ? 1 : 0);
+      SAGNN_LAUNCH_CHECK();
+    }
+    if (oblivious && n > 0) {
+      hipLaunchKernelGGL(fill_all_kernel, dim3(grid_for(n)), dim3(kThreads), 0, s, w.flag, n);
+      SAGNN_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(words_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.flag, w.W,
+                       w.bitmap, w.blocksum);
     SAGNN_LAUNCH_CHECK();
   }
-  if (oblivious && n > 0) {
-    hipLaunchKernelGGL(fill_all_kernel, dim3(grid_for(n)), dim3(kThreads), 0, s, w.flag, n);
-    SAGNN_LAUNCH_CHECK();
-  }
-  hipLaunchKernelGGL(words_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.flag, w.W,
-                     w.bitmap, w.blocksum);
-  SAGNN_LAUNCH_CHECK();
   hipLaunchKernelGGL(scan_blocks_kernel, dim3(1), dim3(kThreads), 0, s, w.blocksum, w.nblk);
   SAGNN_LAUNCH_CHECK();
   hipLaunchKernelGGL(prefix_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.bitmap, w.W,

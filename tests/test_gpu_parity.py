@@ -110,6 +110,36 @@ def test_plan_random_ragged(m, n, nb, avg, seed):
     check_plan(rowptr, colidx, n, colblk)
 
 
+@pytest.mark.parametrize("n,nnz,misalign", [(1_000_000, 4_300_000, 0), (1_245_185, 4_200_003, 1),
+                                            (2_700_001, 4_500_001, 3), (4_980_736, 4_194_304, 0)])
+def test_plan_large_entry_counts_lds_marking(n, nnz, misalign):
+    """Entry counts above 2^22 with at most ~5 M columns take the LDS-bitmap marking path
+    (1 to 4 column ranges); the column array is also given at a 4-byte-but-not-16-byte aligned
+    address.  Power-law-like columns (squared uniform) plus the last column of every range."""
+    rng = np.random.default_rng(n % 97)
+    m = 5000
+    cols = (rng.random(nnz) ** 2 * n).astype(np.int64)
+    cols[:8] = [0, n - 1, min(n - 1, 1_245_183), min(n - 1, 1_245_184), min(n - 1, 2_490_367),
+                min(n - 1, 2_490_368), min(n - 1, 3_735_552), n // 2]
+    cuts = np.sort(rng.integers(0, nnz + 1, size=m - 1))
+    rowptr = np.array([0, *cuts, nnz], dtype=np.int32)
+    colidx = cols.astype(np.int32)
+    colblk = np.array([0, n // 3, n // 3, n - 5, n], dtype=np.int64)
+    buf = torch.empty(nnz + 4, dtype=torch.int32, device="cuda")
+    ci = buf[misalign:misalign + nnz]
+    ci.copy_(torch.from_numpy(colidx))
+    plan = sagnn.spmm_plan_needed_rows(dev(rowptr), ci, n, colblk, validate=True)
+    torch.cuda.synchronize()
+    needed, blk_off, compact = oracle.needed_rows(rowptr, colidx, n, colblk)
+    assert np.array_equal(plan.blk_off, blk_off)
+    assert np.array_equal(plan.needed.cpu().numpy(), needed)
+    assert np.array_equal(plan.colidx_compact.cpu().numpy(), compact)
+    ci[12345] = n                                           # out of range: validation must see it
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_plan_needed_rows(dev(rowptr), ci, n, colblk, validate=True)
+    assert ei.value.code == -3
+
+
 def test_plan_empty_matrix_and_capacity_and_validate():
     rp = np.zeros(6, np.int32)
     plan = sagnn.spmm_plan_needed_rows(dev(rp), torch.empty(0, dtype=torch.int32, device="cuda"), 100,
