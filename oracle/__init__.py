@@ -26,30 +26,34 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def _declare(L):
+    """Argument and result types of the library's entry points."""
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    L.oracle_needed_rows.restype = i64
+    L.oracle_needed_rows.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp]
+    L.oracle_pack_rows.restype = None
+    L.oracle_pack_rows.argtypes = [vp, i64, i32, vp, i64, vp, i64]
+    L.oracle_spmm.restype = None
+    L.oracle_spmm.argtypes = [vp, vp, vp, i64, vp, i64, i32, vp, i64, i32, vp]
+    L.oracle_gemm.restype = None
+    L.oracle_gemm.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i64, i32, vp, i64, vp, vp]
+    L.oracle_gcn_layer_fwd.restype = None
+    L.oracle_gcn_layer_fwd.argtypes = [vp, vp, vp, i64, vp, i64, i32, vp, i32, i32, i32,
+                                       vp, vp, vp, vp, vp]
+    L.oracle_gcn_layer_bwd.restype = None
+    L.oracle_gcn_layer_bwd.argtypes = [vp, vp, vp, i64, vp, i32, vp, i32, vp, vp, i32,
+                                       vp, vp, vp, vp, vp, vp]
+    L.oracle_bf16_round.restype = ctypes.c_float
+    L.oracle_bf16_round.argtypes = [ctypes.c_float]
+    L.oracle_max_threads.restype = i32
+    return L
+
+
 def _L():
     global _lib
     if _lib is None:
         build()
-        L = ctypes.CDLL(_LIB)
-        i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
-        L.oracle_needed_rows.restype = i64
-        L.oracle_needed_rows.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp]
-        L.oracle_pack_rows.restype = None
-        L.oracle_pack_rows.argtypes = [vp, i64, i32, vp, i64, vp, i64]
-        L.oracle_spmm.restype = None
-        L.oracle_spmm.argtypes = [vp, vp, vp, i64, vp, i64, i32, vp, i64, i32, vp]
-        L.oracle_gemm.restype = None
-        L.oracle_gemm.argtypes = [vp, i64, i32, vp, i64, i32, i64, i64, i64, i32, vp, i64, vp, vp]
-        L.oracle_gcn_layer_fwd.restype = None
-        L.oracle_gcn_layer_fwd.argtypes = [vp, vp, vp, i64, vp, i64, i32, vp, i32, i32, i32,
-                                           vp, vp, vp, vp, vp]
-        L.oracle_gcn_layer_bwd.restype = None
-        L.oracle_gcn_layer_bwd.argtypes = [vp, vp, vp, i64, vp, i32, vp, i32, vp, vp, i32,
-                                           vp, vp, vp, vp, vp, vp]
-        L.oracle_bf16_round.restype = ctypes.c_float
-        L.oracle_bf16_round.argtypes = [ctypes.c_float]
-        L.oracle_max_threads.restype = i32
-        _lib = L
+        _lib = _declare(ctypes.CDLL(_LIB))
     return _lib
 
 
