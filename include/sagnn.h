@@ -250,6 +250,24 @@ int spmm_split_colblocks(const int32_t* d_rowptr, const int32_t* d_colidx, const
                          int64_t* h_nnz_off, void* d_ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * CSR transpose (Sec. 2.1 / Sec. 4.1: the forward pass multiplies by A^T, the backward pass by
+ * A; for a directed graph the two differ, and a process needs both orientations of its block).
+ *
+ * Writes A^T (n rows, m columns, nnz entries) as CSR: d_rowptr_t[n+1], d_colidx_t[nnz] (row
+ * ids of A), d_val_t[nnz].  The entries of a transposed row are in ascending order of the
+ * row of A they came from, entries of one row of A that repeat a column keep their stored
+ * order (stable), so the result is unique: bit-exact.  Returns SAGNN_EFORMAT if a column index
+ * is outside [0,n) (outputs are then unspecified, nothing faults).  One-time set-up step;
+ * synchronises the stream once.  d_ws: scratch of spmm_transpose_workspace_bytes() bytes
+ * (about 16 bytes per stored entry).
+ */
+int spmm_transpose_workspace_bytes(int64_t nnz, size_t* bytes);
+int spmm_csr_transpose(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                       int64_t m, int64_t n, int64_t nnz, int32_t* d_rowptr_t,
+                       int32_t* d_colidx_t, float* d_val_t, void* d_ws, size_t ws_bytes,
+                       void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Stage loop of one rank of the 1.5D algorithm (Alg. 2, the loop over k = 0..s-1 with
  * q = j*s + k: obtain the rows NnzCols(i,q) of H, then Z^ <- Z^ + SpMM(A_iq, H^)).
  *

@@ -146,6 +146,7 @@ def gcn_layer_bwd(rowptr, colidx, val, G, W, Zprev, Hprev, bf16=False, want_gpre
     fi = W.shape[0]
     assert W.shape[1] == fo and Hprev.shape == (m, fi)
     Zp = None if Zprev is None else _c(Zprev, np.float32)
+    assert Zp is None or Zp.shape == (m, fi)
     S = np.empty((m, fo), np.float32)
     Gp = np.empty((m, fi), np.float32) if want_gprev else None
     Y = np.empty((fi, fo), np.float32)
@@ -236,3 +237,19 @@ def volume_stats(counts, f, elem_bytes=4):
             "recv_imbalance_pct": imb(recv.max()), "max_send_bytes": send.max(),
             "send_imbalance_pct": imb(send.max()), "cut_rows": off.max(),
             "cut_bytes": off.max() * row_bytes}
+
+
+def transpose_csr(rowptr, colidx, val, n):
+    """CSR of A^T (Sec. 2.1: the forward pass uses A^T, the backward pass A).  Entry (r, c, v) of
+    A becomes entry (c, r, v); inside a row of A^T the entries are ordered by r, entries of one
+    row of A that repeat a column keep their stored order.  That is a stable sort of the entries
+    by column (library sort as the step), the row ids and values carried along."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    colidx = np.asarray(colidx, dtype=np.int64)
+    val = np.asarray(val, dtype=np.float32)
+    m = rowptr.size - 1
+    row_of = np.repeat(np.arange(m, dtype=np.int64), np.diff(rowptr))
+    perm = np.argsort(colidx, kind="stable")
+    rpt = np.zeros(n + 1, dtype=np.int64)
+    rpt[1:] = np.cumsum(np.bincount(colidx, minlength=n)[:n])
+    return rpt.astype(np.int32), row_of[perm].astype(np.int32), val[perm].copy()

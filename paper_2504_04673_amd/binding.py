@@ -20,6 +20,7 @@ EXPORTS = [
     "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_schedule_info", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
+    "spmm_transpose_workspace_bytes", "spmm_csr_transpose",
 ]
 
 
@@ -80,6 +81,8 @@ def lib():
         L.spmm_stage_loop.argtypes = [vp, i32, i64, vp, i64, i64, i32, vp, vp, i64, vp, i64, i32, vp,
                                       vp]
         L.spmm_volume_stats.argtypes = [vp, i32, i32, i32, vp]
+        L.spmm_transpose_workspace_bytes.argtypes = [i64, psz]
+        L.spmm_csr_transpose.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, sz, vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -380,3 +383,22 @@ def spmm_volume_stats(counts, f: int, elem_bytes: int = 4) -> dict:
     keys = ("total_bytes", "avg_bytes", "max_recv_bytes", "recv_imbalance_pct", "max_send_bytes",
             "send_imbalance_pct", "cut_rows", "cut_bytes")
     return dict(zip(keys, (float(x) for x in out)))
+
+
+def spmm_csr_transpose(rowptr, colidx, val, n: int):
+    """CSR of A^T for A = (rowptr, colidx, val) with n columns.  Returns (rowptr_t, colidx_t, val_t)."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    dev = rowptr.device
+    L = lib()
+    wsb = ctypes.c_size_t(0)
+    _check(L.spmm_transpose_workspace_bytes(nnz, ctypes.byref(wsb)), "spmm_transpose_workspace_bytes")
+    ws = _ws(wsb.value, dev)
+    rpt = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    cit = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    vat = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)
+    _check(L.spmm_csr_transpose(_ptr(rowptr), _ptr(colidx), _ptr(val), m, n, nnz, _ptr(rpt), _ptr(cit),
+                                _ptr(vat), _ptr(ws), ws.numel(), _stream()), "spmm_csr_transpose")
+    return rpt, cit[:nnz], vat[:nnz]

@@ -208,6 +208,140 @@ __global__ void split_offsets_kernel(const int32_t* __restrict__ tilesum, int64_
   nnz_off[nb] = run;
 }
 
+// ------------------------------------------------------------------------------------------
+// Transpose by a stable least-significant-digit radix sort of (column, entry index) pairs.
+// One pass = the same three steps as the column-block split, with tiles of kSortTile entries
+// in place of rows and the 256 values of an 8-bit digit in place of the column blocks: count
+// per (digit, tile), scan along the tiles of each digit, scatter with the tile-local stable
+// rank.  Stability makes the entries of a transposed row come out in the order of the rows
+// they came from (ascending), and keeps duplicates in their stored order.
+constexpr int kSortTile = 2048;
+
+template <bool SCATTER>
+__global__ __launch_bounds__(kThreads) void radix_tile_kernel(
+    const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ pay_in, int64_t nnz, int shift,
+    int64_t ntiles, int32_t* __restrict__ counts, const int64_t* __restrict__ digit_off,
+    uint32_t* __restrict__ keys_out, uint32_t* __restrict__ pay_out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
+  const int64_t nwaves = ((int64_t)gridDim.x * kThreads) >> 6;
+  for (int64_t t = wave0; t < ntiles; t += nwaves) {
+    const int64_t b = t * kSortTile;
+    const int64_t e = b + kSortTile < nnz ? b + kSortTile : nnz;
+    int32_t cnt[4] = {0, 0, 0, 0};
+    for (int64_t base = b; base < e; base += 64) {
+      const int64_t i = base + lane;
+      const bool active = i < e;
+      const uint32_t key = active ? keys_in[i] : 0u;
+      const int q = active ? (int)((key >> shift) & 255u) : -1;
+      uint64_t remaining = __ballot(q >= 0);
+      while (remaining) {
+        const int leader = __builtin_ctzll(remaining);
+        const int q0 = __shfl(q, leader, 64);
+        const uint64_t mask = __ballot(q == q0);
+        int32_t have = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int32_t v = __shfl(cnt[j], q0 & 63, 64);
+          if (j == (q0 >> 6)) have = v;
+        }
+        if (SCATTER && q == q0) {
+          const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+          const int64_t o = digit_off[q0] + counts[(int64_t)q0 * (ntiles + 1) + t] + have + rank;
+          if (o >= 0 && o < nnz) {
+            keys_out[o] = key;
+            pay_out[o] = pay_in ? pay_in[i] : (uint32_t)i;
+          }
+        }
+        if (lane == (q0 & 63)) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (j == (q0 >> 6)) cnt[j] += __popcll(mask);
+        }
+        remaining &= ~mask;
+      }
+    }
+    if (!SCATTER) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) counts[(int64_t)(j * 64 + lane) * (ntiles + 1) + t] = cnt[j];
+    }
+  }
+}
+
+// err[0] = 1 if some column index is outside [0, n)
+__global__ __launch_bounds__(kThreads) void transpose_check_kernel(const int32_t* __restrict__ colidx,
+                                                                   int64_t nnz, int64_t n,
+                                                                   int32_t* __restrict__ err) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nnz; i += stride)
+    if (colidx[i] < 0 || colidx[i] >= n) err[0] = 1;
+}
+
+// rowptr_t[c] = number of sorted keys below c (lower bound), c in [0, n]
+__global__ __launch_bounds__(kThreads) void transpose_rowptr_kernel(const uint32_t* __restrict__ keys,
+                                                                    int64_t nnz, int64_t n,
+                                                                    int32_t* __restrict__ rowptr_t) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c <= n; c += stride) {
+    int64_t lo = 0, hi = nnz;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)keys[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    rowptr_t[c] = (int32_t)lo;
+  }
+}
+
+// entry i of the transpose is entry perm[i] of A: its column there is A's row of that entry
+__global__ __launch_bounds__(kThreads) void transpose_gather_kernel(
+    const int32_t* __restrict__ rowptr, const float* __restrict__ val, int64_t m, int64_t nnz,
+    const uint32_t* __restrict__ perm, int32_t* __restrict__ colidx_t, float* __restrict__ val_t) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nnz; i += stride) {
+    const int64_t e = perm[i];
+    int64_t lo = 0, hi = m;            // largest r with rowptr[r] <= e
+    while (hi - lo > 1) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)rowptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    colidx_t[i] = (int32_t)lo;
+    val_t[i] = e < nnz ? val[e] : 0.f;
+  }
+}
+
+struct TransposeWs {
+  uint32_t *keys[2], *pay[2];
+  int32_t* counts;     // [256][ntiles + 1]
+  int32_t* tilesum;    // [256][nscan + 1]
+  int64_t* digit_off;  // [257]
+  int32_t* err;
+  int64_t ntiles, nscan;
+  size_t bytes;
+};
+
+TransposeWs carve_transpose(void* base, int64_t nnz) {
+  TransposeWs w{};
+  w.ntiles = ceil_div(nnz > 0 ? nnz : 1, kSortTile);
+  w.nscan = ceil_div(w.ntiles + 1, kScanTile);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? static_cast<char*>(base) + off : nullptr;
+    off += round_up(bytes, 256);
+    return p;
+  };
+  for (int i = 0; i < 2; ++i) {
+    w.keys[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)(nnz > 0 ? nnz : 1)));
+    w.pay[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)(nnz > 0 ? nnz : 1)));
+  }
+  w.counts = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(w.ntiles + 1)));
+  w.tilesum = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(w.nscan + 1)));
+  w.digit_off = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * 257));
+  w.err = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 4));
+  w.bytes = off;
+  return w;
+}
+
 unsigned wave_grid(int64_t rows) {
   int64_t b = ceil_div(rows, kThreads / 64);
   if (b > 256 * 64) b = 256 * 64;
@@ -273,6 +407,83 @@ SAGNN_EXPORT int spmm_split_colblocks(const int32_t* d_rowptr, const int32_t* d_
                            hipMemcpyDeviceToHost, s));
   SAGNN_HIP(hipStreamSynchronize(s));
   if (h_nnz_off[nb] > nnz) return SAGNN_EFORMAT;   // rows overlap: rowptr is not a CSR row pointer
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_transpose_workspace_bytes(int64_t nnz, size_t* bytes) {
+  using namespace sagnn;
+  if (!bytes || nnz < 0 || nnz > 0x7FFFFFFFll) return SAGNN_EINVAL;
+  *bytes = carve_transpose(nullptr, nnz).bytes;
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_csr_transpose(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                    const float* d_val, int64_t m, int64_t n, int64_t nnz,
+                                    int32_t* d_rowptr_t, int32_t* d_colidx_t, float* d_val_t,
+                                    void* d_ws, size_t ws_bytes, void* stream) {
+  using namespace sagnn;
+  if (m < 0 || n < 0 || nnz < 0 || m > 0x7FFFFFFFll || n > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  if (!d_rowptr || !d_rowptr_t || !d_ws) return SAGNN_EINVAL;
+  if (nnz > 0 && (!d_colidx || !d_val || !d_colidx_t || !d_val_t)) return SAGNN_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return SAGNN_EINVAL;
+  const TransposeWs w = carve_transpose(d_ws, nnz);
+  if (ws_bytes < w.bytes) return SAGNN_ECAPACITY;
+  hipStream_t s = (hipStream_t)stream;
+  auto grid = [](int64_t items) {
+    int64_t b = ceil_div(items, kThreads);
+    if (b > 256 * 32) b = 256 * 32;
+    if (b < 1) b = 1;
+    return dim3((unsigned)b);
+  };
+  SAGNN_HIP(hipMemsetAsync(w.err, 0, sizeof(int32_t) * 4, s));
+  const uint32_t* sorted_keys = reinterpret_cast<const uint32_t*>(d_colidx);
+  const uint32_t* perm = nullptr;
+  if (nnz > 0) {
+    hipLaunchKernelGGL(transpose_check_kernel, grid(nnz), dim3(kThreads), 0, s, d_colidx, nnz, n, w.err);
+    SAGNN_LAUNCH_CHECK();
+    int bits = 1;
+    while (bits < 31 && (1ll << bits) < n) ++bits;
+    const int passes = (bits + 7) / 8;
+    const dim3 sgrid((unsigned)w.nscan, 256u);
+    for (int pass = 0; pass < passes; ++pass) {
+      const uint32_t* kin = pass == 0 ? reinterpret_cast<const uint32_t*>(d_colidx) : w.keys[(pass - 1) & 1];
+      const uint32_t* pin = pass == 0 ? nullptr : w.pay[(pass - 1) & 1];
+      uint32_t* kout = w.keys[pass & 1];
+      uint32_t* pout = w.pay[pass & 1];
+      hipLaunchKernelGGL(radix_tile_kernel<false>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin,
+                         nnz, pass * 8, w.ntiles, w.counts, (const int64_t*)nullptr, (uint32_t*)nullptr,
+                         (uint32_t*)nullptr);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(split_scan_kernel<0>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan,
+                         w.tilesum);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(split_scan_tiles_kernel, dim3(256), dim3(kThreads), 0, s, w.tilesum, w.nscan);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(split_scan_kernel<1>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan,
+                         w.tilesum);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(64), 0, s, w.tilesum, w.nscan, 256, w.digit_off);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(radix_tile_kernel<true>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin,
+                         nnz, pass * 8, w.ntiles, w.counts, (const int64_t*)w.digit_off, kout, pout);
+      SAGNN_LAUNCH_CHECK();
+      sorted_keys = kout;
+      perm = pout;
+    }
+  }
+  hipLaunchKernelGGL(transpose_rowptr_kernel, grid(n + 1), dim3(kThreads), 0, s, sorted_keys, nnz, n,
+                     d_rowptr_t);
+  SAGNN_LAUNCH_CHECK();
+  if (nnz > 0) {
+    hipLaunchKernelGGL(transpose_gather_kernel, grid(nnz), dim3(kThreads), 0, s, d_rowptr, d_val, m, nnz,
+                       perm, d_colidx_t, d_val_t);
+    SAGNN_LAUNCH_CHECK();
+  }
+  int32_t h_err[4] = {0, 0, 0, 0};
+  SAGNN_HIP(hipMemcpyAsync(h_err, w.err, sizeof(h_err), hipMemcpyDeviceToHost, s));
+  SAGNN_HIP(hipStreamSynchronize(s));
+  if (h_err[0]) return SAGNN_EFORMAT;
   return SAGNN_OK;
 }
 

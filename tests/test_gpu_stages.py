@@ -181,3 +181,79 @@ def test_volume_stats_cfg1_all_row_blocks(cfg1):
             assert got[k] == pytest.approx(v, rel=1e-12), k
     aware, obl = sagnn.spmm_volume_stats(counts, 16), sagnn.spmm_volume_stats(np.tile(np.diff(off), (P, 1)), 16)
     assert aware["total_bytes"] < obl["total_bytes"] and aware["cut_rows"] <= 1024
+
+
+def check_transpose(rowptr, colidx, val, n):
+    rpt, cit, vat = sagnn.spmm_csr_transpose(dev(rowptr), dev(colidx), dev(val), n)
+    torch.cuda.synchronize()
+    erp, eci, eva = oracle.transpose_csr(rowptr, colidx, val, n)
+    assert np.array_equal(rpt.cpu().numpy(), erp)
+    assert np.array_equal(cit.cpu().numpy(), eci)
+    assert vat.cpu().numpy().tobytes() == eva.tobytes()
+    return rpt, cit, vat
+
+
+@pytest.mark.parametrize("case", ["cfg1", "rect_unsorted_dup", "hub_and_empty", "three_passes", "four_passes",
+                                  "one_column", "empty"])
+def test_csr_transpose(case, cfg1):
+    g, _ = cfg1
+    rng = np.random.default_rng(12)
+    if case == "cfg1":
+        rpt, cit, vat = check_transpose(g.rowptr, g.colidx, g.val, g.n)
+        # the normalised adjacency matrix is symmetric: its transpose is itself
+        assert np.array_equal(rpt.cpu().numpy(), g.rowptr) and np.array_equal(cit.cpu().numpy(), g.colidx)
+    elif case == "rect_unsorted_dup":
+        rowptr, colidx, val = random_csr(700, 300, 0.05, rng, sort=False, dup=True)
+        check_transpose(rowptr, colidx, val, 300)
+    elif case == "hub_and_empty":
+        hub = np.sort(rng.choice(60000, size=9000, replace=False))
+        rows = [np.empty(0, np.int64), hub, np.empty(0, np.int64)] + \
+               [np.sort(rng.choice(60000, size=5, replace=False)) for _ in range(3000)]
+        rowptr = np.concatenate([[0], np.cumsum([r.size for r in rows])]).astype(np.int32)
+        colidx = np.concatenate(rows).astype(np.int32)
+        val = rng.standard_normal(colidx.size).astype(np.float32)
+        check_transpose(rowptr, colidx, val, 60000)
+    elif case in ("three_passes", "four_passes"):
+        n = 5_000_000 if case == "three_passes" else 20_000_000        # 23 and 25 column bits
+        nnz = 300_000
+        cols = rng.integers(0, n, size=nnz)
+        cols[:3] = [0, n - 1, n - 1]
+        cuts = np.sort(rng.integers(0, nnz + 1, size=999))
+        rowptr = np.array([0, *cuts, nnz], dtype=np.int32)
+        check_transpose(rowptr, cols.astype(np.int32), rng.standard_normal(nnz).astype(np.float32), n)
+    elif case == "one_column":
+        rowptr = np.arange(0, 5001, dtype=np.int32)
+        check_transpose(rowptr, np.zeros(5000, np.int32), rng.standard_normal(5000).astype(np.float32), 1)
+    else:
+        z = np.zeros(0, dtype=np.int32)
+        rpt, cit, vat = sagnn.spmm_csr_transpose(dev(np.zeros(8, np.int32)), dev(z), dev(z.astype(np.float32)), 11)
+        assert rpt.cpu().numpy().tolist() == [0] * 12
+        bad = np.array([0, 5, 11], dtype=np.int32)           # column 11 is outside [0, 11)
+        with pytest.raises(sagnn.SagnnError) as e:
+            sagnn.spmm_csr_transpose(dev(np.array([0, 3], np.int32)), dev(bad), dev(np.ones(3, np.float32)), 11)
+        assert e.value.code == -3
+
+
+def test_directed_graph_layer_uses_both_orientations():
+    """Directed graph: the forward product runs on A^T (Sec. 2.1 forward equation), the backward
+    product on A.  A^T comes from the device transpose; both layer calls against the oracle."""
+    rng = np.random.default_rng(21)
+    n, f_in, f_out = 900, 64, 32
+    rowptr, colidx, val = random_csr(n, n, 0.02, rng, sort=True)
+    H = rng.standard_normal((n, f_in)).astype(np.float32)
+    W = (rng.standard_normal((f_in, f_out)) / 8).astype(np.float32)
+    G = rng.standard_normal((n, f_out)).astype(np.float32)
+    rp, ci, va = dev(rowptr), dev(colidx), dev(val)
+    rpt, cit, vat = sagnn.spmm_csr_transpose(rp, ci, va, n)
+    T, Z, Ho = sagnn.gcn_layer_fwd(rpt, cit, vat, dev(H), dev(W), act=sagnn.ACT_RELU)
+    ot = oracle.transpose_csr(rowptr, colidx, val, n)
+    of = oracle.gcn_layer_fwd(ot[0], ot[1], ot[2], H, W, act=1)
+    assert_close(T, of["T"], of["Tabs"], RTOL_SPMM, "directed T")
+    assert_close(Z, of["Z"], of["Zabs"], 1e-5, "directed Z")
+    assert_close(Ho, of["H"], of["Zabs"], 1e-5, "directed H'")
+    Zprev = rng.standard_normal((n, f_in)).astype(np.float32)     # stand-in for Z^{l-1} (mask source)
+    S, Gp, Y = sagnn.gcn_layer_bwd(rp, ci, va, dev(G), dev(W), dev(Zprev), dev(H))
+    ob = oracle.gcn_layer_bwd(rowptr, colidx, val, G, W, Zprev, H)
+    assert_close(S, ob["S"], ob["Sabs"], RTOL_SPMM, "directed S")
+    assert_close(Gp, ob["Gprev"], ob["Gabs"], 1e-5, "directed Gprev")
+    assert_close(Y, ob["Y"], ob["Yabs"], 1e-5, "directed Y")

@@ -5,6 +5,7 @@ import os
 
 import numpy as np
 import pytest
+import scipy.sparse as sp
 
 import oracle
 from tests.test_oracle_pins import dense_of, random_csr
@@ -129,3 +130,38 @@ def test_stage_loop_equals_dense_product_of_selected_blocks():
     assert np.all(np.abs(Z - ref) <= 1e-6 * Zabs + 1e-30)
     full = oracle.stage_loop(blocks, [needed[off[q]:off[q + 1]] for q in range(5)], H, m)
     assert np.allclose(full, D @ H.astype(np.float64), rtol=0, atol=1e-5)
+
+
+@pytest.mark.parametrize("seed,sort,dup", [(0, True, False), (1, False, True), (2, False, False)])
+def test_transpose_bruteforce_and_scipy(seed, sort, dup):
+    """Entry-by-entry definition in pure Python (rows ascending, stored order inside a row), the
+    dense transpose, and scipy's CSR->CSC conversion where the matrix has no duplicates."""
+    rng = np.random.default_rng(seed)
+    m, n = 17, 29
+    rowptr, colidx, val = random_csr(m, n, 0.25, rng, sort=sort, dup=dup)
+    rpt, cit, vat = oracle.transpose_csr(rowptr, colidx, val, n)
+    exp = [[] for _ in range(n)]
+    for r in range(m):
+        for e in range(rowptr[r], rowptr[r + 1]):
+            exp[int(colidx[e])].append((r, val[e]))
+    assert rpt.tolist() == [0] + list(np.cumsum([len(x) for x in exp]))
+    assert cit.tolist() == [r for x in exp for r, _ in x]
+    assert np.array_equal(vat, np.array([v for x in exp for _, v in x], dtype=np.float32))
+    D = np.array(dense_of(rowptr, colidx, val, n))
+    Dt = np.array(dense_of(rpt, cit, vat, m))
+    assert np.array_equal(Dt, D.T)
+    if not dup:
+        A = sp.csr_matrix((val, colidx, rowptr), shape=(m, n))
+        T = A.tocsc()                       # CSC of A = CSR of A^T, row ids ascending per column
+        T.sort_indices()
+        assert np.array_equal(T.indptr, rpt) and np.array_equal(T.indices, cit) and np.array_equal(T.data, vat)
+
+
+def test_transpose_twice_is_identity_for_sorted_rows():
+    rng = np.random.default_rng(4)
+    rowptr, colidx, val = random_csr(40, 33, 0.2, rng, sort=True)
+    rpt, cit, vat = oracle.transpose_csr(rowptr, colidx, val, 33)
+    rp2, ci2, va2 = oracle.transpose_csr(rpt, cit, vat, 40)
+    assert np.array_equal(rp2, rowptr) and np.array_equal(ci2, colidx) and np.array_equal(va2, val)
+    empty = oracle.transpose_csr(np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32), 5)
+    assert empty[0].tolist() == [0] * 6 and empty[1].size == 0
