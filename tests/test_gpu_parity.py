@@ -225,6 +225,38 @@ def test_spmm_slab_sweep_schedule(f, force_sweep):
     assert_close(got2, ref2, zabs2, RTOL_SPMM, f"sweep accumulate f={f}")
 
 
+@pytest.mark.parametrize("variant", ["sixteen_pieces_per_wavefront", "many_small_windows", "snake_dealing",
+                                     "one_window_long_threshold_64"])
+def test_spmm_slab_sweep_planner_variants(variant, force_sweep, monkeypatch):
+    """The planner's alternatives (pieces per wavefront, dealing windows, dealing order,
+    thresholds) all have to give the same product; small inputs take them through the
+    environment overrides the experiments use."""
+    if variant == "sixteen_pieces_per_wavefront":
+        monkeypatch.setenv("SAGNN_SWEEP_MIN_WAVES", "1")
+    elif variant == "many_small_windows":
+        monkeypatch.setenv("SAGNN_SWEEP_MIN_WAVES", "64")
+        monkeypatch.setenv("SAGNN_SWEEP_WINDOW_PCT", "1")
+    elif variant == "snake_dealing":
+        monkeypatch.setenv("SAGNN_SWEEP_MIN_WAVES", "1")
+        monkeypatch.setenv("SAGNN_SWEEP_LPT", "0")
+    else:
+        monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "64")
+        monkeypatch.setenv("SAGNN_SWEEP_WINDOW_PCT", "0")
+        monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "1")
+    f = 128
+    rng = np.random.default_rng(77)
+    m, n = 9001, 50_000
+    rowptr, colidx, val = random_csr(m, n, 30, rng, empty_frac=0.05,
+                                     hubs=[(0, 20000), (1, 4097), (4500, 2048), (9000, 700), (17, 64), (18, 63)])
+    B = synth.normal((n, f), 3, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    got = run_spmm(rowptr, colidx, val, B, True, expect_mode=1)
+    assert_close(got, ref, zabs, RTOL_SPMM, f"sweep planner variant {variant}")
+    C0 = synth.normal((m, f), 4, synth.STREAM_G)
+    ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
+    assert_close(run_spmm(rowptr, colidx, val, B, True, C0=C0), ref2, zabs2, RTOL_SPMM, f"{variant} accumulate")
+
+
 def test_spmm_slab_sweep_falls_back_on_unsorted_rows(force_sweep):
     rng = np.random.default_rng(5)
     m, n, f = 2000, 30_000, 128
