@@ -56,6 +56,7 @@ struct SpmmWsHeader {       // first 256 bytes of the SpMM workspace (device cop
   // sweep part
   int64_t n_waves, n_long_entries, n_multi_rows, n_multi_pieces;
   int32_t n_slabs, slab_width;
+  int32_t groups;           // lane groups per wavefront in the sweep streams (1, 2 or 4)
 };
 static_assert(sizeof(SpmmWsHeader) <= 256, "header must fit its slot");
 
@@ -76,8 +77,10 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   L.max_waves = ceil_div(L.max_pieces, kSweepSlots) + 1;
   L.max_multi_rows = nnz / 1024 + 1;
   L.max_multi_pieces = 2 * (nnz / 1024) + 2;
-  // sweep streams (each padded to 8 entries) + gap + short CSR entries + padding
-  L.stream_cap = nnz + 8 * L.max_waves + 4 * kSpmmChunk;
+  // sweep streams + gap + short CSR entries + padding.  A wavefront's stream is padded to the
+  // batch of 8 steps; with lane groups (up to 4 zipped streams per wavefront) also to the longest
+  // of its group streams, which the planner keeps within a small piece of each other.
+  L.stream_cap = nnz + nnz / 8 + 64 * L.max_waves + 4 * kSpmmChunk;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   L.header = take(256);
@@ -107,6 +110,7 @@ struct SpmmHostDesc {
   int64_t c_rows, c_nnz, c_nchunks;
   int64_t n_waves, n_multi_rows, sweep_stream_len;
   int32_t has_empty_rows;
+  int32_t groups;
 };
 void spmm_desc_put(const void* ws, const SpmmHostDesc& d);
 bool spmm_desc_get(const void* ws, SpmmHostDesc* d);

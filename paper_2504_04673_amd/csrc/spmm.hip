@@ -653,6 +653,7 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
   desc.c_rows = h.c_rows; desc.c_nnz = h.c_nnz; desc.c_nchunks = h.c_nchunks;
   desc.n_waves = h.n_waves; desc.n_multi_rows = h.n_multi_rows; desc.has_empty_rows = h.has_empty_rows;
   desc.sweep_stream_len = h.n_long_entries;
+  desc.groups = h.groups > 0 ? h.groups : 1;
   spmm_desc_put(d_ws, desc);
   return SAGNN_OK;
 }

@@ -67,20 +67,26 @@ __device__ __forceinline__ int32_t count_upto(int32_t x, int32_t j, int32_t p) {
   return x > j ? (x - j + p - 1) / p : 0;
 }
 
-// One workgroup per wavefront stream: segment the 16 pieces by slab, lay the entries out in
-// (slab, piece) order and encode them.
+// One workgroup per wavefront: segment the 16 pieces by slab, lay the entries out in
+// (slab, piece) order and encode them.  With `groups` = R lane groups the wavefront carries R
+// independent streams (group g owns slots g*16/R ..), stored zipped: entry t of group g at
+// position R*t + g; the shorter streams are padded with entries that multiply row 0 of B by 0.
 __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
     const float* __restrict__ val, const int32_t* __restrict__ piece_info,
     const int32_t* __restrict__ wave_base, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
-    int32_t stagger, uint32_t* __restrict__ code, float* __restrict__ vals) {
+    int32_t stagger, int32_t groups, uint32_t* __restrict__ code, float* __restrict__ vals) {
   __shared__ int32_t lo[kSweepSlots][kSweepMaxSlabs + 1];   // first entry (index in row) of slab s
-  __shared__ int32_t off[kSweepMaxSlabs][kSweepSlots];      // stream offset of segment (s, slot)
+  __shared__ int32_t off[kSweepMaxSlabs][kSweepSlots];      // offset of segment (s, slot) inside its slab
+  __shared__ int32_t slab_base[kSweepMaxSlabs][4];          // stream offset of slab s for group g
+  __shared__ int32_t slab_tot[kSweepMaxSlabs][4];
+  __shared__ int32_t glen[4];
   __shared__ int32_t p_row[kSweepSlots], p_j[kSweepSlots], p_p[kSweepSlots], p_beg[kSweepSlots],
       p_deg[kSweepSlots];
   const int64_t w = blockIdx.x;
   const int tid = threadIdx.x;
   const int S = n_slabs;
+  const int R = groups, SL = kSweepSlots / groups;
   if (tid < kSweepSlots) {
     const int32_t row = piece_info[2 * (w * kSweepSlots + tid)];
     const int32_t jp = piece_info[2 * (w * kSweepSlots + tid) + 1];
@@ -114,32 +120,48 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     lo[slot][s] = res;
   }
   __syncthreads();
+  // entries of segment (s, slot); then per slab the prefix over the slots of each group
+  for (int idx = tid; idx < S * kSweepSlots; idx += kBuildThreads) {
+    const int s = idx / kSweepSlots, slot = idx - s * kSweepSlots;
+    off[s][slot] = p_row[slot] >= 0 ? count_upto(lo[slot][s + 1], p_j[slot], p_p[slot]) -
+                                          count_upto(lo[slot][s], p_j[slot], p_p[slot])
+                                    : 0;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < S * R; idx += kBuildThreads) {
+    const int s = idx / R, gi = idx - s * R;
+    int32_t run = 0;
+    for (int slot = gi * SL; slot < (gi + 1) * SL; ++slot) {
+      const int32_t c = off[s][slot];
+      off[s][slot] = run;
+      run += c;
+    }
+    slab_tot[s][gi] = run;
+  }
+  __syncthreads();
   // The stream is laid out in the order the wavefront will walk the slabs: it starts at slab
   // s0 = xcd * S/8 (xcd = workgroup index mod 8, four wavefronts per workgroup) and wraps.
   const int s0 = stagger ? (int)(((w >> 2) & 7) * S / 8) : 0;
-  __shared__ int32_t total;
-  if (tid == 0) {
+  if (tid < R) {
     int32_t run = 0;
     for (int t = 0; t < S; ++t) {
       const int s = (s0 + t) % S;
-      for (int slot = 0; slot < kSweepSlots; ++slot) {
-        off[s][slot] = run;
-        if (p_row[slot] >= 0)
-          run += count_upto(lo[slot][s + 1], p_j[slot], p_p[slot]) -
-                 count_upto(lo[slot][s], p_j[slot], p_p[slot]);
-      }
+      slab_base[s][tid] = run;
+      run += slab_tot[s][tid];
     }
-    total = run;
+    glen[tid] = run;
   }
   __syncthreads();
   const int64_t base = wave_base[w];
-  // padding up to the next stream: entries that multiply row 0 of B by zero
-  for (int64_t e = base + total + tid; e < wave_base[w + 1]; e += kBuildThreads) {
-    code[e] = 0u;
-    vals[e] = 0.f;
-  }
+  const int64_t steps = (wave_base[w + 1] - base) / R;     // padded length of every group stream
+  for (int gi = 0; gi < R; ++gi)
+    for (int64_t t = glen[gi] + tid; t < steps; t += kBuildThreads) {
+      code[base + t * R + gi] = 0u;
+      vals[base + t * R + gi] = 0.f;
+    }
   for (int slot = 0; slot < kSweepSlots; ++slot) {
     if (p_row[slot] < 0) continue;
+    const int gi = slot / SL;
     const int32_t j = p_j[slot], p = p_p[slot], d = p_deg[slot], beg = p_beg[slot];
     const int32_t size = count_upto(d, j, p);
     for (int32_t t = tid; t < size; t += kBuildThreads) {
@@ -153,8 +175,9 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
       while (s < S - 1 && i >= lo[slot][s + 1]) ++s;
       const int32_t rank = t - count_upto(lo[slot][s], j, p);
       const bool last = i + p >= lo[slot][s + 1];
-      code[base + off[s][slot] + rank] = c | ((uint32_t)slot << kSweepColBits) | (last ? 0x80000000u : 0u);
-      vals[base + off[s][slot] + rank] = val[beg + i];
+      const int64_t pos = base + (int64_t)(slab_base[s][gi] + off[s][slot] + rank) * R + gi;
+      code[pos] = c | ((uint32_t)slot << kSweepColBits) | (last ? 0x80000000u : 0u);
+      vals[pos] = val[beg + i];
     }
   }
 }
@@ -198,7 +221,9 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int64_t w = (int64_t)blockIdx.x * 4 + wave;
   if (w >= d.n_waves) return;
-  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves) return;
+  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves ||
+      hdr->groups != 1)
+    return;
   constexpr int kRow = 64 * FPL;  // floats per accumulator row
   float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lane * FPL;
 #pragma unroll
@@ -240,6 +265,115 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
     const int32_t tgt = piece_target[w * kSweepSlots + s];
     if (tgt == INT32_MIN) continue;
     vec r = *reinterpret_cast<const vec*>(my + s * kRow);
+    if (tgt >= 0) {
+      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)tgt * d.ldc) + loff);
+      if (d.accumulate) r += *p;
+      *p = r;
+    } else {
+      const int64_t pi = -(int64_t)tgt - 1;
+      *reinterpret_cast<vec*>(reinterpret_cast<char*>(partial + pi * d.f_total + d.col0) + loff) = r;
+    }
+  }
+}
+
+// Lane-group variant: the wavefront carries R independent streams (zipped in memory), lane
+// group g = lanes [g*64/R, (g+1)*64/R) walks stream g.  A group's 64/R lanes move one whole row
+// of B with V floats (16 bytes at V = 4) per lane, so one load instruction serves R entries.
+// Column ids and values still arrive by scalar loads; a lane picks its group's pair with
+// selects (the row offset is multiplied on the scalar side first).  Flushes are per group:
+// lanes of other groups are masked off by the divergent branch.
+template <int V, int R, int U, bool BUF>
+__global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
+    const uint32_t* __restrict__ code, const float* __restrict__ vals,
+    const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
+    const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ partial, const SweepDims d) {
+  using vec = typename Vec<V>::T;
+  constexpr int LG = 64 / R;             // lanes per group = lanes per row
+  constexpr int kRow = LG * V;           // floats per row of this launch
+  constexpr int SL = kSweepSlots / R;    // slots per group
+  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][16 slots][kRow]
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t gid = lane / LG, lig = lane % LG;
+  const uint32_t loff = lig * (V * 4);
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+  if (w >= d.n_waves) return;
+  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves ||
+      hdr->groups != R)
+    return;
+  float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lig * V;
+#pragma unroll
+  for (int ls = 0; ls < SL; ++ls) *reinterpret_cast<vec*>(my + (gid * SL + ls) * kRow) = vec(0.f);
+
+  const int32_t base = wave_base[w];
+  const int32_t steps = (wave_base[w + 1] - base) / R;   // a multiple of U (padded when built)
+  const uint32_t* __restrict__ cw = code + base;
+  const float* __restrict__ vw = vals + base;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
+
+  vec acc = 0.f;
+  for (int32_t e = 0; e < steps; e += U) {
+    uint32_t c[U][R];
+    float v[U][R];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int g = 0; g < R; ++g) {
+        c[u][g] = cw[(e + u) * R + g];
+        v[u][g] = vw[(e + u) * R + g];
+      }
+    uint32_t mc[U];
+    float mv[U];
+    vec h[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      mc[u] = c[u][0];
+      mv[u] = v[u][0];
+      if constexpr (BUF) {
+        uint32_t off = (c[u][0] & kColMask) * d.row_bytes;
+#pragma unroll
+        for (int g = 1; g < R; ++g)
+          if (gid == (uint32_t)g) {
+            mc[u] = c[u][g];
+            mv[u] = v[u][g];
+            off = (c[u][g] & kColMask) * d.row_bytes;
+          }
+        off += loff;
+        if constexpr (V == 1) h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+        else if constexpr (V == 2) h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, 0));
+        else h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
+      } else {
+        const char* rowp = reinterpret_cast<const char*>(B + (int64_t)(c[u][0] & kColMask) * d.ldb);
+#pragma unroll
+        for (int g = 1; g < R; ++g)
+          if (gid == (uint32_t)g) {
+            mc[u] = c[u][g];
+            mv[u] = v[u][g];
+            rowp = reinterpret_cast<const char*>(B + (int64_t)(c[u][g] & kColMask) * d.ldb);
+          }
+        h[u] = *reinterpret_cast<const vec*>(rowp + loff);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc += mv[u] * h[u];
+      if (mc[u] >> 31) {   // last entry of a (piece, slab) segment of this lane's group
+        vec* p = reinterpret_cast<vec*>(my + ((mc[u] >> kSweepColBits) & (kSweepSlots - 1)) * kRow);
+        *p += acc;
+        acc = 0.f;
+      }
+    }
+  }
+
+#pragma unroll 1
+  for (int ls = 0; ls < SL; ++ls) {
+    const int slot = (int)gid * SL + ls;
+    const int32_t tgt = piece_target[w * kSweepSlots + slot];
+    if (tgt == INT32_MIN) continue;
+    vec r = *reinterpret_cast<const vec*>(my + slot * kRow);
     if (tgt >= 0) {
       vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)tgt * d.ldc) + loff);
       if (d.accumulate) r += *p;
@@ -338,6 +472,11 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   if (S > kSweepMaxSlabs) S = kSweepMaxSlabs;
   const int64_t width = ceil_div(k, S);
 
+  // Lane groups: at f = 128 half a wavefront, at f = 64 a quarter, moves a whole row of B with
+  // 16 bytes per lane, so one load instruction serves 2 / 4 entries (the vector-memory issue
+  // rate, not bandwidth, bounds B-in-cache cases).  Other widths keep one row per instruction.
+  int64_t R = f == 128 ? 2 : (f == 64 ? 4 : 1);
+  if (env_int("SAGNN_SWEEP_GROUPS", 0) == 1) R = 1;
   std::vector<Piece> pieces;
   int64_t long_entries = 0, short_rows = 0, short_entries = 0;
   bool has_empty = false;
@@ -365,7 +504,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // Pieces per wavefront: all kSweepSlots when there are plenty of pieces; fewer when that would
   // leave the chip short of wavefronts (a row block of a partitioned graph has few long rows).
   int64_t slots_used = ceil_div(P, (int64_t)env_int("SAGNN_SWEEP_MIN_WAVES", 8192));
-  if (slots_used < 1) slots_used = 1;
+  if (slots_used < R) slots_used = R;          // every lane group of a wavefront gets a piece
   if (slots_used > kSweepSlots) slots_used = kSweepSlots;
   if (ceil_div(P, slots_used) + 64 > L.max_waves - 1) slots_used = kSweepSlots;
   // Pieces are dealt window by window.  A window is a run of consecutive long rows holding a
@@ -411,7 +550,6 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   win_wave0.push_back(NW);
   if (NW > L.max_waves - 1) return SAGNN_OK;   // cannot happen with the bounds above; plain schedule
   std::vector<int32_t> info((size_t)NW * kSweepSlots * 2, -1), target((size_t)NW * kSweepSlots, INT32_MIN);
-  std::vector<int64_t> wsize((size_t)NW, 0);
   // multi-piece rows: partial slots in row order
   std::vector<int32_t> multi_row, multi_first;
   {
@@ -427,39 +565,45 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   }
   if ((int64_t)multi_row.size() > L.max_multi_rows || (int64_t)multi_first.back() > L.max_multi_pieces)
     return SAGNN_OK;
-  // Inside a window: largest piece first, each to the wavefront with the shortest stream so far
-  // that still has a free slot (ties: lowest wavefront).  Streams come out equal to within a
-  // piece of the smallest size class, which keeps the wavefronts in step from slab to slab.
-  std::vector<int32_t> used((size_t)NW, 0);
-  using Load = std::pair<int64_t, int64_t>;   // (stream length, wavefront)
+  // Inside a window: largest piece first, each to the stream that is shortest so far and still
+  // has a free slot (ties: lowest index).  Streams come out equal to within a piece of the
+  // smallest size class, which keeps the wavefronts in step from slab to slab.  With R lane
+  // groups a wavefront carries R independent streams (group g owns slots g*16/R ..); the unit of
+  // dealing is then the group stream.
+  const int64_t SL = kSweepSlots / R;           // slots per group stream
+  std::vector<int32_t> used((size_t)NW * R, 0);
+  std::vector<int64_t> uload((size_t)NW * R, 0);
+  using Load = std::pair<int64_t, int64_t>;   // (stream length, unit = wavefront * R + group)
   std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
   int64_t cur_win = -1;
-  const bool lpt = env_int("SAGNN_SWEEP_LPT", 1) != 0;
+  const bool lpt = R > 1 || env_int("SAGNN_SWEEP_LPT", 1) != 0;
   for (int64_t t = 0; t < P; ++t) {
     const int64_t win = t / window, tw = t - win * window;
     const int64_t nw = win_wave0[(size_t)win + 1] - win_wave0[(size_t)win];
-    int64_t wv, round;
+    int64_t wv, slot;
     if (lpt) {
       if (win != cur_win) {
         cur_win = win;
         heap = decltype(heap)();
-        for (int64_t w = 0; w < nw; ++w) heap.push({0, win_wave0[(size_t)win] + w});
+        for (int64_t u = 0; u < nw * R; ++u) heap.push({0, win_wave0[(size_t)win] * R + u});
       }
       if (heap.empty()) return SAGNN_EINVAL;   // nw * kSweepSlots >= pieces of the window
-      wv = heap.top().second;
+      const int64_t unit = heap.top().second;
       heap.pop();
-      round = used[(size_t)wv]++;
-      if (used[(size_t)wv] < kSweepSlots) heap.push({wsize[(size_t)wv] + pieces[(size_t)t].size, wv});
+      wv = unit / R;
+      slot = (unit % R) * SL + used[(size_t)unit]++;
+      uload[(size_t)unit] += pieces[(size_t)t].size;
+      if (used[(size_t)unit] < SL) heap.push({uload[(size_t)unit], unit});
     } else {
-      round = tw / nw;
+      slot = tw / nw;
       const int64_t pos = tw % nw;
-      wv = win_wave0[(size_t)win] + ((round & 1) ? nw - 1 - pos : pos);
+      wv = win_wave0[(size_t)win] + ((slot & 1) ? nw - 1 - pos : pos);
+      uload[(size_t)wv] += pieces[(size_t)t].size;
     }
-    const size_t g = (size_t)(wv * kSweepSlots + round);
+    const size_t g = (size_t)(wv * kSweepSlots + slot);
     const Piece& pc = pieces[(size_t)t];
     info[2 * g] = pc.row;
     info[2 * g + 1] = (pc.j << 16) | pc.p;
-    wsize[(size_t)wv] += pc.size;
     if (pc.p == 1) {
       target[g] = pc.row;
     } else {
@@ -467,13 +611,19 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
       target[g] = -(multi_first[q] + pc.j) - 1;
     }
   }
-  // every stream is padded to a multiple of the kernel's batch (8 entries)
+  // A wavefront's R group streams are stored zipped (entry t of group g at R*t + g), each padded
+  // to the longest of them and to a multiple of the kernel's batch (8 steps)
   std::vector<int32_t> wbase((size_t)NW + 1);
   int64_t run = 0, unpadded = 0;
   for (int64_t wv = 0; wv < NW; ++wv) {
     wbase[(size_t)wv] = (int32_t)run;
-    run += (wsize[(size_t)wv] + 7) / 8 * 8;
-    unpadded += wsize[(size_t)wv];
+    int64_t longest = 0;
+    for (int64_t gi = 0; gi < R; ++gi) {
+      longest = std::max(longest, uload[(size_t)(wv * R + gi)]);
+      unpadded += uload[(size_t)(wv * R + gi)];
+    }
+    run += (longest + 7) / 8 * 8 * R;
+    if (run > 0x7FFFFFF0ll) return SAGNN_OK;
   }
   wbase[(size_t)NW] = (int32_t)run;
   if (unpadded != long_entries) return SAGNN_EINVAL;
@@ -519,7 +669,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW), dim3(kBuildThreads), 0, s, d_rowptr, d_colidx,
                      d_val, reinterpret_cast<const int32_t*>(ws + L.piece_info),
                      reinterpret_cast<const int32_t*>(ws + L.wave_base), (int32_t)S, (int32_t)width, kmax,
-                     (int32_t)env_int("SAGNN_SWEEP_STAGGER", 0),
+                     (int32_t)env_int("SAGNN_SWEEP_STAGGER", 0), (int32_t)R,
                      reinterpret_cast<uint32_t*>(ws + L.code), reinterpret_cast<float*>(ws + L.vals));
   SAGNN_LAUNCH_CHECK();
   // zero the gap between the long stream and the short entries (tail batches read into it)
@@ -545,6 +695,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   h.n_waves = NW; h.n_long_entries = stream_len;   // padded length of the sweep streams
   h.n_multi_rows = (int64_t)multi_row.size(); h.n_multi_pieces = multi_first.back();
   h.n_slabs = (int32_t)S; h.slab_width = (int32_t)width;
+  h.groups = (int32_t)R;
   out->use_sweep = true;
   return SAGNN_OK;
 }
@@ -579,6 +730,15 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
     SAGNN_LAUNCH_CHECK();
     return SAGNN_OK;
   };
+  if (d.groups == 2) {   // prepared for f = 128: half a wavefront per row (or per half row at 64)
+    if (fw == 128) return buf ? go(spmm_sweep_group_kernel<4, 2, 8, true>) : go(spmm_sweep_group_kernel<4, 2, 8, false>);
+    if (fw == 64) return buf ? go(spmm_sweep_group_kernel<2, 2, 8, true>) : go(spmm_sweep_group_kernel<2, 2, 8, false>);
+    return SAGNN_EINVAL;
+  }
+  if (d.groups == 4) {   // prepared for f = 64: a quarter wavefront per row
+    if (fw == 64) return buf ? go(spmm_sweep_group_kernel<4, 4, 8, true>) : go(spmm_sweep_group_kernel<4, 4, 8, false>);
+    return SAGNN_EINVAL;
+  }
   if (fw == 256) return buf ? go(spmm_sweep_kernel<4, 8, true>) : go(spmm_sweep_kernel<4, 8, false>);
   if (fw == 128) return buf ? go(spmm_sweep_kernel<2, 8, true>) : go(spmm_sweep_kernel<2, 8, false>);
   if (fw == 64) return buf ? go(spmm_sweep_kernel<1, 8, true>) : go(spmm_sweep_kernel<1, 8, false>);
