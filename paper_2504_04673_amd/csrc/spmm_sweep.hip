@@ -475,8 +475,13 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // Lane groups: at f = 128 half a wavefront, at f = 64 a quarter, moves a whole row of B with
   // 16 bytes per lane, so one load instruction serves 2 / 4 entries (the vector-memory issue
   // rate, not bandwidth, bounds B-in-cache cases).  Other widths keep one row per instruction.
+  // They pay when the rows of B are re-used from cache (issue-bound: 233 k-vertex graph
+  // 3.38 -> 2.63 ms, 2.45 M-vertex graph 4.85 -> 4.62 ms) and cost ~3 % when almost every gather
+  // misses (rank share of the 111 M-vertex graph, 2.6 entries per row of B): decided below by
+  // the average number of swept entries per row of B.
   int64_t R = f == 128 ? 2 : (f == 64 ? 4 : 1);
-  if (env_int("SAGNN_SWEEP_GROUPS", 0) == 1) R = 1;
+  const int groups_env = env_int("SAGNN_SWEEP_GROUPS", 0);   // 1: never, 2: whenever possible
+  if (groups_env == 1) R = 1;
   std::vector<Piece> pieces;
   int64_t long_entries = 0, short_rows = 0, short_entries = 0;
   bool has_empty = false;
@@ -496,6 +501,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     }
   }
   if (force != 1 && long_entries * 10 < nnz * 3) return SAGNN_OK;   // < 30 % of the entries
+  if (groups_env != 2 && long_entries < 8 * k) R = 1;
   if (pieces.empty() || (int64_t)pieces.size() > L.max_pieces) return SAGNN_OK;
 
   std::vector<char> is_long((size_t)m, 0);

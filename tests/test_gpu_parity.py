@@ -205,6 +205,7 @@ def force_sweep(monkeypatch):
     monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
     monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
     monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "0")
+    monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "2")      # lane-group kernels at f = 128 / 64 even with little reuse
 
 
 @pytest.mark.parametrize("f", [64, 128, 192, 256, 320])
@@ -226,7 +227,7 @@ def test_spmm_slab_sweep_schedule(f, force_sweep):
 
 
 @pytest.mark.parametrize("variant", ["sixteen_pieces_per_wavefront", "many_small_windows", "snake_dealing",
-                                     "one_window_long_threshold_64"])
+                                     "one_window_long_threshold_64", "one_row_per_instruction"])
 def test_spmm_slab_sweep_planner_variants(variant, force_sweep, monkeypatch):
     """The planner's alternatives (pieces per wavefront, dealing windows, dealing order,
     thresholds) all have to give the same product; small inputs take them through the
@@ -239,6 +240,9 @@ def test_spmm_slab_sweep_planner_variants(variant, force_sweep, monkeypatch):
     elif variant == "snake_dealing":
         monkeypatch.setenv("SAGNN_SWEEP_MIN_WAVES", "1")
         monkeypatch.setenv("SAGNN_SWEEP_LPT", "0")
+        monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "1")   # snake dealing exists for one stream per wavefront
+    elif variant == "one_row_per_instruction":
+        monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "1")
     else:
         monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "64")
         monkeypatch.setenv("SAGNN_SWEEP_WINDOW_PCT", "0")
