@@ -426,6 +426,25 @@ __global__ __launch_bounds__(kThreads) void remap_kernel(const int32_t* __restri
     compact[e] = remap_one(colidx[e], n, rank16);
 }
 
+// Every column is needed (N == n, e.g. a whole graph planned as one block): the position of
+// column c in needed[] is c itself, so the remap is a range-checked copy (pure streaming).
+__global__ __launch_bounds__(kThreads) void remap_identity_kernel(const int32_t* __restrict__ colidx,
+                                                                  int64_t nnz, int64_t n,
+                                                                  int32_t* __restrict__ compact,
+                                                                  int aligned) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const int64_t quads = aligned ? (nnz >> 2) : 0;
+  const int4* __restrict__ c4 = reinterpret_cast<const int4*>(colidx);
+  int4* __restrict__ o4 = reinterpret_cast<int4*>(compact);
+  auto one = [n](int32_t c) { return (c < 0 || c >= n) ? -1 : c; };
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < quads; q += stride) {
+    const int4 c = c4[q];
+    o4[q] = make_int4(one(c.x), one(c.y), one(c.z), one(c.w));
+  }
+  for (int64_t e = (quads << 2) + (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += stride)
+    compact[e] = one(colidx[e]);
+}
+
 inline unsigned grid_for(int64_t items, int64_t per_thread = 1) {
   int64_t b = ceil_div(ceil_div(items, per_thread), kThreads);
   const int64_t cap = 256 * 32;  // enough workgroups to fill 256 CUs several times over
@@ -533,9 +552,13 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
     SAGNN_LAUNCH_CHECK();
   }
   if (d_colidx_compact && nnz > 0) {
-    hipLaunchKernelGGL(remap_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz,
-                       n, w.rank16, d_colidx_compact,
-                       (aligned16(d_colidx) && aligned16(d_colidx_compact)) ? 1 : 0);
+    const int al = (aligned16(d_colidx) && aligned16(d_colidx_compact)) ? 1 : 0;
+    if (N == n)
+      hipLaunchKernelGGL(remap_identity_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx,
+                         nnz, n, d_colidx_compact, al);
+    else
+      hipLaunchKernelGGL(remap_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz, n,
+                         w.rank16, d_colidx_compact, al);
     SAGNN_LAUNCH_CHECK();
   }
   return SAGNN_OK;

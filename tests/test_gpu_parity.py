@@ -164,6 +164,13 @@ def test_plan_empty_matrix_and_capacity_and_validate():
     plan = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(bad), 1000, np.array([0, 1000]))
     assert int(plan.colidx_compact[7]) == -1
     sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), 1000, np.array([0, 1000]), validate=True)
+    # every column needed (the remap is then the identity) and one column out of range
+    n = 777
+    rp2 = np.arange(0, n + 2, dtype=np.int32)
+    ci2 = np.concatenate([rng.permutation(n), [n + 3]]).astype(np.int32)
+    plan = sagnn.spmm_plan_needed_rows(dev(rp2), dev(ci2), n, np.array([0, 100, n]))
+    assert plan.N == n and np.array_equal(plan.needed.cpu().numpy(), np.arange(n))
+    assert np.array_equal(plan.colidx_compact.cpu().numpy(), np.concatenate([ci2[:-1], [-1]]))
 
 
 # ------------------------------------------------------------------------------------ SpMM
