@@ -138,9 +138,13 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  *     into the workspace re-ordered by column slab ("slab sweep"), so that all wavefronts of an
  *     XCD touch the same small part of B at the same time (L2 reuse).  Requires ascending
  *     column indices inside long rows and k < 2^27; otherwise the first schedule is used.
+ *     At f = 128 and f = 64 the re-ordered copy is laid out for kernels that fetch two / four
+ *     rows of B per load instruction, which a later call must match: a workspace prepared for
+ *     f = 128 serves calls with f = 128 or 64, one prepared for f = 64 only f = 64.
  * The workspace then holds a private copy of colidx/val: call spmm_csr_prepare() again if
  * they change.  d_ws must be passed unchanged to every spmm_csr_tallskinny() call with the
- * same (rowptr, colidx, val, m, k, nnz) and f <= the prepared f; part of it is scratch for
+ * same (rowptr, colidx, val, m, k, nnz) and f <= the prepared f (a multiple of 64 if the
+ * slab-sweep schedule was chosen, see spmm_csr_schedule_info); part of it is scratch for
  * partial row sums, so two calls that share a workspace must not overlap in time.
  * spmm_csr_prepare() synchronises the stream (it plans on the host from a copy of rowptr) and
  * the library remembers a small host descriptor per prepared workspace address; passing a

@@ -21,7 +21,10 @@
 // through the nonzero-splitting kernels of spmm.hip on a compacted CSR.
 //
 // The entry stream of a wavefront is stored in the workspace as (code, value) pairs sorted by
-// (slab, piece): code = column | piece_slot << 27 | segment_end << 31.
+// (slab, piece): code = column | piece_slot << 27 | segment_end << 31.  At f = 128 / 64 a
+// wavefront can carry 2 / 4 such streams, one per lane group, stored zipped (see
+// spmm_sweep_group_kernel): a group of 32 / 16 lanes moves a whole row of B, so one load
+// instruction serves 2 / 4 entries.
 #include <stdlib.h>
 
 #include <algorithm>
@@ -430,9 +433,9 @@ std::atomic<uint64_t> g_generation{1};
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
-// host side of the preparation: classify rows, cut long rows into pieces, deal pieces to
-// wavefronts (sorted by size, snake order: every wavefront gets one piece per round, so the
-// streams have nearly equal lengths), build the compacted short-row CSR.
+// host side of the preparation: classify rows, cut long rows into pieces, deal pieces to the
+// streams of the wavefronts (largest first, each to the shortest stream so far, so the streams
+// have nearly equal lengths), build the compacted short-row CSR.
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
                   int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
                   hipStream_t s, SweepPlanResult* out) {
@@ -515,7 +518,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   if (ceil_div(P, slots_used) + 64 > L.max_waves - 1) slots_used = kSweepSlots;
   // Pieces are dealt window by window.  A window is a run of consecutive long rows holding a
   // few times as many pieces as the chip keeps resident at once (LDS-limited); inside a window
-  // the pieces are sorted by size and dealt in snake order, so its wavefronts have nearly equal
+  // the pieces are sorted by size and dealt longest-first, so its wavefronts have nearly equal
   // stream lengths (they pass the slabs in step).  A matrix of up to ~4 generations is one
   // window (measured best on randomly labelled graphs: 4.95 ms against 5.4 ms with one window
   // per generation on the 2.45 M-vertex R-MAT graph); a larger one whose row order carries

@@ -268,6 +268,22 @@ def test_spmm_slab_sweep_planner_variants(variant, force_sweep, monkeypatch):
     assert_close(run_spmm(rowptr, colidx, val, B, True, C0=C0), ref2, zabs2, RTOL_SPMM, f"{variant} accumulate")
 
 
+def test_spmm_sweep_workspace_prepared_for_wider_f(force_sweep):
+    """A workspace prepared for f = 128 (two lane groups) or 256 also serves narrower calls."""
+    rng = np.random.default_rng(31)
+    m, n = 3000, 30_000
+    rowptr, colidx, val = random_csr(m, n, 25, rng, hubs=[(2, 6000), (1500, 1500)])
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    for f_prep, f_call in ((128, 64), (256, 128), (256, 64), (192, 128)):
+        ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f_prep)
+        assert ws.info()["mode"] == 1
+        B = synth.normal((n, f_call), f_prep + f_call, synth.STREAM_H)
+        ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+        got = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), ws=ws)
+        torch.cuda.synchronize()
+        assert_close(got, ref, zabs, RTOL_SPMM, f"prepared {f_prep}, called {f_call}")
+
+
 def test_spmm_slab_sweep_falls_back_on_unsorted_rows(force_sweep):
     rng = np.random.default_rng(5)
     m, n, f = 2000, 30_000, 128
