@@ -235,14 +235,20 @@ __global__ __launch_bounds__(kBlock) void spmm_narrow_kernel(SPMM_PTR_PARAMS, co
   constexpr int kSteps = kT / P;
   for (int s0 = 0; s0 < kSteps; s0 += U) {
     if (e0 + s0 * P >= e1) break;
+    // the batch's U*P (<= 64) column ids and values arrive with one coalesced load each (lane l
+    // takes the l-th entry of the batch); a step's group then picks its entry with a lane
+    // permute, which keeps the vector-memory pipeline for the gathers of B
+    static_assert(U * P <= 64, "a batch must fit one wavefront-wide load");
+    const int32_t mine = e0 + s0 * P + lane;
+    const bool have = lane < U * P && mine < e1;
+    const int32_t cb = have ? colidx[mine] : 0;
+    const float vb = have ? val[mine] : 0.f;
     int32_t c[U];
     float v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int32_t me = e0 + (s0 + u) * P + g;
-      const bool valid = me < e1;
-      c[u] = valid ? colidx[me] : 0;
-      v[u] = valid ? val[me] : 0.f;
+      c[u] = __shfl(cb, u * P + g, 64);
+      v[u] = __shfl(vb, u * P + g, 64);
     }
     vec4 h[U];
 #pragma unroll
@@ -550,7 +556,7 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
       else if (rest > 32) launch_waves(spmm_narrow_kernel<16, 4>, blocks, sp, sd, s);
       else if (rest > 16) launch_waves(spmm_narrow_kernel<8, 4>, blocks, sp, sd, s);
       else if (rest > 8) launch_waves(spmm_narrow_kernel<4, 4>, blocks, sp, sd, s);
-      else launch_waves(spmm_narrow_kernel<2, 4>, blocks, sp, sd, s);
+      else launch_waves(spmm_narrow_kernel<2, 2>, blocks, sp, sd, s);
       SAGNN_LAUNCH_CHECK();
     }
     col0 += sd.f;
