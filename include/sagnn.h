@@ -134,7 +134,8 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  * one-time spmm_csr_prepare() builds a schedule in the workspace:
  *   - always: the entries are cut into equal chunks (nonzero splitting) and the row in which
  *     each chunk starts is recorded, so hub rows and runs of short rows are balanced;
- *   - for large power-law matrices with f a multiple of 64: the entries of long rows are copied
+ *   - for large power-law matrices with f a multiple of 64 (or exactly 32 or 16): the entries
+ *     of long rows are copied
  *     into the workspace re-ordered by column slab ("slab sweep"), so that all wavefronts of an
  *     XCD touch the same small part of B at the same time (L2 reuse).  Requires ascending
  *     column indices inside long rows and k < 2^27; otherwise the first schedule is used.
@@ -144,7 +145,8 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  * The workspace then holds a private copy of colidx/val: call spmm_csr_prepare() again if
  * they change.  d_ws must be passed unchanged to every spmm_csr_tallskinny() call with the
  * same (rowptr, colidx, val, m, k, nnz) and f <= the prepared f (a multiple of 64 if the
- * slab-sweep schedule was chosen, see spmm_csr_schedule_info); part of it is scratch for
+ * slab-sweep schedule was chosen, see spmm_csr_schedule_info; exactly the prepared f if that
+ * was 32 or 16); part of it is scratch for
  * partial row sums, so two calls that share a workspace must not overlap in time.
  * spmm_csr_prepare() synchronises the stream (it plans on the host from a copy of rowptr) and
  * the library remembers a small host descriptor per prepared workspace address; passing a

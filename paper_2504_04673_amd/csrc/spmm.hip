@@ -510,7 +510,9 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
     SAGNN_LAUNCH_CHECK();
   }
   if (desc.mode == 1) {
-    if (f & 63) return SAGNN_EINVAL;  // the sweep schedule was prepared for 64-multiples only
+    // the sweep schedule exists for multiples of 64 and, in grouped form, for exactly 32 and 16
+    if ((f & 63) && !((f == 32 || f == 16) && f == desc.f)) return SAGNN_EINVAL;
+    if (desc.groups >= 8 && f != desc.f) return SAGNN_EINVAL;
     // the chunk kernels walk the compacted short-row CSR stored in the workspace
     const int64_t short_base = (int64_t)round_up((size_t)desc.sweep_stream_len + 64, 256);
     p.rowptr = reinterpret_cast<const int32_t*>(base + L.rowptr_s);
@@ -598,7 +600,7 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
   int32_t* d_has_empty = reinterpret_cast<int32_t*>(base + L.carry);  // scratch until the first product
 
   SweepPlanResult plan{};
-  if ((f & 63) == 0) {
+  if ((f & 63) == 0 || f == 32 || f == 16) {
     int rc = sweep_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, base, L, s, &plan);
     if (rc != SAGNN_OK) return rc;
   }

@@ -79,11 +79,20 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     const float* __restrict__ val, const int32_t* __restrict__ piece_info,
     const int32_t* __restrict__ wave_base, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
     int32_t stagger, int32_t groups, uint32_t* __restrict__ code, float* __restrict__ vals) {
-  __shared__ int32_t lo[kSweepSlots][kSweepMaxSlabs + 1];   // first entry (index in row) of slab s
-  __shared__ int32_t off[kSweepMaxSlabs][kSweepSlots];      // offset of segment (s, slot) inside its slab
-  __shared__ int32_t slab_base[kSweepMaxSlabs][4];          // stream offset of slab s for group g
-  __shared__ int32_t slab_tot[kSweepMaxSlabs][4];
-  __shared__ int32_t glen[4];
+  // dynamic LDS (sweep_build_lds_bytes): lo[16][S+1] first entry (index in row) of slab s;
+  // off[S][16] offset of segment (s, slot) inside its slab; slab_base[S][16] stream offset of
+  // slab s for group g; slab_tot[S][16]
+  extern __shared__ __attribute__((aligned(16))) int32_t build_lds[];
+  const int SS = n_slabs;
+  int32_t* lo_ = build_lds;                                  // [16][SS + 1]
+  int32_t* off_ = lo_ + kSweepSlots * (SS + 1);              // [SS][16]
+  int32_t* slab_base_ = off_ + SS * kSweepSlots;             // [SS][16]
+  int32_t* slab_tot_ = slab_base_ + SS * kSweepSlots;        // [SS][16]
+#define LO(slot, s) lo_[(slot) * (SS + 1) + (s)]
+#define OFF(s, slot) off_[(s) * kSweepSlots + (slot)]
+#define SLAB_BASE(s, g) slab_base_[(s) * kSweepSlots + (g)]
+#define SLAB_TOT(s, g) slab_tot_[(s) * kSweepSlots + (g)]
+  __shared__ int32_t glen[kSweepSlots];
   __shared__ int32_t p_row[kSweepSlots], p_j[kSweepSlots], p_p[kSweepSlots], p_beg[kSweepSlots],
       p_deg[kSweepSlots];
   const int64_t w = blockIdx.x;
@@ -120,14 +129,14 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
         res = a;
       }
     }
-    lo[slot][s] = res;
+    LO(slot, s) = res;
   }
   __syncthreads();
   // entries of segment (s, slot); then per slab the prefix over the slots of each group
   for (int idx = tid; idx < S * kSweepSlots; idx += kBuildThreads) {
     const int s = idx / kSweepSlots, slot = idx - s * kSweepSlots;
-    off[s][slot] = p_row[slot] >= 0 ? count_upto(lo[slot][s + 1], p_j[slot], p_p[slot]) -
-                                          count_upto(lo[slot][s], p_j[slot], p_p[slot])
+    OFF(s, slot) = p_row[slot] >= 0 ? count_upto(LO(slot, s + 1), p_j[slot], p_p[slot]) -
+                                          count_upto(LO(slot, s), p_j[slot], p_p[slot])
                                     : 0;
   }
   __syncthreads();
@@ -135,11 +144,11 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     const int s = idx / R, gi = idx - s * R;
     int32_t run = 0;
     for (int slot = gi * SL; slot < (gi + 1) * SL; ++slot) {
-      const int32_t c = off[s][slot];
-      off[s][slot] = run;
+      const int32_t c = OFF(s, slot);
+      OFF(s, slot) = run;
       run += c;
     }
-    slab_tot[s][gi] = run;
+    SLAB_TOT(s, gi) = run;
   }
   __syncthreads();
   // The stream is laid out in the order the wavefront will walk the slabs: it starts at slab
@@ -149,8 +158,8 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     int32_t run = 0;
     for (int t = 0; t < S; ++t) {
       const int s = (s0 + t) % S;
-      slab_base[s][tid] = run;
-      run += slab_tot[s][tid];
+      SLAB_BASE(s, tid) = run;
+      run += SLAB_TOT(s, tid);
     }
     glen[tid] = run;
   }
@@ -174,15 +183,23 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
       int s = (int)(c / (uint32_t)slab_width);
       if (s > S - 1) s = S - 1;
       // the row is ascending, but clamped / equal columns may sit on a slab boundary: trust lo[]
-      while (s > 0 && i < lo[slot][s]) --s;
-      while (s < S - 1 && i >= lo[slot][s + 1]) ++s;
-      const int32_t rank = t - count_upto(lo[slot][s], j, p);
-      const bool last = i + p >= lo[slot][s + 1];
-      const int64_t pos = base + (int64_t)(slab_base[s][gi] + off[s][slot] + rank) * R + gi;
+      while (s > 0 && i < LO(slot, s)) --s;
+      while (s < S - 1 && i >= LO(slot, s + 1)) ++s;
+      const int32_t rank = t - count_upto(LO(slot, s), j, p);
+      const bool last = i + p >= LO(slot, s + 1);
+      const int64_t pos = base + (int64_t)(SLAB_BASE(s, gi) + OFF(s, slot) + rank) * R + gi;
       code[pos] = c | ((uint32_t)slot << kSweepColBits) | (last ? 0x80000000u : 0u);
       vals[pos] = val[beg + i];
     }
   }
+}
+#undef LO
+#undef OFF
+#undef SLAB_BASE
+#undef SLAB_TOT
+
+inline size_t sweep_build_lds_bytes(int64_t S) {
+  return sizeof(int32_t) * (size_t)(kSweepSlots * (S + 1) + 3 * S * kSweepSlots);
 }
 
 // compacted CSR of the short rows: copy entries
@@ -388,6 +405,114 @@ __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
   }
 }
 
+// Narrow operands (rows of 64 / 128 bytes): R = 16 / 8 lane groups of 4 / 8 lanes.  Too many
+// groups for scalar selects, so a batch of 64 stream words (64/R steps x R groups) is fetched with
+// one coalesced load per array and a step's group takes its word with a lane permute.  With 16
+// groups each group owns a single piece and its register accumulator is the piece's accumulator
+// (no LDS at all); with 8 groups two pieces per group share it through LDS as in the wide kernels.
+template <int R, bool BUF>
+__global__ __launch_bounds__(256) void spmm_sweep_perm_kernel(
+    const uint32_t* __restrict__ code, const float* __restrict__ vals,
+    const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
+    const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ partial, const SweepDims d) {
+  typedef float vec __attribute__((ext_vector_type(4)));
+  constexpr int LG = 64 / R;             // lanes per group = lanes per row
+  constexpr int kRow = LG * 4;           // floats per row
+  constexpr int SL = kSweepSlots / R;    // pieces per group
+  constexpr int UB = 64 / R;             // steps per batch of 64 stream words
+  constexpr int NB = 8 / UB;             // batches per iteration: 8 steps (gathers) in flight
+  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][16 slots][kRow], SL > 1 only
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t gid = lane / LG, lig = lane % LG;
+  const uint32_t loff = lig * 16;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+  if (w >= d.n_waves) return;
+  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves ||
+      hdr->groups != R)
+    return;
+  float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lig * 4;
+  if constexpr (SL > 1) {
+#pragma unroll
+    for (int ls = 0; ls < SL; ++ls) *reinterpret_cast<vec*>(my + (gid * SL + ls) * kRow) = vec(0.f);
+  }
+  const int32_t base = wave_base[w];
+  const int32_t steps = (wave_base[w + 1] - base) / R;   // a multiple of 8 (padded when built)
+  const uint32_t* __restrict__ cw = code + base;
+  const float* __restrict__ vw = vals + base;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
+
+  vec acc = 0.f;
+  uint32_t cb[NB];
+  float vb[NB];
+#pragma unroll
+  for (int q = 0; q < NB; ++q) {
+    cb[q] = steps > 0 ? cw[q * 64 + lane] : 0u;
+    vb[q] = steps > 0 ? vw[q * 64 + lane] : 0.f;
+  }
+  for (int32_t e = 0; e < steps; e += 8) {
+    // the next iteration's stream words are requested before this one's gathers are waited for
+    const bool more = e + 8 < steps;
+    uint32_t ncb[NB];
+    float nvb[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      ncb[q] = more ? cw[(e + 8) * R + q * 64 + lane] : 0u;
+      nvb[q] = more ? vw[(e + 8) * R + q * 64 + lane] : 0.f;
+    }
+    uint32_t mc[8];
+    float mv[8];
+    vec h[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      mc[u] = (uint32_t)__shfl((int)cb[u / UB], (u % UB) * R + (int)gid, 64);
+      mv[u] = __shfl(vb[u / UB], (u % UB) * R + (int)gid, 64);
+      const uint32_t col = mc[u] & kColMask;
+      if constexpr (BUF) {
+        h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(rs, col * d.row_bytes + loff, 0, 0));
+      } else {
+        h[u] = *reinterpret_cast<const vec*>(reinterpret_cast<const char*>(B + (int64_t)col * d.ldb) + loff);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) asm volatile("" : "+v"(h[u]));
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      acc += mv[u] * h[u];
+      if constexpr (SL > 1) {
+        if (mc[u] >> 31) {   // last entry of a (piece, slab) segment of this lane's group
+          vec* p = reinterpret_cast<vec*>(my + ((mc[u] >> kSweepColBits) & (kSweepSlots - 1)) * kRow);
+          *p += acc;
+          acc = 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      cb[q] = ncb[q];
+      vb[q] = nvb[q];
+    }
+  }
+
+#pragma unroll 1
+  for (int ls = 0; ls < SL; ++ls) {
+    const int slot = (int)gid * SL + ls;
+    const int32_t tgt = piece_target[w * kSweepSlots + slot];
+    if (tgt == INT32_MIN) continue;
+    vec r = acc;
+    if constexpr (SL > 1) r = *reinterpret_cast<const vec*>(my + slot * kRow);
+    if (tgt >= 0) {
+      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)tgt * d.ldc) + loff);
+      if (d.accumulate) r += *p;
+      *p = r;
+    } else {
+      const int64_t pi = -(int64_t)tgt - 1;
+      *reinterpret_cast<vec*>(reinterpret_cast<char*>(partial + pi * d.f_total + d.col0) + loff) = r;
+    }
+  }
+}
+
 // rows cut into several pieces: C[row] (+)= sum of the pieces' partial rows, fixed order
 __global__ __launch_bounds__(256) void sweep_combine_kernel(
     const int32_t* __restrict__ multi_row, const int32_t* __restrict__ multi_first,
@@ -482,9 +607,11 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // 3.38 -> 2.63 ms, 2.45 M-vertex graph 4.85 -> 4.62 ms) and cost ~3 % when almost every gather
   // misses (rank share of the 111 M-vertex graph, 2.6 entries per row of B): decided below by
   // the average number of swept entries per row of B.
-  int64_t R = f == 128 ? 2 : (f == 64 ? 4 : 1);
+  // Narrow operands (f = 32, 16: rows of 128 / 64 bytes, 8 / 4 lanes each) exist only in the
+  // grouped form, 8 / 16 rows per load.
+  int64_t R = f == 128 ? 2 : (f == 64 ? 4 : (f == 32 ? 8 : (f == 16 ? 16 : 1)));
   const int groups_env = env_int("SAGNN_SWEEP_GROUPS", 0);   // 1: never, 2: whenever possible
-  if (groups_env == 1) R = 1;
+  if (groups_env == 1 && f >= 64) R = 1;
   std::vector<Piece> pieces;
   int64_t long_entries = 0, short_rows = 0, short_entries = 0;
   bool has_empty = false;
@@ -504,7 +631,10 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     }
   }
   if (force != 1 && long_entries * 10 < nnz * 3) return SAGNN_OK;   // < 30 % of the entries
-  if (groups_env != 2 && long_entries < 8 * k) R = 1;
+  if (groups_env != 2 && long_entries < 8 * k) {
+    if (f < 64) return SAGNN_OK;   // no one-row-per-instruction form below 64: plain schedule
+    R = 1;
+  }
   if (pieces.empty() || (int64_t)pieces.size() > L.max_pieces) return SAGNN_OK;
 
   std::vector<char> is_long((size_t)m, 0);
@@ -675,7 +805,10 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   if (unsorted) return SAGNN_OK;
 
   const uint32_t kmax = (uint32_t)(k - 1);
-  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW), dim3(kBuildThreads), 0, s, d_rowptr, d_colidx,
+  const size_t build_lds = sweep_build_lds_bytes(S);
+  SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_build_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)build_lds));
+  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW), dim3(kBuildThreads), build_lds, s, d_rowptr, d_colidx,
                      d_val, reinterpret_cast<const int32_t*>(ws + L.piece_info),
                      reinterpret_cast<const int32_t*>(ws + L.wave_base), (int32_t)S, (int32_t)width, kmax,
                      (int32_t)env_int("SAGNN_SWEEP_STAGGER", 0), (int32_t)R,
@@ -739,6 +872,12 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
     SAGNN_LAUNCH_CHECK();
     return SAGNN_OK;
   };
+  if (d.groups == 16)    // prepared for f = 16: four lanes per row
+    return fw == 16 ? (buf ? go(spmm_sweep_perm_kernel<16, true>) : go(spmm_sweep_perm_kernel<16, false>))
+                    : SAGNN_EINVAL;
+  if (d.groups == 8)     // prepared for f = 32: eight lanes per row
+    return fw == 32 ? (buf ? go(spmm_sweep_perm_kernel<8, true>) : go(spmm_sweep_perm_kernel<8, false>))
+                    : SAGNN_EINVAL;
   if (d.groups == 2) {   // prepared for f = 128: half a wavefront per row (or per half row at 64)
     if (fw == 128) return buf ? go(spmm_sweep_group_kernel<4, 2, 8, true>) : go(spmm_sweep_group_kernel<4, 2, 8, false>);
     if (fw == 64) return buf ? go(spmm_sweep_group_kernel<2, 2, 8, true>) : go(spmm_sweep_group_kernel<2, 2, 8, false>);

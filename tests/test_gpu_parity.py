@@ -215,7 +215,7 @@ def force_sweep(monkeypatch):
     monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "2")      # lane-group kernels at f = 128 / 64 even with little reuse
 
 
-@pytest.mark.parametrize("f", [64, 128, 192, 256, 320])
+@pytest.mark.parametrize("f", [16, 32, 64, 128, 192, 256, 320])
 def test_spmm_slab_sweep_schedule(f, force_sweep):
     rng = np.random.default_rng(100 + f)
     m, n = 5003, 40_000
