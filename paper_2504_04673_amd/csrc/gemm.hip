@@ -171,12 +171,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
   }
 }
 
-template <int NT, bool BF16>
-int launch_nn(const GemmArgs& g, hipStream_t s) {
-  constexpr int WAVES = BF16 ? 8 : 4;
+template <int NT, bool BF16, int WAVES>
+int launch_nn_waves(const GemmArgs& g, size_t lds, hipStream_t s) {
   auto kern = (g.kdim & 31) ? gemm_nn_kernel<NT, BF16, WAVES, true> : gemm_nn_kernel<NT, BF16, WAVES, false>;
-  const size_t lds = (size_t)((g.kdim + 31) & ~31) * NT * 32 * (BF16 ? 2 : 4);
-  if (lds > 160 * 1024) return SAGNN_EINVAL;
   SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int64_t ntiles = (g.m + 31) / 32;
@@ -187,6 +184,16 @@ int launch_nn(const GemmArgs& g, hipStream_t s) {
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES * 64), lds, s, g);
   SAGNN_LAUNCH_CHECK();
   return SAGNN_OK;
+}
+
+template <int NT, bool BF16>
+int launch_nn(const GemmArgs& g, hipStream_t s) {
+  const size_t lds = (size_t)((g.kdim + 31) & ~31) * NT * 32 * (BF16 ? 2 : 4);
+  if (lds > 160 * 1024) return SAGNN_EINVAL;
+  // fp32: 4 wavefronts per workgroup, two workgroups per CU while the W slab allows it; when the
+  // slab is so large that only one workgroup fits a CU, 8 wavefronts keep two per SIMD
+  if (BF16 || lds > 80 * 1024) return launch_nn_waves<NT, BF16, 8>(g, lds, s);
+  return launch_nn_waves<NT, BF16, 4>(g, lds, s);
 }
 
 // ------------------------------------------------------------------------------------------
