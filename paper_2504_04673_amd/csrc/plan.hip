@@ -179,7 +179,21 @@ __global__ __launch_bounds__(kLdsThreads) void mark_lds_kernel(const int32_t* __
     const int64_t q0 = (int64_t)share * per;
     const int64_t q1 = q0 + per < quads ? q0 + per : quads;
     const int4* __restrict__ c4 = reinterpret_cast<const int4*>(colidx);
-    for (int64_t q = q0 + threadIdx.x; q < q1; q += kLdsThreads) {
+    // four independent 16-byte loads per thread in flight (the scan is a pure stream)
+    int64_t q = q0 + threadIdx.x;
+    for (; q + 3 * kLdsThreads < q1; q += 4 * kLdsThreads) {
+      int4 c[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) c[j] = c4[q + j * kLdsThreads];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lds_mark_one(c[j].x, n, c0, bits, err);
+        lds_mark_one(c[j].y, n, c0, bits, err);
+        lds_mark_one(c[j].z, n, c0, bits, err);
+        lds_mark_one(c[j].w, n, c0, bits, err);
+      }
+    }
+    for (; q < q1; q += kLdsThreads) {
       const int4 c = c4[q];
       lds_mark_one(c.x, n, c0, bits, err);
       lds_mark_one(c.y, n, c0, bits, err);
