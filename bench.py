@@ -222,6 +222,9 @@ def main():
         },
     }
 
+    if out["roofline"]["traffic"]:
+        # rate at which the measured (counter) traffic of the profiled run moves at this run's time
+        out["roofline"]["traffic_GBps"] = round(out["roofline"]["traffic"] / (spmm_ms * 1e-3) / 1e9, 1)
     if args.stage_loop:
         out["stage_loop"] = stage_loop_timing(sagnn, torch, wl, plan, rp, va, Hd, m, f, max(args.steps // 2, 3))
     if not args.no_cpu_baseline:
