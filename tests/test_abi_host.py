@@ -86,3 +86,14 @@ def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(ValueError):
         sagnn.spmm_pack_rows(torch.zeros(4, 4), torch.zeros(2, dtype=torch.int32))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's share: --gpus N > 1 exits with a message (no GPU needed)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr or "one GPU" in r.stderr.lower()
+    assert r.stdout.strip() == ""
