@@ -154,18 +154,40 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
       }
     }
 
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int col = g.n0 + nt * 32 + r;
-      if (col >= g.nout) continue;
+    if (t * 32 + 32 <= g.m && g.n0 + NB <= g.nout) {
+      // full tile: no bounds checks; one base pointer per output array, rows reached by adding
+      // the leading dimension (the 16 values of a lane are rows 8*(v/4) + 4*h + v%4)
+      const int64_t row0 = t * 32 + h * 4;
+      const int col0 = g.n0 + r;
+      const float* mk = g.mask ? g.mask + row0 * g.ldmask + col0 : nullptr;
+      float* zp = g.Z ? g.Z + row0 * g.ldz + col0 : nullptr;
+      float* ap = g.A ? g.A + row0 * g.lda + col0 : nullptr;
+      const bool relu = g.act == SAGNN_ACT_RELU;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int64_t ro = t * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-        if (ro >= g.m) continue;
-        float z = acc[nt][v];
-        if (g.mask && !(g.mask[ro * g.ldmask + col] > 0.f)) z = 0.f;
-        if (g.Z) g.Z[ro * g.ldz + col] = z;
-        if (g.A) g.A[ro * g.lda + col] = (g.act == SAGNN_ACT_RELU) ? (z > 0.f ? z : 0.f) : z;
+        const int64_t dr = (v >> 2) * 8 + (v & 3);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          float z = acc[nt][v];
+          if (mk && !(mk[dr * g.ldmask + nt * 32] > 0.f)) z = 0.f;
+          if (zp) zp[dr * g.ldz + nt * 32] = z;
+          if (ap) ap[dr * g.lda + nt * 32] = relu ? (z > 0.f ? z : 0.f) : z;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int col = g.n0 + nt * 32 + r;
+        if (col >= g.nout) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t ro = t * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+          if (ro >= g.m) continue;
+          float z = acc[nt][v];
+          if (g.mask && !(g.mask[ro * g.ldmask + col] > 0.f)) z = 0.f;
+          if (g.Z) g.Z[ro * g.ldz + col] = z;
+          if (g.A) g.A[ro * g.lda + col] = (g.act == SAGNN_ACT_RELU) ? (z > 0.f ? z : 0.f) : z;
+        }
       }
     }
   }
