@@ -44,8 +44,11 @@ struct GemmArgs {
 };
 
 // ------------------------------------------------------------------------------------------
-// KPAD: kdim is not a multiple of 32, loads of X are guarded against the real k extent
-template <int NT, bool BF16, int WAVES, bool KPAD>
+// KPAD: kdim is not a multiple of 32, loads of X are guarded against the real k extent.
+// NG > 0: the k loop has exactly NG groups of 32 and is fully unrolled.  In straight-line code the
+// compiler counts outstanding loads exactly; around a loop back-edge it waits for ALL of them,
+// which would make the prefetch of the next group useless.
+template <int NT, bool BF16, int WAVES, bool KPAD, int NG>
 __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int NB = NT * 32;
@@ -90,14 +93,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
     if (BF16) {
       const bf16x8* __restrict__ Ws = reinterpret_cast<const bf16x8*>(smem);
       constexpr int JB = 2;
-      const int ngroups = kdim / (16 * JB);
+      const int ngroups = NG > 0 ? NG : kdim / (16 * JB);
       float4 cur[JB][2], nxt[JB][2];
 #pragma unroll
       for (int q = 0; q < JB; ++q) {
         cur[q][0] = ldx4(16 * q + 8 * h);
         cur[q][1] = ldx4(16 * q + 8 * h + 4);
       }
-      for (int gi = 0; gi < ngroups; ++gi) {
+#pragma unroll
+      for (int gi = 0; gi < (NG > 0 ? NG : ngroups); ++gi) {
         if (gi + 1 < ngroups) {
 #pragma unroll
           for (int q = 0; q < JB; ++q) {
@@ -105,6 +109,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
             nxt[q][1] = ldx4(16 * ((gi + 1) * JB + q) + 8 * h + 4);
           }
         }
+        if constexpr (NG > 0) __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of this group's MFMAs
 #pragma unroll
         for (int q = 0; q < JB; ++q) {
           const int j = gi * JB + q;
@@ -127,16 +132,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
     } else {
       const float* __restrict__ Ws = reinterpret_cast<const float*>(smem);
       constexpr int JB = 4;
-      const int ngroups = kdim / (8 * JB);
+      const int ngroups = NG > 0 ? NG : kdim / (8 * JB);
       float4 cur[JB], nxt[JB];
 #pragma unroll
       for (int q = 0; q < JB; ++q) cur[q] = ldx4(8 * q + 4 * h);
-      for (int gi = 0; gi < ngroups; ++gi) {
+#pragma unroll
+      for (int gi = 0; gi < (NG > 0 ? NG : ngroups); ++gi) {
         if (gi + 1 < ngroups) {
 #pragma unroll
           for (int q = 0; q < JB; ++q)
             nxt[q] = ldx4(8 * ((gi + 1) * JB + q) + 4 * h);
         }
+        if constexpr (NG > 0) __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of this group's MFMAs
 #pragma unroll
         for (int q = 0; q < JB; ++q) {
           const int j = gi * JB + q;
@@ -195,7 +202,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
 
 template <int NT, bool BF16, int WAVES>
 int launch_nn_waves(const GemmArgs& g, size_t lds, hipStream_t s) {
-  auto kern = (g.kdim & 31) ? gemm_nn_kernel<NT, BF16, WAVES, true> : gemm_nn_kernel<NT, BF16, WAVES, false>;
+  void (*kern)(const GemmArgs) = gemm_nn_kernel<NT, BF16, WAVES, false, 0>;
+  if (g.kdim & 31) kern = gemm_nn_kernel<NT, BF16, WAVES, true, 0>;
+  else if (g.kdim == 128) kern = gemm_nn_kernel<NT, BF16, WAVES, false, 4>;
+  else if (g.kdim == 256) kern = gemm_nn_kernel<NT, BF16, WAVES, false, 8>;
   SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int64_t ntiles = (g.m + 31) / 32;
