@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--stage-loop", action="store_true",
                     help="also time the 1.5D stage loop (Alg. 2) over the workload's column blocks, with one "
                          "and with two streams; reported under \"stage_loop\" (not part of `value`)")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the SpMM with the caches flushed before every call (a 1 GiB fill "
+                         "between iterations); reported under \"cold\" (not part of `value`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
                          "known traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -225,6 +228,22 @@ def main():
     if out["roofline"]["traffic"]:
         # rate at which the measured (counter) traffic of the profiled run moves at this run's time
         out["roofline"]["traffic_GBps"] = round(out["roofline"]["traffic"] / (spmm_ms * 1e-3) / 1e9, 1)
+    if args.cold:
+        # steady state is the headline (training repeats the same product every epoch); this is
+        # the same call with L2 and the memory-side cache flushed by a 1 GiB fill before it
+        flush = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        cold = []
+        for _ in range(max(args.steps // 2, 3)):
+            flush.fill_(1.0)
+            a, b = ev(), ev()
+            a.record()
+            sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, va, Hn, C=T, ws=ws)
+            b.record()
+            torch.cuda.synchronize()
+            cold.append(a.elapsed_time(b))
+        del flush
+        out["cold"] = {"spmm_median_ms": round(float(np.median(cold)), 4), "spmm_min_ms": round(min(cold), 4),
+                       "flush": "1 GiB device fill before every call"}
     if args.stage_loop:
         out["stage_loop"] = stage_loop_timing(sagnn, torch, wl, plan, rp, va, Hd, m, f, max(args.steps // 2, 3))
     if not args.no_cpu_baseline:
