@@ -40,6 +40,8 @@ constexpr uint32_t kSpmmMagic = 0x53A66E02u;
 
 // Slab-sweep schedule (long rows): a wavefront owns kSweepSlots row pieces.
 constexpr int kSweepSlots = 16;
+// longest run of entries summed into one register before it is folded into the piece's slot
+constexpr int kSweepRunMax = 128;
 constexpr int kSweepMaxSlabs = 384;
 constexpr int kSweepColBits = 27;           // column id bits in an encoded entry
 constexpr int kSweepMinLong = 16;           // smallest degree a "long" row can be given

@@ -186,7 +186,9 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
       while (s > 0 && i < LO(slot, s)) --s;
       while (s < S - 1 && i >= LO(slot, s + 1)) ++s;
       const int32_t rank = t - count_upto(LO(slot, s), j, p);
-      const bool last = i + p >= LO(slot, s + 1);
+      // a segment also ends every kSweepRunMax entries, which bounds the length of any serial
+      // fp32 accumulation (and with it the rounding bias on rows of equal terms)
+      const bool last = i + p >= LO(slot, s + 1) || (rank & (kSweepRunMax - 1)) == kSweepRunMax - 1;
       const int64_t pos = base + (int64_t)(SLAB_BASE(s, gi) + OFF(s, slot) + rank) * R + gi;
       code[pos] = c | ((uint32_t)slot << kSweepColBits) | (last ? 0x80000000u : 0u);
       vals[pos] = val[beg + i];
@@ -443,7 +445,7 @@ __global__ __launch_bounds__(256) void spmm_sweep_perm_kernel(
   const float* __restrict__ vw = vals + base;
   const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
 
-  vec acc = 0.f;
+  vec acc = 0.f, tot = 0.f;
   uint32_t cb[NB];
   float vb[NB];
 #pragma unroll
@@ -488,12 +490,20 @@ __global__ __launch_bounds__(256) void spmm_sweep_perm_kernel(
         }
       }
     }
+    if constexpr (SL == 1) {
+      // no slots to flush into: fold the running sum every 64 entries instead (two-level sum)
+      if ((e & 63) == 56) {
+        tot += acc;
+        acc = 0.f;
+      }
+    }
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       cb[q] = ncb[q];
       vb[q] = nvb[q];
     }
   }
+  if constexpr (SL == 1) acc += tot;
 
 #pragma unroll 1
   for (int ls = 0; ls < SL; ++ls) {

@@ -1,6 +1,8 @@
 """GPU parity: every step of the hot path, called through the C ABI, element by element against
 the CPU oracle on the same seeded inputs.  Integer results bit-exact; fp32 SpMM within
 1e-5 * sum|terms|; bf16 GEMM within 1e-2 * sum|terms|."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -297,6 +299,29 @@ def test_spmm_slab_sweep_falls_back_on_unsorted_rows(force_sweep):
     ref, zabs = oracle.spmm(rowptr2, np.minimum(colidx2, n - 1), val2, B, want_abs=True)
     assert_close(run_spmm(rowptr2, colidx2, val2, B, True, expect_mode=0), ref, zabs, RTOL_SPMM, "clamped column")
     _ = bad
+
+
+@pytest.mark.parametrize("sweep", ["0", "1"])
+@pytest.mark.parametrize("f", [16, 32, 64, 128, 256])
+def test_spmm_long_rows_of_equal_terms_stay_within_tolerance(f, sweep, monkeypatch):
+    """Rows whose products are all the same positive number are the worst case for fp32 rounding:
+    every addition of a long serial sum rounds the same way, so the error grows with the length of
+    the sum instead of its square root.  The kernels keep every serial run short; the result must
+    stay within the SpMM tolerance of the exact value (here known in closed form)."""
+    monkeypatch.setenv("SAGNN_SWEEP", sweep)
+    rng = np.random.default_rng(f)
+    n = 65_536
+    # enough entries in long rows for the planner to keep the sweep at every width
+    degs = np.concatenate([[60_000] * 8, [33_333] * 4, [4096, 4097, 9000], rng.integers(1, 40, size=3000)])
+    rowptr = np.zeros(degs.size + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum(degs)
+    colidx = np.concatenate([np.sort(rng.choice(n, size=int(d), replace=False)) for d in degs]).astype(np.int32)
+    val = np.concatenate([np.full(int(d), np.float32(1.0 / math.sqrt(d))) for d in degs]).astype(np.float32)
+    B = np.full((n, f), np.float32(math.sqrt(3.0)), dtype=np.float32)
+    exact = degs.astype(np.float64) * val[rowptr[:-1]].astype(np.float64) * float(B[0, 0])
+    got = run_spmm(rowptr, colidx, val, B, True, expect_mode=int(sweep)).cpu().numpy().astype(np.float64)
+    rel = np.abs(got - exact[:, None]) / exact[:, None]
+    assert rel.max() <= RTOL_SPMM, (rel.max(), int(rel.max(axis=1).argmax()))
 
 
 def test_spmm_rmat_with_and_without_sweep(monkeypatch):
