@@ -126,8 +126,9 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  * accumulate = 1 adds to it (the per-block accumulation of the algorithms).  fp32 FMA.
  * The summation order is a fixed function of (rowptr, colidx, m, k, nnz, f), so results are
  * reproducible run to run and across preparations (no floating-point atomics); it differs
- * from the stored order, so they agree with a sequential sum up to rounding
- * (|err| <= ~1e-6 * sum |val||B|).
+ * from the stored order, so they agree with a sequential sum up to rounding.  No serial run of
+ * additions is longer than 256 terms (partial sums are folded in a second level), which keeps
+ * |err| <= 1e-5 * sum |val||B| even for rows whose products are all equal; ~1e-7 is typical.
  * A column index outside [0,k) is clamped into range (never read out of bounds).
  *
  * Scheduling: the pattern (and here also the values) of A is fixed during training, so a
@@ -154,6 +155,10 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  * memory was overwritten after preparation, C is unspecified (the kernels check a generation
  * tag and exit), but nothing faults.
  * With d_ws == NULL a simple one-wavefront-per-row kernel is used (no preparation).
+ * The planner's choices can be overridden for experiments through environment variables read
+ * at spmm_csr_prepare() (SAGNN_SWEEP = 0/1 forces the schedule; SAGNN_SWEEP_MINDEG, _PIECE,
+ * _SLAB_MB, _MIN_WAVES, _WINDOW_PCT, _LPT, _GROUPS, _STAGGER tune it); every setting gives the
+ * same product up to rounding.
  * B and C must not overlap.
  */
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
