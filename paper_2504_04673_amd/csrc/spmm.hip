@@ -360,14 +360,21 @@ __global__ __launch_bounds__(kBlock) void spmm_row_kernel(SPMM_PTR_PARAMS, const
     lo = lo < 0 ? 0 : lo;
     hi = hi > d.nnz ? (int32_t)d.nnz : hi;
     for (int c4 = lane; c4 * 4 < f_total; c4 += 64) {
-      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      // two-level sum: runs of 128 entries, then the runs (keeps the rounding error of a long
+      // row of equal terms from growing with the row length)
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), tot = acc;
       for (int32_t e = lo; e < hi; ++e) {
         const uint32_t c = (uint32_t)colidx[e];
         const uint32_t cc = c > d.kmax ? d.kmax : c;
         const float v = val[e];
         const float4 h = *reinterpret_cast<const float4*>(B + (int64_t)cc * d.ldb + c4 * 4);
         acc.x += v * h.x; acc.y += v * h.y; acc.z += v * h.z; acc.w += v * h.w;
+        if (((e - lo) & 127) == 127) {
+          tot.x += acc.x; tot.y += acc.y; tot.z += acc.z; tot.w += acc.w;
+          acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
       }
+      acc.x += tot.x; acc.y += tot.y; acc.z += tot.z; acc.w += tot.w;
       float4* p = reinterpret_cast<float4*>(C + r * d.ldc + c4 * 4);
       if (d.accumulate) {
         const float4 o = *p;

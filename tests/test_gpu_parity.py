@@ -322,6 +322,10 @@ def test_spmm_long_rows_of_equal_terms_stay_within_tolerance(f, sweep, monkeypat
     got = run_spmm(rowptr, colidx, val, B, True, expect_mode=int(sweep)).cpu().numpy().astype(np.float64)
     rel = np.abs(got - exact[:, None]) / exact[:, None]
     assert rel.max() <= RTOL_SPMM, (rel.max(), int(rel.max(axis=1).argmax()))
+    if sweep == "0":                                          # the kernel for calls without a workspace
+        got = run_spmm(rowptr, colidx, val, B, False).cpu().numpy().astype(np.float64)
+        rel = np.abs(got - exact[:, None]) / exact[:, None]
+        assert rel.max() <= RTOL_SPMM, (rel.max(), int(rel.max(axis=1).argmax()))
 
 
 def test_spmm_rmat_with_and_without_sweep(monkeypatch):
