@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="also time the SpMM with the caches flushed before every call (a 1 GiB fill "
                          "between iterations); reported under \"cold\" (not part of `value`)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time pack+spmm+gemm issued eagerly and replayed from a HIP graph "
+                         "(the plan synchronises with the host and stays outside)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy before the timed region (a kernel of "
                          "known traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -244,6 +247,35 @@ def main():
         del flush
         out["cold"] = {"spmm_median_ms": round(float(np.median(cold)), 4), "spmm_min_ms": round(min(cold), 4),
                        "flush": "1 GiB device fill before every call"}
+    if args.graph:
+        def tail():
+            sagnn.spmm_pack_rows(Hd, plan.needed, out=Hn)
+            sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, va, Hn, C=T, ws=ws)
+            sagnn.dense_gemm_act(T, W, act=sagnn.ACT_RELU, want_z=False, want_act=True, out=(None, Ho))
+        gr = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            tail()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(gr, stream=side):
+                tail()
+        torch.cuda.synchronize()
+        ref = Ho.clone()
+
+        def wall(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+        reps = max(args.steps, 10)
+        eager_ms, replay_ms = wall(tail, reps), wall(gr.replay, reps)
+        assert torch.equal(ref, Ho), "graph replay differs from the eager calls"
+        out["graph"] = {"calls": "pack+spmm+gemm_relu", "eager_ms": round(eager_ms, 4),
+                        "replay_ms": round(replay_ms, 4), "reps": reps}
     if args.stage_loop:
         out["stage_loop"] = stage_loop_timing(sagnn, torch, wl, plan, rp, va, Hd, m, f, max(args.steps // 2, 3))
     if not args.no_cpu_baseline:

@@ -106,6 +106,17 @@ int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx, int6
                           uint32_t flags, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Streams and graphs.  Every entry point enqueues its work on the stream it is given.  The
+ * set-up calls (spmm_plan_needed_rows, spmm_csr_prepare, spmm_split_colblocks,
+ * spmm_csr_transpose) copy small results back and synchronise that stream, so they cannot be
+ * recorded into a graph.  The per-step calls (spmm_pack_rows, spmm_csr_tallskinny,
+ * dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd, spmm_stage_loop) only launch kernels and, in the
+ * stage loop, record and wait for events between its two streams (forked from and joined back
+ * into the product stream): no host synchronisation, no memset, no allocation.  They may be
+ * captured into a HIP graph and replayed; a replay gives the same bits as the eager calls.
+ */
+
+/* ---------------------------------------------------------------------------------------
  * Step 2: pack / gather (Alg. 1 first statement; Alg. 2 "H[srows,:]").
  *
  *   d_out[r, 0:f) = d_H[d_rows[r], 0:f)   for r in [0,N)
