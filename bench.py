@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--cold", action="store_true",
                     help="also time the SpMM with the caches flushed before every call (a 1 GiB fill "
                          "between iterations); reported under \"cold\" (not part of `value`)")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="prepare the SpMM schedule without the measured choice between plan variants")
     ap.add_argument("--graph", action="store_true",
                     help="also time pack+spmm+gemm issued eagerly and replayed from a HIP graph "
                          "(the plan synchronises with the host and stays outside)")
@@ -133,9 +135,15 @@ def main():
     Hn = torch.empty((N, f), dtype=torch.float32, device=dev)
     T = torch.empty((m, f), dtype=torch.float32, device=dev)
     Ho = torch.empty((m, f_out), dtype=torch.float32, device=dev)
-    ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, va, N, f)
+    # one-time preparation of the product's schedule, outside the timed region (the pattern is
+    # fixed for a training run); by default with the measured choice between plan variants
+    if args.no_tune:
+        ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, va, N, f)
+    else:
+        sagnn.spmm_pack_rows(Hd, plan.needed, out=Hn)
+        ws = sagnn.spmm_csr_prepare_tuned(rp, plan.colidx_compact, va, Hn, C=T)
     torch.cuda.synchronize()
-    log(f"[bench] spmm schedule: {ws.info()}")
+    log(f"[bench] spmm schedule: {ws.info()} tuned: {ws.choice}")
     models = workloads.byte_models(m, n, nnz, N, f, f_out, nb)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -203,7 +211,7 @@ def main():
             "cfg5": "SBM 2M vertices, rank-0 block of 16, ordered by community",
         }[wl.name] + f", m={m} n={n} nnz={nnz} N_needed={N} f={f} f_out={f_out} nb={nb}",
             "step": ("" if args.no_plan else "plan+") + "pack+spmm+gemm_relu", "seed": 0,
-            "spmm_schedule": ws.info(),
+            "spmm_schedule": dict(ws.info(), tuned=ws.choice),
             "scale": args.scale},
         "roofline": {
             "kernel": "spmm_csr_tallskinny (all kernels of one call: slab-sweep + nonzero-splitting "
@@ -296,9 +304,10 @@ def train_step_bench(args, sagnn, workloads, torch, np, dev, kw):
     d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
     rp, ci, va = d(g.rowptr), d(g.colidx), d(g.val)
     H0, W1, W2, G2 = d(wl.H), d(wl.W), d(wl.extra["W2"]), d(wl.extra["G2"])
-    ws = sagnn.spmm_csr_prepare(rp, ci, va, m, f)
-    log(f"[bench] spmm schedule: {ws.info()}")
     T1 = torch.empty((m, f), dtype=torch.float32, device=dev)
+    ws = sagnn.spmm_csr_prepare(rp, ci, va, m, f) if args.no_tune else \
+        sagnn.spmm_csr_prepare_tuned(rp, ci, va, H0, C=T1)
+    log(f"[bench] spmm schedule: {ws.info()} tuned: {ws.choice}")
     Z1, H1, T2, Z2 = (torch.empty_like(T1) for _ in range(4))
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
@@ -346,7 +355,7 @@ def train_step_bench(args, sagnn, workloads, torch, np, dev, kw):
         "config": {"workload": f"cfg5_train: SBM 2M vertices ordered by community, whole graph, m=n={m} nnz={nnz} "
                                f"f={f}, 2-layer GCN forward + backward, GEMM operands bf16 (fp32 accumulate)",
                    "step": "spmm+gemm_relu, spmm+gemm, bwd layer 2 (spmm, S W^T .* mask, H^T S), bwd layer 1 (spmm, H^T S)",
-                   "seed": 0, "spmm_schedule": ws.info(), "scale": args.scale},
+                   "seed": 0, "spmm_schedule": dict(ws.info(), tuned=ws.choice), "scale": args.scale},
         "roofline": {"kernel": "spmm_csr_tallskinny (the two forward calls, bracketed by events)", "bound": "hbm",
                      "achieved": round(spmm_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(spmm_gbps / HBM_PEAK_GBPS, 4), "traffic": parse_traffic("cfg5_train", f),

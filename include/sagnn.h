@@ -107,7 +107,7 @@ int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx, int6
 
 /* ---------------------------------------------------------------------------------------
  * Streams and graphs.  Every entry point enqueues its work on the stream it is given.  The
- * set-up calls (spmm_plan_needed_rows, spmm_csr_prepare, spmm_split_colblocks,
+ * set-up calls (spmm_plan_needed_rows, spmm_csr_prepare, spmm_csr_prepare_tuned, spmm_split_colblocks,
  * spmm_csr_transpose) copy small results back and synchronise that stream, so they cannot be
  * recorded into a graph.  The per-step calls (spmm_pack_rows, spmm_csr_tallskinny,
  * dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd, spmm_stage_loop) only launch kernels and, in the
@@ -176,6 +176,24 @@ int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
 int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                      int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws, size_t ws_bytes,
                      void* stream);
+/* spmm_csr_prepare() with a measured choice between a few variants of the slab-sweep plan (how
+ * long rows are cut into pieces, from which length a row counts as long): each variant is
+ * prepared into d_ws and the product is run six times on the caller's operand d_B (k x f,
+ * ldb), writing d_C (m x f, ldc; overwritten, holds a valid product afterwards); the fastest
+ * variant is left in d_ws.  Which wavefronts share a part of B in cache at a time depends on
+ * such details and moves the time of the product by a few per cent either way, differently for
+ * every matrix and width; the pattern is fixed for a training run, so measuring once pays.
+ * A variant replaces the default plan only if it is more than 1.5 % faster.  Costs about five
+ * preparations and thirty products; synchronises the stream.  When the plain
+ * schedule is chosen there is nothing to vary and the call equals spmm_csr_prepare().  Every
+ * variant computes the same product up to rounding order.
+ * h_choice (host, 4 values, may be NULL): piece length and long-row threshold of the variant
+ * kept (0 = default), its best time in microseconds, its index.
+ */
+int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                           int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws,
+                           size_t ws_bytes, const float* d_B, int64_t ldb, float* d_C,
+                           int64_t ldc, int32_t* h_choice, void* stream);
 /* What spmm_csr_prepare() decided for a workspace (host query, no GPU work).  h_info[8]:
  * [0] schedule (0 nonzero splitting, 1 slab sweep + nonzero splitting for short rows),
  * [1] wavefront streams of the sweep, [2] entries in them, [3] rows, [4] entries and

@@ -17,7 +17,8 @@ PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_pack_rows",
-    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_schedule_info", "spmm_csr_tallskinny",
+    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
+    "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
     "spmm_transpose_workspace_bytes", "spmm_csr_transpose",
@@ -66,6 +67,7 @@ def lib():
         L.spmm_pack_rows.argtypes = [vp, i64, i64, i32, vp, i64, vp, i64, vp]
         L.spmm_csr_workspace_bytes.argtypes = [i64, i64, i32, psz]
         L.spmm_csr_prepare.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
+        L.spmm_csr_prepare_tuned.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, i64, vp, i64, vp, vp]
         L.spmm_csr_schedule_info.argtypes = [vp, vp]
         L.spmm_csr_tallskinny.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i64, i32, vp,
                                           sz, vp]
@@ -184,6 +186,7 @@ class SpmmWorkspace:
     m: int
     nnz: int
     f: int
+    choice: dict = None           # filled in by spmm_csr_prepare_tuned
 
     def info(self) -> dict:
         """Schedule chosen by spmm_csr_prepare (see spmm_csr_schedule_info)."""
@@ -208,6 +211,31 @@ def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int) -> SpmmWorkspace:
     _check(L.spmm_csr_prepare(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
                               buf.numel(), _stream()), "spmm_csr_prepare")
     return SpmmWorkspace(buf, m, nnz, f)
+
+
+def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None) -> SpmmWorkspace:
+    """spmm_csr_prepare with a measured choice between a few plan variants, timed on B (k x f).
+    C (m x f) is overwritten with the product; allocated here when not given."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    B = _dev(B, torch.float32, "B")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    k, f = B.shape
+    if C is None:
+        C = torch.empty((m, f), dtype=torch.float32, device=B.device)
+    _dev(C, torch.float32, "C")
+    L = lib()
+    wsb = ctypes.c_size_t(0)
+    _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
+    buf = _ws(wsb.value, rowptr.device)
+    choice = np.zeros(4, dtype=np.int32)
+    _check(L.spmm_csr_prepare_tuned(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
+                                    buf.numel(), _ptr(B), B.stride(0), _ptr(C), C.stride(0),
+                                    choice.ctypes.data_as(ctypes.c_void_p), _stream()),
+           "spmm_csr_prepare_tuned")
+    return SpmmWorkspace(buf, m, nnz, f, {"piece": int(choice[0]), "min_long": int(choice[1]),
+                                         "best_us": int(choice[2]), "variant": int(choice[3])})
 
 
 def spmm_csr_tallskinny(rowptr, colidx, val, B, C=None, accumulate=False, ws: SpmmWorkspace = None):

@@ -130,6 +130,13 @@ struct SweepPlanResult {
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
                   int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
                   hipStream_t s, SweepPlanResult* out);
+// Planner parameters a tuning call may set for the next sweep_prepare() of this thread
+// (0 = the default; environment overrides win over both).
+struct SweepTuning {
+  int piece;      // longest piece a long row is cut into
+  int min_long;   // long-row threshold used where the planner would pick 64
+};
+void sweep_set_tuning(SweepTuning t);
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
                  int32_t accumulate, int32_t f_total, hipStream_t s);

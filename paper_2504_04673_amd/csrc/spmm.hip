@@ -673,6 +673,69 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
   return SAGNN_OK;
 }
 
+SAGNN_EXPORT int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                        const float* d_val, int64_t m, int64_t k, int64_t nnz,
+                                        int32_t f, void* d_ws, size_t ws_bytes, const float* d_B,
+                                        int64_t ldb, float* d_C, int64_t ldc, int32_t* h_choice,
+                                        void* stream) {
+  using namespace sagnn;
+  if (!d_B || !d_C || ldb < f || ldc < f) return SAGNN_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  // (piece, long-row threshold) variants of the slab-sweep plan; {0, 0} is spmm_csr_prepare's own
+  static const SweepTuning cand[] = {{0, 0}, {4608, 0}, {3584, 0}, {0, 96}, {4608, 96}};
+  const int n_cand = (int)(sizeof(cand) / sizeof(cand[0]));
+  int best = -1, last = -1;
+  float best_ms = 0.f;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&]() {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    sweep_set_tuning(SweepTuning{0, 0});
+  };
+  for (int c = 0; c < n_cand; ++c) {
+    sweep_set_tuning(cand[c]);
+    int rc = spmm_csr_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, stream);
+    sweep_set_tuning(SweepTuning{0, 0});
+    if (rc != SAGNN_OK) { cleanup(); return rc; }
+    last = c;
+    SpmmHostDesc desc{};
+    if (!spmm_desc_get(d_ws, &desc) || desc.mode != 1) { best = c; break; }   // nothing to tune
+    if (!e0) {
+      hipError_t e = hipEventCreate(&e0);
+      if (e == hipSuccess) e = hipEventCreate(&e1);
+      if (e != hipSuccess) { set_hip_error(e); cleanup(); return SAGNN_EHIP; }
+    }
+    float ms_min = 0.f;
+    for (int rep = 0; rep < 6; ++rep) {   // the first run warms the caches and is not counted
+      hipError_t e = hipEventRecord(e0, s);
+      if (e != hipSuccess) { set_hip_error(e); cleanup(); return SAGNN_EHIP; }
+      rc = launch_spmm(d_rowptr, d_colidx, d_val, m, k, nnz, d_B, ldb, f, d_C, ldc, 0, d_ws, ws_bytes, s);
+      if (rc != SAGNN_OK) { cleanup(); return rc; }
+      float ms = 0.f;
+      e = hipEventRecord(e1, s);
+      if (e == hipSuccess) e = hipEventSynchronize(e1);
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+      if (e != hipSuccess) { set_hip_error(e); cleanup(); return SAGNN_EHIP; }
+      if (rep == 1 || (rep > 1 && ms < ms_min)) ms_min = ms;
+    }
+    // a variant has to beat the default plan by more than the run-to-run noise of the timing
+    if (best < 0 || ms_min < (best == 0 ? 0.985f * best_ms : best_ms)) { best = c; best_ms = ms_min; }
+  }
+  if (best != last) {
+    sweep_set_tuning(cand[best]);
+    int rc = spmm_csr_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, stream);
+    if (rc != SAGNN_OK) { cleanup(); return rc; }
+  }
+  cleanup();
+  if (h_choice) {
+    h_choice[0] = cand[best].piece;
+    h_choice[1] = cand[best].min_long;
+    h_choice[2] = (int32_t)(best_ms * 1000.f);
+    h_choice[3] = best;
+  }
+  return SAGNN_OK;
+}
+
 SAGNN_EXPORT int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info) {
   using namespace sagnn;
   if (!d_ws || !h_info) return SAGNN_EINVAL;

@@ -564,8 +564,11 @@ struct Piece {
 };
 
 std::atomic<uint64_t> g_generation{1};
+thread_local SweepTuning g_tuning{0, 0};
 
 }  // namespace
+
+void sweep_set_tuning(SweepTuning t) { g_tuning = t; }
 
 // ---------------------------------------------------------------------------------------
 // host side of the preparation: classify rows, cut long rows into pieces, deal pieces to the
@@ -598,10 +601,10 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
       const int64_t d = (int64_t)rp[r + 1] - rp[r];
       if (d >= kSweepMinLong && d < 64) mid += d;
     }
-    min_long = (mid * 4 >= nnz) ? kSweepMinLong : 64;
+    min_long = (mid * 4 >= nnz) ? kSweepMinLong : (g_tuning.min_long > 0 ? g_tuning.min_long : 64);
   }
   if (min_long < kSweepMinLong) min_long = kSweepMinLong;
-  int piece_max = env_int("SAGNN_SWEEP_PIECE", 4096);
+  int piece_max = env_int("SAGNN_SWEEP_PIECE", g_tuning.piece > 0 ? g_tuning.piece : 4096);
   if (piece_max < 1024) piece_max = 1024;
   if (piece_max > 32768) piece_max = 32768;
   const int64_t slab_bytes = (int64_t)env_int("SAGNN_SWEEP_SLAB_MB", 4) << 20;

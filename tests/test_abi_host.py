@@ -60,6 +60,7 @@ def test_argument_validation_before_launch():
     assert L.spmm_csr_tallskinny(None, None, None, 0, 4, 0, None, 16, 16, None, 16, 0, None, 0, None) == 0
     assert L.spmm_csr_tallskinny(None, None, None, 4, 4, 4, None, 16, 18, None, 16, 0, None, 0, None) == -1
     assert L.spmm_csr_prepare(None, None, None, 4, 4, 4, 16, None, 0, None) == -1
+    assert L.spmm_csr_prepare_tuned(None, None, None, 4, 4, 4, 16, None, 0, None, 16, None, 16, None, None) == -1
     # plan: missing host arrays
     assert L.spmm_plan_needed_rows(None, None, 4, 4, 0, None, 1, None, 0, None, None, None, 0, 0, None) == -1
     # GEMM: unsupported sizes

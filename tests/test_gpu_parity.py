@@ -328,6 +328,31 @@ def test_spmm_long_rows_of_equal_terms_stay_within_tolerance(f, sweep, monkeypat
         assert rel.max() <= RTOL_SPMM, (rel.max(), int(rel.max(axis=1).argmax()))
 
 
+def test_spmm_prepare_tuned_keeps_a_correct_plan(monkeypatch):
+    """The tuned preparation tries several plan variants on the caller's operand; whichever it
+    keeps has to give the product, in the buffer it wrote during tuning and in later calls.  A
+    matrix too small for the sweep has nothing to vary and behaves like the plain preparation."""
+    g = synth.rmat_graph(60_000, 4_000_000, 11)
+    H = synth.normal((g.n, 128), 11, synth.STREAM_H)
+    ref, zabs = oracle.spmm(g.rowptr, g.colidx, g.val, H, want_abs=True)
+    rp, ci, v = dev(g.rowptr), dev(g.colidx), dev(g.val)
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    C = torch.full((g.m, 128), float("nan"), device="cuda")
+    ws = sagnn.spmm_csr_prepare_tuned(rp, ci, v, dev(H), C=C)
+    torch.cuda.synchronize()
+    assert ws.info()["mode"] == 1 and 0 <= ws.choice["variant"] < 5 and ws.choice["best_us"] > 0
+    assert_close(C, ref, zabs, RTOL_SPMM, "product left by the tuning runs")
+    got = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(H), ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got, ref, zabs, RTOL_SPMM, f"tuned plan {ws.choice}")
+    monkeypatch.setenv("SAGNN_SWEEP", "0")
+    ws0 = sagnn.spmm_csr_prepare_tuned(rp, ci, v, dev(H))
+    assert ws0.info()["mode"] == 0 and ws0.choice["variant"] == 0
+    got0 = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(H), ws=ws0)
+    torch.cuda.synchronize()
+    assert_close(got0, ref, zabs, RTOL_SPMM, "plain schedule through the tuned entry point")
+
+
 def test_spmm_rmat_with_and_without_sweep(monkeypatch):
     g = synth.rmat_graph(60_000, 4_000_000, 9)
     H = synth.normal((g.n, 128), 9, synth.STREAM_H)
