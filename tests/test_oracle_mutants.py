@@ -45,6 +45,12 @@ def gemm_pins():
     pins.test_gemm_bf16_rounds_operands()
 
 
+def magnitude_pins():
+    for tx, tw in ((False, False), (False, True), (True, False), (True, True)):
+        pins.test_gemm_magnitude_companion_with_given_scale(tx, tw)
+    pins.test_layer_magnitude_companions_propagate_the_spmm_scale()
+
+
 def layer_pins():
     pins.test_gcn_layer_fwd_against_dense_numpy()
     pins.test_gcn_backward_finite_differences()
@@ -84,6 +90,17 @@ MUTANTS = [
     ("layer forward multiplies before aggregating with the wrong operand order kept: T is H",
      "oracle_spmm(rowptr, colidx, val, m, H, ldh, f_in, T, f_in, 0, Tabs);\n  oracle_gemm(T,",
      "oracle_spmm(rowptr, colidx, val, m, H, ldh, f_in, T, f_in, 0, Tabs);\n  oracle_gemm(H,", layer_pins),
+    ("gemm magnitude ignores the scale handed down from the earlier product",
+     "double xa = Xabs ? (transX ? Xabs[p * m + i] : Xabs[i * k + p]) : fabs((double)x);",
+     "double xa = fabs((double)x);", magnitude_pins),
+    ("gemm magnitude reads the handed-down scale untransposed",
+     "(transX ? Xabs[p * m + i] : Xabs[i * k + p])", "Xabs[i * k + p]", magnitude_pins),
+    ("gemm magnitude multiplies by signed weights", "a += xa * fabs((double)w);", "a += xa * (double)w;",
+     magnitude_pins),
+    ("layer forward does not hand the SpMM scale to the GEMM", "bf16, Z, f_out, Tabs, Zabs);",
+     "bf16, Z, f_out, NULL, Zabs);", magnitude_pins),
+    ("layer backward does not hand the SpMM scale to the GEMM", "Gprev, f_in, Sabs, Gabs);",
+     "Gprev, f_in, NULL, Gabs);", magnitude_pins),
 ]
 
 

@@ -249,6 +249,55 @@ def test_gemm_vs_numpy_fp64(m, k, n, tx, tw):
     assert np.allclose(Zabs, np.abs(Xe.astype(np.float64)) @ np.abs(We.astype(np.float64)), rtol=1e-12)
 
 
+@pytest.mark.parametrize("tx,tw", [(False, False), (False, True), (True, False), (True, True)])
+def test_gemm_magnitude_companion_with_given_scale(tx, tw):
+    """The scale of the rounding-error bound can be handed down from an earlier product: with
+    Xabs given, Zabs = op(Xabs) |op(W)| (numpy fp64, an independent evaluation), whatever X holds;
+    without it, |op(X)| |op(W)|.  Non-square shapes so that a transposed index cannot pass."""
+    rng = np.random.default_rng(17 + 2 * tx + tw)
+    m, k, n = 6, 11, 4
+    X = rng.standard_normal((k, m) if tx else (m, k)).astype(np.float32)
+    W = rng.standard_normal((n, k) if tw else (k, n)).astype(np.float32)
+    A = rng.random(X.shape) * 5.0 + 0.5                      # a scale unrelated to |X|
+    Ae = A.T if tx else A
+    We = np.abs((W.T if tw else W).astype(np.float64))
+    Z, Zabs = oracle.gemm(X, W, transX=tx, transW=tw, Xabs=A, want_abs=True)
+    assert np.allclose(Zabs, Ae @ We, rtol=1e-13, atol=0)
+    Z0, Zabs0 = oracle.gemm(X, W, transX=tx, transW=tw, want_abs=True)
+    assert np.array_equal(Z, Z0)                             # the scale never touches the product
+    assert np.allclose(Zabs0, np.abs((X.T if tx else X).astype(np.float64)) @ We, rtol=1e-13, atol=0)
+    assert not np.allclose(Zabs, Zabs0, rtol=1e-3)
+    # bfloat16 mode: the handed-down scale multiplies the magnitudes of the ROUNDED weights
+    _, Zb = oracle.gemm(X, W, bf16=True, transX=tx, transW=tw, Xabs=A, want_abs=True)
+    Wb = np.abs(oracle.bf16_round(W).astype(np.float64))
+    assert np.allclose(Zb, Ae @ (Wb.T if tw else Wb), rtol=1e-13, atol=0)
+
+
+def test_layer_magnitude_companions_propagate_the_spmm_scale():
+    """Tabs = |A||H|; Zabs = Tabs |W|; Sabs = |A||G|; Gabs = Sabs |W^T|; Yabs = |Hprev^T| |S| --
+    each checked against dense numpy fp64 on a rectangular-feature, non-symmetric case."""
+    rng = np.random.default_rng(33)
+    n, fi, fo = 19, 7, 5
+    rowptr, colidx, val = random_csr(n, n, 0.25, rng)
+    A = np.abs(np.array(dense_of(rowptr, colidx, val, n)))
+    H = rng.standard_normal((n, fi)).astype(np.float32)
+    W = rng.standard_normal((fi, fo)).astype(np.float32)
+    G = rng.standard_normal((n, fo)).astype(np.float32)
+    Zp = rng.standard_normal((n, fi)).astype(np.float32)
+    aW = np.abs(W.astype(np.float64))
+    fwd = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1)
+    Tabs = A @ np.abs(H.astype(np.float64))
+    assert np.allclose(fwd["Tabs"], Tabs, rtol=1e-13, atol=0)
+    assert np.allclose(fwd["Zabs"], Tabs @ aW, rtol=1e-13, atol=0)
+    assert not np.allclose(fwd["Zabs"], np.abs(fwd["T"].astype(np.float64)) @ aW, rtol=1e-3)
+    bwd = oracle.gcn_layer_bwd(rowptr, colidx, val, G, W, Zp, H)
+    Sabs = A @ np.abs(G.astype(np.float64))
+    assert np.allclose(bwd["Sabs"], Sabs, rtol=1e-13, atol=0)
+    assert np.allclose(bwd["Gabs"], Sabs @ aW.T, rtol=1e-13, atol=0)
+    assert np.allclose(bwd["Yabs"], np.abs(H.astype(np.float64)).T @ np.abs(bwd["S"].astype(np.float64)),
+                       rtol=1e-13, atol=0)
+
+
 def test_bf16_round_known_values_and_torch():
     """bfloat16 keeps 8 significand bits; ties go to even."""
     one = np.float32(1.0)
