@@ -21,7 +21,8 @@
  * Conventions for every entry point
  *   - d_* pointers are device memory owned by the caller, h_* pointers are host memory
  *     owned by the caller.  The library allocates no device memory and keeps no state
- *     besides the last HIP error code and the descriptors of prepared SpMM workspaces.
+ *     besides the last HIP error code and one small host descriptor per prepared SpMM
+ *     workspace, from spmm_csr_prepare() until spmm_csr_release().
  *   - Matrices are row-major; ld* are leading dimensions in elements.
  *   - CSR: rowptr has m+1 int32 entries with rowptr[0] = 0 and rowptr[m] = nnz; colidx and
  *     val have nnz entries.  Entries of a row may be unsorted and may repeat: the planner
@@ -200,6 +201,11 @@ int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx, con
  * [5] chunks of the nonzero-splitting part, [6] rows cut into several pieces,
  * [7] 1 if the matrix has empty rows.  SAGNN_EINVAL if the workspace is unknown. */
 int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info);
+/* Forget the host descriptor of a prepared workspace.  Call it before the workspace memory is
+ * freed or reused for something else: afterwards the address is unknown to the library again
+ * (spmm_csr_tallskinny with it returns SAGNN_EINVAL until it is prepared anew), and nothing of
+ * the preparation stays behind in the process.  Unknown addresses are accepted (no-op). */
+int spmm_csr_release(const void* d_ws);
 int spmm_csr_tallskinny(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                         int64_t m, int64_t k, int64_t nnz, const float* d_B, int64_t ldb,
                         int32_t f, float* d_C, int64_t ldc, int32_t accumulate, void* d_ws,

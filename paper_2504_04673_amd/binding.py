@@ -18,7 +18,7 @@ EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_pack_rows",
     "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
-    "spmm_csr_tallskinny",
+    "spmm_csr_release", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
     "spmm_transpose_workspace_bytes", "spmm_csr_transpose",
@@ -69,6 +69,7 @@ def lib():
         L.spmm_csr_prepare.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
         L.spmm_csr_prepare_tuned.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, i64, vp, i64, vp, vp]
         L.spmm_csr_schedule_info.argtypes = [vp, vp]
+        L.spmm_csr_release.argtypes = [vp]
         L.spmm_csr_tallskinny.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i64, i32, vp,
                                           sz, vp]
         L.dense_gemm_act.argtypes = [vp, i64, vp, i64, i32, i64, i32, i32, i32, i32, vp, i64, vp, i64,
@@ -110,6 +111,22 @@ def _dev(t: torch.Tensor, dtype, name: str):
     if t.dtype != dtype or not t.is_contiguous():
         raise ValueError(f"{name}: expected contiguous {dtype}")
     return t
+
+
+def _mat(t: torch.Tensor, name: str):
+    """A row-major fp32 matrix, possibly a column slice of a wider one: unit stride along a row,
+    the row stride is passed to the library as the leading dimension."""
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a CUDA/HIP tensor (there is no CPU path)")
+    if t.dtype != torch.float32 or t.dim() != 2:
+        raise ValueError(f"{name}: expected a 2-D float32 tensor")
+    if t.shape[0] > 1 and t.shape[1] > 0 and (t.stride(1) != 1 or t.stride(0) < t.shape[1]):
+        raise ValueError(f"{name}: rows must be contiguous (unit stride inside a row)")
+    return t
+
+
+def _ld(t: torch.Tensor) -> int:
+    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.stride(0)), int(t.shape[1]))
 
 
 def _ws(nbytes: int, device) -> torch.Tensor:
@@ -168,14 +185,14 @@ def plan_buffers(m, n, nnz, nb, device, cap=None, want_compact=True):
 
 def spmm_pack_rows(H, rows, out=None):
     """out[r,:] = H[rows[r],:] (Alg. 1, packed buffer)."""
-    H = _dev(H, torch.float32, "H")
+    H = _mat(H, "H")
     rows = _dev(rows, torch.int32, "rows")
     n, f = H.shape
     N = rows.numel()
     if out is None:
         out = torch.empty((N, f), dtype=torch.float32, device=H.device)
-    _dev(out, torch.float32, "out")
-    _check(lib().spmm_pack_rows(_ptr(H), n, H.stride(0), f, _ptr(rows), N, _ptr(out), out.stride(0),
+    _mat(out, "out")
+    _check(lib().spmm_pack_rows(_ptr(H), n, _ld(H), f, _ptr(rows), N, _ptr(out), _ld(out),
                                 _stream()), "spmm_pack_rows")
     return out
 
@@ -187,6 +204,19 @@ class SpmmWorkspace:
     nnz: int
     f: int
     choice: dict = None           # filled in by spmm_csr_prepare_tuned
+    k: int = 0                    # rows of B the schedule was prepared for
+
+    def release(self):
+        """Drop the library's host descriptor of this workspace (spmm_csr_release)."""
+        if self.buf is not None:
+            lib().spmm_csr_release(_ptr(self.buf))
+            self.buf = None
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:
+            pass
 
     def info(self) -> dict:
         """Schedule chosen by spmm_csr_prepare (see spmm_csr_schedule_info)."""
@@ -210,7 +240,7 @@ def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int) -> SpmmWorkspace:
     buf = _ws(wsb.value, rowptr.device)
     _check(L.spmm_csr_prepare(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
                               buf.numel(), _stream()), "spmm_csr_prepare")
-    return SpmmWorkspace(buf, m, nnz, f)
+    return SpmmWorkspace(buf, m, nnz, f, None, int(k))
 
 
 def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None) -> SpmmWorkspace:
@@ -235,7 +265,7 @@ def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None) -> SpmmWorkspace:
                                     choice.ctypes.data_as(ctypes.c_void_p), _stream()),
            "spmm_csr_prepare_tuned")
     return SpmmWorkspace(buf, m, nnz, f, {"piece": int(choice[0]), "min_long": int(choice[1]),
-                                         "best_us": int(choice[2]), "variant": int(choice[3])})
+                                         "best_us": int(choice[2]), "variant": int(choice[3])}, int(k))
 
 
 def spmm_csr_tallskinny(rowptr, colidx, val, B, C=None, accumulate=False, ws: SpmmWorkspace = None):
@@ -243,18 +273,18 @@ def spmm_csr_tallskinny(rowptr, colidx, val, B, C=None, accumulate=False, ws: Sp
     rowptr = _dev(rowptr, torch.int32, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     val = _dev(val, torch.float32, "val")
-    B = _dev(B, torch.float32, "B")
+    B = _mat(B, "B")
     m, nnz = rowptr.numel() - 1, colidx.numel()
     k, f = B.shape
     if C is None:
         if accumulate:
             raise ValueError("accumulate needs C")
         C = torch.empty((m, f), dtype=torch.float32, device=B.device)
-    _dev(C, torch.float32, "C")
-    if ws is not None and (ws.m != m or ws.nnz != nnz or ws.f < f):
-        raise ValueError("workspace was prepared for another matrix")
+    _mat(C, "C")
+    if ws is not None and (ws.m != m or ws.nnz != nnz or ws.f < f or k < ws.k):
+        raise ValueError("workspace was prepared for another matrix or a taller operand")
     rc = lib().spmm_csr_tallskinny(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(B),
-                                   B.stride(0), f, _ptr(C), C.stride(0), int(accumulate),
+                                   _ld(B), f, _ptr(C), _ld(C), int(accumulate),
                                    _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0,
                                    _stream())
     _check(rc, "spmm_csr_tallskinny")
@@ -263,8 +293,8 @@ def spmm_csr_tallskinny(rowptr, colidx, val, B, C=None, accumulate=False, ws: Sp
 
 def dense_gemm_act(X, W, transW=False, prec=GEMM_FP32, act=ACT_IDENTITY, mask=None, want_z=True,
                    want_act=False, out=None):
-    X = _dev(X, torch.float32, "X")
-    W = _dev(W, torch.float32, "W")
+    X = _mat(X, "X")
+    W = _mat(W, "W")
     m, kdim = X.shape
     nout = W.shape[0] if transW else W.shape[1]
     if out is not None:
@@ -272,8 +302,8 @@ def dense_gemm_act(X, W, transW=False, prec=GEMM_FP32, act=ACT_IDENTITY, mask=No
     else:
         Z = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_z else None
         A = torch.empty((m, nout), dtype=torch.float32, device=X.device) if want_act else None
-    rc = lib().dense_gemm_act(_ptr(X), X.stride(0), _ptr(W), W.stride(0), int(transW), m, kdim, nout,
-                              prec, act, _ptr(mask), mask.stride(0) if mask is not None else 0,
+    rc = lib().dense_gemm_act(_ptr(X), _ld(X), _ptr(W), _ld(W), int(transW), m, kdim, nout,
+                              prec, act, _ptr(mask), _ld(mask) if mask is not None else 0,
                               _ptr(Z), nout, _ptr(A), nout, _stream())
     _check(rc, "dense_gemm_act")
     return Z, A
@@ -285,7 +315,7 @@ def gcn_layer_fwd(rowptr, colidx, val, H, W, act=ACT_RELU, prec=GEMM_FP32, ws: S
     rowptr = _dev(rowptr, torch.int32, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     val = _dev(val, torch.float32, "val")
-    H = _dev(H, torch.float32, "H")
+    H = _mat(H, "H")
     W = _dev(W, torch.float32, "W")
     m, nnz = rowptr.numel() - 1, colidx.numel()
     k, f_in = H.shape
@@ -296,7 +326,7 @@ def gcn_layer_fwd(rowptr, colidx, val, H, W, act=ACT_RELU, prec=GEMM_FP32, ws: S
         Ho = torch.empty((m, f_out), dtype=torch.float32, device=H.device) if want_h else None
     else:
         T, Z, Ho = out
-    rc = lib().gcn_layer_fwd(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(H), H.stride(0),
+    rc = lib().gcn_layer_fwd(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(H), _ld(H),
                              f_in, _ptr(W), f_out, act, prec, _ptr(T), _ptr(Z), _ptr(Ho),
                              _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0, _stream())
     _check(rc, "gcn_layer_fwd")

@@ -19,6 +19,10 @@ void spmm_desc_put(const void* ws, const SpmmHostDesc& d) {
   std::lock_guard<std::mutex> lock(g_desc_mutex);
   g_desc[ws] = d;
 }
+void spmm_desc_erase(const void* ws) {
+  std::lock_guard<std::mutex> lock(g_desc_mutex);
+  g_desc.erase(ws);
+}
 bool spmm_desc_get(const void* ws, SpmmHostDesc* d) {
   std::lock_guard<std::mutex> lock(g_desc_mutex);
   auto it = g_desc.find(ws);
@@ -41,7 +45,13 @@ SAGNN_EXPORT const char* sagnn_strerror(int code) {
 
 SAGNN_EXPORT int sagnn_last_hip_error(void) { return sagnn::g_last_hip_error.load(); }
 
-SAGNN_EXPORT int sagnn_version(void) { return 100; }
+SAGNN_EXPORT int sagnn_version(void) { return 200; }
+
+SAGNN_EXPORT int spmm_csr_release(const void* d_ws) {
+  if (!d_ws) return SAGNN_EINVAL;
+  sagnn::spmm_desc_erase(d_ws);
+  return SAGNN_OK;
+}
 
 SAGNN_EXPORT int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx,
                                const float* d_val, int64_t m, int64_t k, int64_t nnz,

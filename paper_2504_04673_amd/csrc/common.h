@@ -113,9 +113,11 @@ struct SpmmHostDesc {
   int64_t n_waves, n_multi_rows, sweep_stream_len;
   int32_t has_empty_rows;
   int32_t groups;
+  int64_t k;                // rows of B the schedule was prepared for (stream columns are < k)
 };
 void spmm_desc_put(const void* ws, const SpmmHostDesc& d);
 bool spmm_desc_get(const void* ws, SpmmHostDesc* d);
+void spmm_desc_erase(const void* ws);
 
 // --- entry points implemented per translation unit (called by the layer functions) --------
 int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,

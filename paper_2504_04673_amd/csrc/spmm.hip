@@ -503,6 +503,9 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
   SpmmHostDesc desc{};
   if (!spmm_desc_get(ws, &desc)) return SAGNN_EINVAL;        // never prepared in this process
   if (desc.m != m || desc.nnz != nnz || desc.f < f) return SAGNN_EINVAL;
+  // the re-ordered entry streams hold column ids checked against the k of the preparation: an
+  // operand with fewer rows would be read out of range
+  if (nnz > 0 && k < desc.k) return SAGNN_EINVAL;
   const SpmmWsLayout L = spmm_ws_layout(m, nnz, desc.f);
   if (ws_bytes < L.total) return SAGNN_ECAPACITY;
   char* base = reinterpret_cast<char*>(ws);
@@ -669,6 +672,7 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
   desc.n_waves = h.n_waves; desc.n_multi_rows = h.n_multi_rows; desc.has_empty_rows = h.has_empty_rows;
   desc.sweep_stream_len = h.n_long_entries;
   desc.groups = h.groups > 0 ? h.groups : 1;
+  desc.k = k;
   spmm_desc_put(d_ws, desc);
   return SAGNN_OK;
 }

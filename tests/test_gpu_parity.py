@@ -301,6 +301,129 @@ def test_spmm_slab_sweep_falls_back_on_unsorted_rows(force_sweep):
     _ = bad
 
 
+def _strided(a, pad, fill):
+    """Device matrix whose rows are `pad` floats apart wider than a's: returns (view, whole)."""
+    m, f = a.shape
+    whole = torch.full((m, f + pad), fill, dtype=torch.float32, device="cuda")
+    whole[:, :f] = dev(a)
+    return whole[:, :f], whole
+
+
+@pytest.mark.parametrize("schedule", ["no_workspace", "nonzero_splitting", "sweep", "sweep_one_row_per_load"])
+@pytest.mark.parametrize("f", [16, 32, 48, 64, 100, 128, 192, 256, 320])
+def test_spmm_leading_dimensions_wider_than_f(f, schedule, monkeypatch):
+    """B and C as column slices of wider matrices (ldb = f + 4, ldc = f + 8), overwrite and
+    accumulate; the padding columns of C must come back untouched."""
+    if schedule.startswith("sweep"):
+        if f not in (16, 32, 64, 128, 192, 256, 320) or (schedule == "sweep_one_row_per_load" and f < 64):
+            pytest.skip("no such kernel at this width")
+        monkeypatch.setenv("SAGNN_SWEEP", "1")
+        monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
+        monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+        monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "0")
+        monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "1" if schedule == "sweep_one_row_per_load" else "2")
+    else:
+        monkeypatch.setenv("SAGNN_SWEEP", "0")
+    rng = np.random.default_rng(1000 + f)
+    m, n = 4001, 30_000
+    rowptr, colidx, val = random_csr(m, n, 18, rng, empty_frac=0.1,
+                                     hubs=[(3, 7000), (9, 2049), (2000, 1024), (4000, 100), (17, 16)])
+    B = synth.normal((n, f), f, synth.STREAM_H)
+    C0 = synth.normal((m, f), f + 1, synth.STREAM_G)
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    Bv, _ = _strided(B, 4, 123.0)
+    ws = None
+    if schedule != "no_workspace":
+        ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f)
+        assert ws.info()["mode"] == (1 if schedule.startswith("sweep") else 0), ws.info()
+    for acc in (False, True):
+        ref, zabs = oracle.spmm(rowptr, colidx, val, B, C=C0 if acc else None, want_abs=True)
+        Cv, Cw = _strided(C0, 8, -77.0)
+        sagnn.spmm_csr_tallskinny(rp, ci, v, Bv, C=Cv, accumulate=acc, ws=ws)
+        torch.cuda.synchronize()
+        assert_close(Cv, ref, zabs, RTOL_SPMM, f"strided f={f} {schedule} accumulate={acc}")
+        assert torch.all(Cw[:, f:] == -77.0)
+
+
+@pytest.mark.parametrize("case", ["f128_lane_groups", "f128_one_row_per_load", "f256_one_row_per_load", "f64_quarter_groups",
+                                  "f32_perm", "f16_perm", "f128_nonzero_splitting", "f128_no_workspace",
+                                  "f100_slabs_and_remainder"])
+def test_spmm_operand_larger_than_4gib(case, monkeypatch):
+    """Rows of B beyond byte offset 2^32 (k * ldb * 4 > 2^32): the kernels cannot use 32-bit
+    buffer offsets and switch to 64-bit addressing; every schedule has such a variant.  B is a
+    4.6 GB allocation in which only the referenced rows are filled; the oracle multiplies by
+    those rows alone (columns renumbered), which is the same product."""
+    f = int(case[1:case.index("_")])
+    ld = 256 if f > 128 else 128
+    k = (9_000_000 * 128) // ld
+    sweep = not ("nonzero" in case or "no_workspace" in case or "slabs" in case)
+    monkeypatch.setenv("SAGNN_SWEEP", "1" if sweep else "0")
+    if sweep:
+        monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
+        monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+        monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "64")
+        monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "1" if "one_row" in case else "2")
+    rng = np.random.default_rng(len(case) + f)
+    m = 3000
+    rowptr, colidx, val = random_csr(m, k, 14, rng, empty_frac=0.05, hubs=[(5, 6000), (70, 1500), (2999, 64)])
+    # make sure both sides of the 2^32-byte line and the very last row are referenced
+    line = (1 << 32) // (ld * 4)
+    colidx[rowptr[5]:rowptr[5] + 6] = np.sort(np.array([0, line - 1, line, line + 1, k - 2, k - 1], np.int32))
+    colidx[rowptr[5]:rowptr[6]].sort()
+    ucols, inv = np.unique(colidx, return_inverse=True)
+    assert ucols[-1] == k - 1 and (ucols.astype(np.int64) * ld * 4 >= (1 << 32)).sum() > 1000
+    Bsmall = synth.normal((ucols.size, f), f, synth.STREAM_H)
+    buf = torch.empty(9_000_000 * 128, dtype=torch.float32, device="cuda")
+    Bfull = buf.view(k, ld)
+    Bfull[torch.from_numpy(ucols.astype(np.int64)).cuda(), :f] = dev(Bsmall)
+    Bv = Bfull[:, :f]
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    ws = None if "no_workspace" in case else sagnn.spmm_csr_prepare(rp, ci, v, k, f)
+    if ws is not None:
+        assert ws.info()["mode"] == (1 if sweep else 0), ws.info()
+    C0 = synth.normal((m, f), 5, synth.STREAM_G)
+    for acc in (False, True):
+        ref, zabs = oracle.spmm(rowptr, inv.astype(np.int32), val, Bsmall, C=C0 if acc else None, want_abs=True)
+        Cv, Cw = _strided(C0, 8, -77.0)
+        sagnn.spmm_csr_tallskinny(rp, ci, v, Bv, C=Cv, accumulate=acc, ws=ws)
+        torch.cuda.synchronize()
+        assert_close(Cv, ref, zabs, RTOL_SPMM, f"{case} accumulate={acc}")
+        assert torch.all(Cw[:, f:] == -77.0)
+    del buf, Bfull, Bv
+
+
+def test_spmm_workspace_rejects_a_shorter_operand_and_release_forgets_it(monkeypatch):
+    """A schedule prepared for k rows of B holds column ids up to k-1: a call with fewer rows is
+    refused on the host (nothing launched).  After spmm_csr_release the address is unknown."""
+    import ctypes
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    rng = np.random.default_rng(8)
+    m, n, f = 2000, 20_000, 128
+    rowptr, colidx, val = random_csr(m, n, 30, rng, hubs=[(1, 4000)])
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    B = dev(synth.normal((n, f), 1, synth.STREAM_H))
+    for sweep in ("1", "0"):
+        monkeypatch.setenv("SAGNN_SWEEP", sweep)
+        ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f)
+        with pytest.raises(ValueError):
+            sagnn.spmm_csr_tallskinny(rp, ci, v, B[: n - 1], ws=ws)
+        C = torch.zeros((m, f), device="cuda")
+        L = sagnn.lib()
+        args = lambda kk: (ctypes.c_void_p(rp.data_ptr()), ctypes.c_void_p(ci.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+                           m, kk, ci.numel(), ctypes.c_void_p(B.data_ptr()), f, f, ctypes.c_void_p(C.data_ptr()), f, 0,
+                           ctypes.c_void_p(ws.buf.data_ptr()), ws.buf.numel(), None)
+        assert L.spmm_csr_tallskinny(*args(n - 1)) == -1
+        assert L.spmm_csr_tallskinny(*args(n)) == 0
+        torch.cuda.synchronize()
+        ptr = ctypes.c_void_p(ws.buf.data_ptr())
+        keep = ws.buf
+        assert L.spmm_csr_release(ptr) == 0
+        assert L.spmm_csr_tallskinny(*args(n)) == -1           # unknown workspace now
+        assert L.spmm_csr_release(ptr) == 0                    # releasing twice is harmless
+        ws.buf = None
+        del keep
+
+
 @pytest.mark.parametrize("sweep", ["0", "1"])
 @pytest.mark.parametrize("f", [16, 32, 64, 128, 256])
 def test_spmm_long_rows_of_equal_terms_stay_within_tolerance(f, sweep, monkeypatch):
@@ -507,6 +630,11 @@ def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     assert_close(T, o["T"], o["Tabs"], RTOL_SPMM, "layer T")
     assert_close(Z, o["Z"], o["Zabs"], rtol, "layer Z")
     assert_close(Ho, o["H"], o["Zabs"], rtol, "layer H")
+    # the dense stage by itself, on the very T the library produced: scale |T| |W| (no slack
+    # inherited from the sparse product's sum of magnitudes)
+    Tg = T.cpu().numpy()
+    zt, ztabs = oracle.gemm(Tg, W, bf16=bool(prec), want_abs=True)
+    assert_close(Z, zt, ztabs, rtol, "layer Z vs oracle GEMM of the library's T")
     # backward of this layer with the oracle's own Z / inputs as given data
     Zprev = synth.normal((g.n, fin), 2, synth.STREAM_G)
     ob = oracle.gcn_layer_bwd(g.rowptr, g.colidx, g.val, G, W, Zprev, H, bf16=bool(prec))
@@ -515,3 +643,8 @@ def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     assert_close(S, ob["S"], ob["Sabs"], RTOL_SPMM, "bwd S")
     assert_close(Gp, ob["Gprev"], ob["Gabs"], rtol, "bwd Gprev")
     assert_close(Y, ob["Y"], ob["Yabs"], rtol, "bwd Y")
+    Sg = S.cpu().numpy()
+    gt, gtabs = oracle.gemm(Sg, W, bf16=bool(prec), transW=True, want_abs=True)
+    assert_close(Gp, np.where(Zprev > 0, gt, 0), gtabs, rtol, "bwd Gprev vs oracle GEMM of the library's S")
+    yt, ytabs = oracle.gemm(H, Sg, bf16=bool(prec), transX=True, want_abs=True)
+    assert_close(Y, yt, ytabs, rtol, "bwd Y vs oracle GEMM of the library's S")
