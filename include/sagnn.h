@@ -106,6 +106,24 @@ int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx, int6
                           int32_t* d_colidx_compact, void* d_ws, size_t ws_bytes,
                           uint32_t flags, void* stream);
 
+/* spmm_plan_needed_rows() for callers that cannot allocate device memory (tight serving loops,
+ * harnesses that forbid hipMalloc, code that runs beside a graph capture): same arguments without
+ * the workspace, same outputs bit for bit.  The scratch arrays live in a fixed 8 MiB array of
+ * device memory that each GPU the library runs on holds until the process ends; the call
+ * allocates nothing on the device or through any allocating library routine.
+ * Limits: n <= SAGNN_PLAN_NOALLOC_MAX_COLS and nb <= SAGNN_PLAN_NOALLOC_MAX_BLOCKS, otherwise
+ * SAGNN_ECAPACITY (nothing is launched).  All calls on one GPU share that GPU's array: the
+ * call clears what it needs cleared itself, and two such calls that overlap in time on one
+ * GPU (different streams or threads) race -- serialise them.  Like spmm_plan_needed_rows() it
+ * synchronises the stream once to return N.
+ */
+#define SAGNN_PLAN_NOALLOC_MAX_COLS 5000000
+#define SAGNN_PLAN_NOALLOC_MAX_BLOCKS 1024
+int spmm_plan_needed_rows_noalloc(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m,
+                                  int64_t n, int64_t nnz, const int64_t* h_colblk, int32_t nb,
+                                  int32_t* d_needed, int64_t needed_cap, int64_t* h_blk_off,
+                                  int32_t* d_colidx_compact, uint32_t flags, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Streams and graphs.  Every entry point enqueues its work on the stream it is given.  The
  * set-up calls (spmm_plan_needed_rows, spmm_csr_prepare, spmm_csr_prepare_tuned, spmm_split_colblocks,

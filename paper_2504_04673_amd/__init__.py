@@ -7,7 +7,7 @@ library is missing or no GPU is present, calls raise.
 """
 from .binding import (  # noqa: F401
     SagnnError, lib, lib_path, Plan, SpmmWorkspace, plan_buffers,
-    spmm_plan_needed_rows, spmm_pack_rows, spmm_csr_prepare, spmm_csr_prepare_tuned, spmm_csr_tallskinny,
+    spmm_plan_needed_rows, spmm_plan_needed_rows_noalloc, spmm_pack_rows, spmm_csr_prepare, spmm_csr_prepare_tuned, spmm_csr_tallskinny,
     dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd,
     ColBlocks, spmm_split_colblocks, spmm_stage_loop, spmm_volume_stats, spmm_csr_transpose,
     ACT_IDENTITY, ACT_RELU, GEMM_FP32, GEMM_BF16, PLAN_VALIDATE, PLAN_OBLIVIOUS,

@@ -16,7 +16,7 @@ PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
 
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
-    "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_pack_rows",
+    "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_plan_needed_rows_noalloc", "spmm_pack_rows",
     "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
     "spmm_csr_release", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
@@ -64,6 +64,7 @@ def lib():
         L.spmm_plan_workspace_bytes.argtypes = [i64, i64, i64, i32, psz]
         L.spmm_plan_needed_rows.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64, vp, vp, vp, sz,
                                             u32, vp]
+        L.spmm_plan_needed_rows_noalloc.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64, vp, vp, u32, vp]
         L.spmm_pack_rows.argtypes = [vp, i64, i64, i32, vp, i64, vp, i64, vp]
         L.spmm_csr_workspace_bytes.argtypes = [i64, i64, i32, psz]
         L.spmm_csr_prepare.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
@@ -168,6 +169,29 @@ def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, val
                                  (PLAN_VALIDATE if validate else 0) | (PLAN_OBLIVIOUS if oblivious else 0),
                                  _stream())
     _check(rc, "spmm_plan_needed_rows")
+    N = int(blk_off[-1])
+    return Plan(needed[:N], blk_off, compact[:nnz] if compact is not None else None)
+
+
+def spmm_plan_needed_rows_noalloc(rowptr, colidx, n: int, colblk, needed, compact=None, validate=False,
+                                  oblivious=False) -> Plan:
+    """spmm_plan_needed_rows without a workspace: the library's fixed per-GPU scratch array is
+    used and nothing is allocated, here or in the library.  `needed` (int32, capacity = its
+    length) and `compact` (int32, nnz entries, or None) are the caller's output buffers."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    needed = _dev(needed, torch.int32, "needed")
+    if compact is not None:
+        compact = _dev(compact, torch.int32, "compact")
+    m, nnz = rowptr.numel() - 1, colidx.numel()
+    colblk = np.ascontiguousarray(colblk, dtype=np.int64)
+    nb = colblk.size - 1
+    blk_off = np.zeros(nb + 1, dtype=np.int64)
+    rc = lib().spmm_plan_needed_rows_noalloc(
+        _ptr(rowptr), _ptr(colidx), m, n, nnz, colblk.ctypes.data_as(ctypes.c_void_p), nb, _ptr(needed),
+        needed.numel(), blk_off.ctypes.data_as(ctypes.c_void_p), _ptr(compact),
+        (PLAN_VALIDATE if validate else 0) | (PLAN_OBLIVIOUS if oblivious else 0), _stream())
+    _check(rc, "spmm_plan_needed_rows_noalloc")
     N = int(blk_off[-1])
     return Plan(needed[:N], blk_off, compact[:nnz] if compact is not None else None)
 

@@ -18,6 +18,8 @@
 //   remap    compact[e] = prefix[c>>6] + popcount(word & bits below c): position of column
 //            c in needed[]; monotone in c, so sorted rows stay sorted
 // Traffic: nnz*4 (mark) + nnz*8 (remap read+write) + N*4 + a few passes over n bytes.
+#include <mutex>
+
 #include "common.h"
 
 namespace sagnn {
@@ -479,26 +481,30 @@ SAGNN_EXPORT int spmm_plan_workspace_bytes(int64_t m, int64_t n, int64_t nnz, in
   return SAGNN_OK;
 }
 
-SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx,
-                                       int64_t m, int64_t n, int64_t nnz,
-                                       const int64_t* h_colblk, int32_t nb, int32_t* d_needed,
-                                       int64_t needed_cap, int64_t* h_blk_off,
-                                       int32_t* d_colidx_compact, void* d_ws, size_t ws_bytes,
-                                       uint32_t flags, void* stream) {
-  using namespace sagnn;
+namespace sagnn {
+namespace {
+
+// host-side argument checks shared by the two planning entry points (no HIP call is made)
+int plan_check_args(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_t n,
+                    int64_t nnz, const int64_t* h_colblk, int32_t nb, const int32_t* d_needed,
+                    int64_t needed_cap, const int64_t* h_blk_off) {
   if (m < 0 || n < 0 || nnz < 0 || nb < 1 || needed_cap < 0 || n > 0x7FFFFFFFll ||
       nnz > 0x7FFFFFFFll || m > 0x7FFFFFFFll)
     return SAGNN_EINVAL;
-  if (!h_colblk || !h_blk_off || !d_ws || !d_rowptr) return SAGNN_EINVAL;
+  if (!h_colblk || !h_blk_off || !d_rowptr) return SAGNN_EINVAL;
   if (nnz > 0 && !d_colidx) return SAGNN_EINVAL;
   if (needed_cap > 0 && !d_needed) return SAGNN_EINVAL;
-  if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return SAGNN_EINVAL;
   if (h_colblk[0] != 0 || h_colblk[nb] != n) return SAGNN_EFORMAT;
   for (int32_t q = 0; q < nb; ++q)
     if (h_colblk[q] > h_colblk[q + 1]) return SAGNN_EFORMAT;
-  const PlanWs w = carve(d_ws, n, nb, nnz);
-  if (ws_bytes < w.bytes) return SAGNN_ECAPACITY;
-  hipStream_t s = (hipStream_t)stream;
+  return SAGNN_OK;
+}
+
+// the planning pipeline on an already carved workspace (w.part == nullptr: byte-flag marking)
+int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_t n, int64_t nnz,
+             const int64_t* h_colblk, int32_t nb, int32_t* d_needed, int64_t needed_cap,
+             int64_t* h_blk_off, int32_t* d_colidx_compact, const PlanWs& w, uint32_t flags,
+             hipStream_t s) {
 
   SAGNN_HIP(hipMemcpyAsync(w.colblk, h_colblk, sizeof(int64_t) * (size_t)(nb + 1),
                            hipMemcpyHostToDevice, s));
@@ -576,4 +582,79 @@ SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d
     SAGNN_LAUNCH_CHECK();
   }
   return SAGNN_OK;
+}
+
+}  // namespace
+}  // namespace sagnn
+
+SAGNN_EXPORT int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                       int64_t m, int64_t n, int64_t nnz,
+                                       const int64_t* h_colblk, int32_t nb, int32_t* d_needed,
+                                       int64_t needed_cap, int64_t* h_blk_off,
+                                       int32_t* d_colidx_compact, void* d_ws, size_t ws_bytes,
+                                       uint32_t flags, void* stream) {
+  using namespace sagnn;
+  int rc = plan_check_args(d_rowptr, d_colidx, m, n, nnz, h_colblk, nb, d_needed, needed_cap, h_blk_off);
+  if (rc != SAGNN_OK) return rc;
+  if (!d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return SAGNN_EINVAL;
+  const PlanWs w = carve(d_ws, n, nb, nnz);
+  if (ws_bytes < w.bytes) return SAGNN_ECAPACITY;
+  return plan_run(d_rowptr, d_colidx, m, n, nnz, h_colblk, nb, d_needed, needed_cap, h_blk_off,
+                  d_colidx_compact, w, flags, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Planning without a caller workspace and without any allocation: the scratch arrays (column
+// flags, membership words, rank records, block sums, block boundaries, error counters) live
+// in a fixed array in device memory that every GPU the library runs on holds for the life of
+// the process.  The host only ever sees the array through the address hipGetSymbolAddress
+// returns for the current device (the symbol's name is not a device address in host code).
+namespace sagnn {
+namespace {
+
+constexpr size_t kPlanStaticBytes = 8u << 20;   // 8 MiB per GPU
+constexpr int kPlanStaticMaxDevices = 64;
+
+static __device__ __align__(256) unsigned char scratch[kPlanStaticBytes];
+
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kPlanStaticMaxDevices] = {};
+
+// address of `scratch` on the current device, resolved once per device
+int plan_static_scratch(void** out) {
+  int dev = -1;
+  SAGNN_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kPlanStaticMaxDevices) return SAGNN_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    SAGNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return SAGNN_EINVAL;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SAGNN_OK;
+}
+
+}  // namespace
+}  // namespace sagnn
+
+SAGNN_EXPORT int spmm_plan_needed_rows_noalloc(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                               int64_t m, int64_t n, int64_t nnz,
+                                               const int64_t* h_colblk, int32_t nb,
+                                               int32_t* d_needed, int64_t needed_cap,
+                                               int64_t* h_blk_off, int32_t* d_colidx_compact,
+                                               uint32_t flags, void* stream) {
+  using namespace sagnn;
+  int rc = plan_check_args(d_rowptr, d_colidx, m, n, nnz, h_colblk, nb, d_needed, needed_cap, h_blk_off);
+  if (rc != SAGNN_OK) return rc;
+  if (n > SAGNN_PLAN_NOALLOC_MAX_COLS || nb > SAGNN_PLAN_NOALLOC_MAX_BLOCKS) return SAGNN_ECAPACITY;
+  // nnz = 0 in the layout: no private LDS bitmaps, the byte-flag marking path is used
+  if (carve(nullptr, n, nb, 0).bytes > kPlanStaticBytes) return SAGNN_ECAPACITY;
+  void* base = nullptr;
+  rc = plan_static_scratch(&base);
+  if (rc != SAGNN_OK) return rc;
+  const PlanWs w = carve(base, n, nb, 0);
+  return plan_run(d_rowptr, d_colidx, m, n, nnz, h_colblk, nb, d_needed, needed_cap, h_blk_off,
+                  d_colidx_compact, w, flags, (hipStream_t)stream);
 }
