@@ -290,8 +290,8 @@ int gcn_layer_bwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
                   void* d_yws, size_t yws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Column-block split (Sec. 4.2: every row block A_i "is further partitioned in p/c block
- * columns"; Alg. 2 multiplies one block A_iq per stage).
+ * Column-block split (Sec. 4.2 column-block partition of a row block; Alg. 2 multiplies one
+ * block A_iq per stage).
  *
  * Splits the CSR row block (m rows) into nb CSR matrices, one per contiguous range
  * [h_bounds[q], h_bounds[q+1]) of the index space d_colidx lives in: global column ids with
