@@ -332,6 +332,37 @@ int spmm_csr_transpose(const int32_t* d_rowptr, const int32_t* d_colidx, const f
                        void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Locality reordering (Sec. 5 and Sec. 6.1: the graph is partitioned, the vertices are renumbered
+ * so that every part owns a contiguous range, A is permuted symmetrically and the rows of the
+ * dense matrices follow; Sec. 5 argues that this is what makes NnzCols small).
+ *
+ * spmm_perm_from_labels: d_labels[v] in [0, n_parts) is the part of vertex v.  Writes
+ *   d_perm[i] = old id of the vertex that gets new id i (vertices ordered by label, inside a
+ *               part by old id: a stable sort, so the result is unique)
+ *   d_inv[v]  = new id of old vertex v
+ *   h_part_off[0..n_parts] (host): part q owns new ids [h_part_off[q], h_part_off[q+1])
+ * n_parts <= 1024.  SAGNN_EFORMAT if a label is out of range.
+ *
+ * spmm_csr_permute_symmetric: B = P A P^T for the square CSR matrix A (n x n):
+ *   B[d_inv[r], d_inv[c]] = A[r, c].  Rows of B come out with ascending column ids (entries
+ *   that repeat a position keep their stored order), so B is unique: bit-exact.
+ *   SAGNN_EFORMAT if d_inv is not a permutation of [0, n) or a column index is out of range.
+ *
+ * The dense side needs no call of its own: H_new = H[d_perm, :] is spmm_pack_rows(H, d_perm)
+ * and Z_old = Z_new[d_inv, :] is spmm_pack_rows(Z_new, d_inv).
+ * One-time set-up steps; both synchronise the stream.  d_ws: scratch of
+ * spmm_permute_workspace_bytes(n, nnz) bytes (serves both calls).
+ */
+int spmm_permute_workspace_bytes(int64_t n, int64_t nnz, size_t* bytes);
+int spmm_perm_from_labels(const int32_t* d_labels, int64_t n, int32_t n_parts, int32_t* d_perm,
+                          int32_t* d_inv, int64_t* h_part_off, void* d_ws, size_t ws_bytes,
+                          void* stream);
+int spmm_csr_permute_symmetric(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                               int64_t n, int64_t nnz, const int32_t* d_inv, int32_t* d_rowptr_p,
+                               int32_t* d_colidx_p, float* d_val_p, void* d_ws, size_t ws_bytes,
+                               void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Stage loop of one rank of the 1.5D algorithm (Alg. 2, the loop over k = 0..s-1 with
  * q = j*s + k: obtain the rows NnzCols(i,q) of H, then Z^ <- Z^ + SpMM(A_iq, H^)).
  *

@@ -253,3 +253,34 @@ def transpose_csr(rowptr, colidx, val, n):
     rpt = np.zeros(n + 1, dtype=np.int64)
     rpt[1:] = np.cumsum(np.bincount(colidx, minlength=n)[:n])
     return rpt.astype(np.int32), row_of[perm].astype(np.int32), val[perm].copy()
+
+
+def perm_from_labels(labels, n_parts):
+    """Renumbering by partition label (Sec. 5, Sec. 6.1): the vertices of part 0 first, then
+    part 1, ...; inside a part the old order is kept (a stable sort, library sort as the step).
+    Returns (perm, inv, part_off): perm[i] = old id of new vertex i, inv[v] = new id of v."""
+    labels = np.asarray(labels, dtype=np.int64)
+    n = labels.size
+    perm = np.argsort(labels, kind="stable")
+    inv = np.empty(n, dtype=np.int64)
+    inv[perm] = np.arange(n, dtype=np.int64)
+    off = np.zeros(n_parts + 1, dtype=np.int64)
+    off[1:] = np.cumsum(np.bincount(labels, minlength=n_parts)[:n_parts])
+    return perm.astype(np.int32), inv.astype(np.int32), off
+
+
+def permute_symmetric(rowptr, colidx, val, inv):
+    """B = P A P^T for a square CSR matrix: entry (r, c, v) of A becomes entry (inv[r], inv[c], v)
+    of B; the entries of B are listed by row, inside a row by column, entries that repeat a
+    position in their stored order (a stable sort of the relabelled coordinate list)."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    colidx = np.asarray(colidx, dtype=np.int64)
+    val = np.asarray(val, dtype=np.float32)
+    inv = np.asarray(inv, dtype=np.int64)
+    n = rowptr.size - 1
+    row_of = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    nr, nc = inv[row_of], inv[colidx]
+    order = np.lexsort((nc, nr))                      # by new row, then new column; stable
+    rpp = np.zeros(n + 1, dtype=np.int64)
+    rpp[1:] = np.cumsum(np.bincount(nr, minlength=n)[:n])
+    return rpp.astype(np.int32), nc[order].astype(np.int32), val[order].copy()

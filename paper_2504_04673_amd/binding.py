@@ -22,6 +22,7 @@ EXPORTS = [
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
     "spmm_transpose_workspace_bytes", "spmm_csr_transpose",
+    "spmm_permute_workspace_bytes", "spmm_perm_from_labels", "spmm_csr_permute_symmetric",
 ]
 
 
@@ -87,6 +88,9 @@ def lib():
         L.spmm_volume_stats.argtypes = [vp, i32, i32, i32, vp]
         L.spmm_transpose_workspace_bytes.argtypes = [i64, psz]
         L.spmm_csr_transpose.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, sz, vp]
+        L.spmm_permute_workspace_bytes.argtypes = [i64, i64, psz]
+        L.spmm_perm_from_labels.argtypes = [vp, i64, i32, vp, vp, vp, vp, sz, vp]
+        L.spmm_csr_permute_symmetric.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -484,3 +488,45 @@ def spmm_csr_transpose(rowptr, colidx, val, n: int):
     _check(L.spmm_csr_transpose(_ptr(rowptr), _ptr(colidx), _ptr(val), m, n, nnz, _ptr(rpt), _ptr(cit),
                                 _ptr(vat), _ptr(ws), ws.numel(), _stream()), "spmm_csr_transpose")
     return rpt, cit[:nnz], vat[:nnz]
+
+
+def _permute_ws(n: int, nnz: int, device):
+    wsb = ctypes.c_size_t(0)
+    _check(lib().spmm_permute_workspace_bytes(n, nnz, ctypes.byref(wsb)), "spmm_permute_workspace_bytes")
+    return _ws(wsb.value, device)
+
+
+def spmm_perm_from_labels(labels, n_parts: int):
+    """Vertex order by part label (Sec. 5 / 6.1 renumbering).  Returns (perm, inv, part_off): perm[i] =
+    old id of new vertex i, inv[v] = new id of old vertex v, part_off (host, n_parts+1)."""
+    labels = _dev(labels, torch.int32, "labels")
+    n = labels.numel()
+    dev = labels.device
+    ws = _permute_ws(n, n, dev)
+    perm = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    inv = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    off = np.zeros(n_parts + 1, dtype=np.int64)
+    _check(lib().spmm_perm_from_labels(_ptr(labels), n, n_parts, _ptr(perm), _ptr(inv),
+                                       off.ctypes.data_as(ctypes.c_void_p), _ptr(ws), ws.numel(), _stream()),
+           "spmm_perm_from_labels")
+    return perm[:n], inv[:n], off
+
+
+def spmm_csr_permute_symmetric(rowptr, colidx, val, inv):
+    """B = P A P^T with B[inv[r], inv[c]] = A[r, c].  Returns (rowptr_p, colidx_p, val_p)."""
+    rowptr = _dev(rowptr, torch.int32, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    inv = _dev(inv, torch.int32, "inv")
+    n, nnz = rowptr.numel() - 1, colidx.numel()
+    if inv.numel() != n:
+        raise ValueError("inv must have one entry per row")
+    dev = rowptr.device
+    ws = _permute_ws(n, nnz, dev)
+    rpp = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    cip = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    vap = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)
+    _check(lib().spmm_csr_permute_symmetric(_ptr(rowptr), _ptr(colidx), _ptr(val), n, nnz, _ptr(inv), _ptr(rpp),
+                                            _ptr(cip), _ptr(vap), _ptr(ws), ws.numel(), _stream()),
+           "spmm_csr_permute_symmetric")
+    return rpp, cip[:nnz], vap[:nnz]

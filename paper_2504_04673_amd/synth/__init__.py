@@ -266,6 +266,18 @@ def sbm_graph(n: int, ncomm: int, mean_in: float, mean_out: float, seed: int,
     return g
 
 
+def sbm_labels(g: CSR) -> np.ndarray:
+    """Community label of every vertex of an sbm_graph, in the graph's own vertex numbering
+    (what a partitioner would hand back: the input of the reordering step)."""
+    n, ncomm = g.n, int(g.meta["ncomm"])
+    planted = (np.arange(n, dtype=np.int64) // (n // ncomm)).astype(np.int32)
+    if g.meta.get("order") == "community":
+        return planted
+    labels = np.empty(n, dtype=np.int32)
+    labels[g.meta["perm"]] = planted            # vertex v of the planted order became perm[v]
+    return labels
+
+
 def random_permutation(n: int, seed: int) -> np.ndarray:
     """Seeded permutation of [0,n): rank of a counter-based hash (ties broken by index)."""
     h = _mix_np(np.arange(n, dtype=np.uint64) ^ np.uint64(int(_L().synth_ctr64(seed, STREAM_PERM, 1))))

@@ -218,12 +218,31 @@ def test_cfg5_reordering_and_two_layer_training_step():
         torch.cuda.synchronize()
         check_spmm_full(gb, Z, wl.H, f"cfg5 block {name}")
         del Hd, Hn, Z
+    # the same "before -> after" step done by the library on the device: renumber the randomly
+    # ordered graph by its community labels (the partitioner's output), permute it symmetrically,
+    # plan rank 0's block of the result (Sec. 5: the reordering is what shrinks NnzCols)
+    gr = before.g
+    labels = synth.sbm_labels(gr)
+    perm, inv, part_off = sagnn.spmm_perm_from_labels(dev(labels), 16)
+    rpp, cip, vap = sagnn.spmm_csr_permute_symmetric(*csr_dev(gr), inv)
+    torch.cuda.synchronize()
+    operm, oinv, ooff = oracle.perm_from_labels(labels, 16)
+    assert np.array_equal(perm.cpu().numpy(), operm) and np.array_equal(part_off, ooff)
+    assert np.array_equal(part_off, np.arange(17) * blk)
+    orp, oci, ova = oracle.permute_symmetric(gr.rowptr, gr.colidx, gr.val, oinv)
+    assert np.array_equal(rpp.cpu().numpy(), orp) and np.array_equal(cip.cpu().numpy(), oci)
+    assert vap.cpu().numpy().tobytes() == ova.tobytes()
+    e0 = int(orp[blk])
+    plan_dev = sagnn.spmm_plan_needed_rows(rpp[:blk + 1].contiguous(), cip[:e0].contiguous(), n, before.colblk)
+    counts["device_reordered"] = plan_dev.N
+    del rpp, cip, vap, orp, oci, ova
     # closed-form expectations of the needed-row counts (Poisson thinning)
     e_before = blk + (n - blk) * (1 - math.exp(-42.0 / 16))
     e_after = blk + (n - blk) * (1 - math.exp(-2.0 * blk / (n - blk)))
     assert abs(counts["before"] - e_before) < 0.01 * e_before
     assert abs(counts["after"] - e_after) < 0.02 * e_after
     assert counts["after"] < 0.25 * counts["before"]
+    assert abs(counts["device_reordered"] - e_after) < 0.02 * e_after
 
     # two-layer GCN forward + backward on the whole reordered graph, bf16 MFMA GEMMs.
     # Each layer call is checked with seeded inputs (never with another GPU result as input).

@@ -257,3 +257,73 @@ def test_directed_graph_layer_uses_both_orientations():
     assert_close(S, ob["S"], ob["Sabs"], RTOL_SPMM, "directed S")
     assert_close(Gp, ob["Gprev"], ob["Gabs"], 1e-5, "directed Gprev")
     assert_close(Y, ob["Y"], ob["Yabs"], 1e-5, "directed Y")
+
+
+# ------------------------------------------------------------------------------------ reordering
+
+@pytest.mark.parametrize("case", ["cfg1_random_labels", "sbm_communities", "unsorted_dup", "one_part", "tiny"])
+def test_reorder_by_labels_and_permute_symmetric(case, cfg1):
+    """Renumbering by partition labels and the symmetric permutation of A (Sec. 5 / 6.1), bit for
+    bit against the oracle; then the product in the new numbering, moved back with the inverse
+    row gather, against the oracle's product in the old numbering."""
+    rng = np.random.default_rng(len(case))
+    if case == "cfg1_random_labels":
+        g, _ = cfg1
+        rowptr, colidx, val, n, parts = g.rowptr, g.colidx, g.val, g.n, 4
+        labels = rng.integers(0, parts, size=n).astype(np.int32)
+    elif case == "sbm_communities":
+        g = synth.sbm_graph(8000, 16, 20, 2, 5, order="random")
+        rowptr, colidx, val, n, parts = g.rowptr, g.colidx, g.val, g.n, 16
+        labels = synth.sbm_labels(g)
+    elif case == "unsorted_dup":
+        n, parts = 3001, 7
+        rowptr, colidx, val = random_csr(n, n, 0.004, rng, sort=False, dup=True)
+        labels = rng.integers(0, parts, size=n).astype(np.int32)
+        labels[labels == 3] = 4                       # an empty part
+    elif case == "one_part":
+        n, parts = 513, 1
+        rowptr, colidx, val = random_csr(n, n, 0.02, rng)
+        labels = np.zeros(n, np.int32)
+    else:
+        n, parts = 1, 1
+        rowptr, colidx, val = np.array([0, 1], np.int32), np.array([0], np.int32), np.array([2.0], np.float32)
+        labels = np.zeros(1, np.int32)
+    perm, inv, off = sagnn.spmm_perm_from_labels(dev(labels), parts)
+    operm, oinv, ooff = oracle.perm_from_labels(labels, parts)
+    assert np.array_equal(perm.cpu().numpy(), operm) and np.array_equal(inv.cpu().numpy(), oinv)
+    assert np.array_equal(off, ooff)
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    rpp, cip, vap = sagnn.spmm_csr_permute_symmetric(rp, ci, v, inv)
+    torch.cuda.synchronize()
+    orp, oci, ova = oracle.permute_symmetric(rowptr, colidx, val, oinv)
+    assert np.array_equal(rpp.cpu().numpy(), orp)
+    assert np.array_equal(cip.cpu().numpy(), oci)
+    assert vap.cpu().numpy().tobytes() == ova.tobytes()
+    # product in the new numbering, moved back: Z_old = pack(Z_new, inv), H_new = pack(H, perm)
+    f = 32
+    H = synth.normal((n, f), 3, synth.STREAM_H)
+    Hn = sagnn.spmm_pack_rows(dev(H), perm)
+    Zn = sagnn.spmm_csr_tallskinny(rpp, cip, vap, Hn)
+    Z = sagnn.spmm_pack_rows(Zn, inv)
+    torch.cuda.synchronize()
+    ref, zabs = oracle.spmm(rowptr, colidx, val, H, want_abs=True)
+    assert_close(Z, ref, zabs, RTOL_SPMM, f"reordered product {case}")
+
+
+def test_reorder_rejects_bad_labels_and_maps():
+    labels = dev(np.array([0, 1, 2, 5, 1], np.int32))
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_perm_from_labels(labels, 3)
+    assert ei.value.code == -3
+    rowptr, colidx, val = random_csr(6, 6, 0.5, np.random.default_rng(0))
+    for bad in ([0, 1, 2, 3, 4, 4], [0, 1, 2, 3, 4, 6], [0, 1, 2, 3, 4, -1]):
+        with pytest.raises(sagnn.SagnnError) as ei:
+            sagnn.spmm_csr_permute_symmetric(dev(rowptr), dev(colidx), dev(val), dev(np.array(bad, np.int32)))
+        assert ei.value.code == -3
+    ok = dev(np.array([5, 4, 3, 2, 1, 0], np.int32))
+    badcol = colidx.copy()
+    badcol[0] = 6
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_csr_permute_symmetric(dev(rowptr), dev(badcol), dev(val), ok)
+    assert ei.value.code == -3
+    sagnn.spmm_csr_permute_symmetric(dev(rowptr), dev(colidx), dev(val), ok)

@@ -165,3 +165,53 @@ def test_transpose_twice_is_identity_for_sorted_rows():
     assert np.array_equal(rp2, rowptr) and np.array_equal(ci2, colidx) and np.array_equal(va2, val)
     empty = oracle.transpose_csr(np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32), 5)
     assert empty[0].tolist() == [0] * 6 and empty[1].size == 0
+
+
+# ----------------------------------------------------------------------------- reordering
+
+@pytest.mark.parametrize("n,n_parts,seed", [(1, 1, 0), (13, 3, 1), (40, 7, 2), (64, 64, 3)])
+def test_perm_from_labels_bruteforce(n, n_parts, seed):
+    """Renumbering by part label, written out as Python loops: part 0's vertices first in their
+    old order, then part 1's, ...  (Sec. 5 / 6.1: every part owns a contiguous range)."""
+    rng = np.random.default_rng(seed)
+    labels = rng.integers(0, n_parts, size=n)
+    perm, inv, off = oracle.perm_from_labels(labels, n_parts)
+    expect = [v for q in range(n_parts) for v in range(n) if labels[v] == q]
+    assert list(perm) == expect
+    assert all(inv[perm[i]] == i for i in range(n))
+    assert list(off) == [sum(1 for v in range(n) if labels[v] < q) for q in range(n_parts + 1)]
+
+
+@pytest.mark.parametrize("seed,dup", [(0, False), (1, True), (2, False)])
+def test_permute_symmetric_against_dense_and_product(seed, dup):
+    """B = P A P^T: dense copies agree entry by entry (B[i][j] = A[perm[i]][perm[j]]), rows come
+    out ascending, the product commutes with the renumbering ((P A P^T)(P x) = P (A x)) and the
+    inverse permutation gives A back bit for bit.  A is non-symmetric, so a transposed result or
+    perm used in place of inv fails."""
+    rng = np.random.default_rng(seed)
+    n = 23
+    rowptr, colidx, val = random_csr(n, n, 0.2, rng, sort=True, dup=dup)
+    if dup:                                          # duplicates adjacent, as a sorted row stores them
+        for r in range(n):
+            colidx[rowptr[r]:rowptr[r + 1]].sort()
+    labels = rng.integers(0, 4, size=n)
+    perm, inv, _ = oracle.perm_from_labels(labels, 4)
+    rpp, cip, vap = oracle.permute_symmetric(rowptr, colidx, val, inv)
+    A = np.array(dense_of(rowptr, colidx, val, n))
+    B = np.array(dense_of(rpp, cip, vap, n))
+    for i in range(n):
+        for j in range(n):
+            assert B[i][j] == pytest.approx(A[perm[i]][perm[j]], abs=1e-12)
+        assert np.all(np.diff(cip[rpp[i]:rpp[i + 1]]) >= 0)
+    assert rpp[-1] == rowptr[-1]
+    x = rng.standard_normal((n, 3)).astype(np.float32)
+    lhs = oracle.spmm(rpp, cip, vap, x[perm])
+    rhs = oracle.spmm(rowptr, colidx, val, x)[perm]
+    assert np.allclose(lhs, rhs, rtol=1e-6, atol=1e-6)
+    # undo: permuting B with the inverse map (old id of new vertex i is perm[i]) restores A
+    rp2, ci2, va2 = oracle.permute_symmetric(rpp, cip, vap, perm)
+    assert np.array_equal(rp2, rowptr) and np.array_equal(ci2, colidx) and va2.tobytes() == val.tobytes()
+    # stored values travel with their entries (not re-derived): multiset of values per new row
+    for i in range(n):
+        old = perm[i]
+        assert sorted(vap[rpp[i]:rpp[i + 1]].tolist()) == sorted(val[rowptr[old]:rowptr[old + 1]].tolist())
