@@ -211,7 +211,7 @@ def main():
             "cfg5": "SBM 2M vertices, rank-0 block of 16, ordered by community",
         }[wl.name] + f", m={m} n={n} nnz={nnz} N_needed={N} f={f} f_out={f_out} nb={nb}",
             "step": ("" if args.no_plan else "plan+") + "pack+spmm+gemm_relu", "seed": 0,
-            "spmm_schedule": dict(ws.info(), tuned=ws.choice),
+            "spmm_schedule": dict(ws.info(), tuned=ws.choice, barriers_gave_up=ws.barriers_gave_up()),
             "scale": args.scale},
         "roofline": {
             "kernel": "spmm_csr_tallskinny (all kernels of one call: slab-sweep + nonzero-splitting "
@@ -355,7 +355,7 @@ def train_step_bench(args, sagnn, workloads, torch, np, dev, kw):
         "config": {"workload": f"cfg5_train: SBM 2M vertices ordered by community, whole graph, m=n={m} nnz={nnz} "
                                f"f={f}, 2-layer GCN forward + backward, GEMM operands bf16 (fp32 accumulate)",
                    "step": "spmm+gemm_relu, spmm+gemm, bwd layer 2 (spmm, S W^T .* mask, H^T S), bwd layer 1 (spmm, H^T S)",
-                   "seed": 0, "spmm_schedule": dict(ws.info(), tuned=ws.choice), "scale": args.scale},
+                   "seed": 0, "spmm_schedule": dict(ws.info(), tuned=ws.choice, barriers_gave_up=ws.barriers_gave_up()), "scale": args.scale},
         "roofline": {"kernel": "spmm_csr_tallskinny (the two forward calls, bracketed by events)", "bound": "hbm",
                      "achieved": round(spmm_gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(spmm_gbps / HBM_PEAK_GBPS, 4), "traffic": parse_traffic("cfg5_train", f),

@@ -185,16 +185,52 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  * memory was overwritten after preparation, C is unspecified (the kernels check a generation
  * tag and exit), but nothing faults.
  * With d_ws == NULL a simple one-wavefront-per-row kernel is used (no preparation).
- * The planner's choices can be overridden for experiments through environment variables read
- * at spmm_csr_prepare() (SAGNN_SWEEP = 0/1 forces the schedule; SAGNN_SWEEP_MINDEG, _PIECE,
- * _SLAB_MB, _MIN_WAVES, _WINDOW_PCT, _LPT, _GROUPS, _STAGGER tune it); every setting gives the
- * same product up to rounding.
+ * The planner's choices can be overridden through spmm_csr_prepare_opt() (the library reads no
+ * environment variables); every setting gives the same product up to rounding.
  * B and C must not overlap.
  */
+/* Planner options of the slab-sweep schedule.  A zeroed struct (or NULL) means "let the library
+ * decide"; the fields exist for experiments and for tests that force a particular code path on
+ * small inputs.  Every combination gives the same product up to rounding order. */
+typedef struct sagnn_spmm_options {
+  int32_t schedule;        /* 0 heuristic, 1 nonzero splitting only, 2 slab sweep whenever possible */
+  int32_t min_long;        /* rows with at least this many entries are swept (0 = decide; >= 16;
+                              negative: -min_long replaces 64 where the rule would pick 64)         */
+  int32_t piece;           /* longest piece a swept row is cut into (0 = 4096; 1024..32768)         */
+  int32_t slab_kb;         /* KiB of B per slab (0 = 4096); -1 = as many slabs as the format allows  */
+  int32_t min_waves;       /* fewer than 16 pieces per wavefront below this many wavefronts (0 = 8192) */
+  int32_t window_pct;      /* dealing window in % of the resident pieces (0 = 400); -1 = one window  */
+  int32_t snake;           /* 1: deal pieces in snake order instead of longest-first (one stream per wavefront) */
+  int32_t groups;          /* lane groups: 0 decide, 1 never, 2 whenever the width has them         */
+  int32_t sync_slabs;      /* slabs per interval of the sweep (0 = decide, -1 = one interval).  At
+                              interval boundaries the wavefronts are kept in step, by pacing or
+                              by barriers (next two fields); without either the layout is inert  */
+  int32_t pace_ps_per_step;/* pacing: a wavefront does not start interval i before its own start
+                              time + this many picoseconds x the average number of stream steps
+                              up to i, so that all wavefronts pass the slabs at one pace and an
+                              XCD's L2 has to hold one part of B at a time.  0 = none (plain
+                              prepare) / measured (spmm_csr_prepare_tuned); -1 = never            */
+  int32_t barriers;        /* 1: instead of pacing, the workgroups of an XCD that run together
+                              wait for each other at every interval boundary (bounded wait).
+                              Kept for experiments: it moves less data than pacing and is slower */
+  int32_t sync_timeout_us; /* longest wait at such a barrier before all barriers of the launch are
+                              given up (0 = 200)                                                    */
+  int32_t sync_test_extra; /* test hook: added to the number of arrivals a barrier waits for, so
+                              that every wait runs into the time limit and the give-up path runs   */
+  int32_t narrow_slots;    /* 1: at width 128 a wavefront owns 14 (15 without lane groups) pieces
+                              instead of 16, which lets a CU hold five workgroups instead of four
+                              (16 rows need 32768 bytes of LDS per workgroup and 5 x 32768 do not
+                              fit).  Measured slower on the free-running sweep (more wavefronts
+                              thrash the L2 more) and equal under pacing; off unless asked for     */
+  int32_t reserved[2];     /* must be 0 */
+} sagnn_spmm_options;
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
 int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                      int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws, size_t ws_bytes,
                      void* stream);
+int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                         int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws, size_t ws_bytes,
+                         const sagnn_spmm_options* h_opt, void* stream);
 /* spmm_csr_prepare() with a measured choice between a few variants of the slab-sweep plan (how
  * long rows are cut into pieces, from which length a row counts as long): each variant is
  * prepared into d_ws and the product is run six times on the caller's operand d_B (k x f,
@@ -207,17 +243,24 @@ int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const flo
  * schedule is chosen there is nothing to vary and the call equals spmm_csr_prepare().  Every
  * variant computes the same product up to rounding order.
  * h_choice (host, 4 values, may be NULL): piece length and long-row threshold of the variant
- * kept (0 = default), its best time in microseconds, its index.
+ * kept (0 = default), its best time in microseconds, its index.  h_opt (may be NULL): options
+ * every variant starts from (see sagnn_spmm_options below).
  */
 int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                            int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws,
                            size_t ws_bytes, const float* d_B, int64_t ldb, float* d_C,
-                           int64_t ldc, int32_t* h_choice, void* stream);
-/* What spmm_csr_prepare() decided for a workspace (host query, no GPU work).  h_info[8]:
+                           int64_t ldc, int32_t* h_choice, const sagnn_spmm_options* h_opt,
+                           void* stream);
+/* What spmm_csr_prepare() decided for a workspace (host query, no GPU work).  h_info[16]:
  * [0] schedule (0 nonzero splitting, 1 slab sweep + nonzero splitting for short rows),
  * [1] wavefront streams of the sweep, [2] entries in them, [3] rows, [4] entries and
  * [5] chunks of the nonzero-splitting part, [6] rows cut into several pieces,
- * [7] 1 if the matrix has empty rows.  SAGNN_EINVAL if the workspace is unknown. */
+ * [7] 1 if the matrix has empty rows, [8] barrier intervals of the sweep, [9] slabs per
+ * interval (0 = one interval), [10] byte offset inside the workspace of a 32-bit flag that the
+ * most recent product left at 1 if a barrier wait ran into its time limit (the product is
+ * correct either way), [11] lane groups per wavefront, [12] pacing in picoseconds per stream
+ * step (0 = none), [13] 1 if barriers are used, [14] accumulator rows per wavefront.
+ * SAGNN_EINVAL if the workspace is unknown. */
 int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info);
 /* Forget the host descriptor of a prepared workspace.  Call it before the workspace memory is
  * freed or reused for something else: afterwards the address is unknown to the library again

@@ -6,7 +6,7 @@ and the stream, every step runs in the library's kernels.  There is no CPU fallb
 library is missing or no GPU is present, calls raise.
 """
 from .binding import (  # noqa: F401
-    SagnnError, lib, lib_path, Plan, SpmmWorkspace, plan_buffers,
+    SagnnError, lib, lib_path, Plan, SpmmWorkspace, SpmmOptions, options_from_env, plan_buffers,
     spmm_plan_needed_rows, spmm_plan_needed_rows_noalloc, spmm_pack_rows, spmm_csr_prepare, spmm_csr_prepare_tuned, spmm_csr_tallskinny,
     dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd,
     ColBlocks, spmm_split_colblocks, spmm_stage_loop, spmm_volume_stats, spmm_csr_transpose,

@@ -17,7 +17,7 @@ PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_plan_needed_rows_noalloc", "spmm_pack_rows",
-    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
+    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_opt", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
     "spmm_csr_release", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
@@ -31,6 +31,56 @@ class _Stage(ctypes.Structure):
     _fields_ = [("d_rowptr", ctypes.c_void_p), ("d_colidx", ctypes.c_void_p),
                 ("d_val", ctypes.c_void_p), ("nnz", ctypes.c_int64), ("d_rows", ctypes.c_void_p),
                 ("N", ctypes.c_int64), ("d_ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+
+
+class SpmmOptions(ctypes.Structure):
+    """struct sagnn_spmm_options of the C header (zero = let the library decide)."""
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("schedule", "min_long", "piece", "slab_kb", "min_waves", "window_pct", "snake", "groups",
+                 "sync_slabs", "pace_ps_per_step", "barriers", "sync_timeout_us", "sync_test_extra",
+                 "narrow_slots")] + [("reserved", ctypes.c_int32 * 2)]
+
+
+# The library itself reads no environment variables.  For experiments and for tests that force a
+# code path on small inputs, the binding translates these variables into the options struct:
+#   SAGNN_SWEEP=0|1 (never / whenever possible), SAGNN_SWEEP_MINDEG, SAGNN_SWEEP_PIECE,
+#   SAGNN_SWEEP_SLAB_MB (0 = as many slabs as possible), SAGNN_SWEEP_MIN_WAVES,
+#   SAGNN_SWEEP_WINDOW_PCT (0 = one window), SAGNN_SWEEP_LPT=0 (snake dealing),
+#   SAGNN_SWEEP_GROUPS=1|2, SAGNN_SWEEP_SYNC (slabs per interval, 0 = one interval),
+#   SAGNN_SWEEP_PACE_PS (picoseconds per stream step, -1 = never pace), SAGNN_SWEEP_BARRIERS=1,
+#   SAGNN_SWEEP_SYNC_US, SAGNN_SWEEP_SYNC_TEST_EXTRA, SAGNN_SWEEP_NARROW_SLOTS=1
+def options_from_env() -> SpmmOptions:
+    o = SpmmOptions()
+    env = os.environ.get
+
+    def num(name):
+        v = env(name)
+        return None if v is None or v == "" else int(v)
+
+    v = num("SAGNN_SWEEP")
+    if v is not None:
+        o.schedule = 1 if v == 0 else (2 if v == 1 else 0)
+    for name, field in (("SAGNN_SWEEP_MINDEG", "min_long"), ("SAGNN_SWEEP_PIECE", "piece"),
+                        ("SAGNN_SWEEP_MIN_WAVES", "min_waves"), ("SAGNN_SWEEP_GROUPS", "groups"),
+                        ("SAGNN_SWEEP_SYNC_US", "sync_timeout_us"), ("SAGNN_SWEEP_PACE_PS", "pace_ps_per_step"),
+                        ("SAGNN_SWEEP_BARRIERS", "barriers"), ("SAGNN_SWEEP_NARROW_SLOTS", "narrow_slots"),
+                        ("SAGNN_SWEEP_SYNC_TEST_EXTRA", "sync_test_extra")):
+        v = num(name)
+        if v is not None:
+            setattr(o, field, v)
+    v = num("SAGNN_SWEEP_SLAB_MB")
+    if v is not None:
+        o.slab_kb = -1 if v <= 0 else v * 1024
+    v = num("SAGNN_SWEEP_WINDOW_PCT")
+    if v is not None:
+        o.window_pct = -1 if v <= 0 else v
+    v = num("SAGNN_SWEEP_LPT")
+    if v is not None:
+        o.snake = 1 if v == 0 else 0
+    v = num("SAGNN_SWEEP_SYNC")
+    if v is not None:
+        o.sync_slabs = -1 if v <= 0 else v
+    return o
 
 
 class SagnnError(RuntimeError):
@@ -69,7 +119,8 @@ def lib():
         L.spmm_pack_rows.argtypes = [vp, i64, i64, i32, vp, i64, vp, i64, vp]
         L.spmm_csr_workspace_bytes.argtypes = [i64, i64, i32, psz]
         L.spmm_csr_prepare.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
-        L.spmm_csr_prepare_tuned.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, i64, vp, i64, vp, vp]
+        L.spmm_csr_prepare_opt.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, vp]
+        L.spmm_csr_prepare_tuned.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, i64, vp, i64, vp, vp, vp]
         L.spmm_csr_schedule_info.argtypes = [vp, vp]
         L.spmm_csr_release.argtypes = [vp]
         L.spmm_csr_tallskinny.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i64, i32, vp,
@@ -248,16 +299,23 @@ class SpmmWorkspace:
 
     def info(self) -> dict:
         """Schedule chosen by spmm_csr_prepare (see spmm_csr_schedule_info)."""
-        a = np.zeros(8, dtype=np.int64)
+        a = np.zeros(16, dtype=np.int64)
         _check(lib().spmm_csr_schedule_info(_ptr(self.buf), a.ctypes.data_as(ctypes.c_void_p)),
                "spmm_csr_schedule_info")
         keys = ("mode", "sweep_waves", "sweep_entries", "chunk_rows", "chunk_entries", "chunks",
-                "split_rows", "has_empty_rows")
+                "split_rows", "has_empty_rows", "intervals", "sync_slabs", "gave_up_offset", "groups",
+                "pace_ps_per_step", "barriers", "slots")
         return dict(zip(keys, (int(x) for x in a)))
 
+    def barriers_gave_up(self) -> bool:
+        """True if a barrier wait of the most recent product hit its time limit (synchronises)."""
+        off = self.info()["gave_up_offset"]
+        return bool(self.buf[off:off + 4].view(torch.int32).item() != 0)
 
-def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int) -> SpmmWorkspace:
-    """One-time schedule for C = A*B with A = (rowptr, colidx, val), B of k rows and width f."""
+
+def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int, options: SpmmOptions = None) -> SpmmWorkspace:
+    """One-time schedule for C = A*B with A = (rowptr, colidx, val), B of k rows and width f.
+    `options` defaults to options_from_env() (all zero unless SAGNN_SWEEP* variables are set)."""
     rowptr = _dev(rowptr, torch.int32, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     val = _dev(val, torch.float32, "val")
@@ -266,12 +324,13 @@ def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int) -> SpmmWorkspace:
     wsb = ctypes.c_size_t(0)
     _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
     buf = _ws(wsb.value, rowptr.device)
-    _check(L.spmm_csr_prepare(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
-                              buf.numel(), _stream()), "spmm_csr_prepare")
+    opt = options if options is not None else options_from_env()
+    _check(L.spmm_csr_prepare_opt(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
+                                  buf.numel(), ctypes.byref(opt), _stream()), "spmm_csr_prepare_opt")
     return SpmmWorkspace(buf, m, nnz, f, None, int(k))
 
 
-def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None) -> SpmmWorkspace:
+def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None, options: SpmmOptions = None) -> SpmmWorkspace:
     """spmm_csr_prepare with a measured choice between a few plan variants, timed on B (k x f).
     C (m x f) is overwritten with the product; allocated here when not given."""
     rowptr = _dev(rowptr, torch.int32, "rowptr")
@@ -288,9 +347,10 @@ def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None) -> SpmmWorkspace:
     _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
     buf = _ws(wsb.value, rowptr.device)
     choice = np.zeros(4, dtype=np.int32)
+    opt = options if options is not None else options_from_env()
     _check(L.spmm_csr_prepare_tuned(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
                                     buf.numel(), _ptr(B), B.stride(0), _ptr(C), C.stride(0),
-                                    choice.ctypes.data_as(ctypes.c_void_p), _stream()),
+                                    choice.ctypes.data_as(ctypes.c_void_p), ctypes.byref(opt), _stream()),
            "spmm_csr_prepare_tuned")
     return SpmmWorkspace(buf, m, nnz, f, {"piece": int(choice[0]), "min_long": int(choice[1]),
                                          "best_us": int(choice[2]), "variant": int(choice[3])}, int(k))

@@ -45,6 +45,11 @@ constexpr int kSweepRunMax = 128;
 constexpr int kSweepMaxSlabs = 384;
 constexpr int kSweepColBits = 27;           // column id bits in an encoded entry
 constexpr int kSweepMinLong = 16;           // smallest degree a "long" row can be given
+// The sweep is cut into intervals of `sync_slabs` slabs; between two intervals the workgroups of
+// an XCD that run at the same time wait for each other (bounded), so that they stay in the same
+// part of B.  A wavefront's stream is padded to a whole batch at every interval boundary.
+constexpr int kSweepMaxIntervals = 64;
+constexpr int kSweepBarrierSlots = 65536;   // arrival counters (cohort x XCD x interval)
 
 struct SpmmWsHeader {       // first 256 bytes of the SpMM workspace (device copy)
   uint32_t magic;
@@ -59,13 +64,21 @@ struct SpmmWsHeader {       // first 256 bytes of the SpMM workspace (device cop
   int64_t n_waves, n_long_entries, n_multi_rows, n_multi_pieces;
   int32_t n_slabs, slab_width;
   int32_t groups;           // lane groups per wavefront in the sweep streams (1, 2 or 4)
+  int32_t n_intervals;      // >= 1; interval boundaries are barrier points when sync_slabs > 0
+  int32_t sync_slabs;       // slabs per interval (0: no barriers, one interval)
+  int32_t wg_per_cohort;    // workgroups that are resident together (a multiple of 8)
+  int32_t sync_timeout_ticks;  // bounded wait at a barrier, in 100 MHz ticks
+  int32_t sync_test_extra;  // test hook: added to the expected arrivals (forces the give-up path)
+  int32_t slots;            // accumulator rows (pieces) per wavefront actually used, <= kSweepSlots
+  int32_t barriers;         // 1: barriers at interval boundaries
+  int32_t pace_ps_per_step; // pacing asked for at prepare time (0: none)
 };
 static_assert(sizeof(SpmmWsHeader) <= 256, "header must fit its slot");
 
 // Fixed layout (a function of m, k, nnz, f only; every array has its worst-case size):
 struct SpmmWsLayout {
   size_t header, chunk_row, flags, rowptr_s, rowmap_s, code, vals, piece_info, piece_target,
-      wave_base, multi_row, multi_first, partial, carry, total;
+      wave_base, wave_steps, sync_off, barrier, sched, multi_row, multi_first, partial, carry, total;
   int64_t max_chunks, max_pieces, max_waves, max_multi_rows, max_multi_pieces, stream_cap;
 };
 
@@ -80,9 +93,10 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   L.max_multi_rows = nnz / 1024 + 1;
   L.max_multi_pieces = 2 * (nnz / 1024) + 2;
   // sweep streams + gap + short CSR entries + padding.  A wavefront's stream is padded to the
-  // batch of 8 steps; with lane groups (up to 4 zipped streams per wavefront) also to the longest
-  // of its group streams, which the planner keeps within a small piece of each other.
-  L.stream_cap = nnz + nnz / 8 + 64 * L.max_waves + 4 * kSpmmChunk;
+  // batch of 8 steps at every interval boundary; with lane groups (up to 4 zipped streams per
+  // wavefront) also to the longest of its group streams inside every interval.  If a pattern
+  // needs more than this, the planner lays the streams out as one interval.
+  L.stream_cap = nnz + nnz / 4 + 256 * L.max_waves + 4 * kSpmmChunk;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   L.header = take(256);
@@ -95,6 +109,10 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   L.piece_info = take(sizeof(int32_t) * 2 * (size_t)(L.max_waves * kSweepSlots));
   L.piece_target = take(sizeof(int32_t) * (size_t)(L.max_waves * kSweepSlots));
   L.wave_base = take(sizeof(int32_t) * (size_t)(L.max_waves + 1));
+  L.wave_steps = take(sizeof(int32_t) * (size_t)(L.max_waves + 1));
+  L.sync_off = take(sizeof(int32_t) * (size_t)L.max_waves * (kSweepMaxIntervals + 1));
+  L.barrier = take(sizeof(uint32_t) * (size_t)(kSweepBarrierSlots + 64));
+  L.sched = take(sizeof(float) * (size_t)(kSweepMaxIntervals + 1));
   L.multi_row = take(sizeof(int32_t) * (size_t)L.max_multi_rows);
   L.multi_first = take(sizeof(int32_t) * (size_t)(L.max_multi_rows + 1));
   L.partial = take(sizeof(float) * (size_t)L.max_multi_pieces * (size_t)f);
@@ -114,7 +132,22 @@ struct SpmmHostDesc {
   int32_t has_empty_rows;
   int32_t groups;
   int64_t k;                // rows of B the schedule was prepared for (stream columns are < k)
+  int32_t n_intervals, sync_slabs, wg_per_cohort, sync_timeout_ticks, sync_test_extra;
+  int32_t slots;
+  int32_t barriers, pace_ps_per_step;
+  float mean_steps;         // average stream steps per wavefront (the end of the pacing schedule)
 };
+
+// Workgroups of `lds` bytes of LDS each that a CU really holds at once.  Measured on MI355X:
+// 5 x 32000 bytes fit, 5 x 32768 do not (the runtime's occupancy query says 5 for both), 2 x 65536
+// fit, 3 x 53248 were not tried.  Modelled as 160 KB minus 2 KB, allocations rounded up to 1280
+// bytes; an estimate on the low side is harmless wherever this is used.
+inline int lds_resident_workgroups(size_t lds) {
+  const size_t unit = round_up(lds > 0 ? lds : 1, 1280);
+  size_t n = (160u * 1024u - 2048u) / unit;
+  if (n > 8) n = 8;   // 32 wavefronts per CU, four per workgroup
+  return (int)n;
+}
 void spmm_desc_put(const void* ws, const SpmmHostDesc& d);
 bool spmm_desc_get(const void* ws, SpmmHostDesc* d);
 void spmm_desc_erase(const void* ws);
@@ -127,18 +160,12 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
 // slab-sweep part (spmm_sweep.hip)
 struct SweepPlanResult {
   bool use_sweep;
+  float mean_steps;  // average stream steps per wavefront
   SpmmWsHeader hdr;  // filled in for mode 1 (sweep part + short CSR sizes)
 };
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
                   int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
-                  hipStream_t s, SweepPlanResult* out);
-// Planner parameters a tuning call may set for the next sweep_prepare() of this thread
-// (0 = the default; environment overrides win over both).
-struct SweepTuning {
-  int piece;      // longest piece a long row is cut into
-  int min_long;   // long-row threshold used where the planner would pick 64
-};
-void sweep_set_tuning(SweepTuning t);
+                  const sagnn_spmm_options& opt, hipStream_t s, SweepPlanResult* out);
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
                  int32_t accumulate, int32_t f_total, hipStream_t s);

@@ -594,10 +594,15 @@ SAGNN_EXPORT int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, siz
   return SAGNN_OK;
 }
 
-SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx,
-                                  const float* d_val, int64_t m, int64_t k, int64_t nnz, int32_t f,
-                                  void* d_ws, size_t ws_bytes, void* stream) {
+SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                      const float* d_val, int64_t m, int64_t k, int64_t nnz, int32_t f,
+                                      void* d_ws, size_t ws_bytes, const sagnn_spmm_options* h_opt,
+                                      void* stream) {
   using namespace sagnn;
+  sagnn_spmm_options opt{};
+  if (h_opt) opt = *h_opt;
+  for (int i = 0; i < 2; ++i)
+    if (opt.reserved[i] != 0) return SAGNN_EINVAL;
   if (m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || m > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll ||
       k > 0x7FFFFFFFll)
     return SAGNN_EINVAL;
@@ -611,11 +616,11 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
 
   SweepPlanResult plan{};
   if ((f & 63) == 0 || f == 32 || f == 16) {
-    int rc = sweep_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, base, L, s, &plan);
+    int rc = sweep_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, base, L, opt, s, &plan);
     if (rc != SAGNN_OK) return rc;
   }
   SpmmWsHeader h{};
-  SAGNN_HIP(hipMemsetAsync(d_has_empty, 0, 4, s));
+  SAGNN_HIP(hipMemsetAsync(d_has_empty, 0, 4, s));   // set-up call: never recorded into a graph
   if (plan.use_sweep) {
     h = plan.hdr;
     int rc = build_chunk_tables(reinterpret_cast<const int32_t*>(base + L.rowptr_s), h.c_rows, h.c_nnz,
@@ -673,33 +678,52 @@ SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_coli
   desc.sweep_stream_len = h.n_long_entries;
   desc.groups = h.groups > 0 ? h.groups : 1;
   desc.k = k;
+  desc.n_intervals = h.n_intervals; desc.sync_slabs = h.sync_slabs; desc.wg_per_cohort = h.wg_per_cohort;
+  desc.sync_timeout_ticks = h.sync_timeout_ticks; desc.sync_test_extra = h.sync_test_extra;
+  desc.slots = h.slots;
+  desc.barriers = h.barriers; desc.pace_ps_per_step = h.pace_ps_per_step > 0 ? h.pace_ps_per_step : 0;
+  desc.mean_steps = plan.mean_steps;
   spmm_desc_put(d_ws, desc);
   return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                  const float* d_val, int64_t m, int64_t k, int64_t nnz, int32_t f,
+                                  void* d_ws, size_t ws_bytes, void* stream) {
+  return spmm_csr_prepare_opt(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, nullptr, stream);
 }
 
 SAGNN_EXPORT int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx,
                                         const float* d_val, int64_t m, int64_t k, int64_t nnz,
                                         int32_t f, void* d_ws, size_t ws_bytes, const float* d_B,
                                         int64_t ldb, float* d_C, int64_t ldc, int32_t* h_choice,
-                                        void* stream) {
+                                        const sagnn_spmm_options* h_opt, void* stream) {
   using namespace sagnn;
   if (!d_B || !d_C || ldb < f || ldc < f) return SAGNN_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   // (piece, long-row threshold) variants of the slab-sweep plan; {0, 0} is spmm_csr_prepare's own
-  static const SweepTuning cand[] = {{0, 0}, {4608, 0}, {3584, 0}, {0, 96}, {4608, 96}};
+  struct Cand { int piece, min_long; };
+  static const Cand cand[] = {{0, 0}, {4608, 0}, {3584, 0}, {0, 96}, {4608, 96}};
   const int n_cand = (int)(sizeof(cand) / sizeof(cand[0]));
+  // a variant only replaces choices the planner would make by itself: where it picks the
+  // lower long-row threshold (near-regular matrices) the candidate threshold is not forced
+  auto options_of = [&](int c) {
+    sagnn_spmm_options o{};
+    if (h_opt) o = *h_opt;
+    if (cand[c].piece > 0) o.piece = cand[c].piece;
+    if (cand[c].min_long > 0) o.min_long = -cand[c].min_long;   // negative: "where you would pick 64"
+    return o;
+  };
   int best = -1, last = -1;
   float best_ms = 0.f;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   auto cleanup = [&]() {
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
-    sweep_set_tuning(SweepTuning{0, 0});
   };
   for (int c = 0; c < n_cand; ++c) {
-    sweep_set_tuning(cand[c]);
-    int rc = spmm_csr_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, stream);
-    sweep_set_tuning(SweepTuning{0, 0});
+    const sagnn_spmm_options o = options_of(c);
+    int rc = spmm_csr_prepare_opt(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, &o, stream);
     if (rc != SAGNN_OK) { cleanup(); return rc; }
     last = c;
     SpmmHostDesc desc{};
@@ -726,9 +750,70 @@ SAGNN_EXPORT int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* 
     if (best < 0 || ms_min < (best == 0 ? 0.985f * best_ms : best_ms)) { best = c; best_ms = ms_min; }
   }
   if (best != last) {
-    sweep_set_tuning(cand[best]);
-    int rc = spmm_csr_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, stream);
+    const sagnn_spmm_options o = options_of(best);
+    int rc = spmm_csr_prepare_opt(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, &o, stream);
     if (rc != SAGNN_OK) { cleanup(); return rc; }
+  }
+  // Pacing of the sweep (see sweep_pace_until): lay the kept plan out with intervals and search
+  // the time per stream step that makes the product fastest.  Upper end: the whole free-running
+  // call time spread over the schedule of the generations of wavefronts; the useful values lie
+  // below it, because a paced sweep misses less in L2.  Below some value the wavefronts cannot
+  // keep to the schedule and the product falls back to its free-running time, so the search
+  // walks down and stops there.  If pacing does not pay, the plain layout is restored.
+  {
+    SpmmHostDesc desc{};
+    const bool never = h_opt && (h_opt->pace_ps_per_step != 0 || h_opt->barriers == 1 || h_opt->sync_slabs < 0);
+    if (!never && spmm_desc_get(d_ws, &desc) && desc.mode == 1 && (desc.groups == 2 || desc.groups == 4) &&
+        best_ms > 0.f) {
+      sagnn_spmm_options o = options_of(best);
+      if (o.sync_slabs == 0) o.sync_slabs = 16;
+      int rc = spmm_csr_prepare_opt(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, &o, stream);
+      if (rc != SAGNN_OK) { cleanup(); return rc; }
+      int32_t best_pace = 0;
+      if (spmm_desc_get(d_ws, &desc) && desc.mode == 1 && desc.n_intervals > 1 && desc.mean_steps > 0.f) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const int32_t fw = f >= 256 ? 256 : (f >= 128 ? 128 : f);
+        const int64_t resident = (int64_t)cus * lds_resident_workgroups((size_t)4 * desc.slots * fw * 4) * 4;
+        const double gens = (double)ceil_div(desc.n_waves, resident > 0 ? resident : 1);
+        const double ps_hi = (double)best_ms * 1e9 / (gens * (double)desc.mean_steps);
+        float paced_best = 0.f, prev = 0.f;
+        for (int step = 0; step < 14; ++step) {
+          desc.pace_ps_per_step = (int32_t)(ps_hi * (0.96 - 0.04 * step));
+          spmm_desc_put(d_ws, desc);
+          float ms_min = 0.f;
+          for (int rep = 0; rep < 5; ++rep) {
+            hipError_t e = hipEventRecord(e0, s);
+            if (e != hipSuccess) { set_hip_error(e); cleanup(); return SAGNN_EHIP; }
+            rc = launch_spmm(d_rowptr, d_colidx, d_val, m, k, nnz, d_B, ldb, f, d_C, ldc, 0, d_ws, ws_bytes, s);
+            if (rc != SAGNN_OK) { cleanup(); return rc; }
+            float ms = 0.f;
+            e = hipEventRecord(e1, s);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+            if (e != hipSuccess) { set_hip_error(e); cleanup(); return SAGNN_EHIP; }
+            if (rep == 1 || (rep > 1 && ms < ms_min)) ms_min = ms;
+          }
+          if (paced_best == 0.f || ms_min < paced_best) { paced_best = ms_min; best_pace = desc.pace_ps_per_step; }
+          if (prev > 0.f && ms_min > 1.08f * prev) break;    // fell off the schedule: slower again
+          prev = ms_min;
+        }
+        if (paced_best > 0.f && paced_best < 0.985f * best_ms) {
+          best_ms = paced_best;
+          // one step above the fastest value: a margin against run-to-run variation of the point
+          // where the wavefronts stop keeping up
+          desc.pace_ps_per_step = best_pace + (int32_t)(ps_hi * 0.02);
+          spmm_desc_put(d_ws, desc);
+        } else {
+          best_pace = 0;
+        }
+      }
+      if (best_pace == 0) {   // restore the layout without intervals
+        const sagnn_spmm_options o2 = options_of(best);
+        rc = spmm_csr_prepare_opt(d_rowptr, d_colidx, d_val, m, k, nnz, f, d_ws, ws_bytes, &o2, stream);
+        if (rc != SAGNN_OK) { cleanup(); return rc; }
+      }
+    }
   }
   cleanup();
   if (h_choice) {
@@ -753,6 +838,16 @@ SAGNN_EXPORT int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info) {
   h_info[5] = d.c_nchunks;
   h_info[6] = d.n_multi_rows;
   h_info[7] = d.has_empty_rows;
+  h_info[8] = d.mode == 1 ? d.n_intervals : 0;
+  h_info[9] = d.mode == 1 ? d.sync_slabs : 0;
+  // byte offset, inside the workspace, of the 32-bit flag the sweep kernels set when a barrier
+  // wait ran into its time limit during the most recent product (0 = all barriers were met)
+  h_info[10] = (int64_t)(spmm_ws_layout(d.m, d.nnz, d.f).barrier + sizeof(uint32_t) * kSweepBarrierSlots);
+  h_info[11] = d.groups;
+  h_info[12] = d.mode == 1 ? d.pace_ps_per_step : 0;
+  h_info[13] = d.mode == 1 ? d.barriers : 0;
+  h_info[14] = d.mode == 1 ? d.slots : 0;
+  h_info[15] = 0;
   return SAGNN_OK;
 }
 

@@ -70,56 +70,50 @@ __device__ __forceinline__ int32_t count_upto(int32_t x, int32_t j, int32_t p) {
   return x > j ? (x - j + p - 1) / p : 0;
 }
 
-// One workgroup per wavefront: segment the 16 pieces by slab, lay the entries out in
-// (slab, piece) order and encode them.  With `groups` = R lane groups the wavefront carries R
-// independent streams (group g owns slots g*16/R ..), stored zipped: entry t of group g at
-// position R*t + g; the shorter streams are padded with entries that multiply row 0 of B by 0.
-__global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
-    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-    const float* __restrict__ val, const int32_t* __restrict__ piece_info,
-    const int32_t* __restrict__ wave_base, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
-    int32_t stagger, int32_t groups, uint32_t* __restrict__ code, float* __restrict__ vals) {
-  // dynamic LDS (sweep_build_lds_bytes): lo[16][S+1] first entry (index in row) of slab s;
-  // off[S][16] offset of segment (s, slot) inside its slab; slab_base[S][16] stream offset of
-  // slab s for group g; slab_tot[S][16]
-  extern __shared__ __attribute__((aligned(16))) int32_t build_lds[];
-  const int SS = n_slabs;
-  int32_t* lo_ = build_lds;                                  // [16][SS + 1]
-  int32_t* off_ = lo_ + kSweepSlots * (SS + 1);              // [SS][16]
-  int32_t* slab_base_ = off_ + SS * kSweepSlots;             // [SS][16]
-  int32_t* slab_tot_ = slab_base_ + SS * kSweepSlots;        // [SS][16]
-#define LO(slot, s) lo_[(slot) * (SS + 1) + (s)]
-#define OFF(s, slot) off_[(s) * kSweepSlots + (slot)]
-#define SLAB_BASE(s, g) slab_base_[(s) * kSweepSlots + (g)]
-#define SLAB_TOT(s, g) slab_tot_[(s) * kSweepSlots + (g)]
-  __shared__ int32_t glen[kSweepSlots];
-  __shared__ int32_t p_row[kSweepSlots], p_j[kSweepSlots], p_p[kSweepSlots], p_beg[kSweepSlots],
-      p_deg[kSweepSlots];
-  const int64_t w = blockIdx.x;
+// Per-wavefront segment tables shared by the counting and the building kernel (dynamic LDS):
+//   lo[16][S+1]      first entry (index in its row) of slab s for the piece in a slot
+//   off[S][16]       offset of segment (s, slot) inside its slab, per lane group
+//   slab_tot[S][16]  entries of slab s per lane group
+struct BuildTables {
+  int32_t *lo, *off, *slab_tot;
+  int SS;
+  __device__ int32_t& LO(int slot, int s) const { return lo[slot * (SS + 1) + s]; }
+  __device__ int32_t& OFF(int s, int slot) const { return off[s * kSweepSlots + slot]; }
+  __device__ int32_t& TOT(int s, int g) const { return slab_tot[s * kSweepSlots + g]; }
+};
+
+struct BuildPieces {
+  int32_t row[kSweepSlots], j[kSweepSlots], p[kSweepSlots], beg[kSweepSlots], deg[kSweepSlots];
+};
+
+// fills pc (shared) and the tables for wavefront w; all threads of the workgroup take part
+__device__ __forceinline__ void build_tables(const int32_t* __restrict__ rowptr,
+                                             const int32_t* __restrict__ colidx,
+                                             const int32_t* __restrict__ piece_info, int64_t w, int S,
+                                             int32_t slab_width, uint32_t kmax, int R, int SL,
+                                             BuildPieces& pc, const BuildTables& T) {
   const int tid = threadIdx.x;
-  const int S = n_slabs;
-  const int R = groups, SL = kSweepSlots / groups;
   if (tid < kSweepSlots) {
     const int32_t row = piece_info[2 * (w * kSweepSlots + tid)];
     const int32_t jp = piece_info[2 * (w * kSweepSlots + tid) + 1];
-    p_row[tid] = row;
-    p_j[tid] = jp >> 16;
-    p_p[tid] = jp & 0xFFFF;
-    p_beg[tid] = row >= 0 ? rowptr[row] : 0;
-    p_deg[tid] = row >= 0 ? rowptr[row + 1] - rowptr[row] : 0;
+    pc.row[tid] = row;
+    pc.j[tid] = jp >> 16;
+    pc.p[tid] = jp & 0xFFFF;
+    pc.beg[tid] = row >= 0 ? rowptr[row] : 0;
+    pc.deg[tid] = row >= 0 ? rowptr[row + 1] - rowptr[row] : 0;
   }
   __syncthreads();
   for (int idx = tid; idx < kSweepSlots * (S + 1); idx += kBuildThreads) {
     const int slot = idx / (S + 1), s = idx - slot * (S + 1);
     int32_t res = 0;
-    if (p_row[slot] >= 0) {
-      const int32_t d = p_deg[slot];
+    if (pc.row[slot] >= 0) {
+      const int32_t d = pc.deg[slot];
       if (s == S) {
         res = d;
       } else {
         // lower bound of column s*slab_width in the (ascending) row
         const int64_t target = (int64_t)s * slab_width;
-        const int32_t* __restrict__ c = colidx + p_beg[slot];
+        const int32_t* __restrict__ c = colidx + pc.beg[slot];
         int32_t a = 0, b = d;
         while (a < b) {
           const int32_t mid = (a + b) >> 1;
@@ -129,52 +123,152 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
         res = a;
       }
     }
-    LO(slot, s) = res;
+    T.LO(slot, s) = res;
   }
   __syncthreads();
   // entries of segment (s, slot); then per slab the prefix over the slots of each group
   for (int idx = tid; idx < S * kSweepSlots; idx += kBuildThreads) {
     const int s = idx / kSweepSlots, slot = idx - s * kSweepSlots;
-    OFF(s, slot) = p_row[slot] >= 0 ? count_upto(LO(slot, s + 1), p_j[slot], p_p[slot]) -
-                                          count_upto(LO(slot, s), p_j[slot], p_p[slot])
-                                    : 0;
+    T.OFF(s, slot) = pc.row[slot] >= 0 ? count_upto(T.LO(slot, s + 1), pc.j[slot], pc.p[slot]) -
+                                             count_upto(T.LO(slot, s), pc.j[slot], pc.p[slot])
+                                       : 0;
   }
   __syncthreads();
   for (int idx = tid; idx < S * R; idx += kBuildThreads) {
     const int s = idx / R, gi = idx - s * R;
     int32_t run = 0;
     for (int slot = gi * SL; slot < (gi + 1) * SL; ++slot) {
-      const int32_t c = OFF(s, slot);
-      OFF(s, slot) = run;
+      const int32_t c = T.OFF(s, slot);
+      T.OFF(s, slot) = run;
       run += c;
     }
-    SLAB_TOT(s, gi) = run;
+    T.TOT(s, gi) = run;
   }
   __syncthreads();
-  // The stream is laid out in the order the wavefront will walk the slabs: it starts at slab
-  // s0 = xcd * S/8 (xcd = workgroup index mod 8, four wavefronts per workgroup) and wraps.
-  const int s0 = stagger ? (int)(((w >> 2) & 7) * S / 8) : 0;
-  if (tid < R) {
+}
+
+__device__ __forceinline__ BuildTables carve_tables(int32_t* lds, int S) {
+  BuildTables T;
+  T.SS = S;
+  T.lo = lds;
+  T.off = T.lo + kSweepSlots * (S + 1);
+  T.slab_tot = T.off + S * kSweepSlots;
+  return T;
+}
+
+// Pass 1: length of every interval of a wavefront's stream.  An interval's R group streams are
+// padded to the longest of them and to a whole batch (8 steps), so that every wavefront reaches
+// an interval boundary at a batch boundary.  sync_off[w][i] = first step of interval i,
+// wave_steps[w] = total steps.
+__global__ __launch_bounds__(kBuildThreads) void sweep_count_kernel(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+    const int32_t* __restrict__ piece_info, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
+    int32_t groups, int32_t slots_per_group, int32_t n_intervals, int32_t sync_slabs,
+    int32_t* __restrict__ sync_off, int32_t* __restrict__ wave_steps) {
+  extern __shared__ __attribute__((aligned(16))) int32_t build_lds[];
+  __shared__ BuildPieces pc;
+  __shared__ int32_t ivl_len[kSweepMaxIntervals];
+  const int64_t w = blockIdx.x;
+  const int S = n_slabs, R = groups;
+  const BuildTables T = carve_tables(build_lds, S);
+  build_tables(rowptr, colidx, piece_info, w, S, slab_width, kmax, R, slots_per_group, pc, T);
+  const int per = sync_slabs > 0 ? sync_slabs : S;
+  for (int i = threadIdx.x; i < n_intervals; i += kBuildThreads) {
+    const int s0 = i * per, s1 = (i + 1) * per < S ? (i + 1) * per : S;
+    int32_t longest = 0;
+    for (int gi = 0; gi < R; ++gi) {
+      int32_t t = 0;
+      for (int s = s0; s < s1; ++s) t += T.TOT(s, gi);
+      longest = t > longest ? t : longest;
+    }
+    ivl_len[i] = (longest + 7) & ~7;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
     int32_t run = 0;
-    for (int t = 0; t < S; ++t) {
-      const int s = (s0 + t) % S;
-      SLAB_BASE(s, tid) = run;
-      run += SLAB_TOT(s, tid);
+    int32_t* so = sync_off + w * (kSweepMaxIntervals + 1);
+    for (int i = 0; i < n_intervals; ++i) {
+      so[i] = run;
+      run += ivl_len[i];
     }
-    glen[tid] = run;
+    so[n_intervals] = run;
+    wave_steps[w] = run;
+  }
+}
+
+// Pass 2 (one workgroup): wave_base[w] = R * (steps of the wavefronts before w); wave_base[NW]
+// is the total stream length.  overflow[0] = 1 if it does not fit 31 bits.
+__global__ __launch_bounds__(1024) void sweep_scan_kernel(const int32_t* __restrict__ wave_steps,
+                                                          int64_t n_waves, int32_t groups,
+                                                          int32_t* __restrict__ wave_base,
+                                                          int32_t* __restrict__ overflow) {
+  __shared__ int64_t part[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (n_waves + 1023) / 1024;
+  const int64_t a = tid * per, b = a + per < n_waves ? a + per : n_waves;
+  int64_t sum = 0;
+  for (int64_t w = a; w < b; ++w) sum += (int64_t)wave_steps[w] * groups;
+  part[tid] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    int64_t run = 0;
+    for (int i = 0; i < 1024; ++i) {
+      const int64_t t = part[i];
+      part[i] = run;
+      run += t;
+    }
+    overflow[0] = run > 0x7FFFFFF0ll ? 1 : 0;
+    wave_base[n_waves] = (int32_t)(run > 0x7FFFFFF0ll ? 0x7FFFFFF0ll : run);
   }
   __syncthreads();
-  const int64_t base = wave_base[w];
-  const int64_t steps = (wave_base[w + 1] - base) / R;     // padded length of every group stream
-  for (int gi = 0; gi < R; ++gi)
-    for (int64_t t = glen[gi] + tid; t < steps; t += kBuildThreads) {
-      code[base + t * R + gi] = 0u;
-      vals[base + t * R + gi] = 0.f;
+  int64_t run = part[tid];
+  for (int64_t w = a; w < b; ++w) {
+    wave_base[w] = (int32_t)(run > 0x7FFFFFF0ll ? 0x7FFFFFF0ll : run);
+    run += (int64_t)wave_steps[w] * groups;
+  }
+}
+
+// Pass 3, one workgroup per wavefront: lay the entries out in (interval, slab, piece) order and
+// encode them.  With `groups` = R lane groups the wavefront carries R independent streams (group
+// g owns slots g*SL .. g*SL+SL-1), stored zipped: step t of group g at position R*t + g.  Steps that no
+// entry lands on (padding of the shorter group streams and at interval boundaries) multiply
+// row 0 of B by 0.
+__global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
+    const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+    const float* __restrict__ val, const int32_t* __restrict__ piece_info,
+    const int32_t* __restrict__ wave_base, const int32_t* __restrict__ sync_off, int32_t n_slabs,
+    int32_t slab_width, uint32_t kmax, int32_t groups, int32_t slots_per_group, int32_t n_intervals,
+    int32_t sync_slabs, uint32_t* __restrict__ code, float* __restrict__ vals) {
+  extern __shared__ __attribute__((aligned(16))) int32_t build_lds[];
+  __shared__ BuildPieces pc;
+  const int64_t w = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int S = n_slabs, R = groups, SL = slots_per_group;
+  const BuildTables T = carve_tables(build_lds, S);
+  int32_t* slab_base_ = T.slab_tot + S * kSweepSlots;          // [S][16]: first step of slab s, group g
+  build_tables(rowptr, colidx, piece_info, w, S, slab_width, kmax, R, SL, pc, T);
+  const int per = sync_slabs > 0 ? sync_slabs : S;
+  const int32_t* __restrict__ so = sync_off + w * (kSweepMaxIntervals + 1);
+  for (int idx = tid; idx < n_intervals * R; idx += kBuildThreads) {
+    const int i = idx / R, gi = idx - i * R;
+    const int s0 = i * per, s1 = (i + 1) * per < S ? (i + 1) * per : S;
+    int32_t run = so[i];
+    for (int s = s0; s < s1; ++s) {
+      slab_base_[s * kSweepSlots + gi] = run;
+      run += T.TOT(s, gi);
     }
+  }
+  const int64_t base = wave_base[w];
+  const int64_t words = (int64_t)so[n_intervals] * R;
+  for (int64_t t = tid; t < words; t += kBuildThreads) {
+    code[base + t] = 0u;
+    vals[base + t] = 0.f;
+  }
+  __syncthreads();
   for (int slot = 0; slot < kSweepSlots; ++slot) {
-    if (p_row[slot] < 0) continue;
+    if (pc.row[slot] < 0) continue;
     const int gi = slot / SL;
-    const int32_t j = p_j[slot], p = p_p[slot], d = p_deg[slot], beg = p_beg[slot];
+    const int32_t j = pc.j[slot], p = pc.p[slot], d = pc.deg[slot], beg = pc.beg[slot];
     const int32_t size = count_upto(d, j, p);
     for (int32_t t = tid; t < size; t += kBuildThreads) {
       const int32_t i = j + t * p;
@@ -183,25 +277,36 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
       int s = (int)(c / (uint32_t)slab_width);
       if (s > S - 1) s = S - 1;
       // the row is ascending, but clamped / equal columns may sit on a slab boundary: trust lo[]
-      while (s > 0 && i < LO(slot, s)) --s;
-      while (s < S - 1 && i >= LO(slot, s + 1)) ++s;
-      const int32_t rank = t - count_upto(LO(slot, s), j, p);
+      while (s > 0 && i < T.LO(slot, s)) --s;
+      while (s < S - 1 && i >= T.LO(slot, s + 1)) ++s;
+      const int32_t rank = t - count_upto(T.LO(slot, s), j, p);
       // a segment also ends every kSweepRunMax entries, which bounds the length of any serial
       // fp32 accumulation (and with it the rounding bias on rows of equal terms)
-      const bool last = i + p >= LO(slot, s + 1) || (rank & (kSweepRunMax - 1)) == kSweepRunMax - 1;
-      const int64_t pos = base + (int64_t)(SLAB_BASE(s, gi) + OFF(s, slot) + rank) * R + gi;
+      const bool last = i + p >= T.LO(slot, s + 1) || (rank & (kSweepRunMax - 1)) == kSweepRunMax - 1;
+      const int64_t pos = base + (int64_t)(slab_base_[s * kSweepSlots + gi] + T.OFF(s, slot) + rank) * R + gi;
       code[pos] = c | ((uint32_t)slot << kSweepColBits) | (last ? 0x80000000u : 0u);
       vals[pos] = val[beg + i];
     }
   }
 }
-#undef LO
-#undef OFF
-#undef SLAB_BASE
-#undef SLAB_TOT
 
+inline size_t sweep_count_lds_bytes(int64_t S) {
+  return sizeof(int32_t) * (size_t)(kSweepSlots * (S + 1) + 2 * S * kSweepSlots);
+}
 inline size_t sweep_build_lds_bytes(int64_t S) {
   return sizeof(int32_t) * (size_t)(kSweepSlots * (S + 1) + 3 * S * kSweepSlots);
+}
+
+__global__ void sweep_zero_flags_kernel(int32_t* __restrict__ flags) {
+  if (threadIdx.x < 4) flags[threadIdx.x] = 0;
+}
+
+__global__ __launch_bounds__(256) void sweep_zero_gap_kernel(uint32_t* __restrict__ code,
+                                                            float* __restrict__ vals, int32_t n) {
+  for (int i = threadIdx.x; i < n; i += 256) {
+    code[i] = 0u;
+    vals[i] = 0.f;
+  }
 }
 
 // compacted CSR of the short rows: copy entries
@@ -228,7 +333,76 @@ struct SweepDims {
   uint32_t b_bytes;     // bytes addressable from B + col0 (buffer-load variant)
   uint32_t row_bytes;   // ldb * 4
   int32_t col0, accumulate;
+  // interval barriers (lane-group kernels): 0 intervals = walk the stream in one go
+  int32_t n_intervals, wg_per_cohort, sync_timeout_ticks, sync_test_extra;
+  int32_t slots;        // accumulator rows per wavefront (<= kSweepSlots)
+  float pace_ticks;     // pacing: 100 MHz ticks per stream step (0: none)
 };
+
+// Barrier between two intervals of the sweep for the workgroups that run at the same time on
+// one XCD ("cohort" c = workgroup index / wg_per_cohort, XCD = workgroup index mod 8: workgroups
+// are handed to the XCDs round-robin).  It only paces the workgroups -- no data passes through
+// it -- so that all of them read the same part of B at the same time and the XCD's L2 serves
+// every row once.  The wait is bounded: after `timeout` ticks of the 100 MHz clock the waiter
+// sets a flag that makes every later barrier of the launch fall through (the kernel then
+// free-runs, correct but with more cache misses), so a launch whose cohort is not resident
+// together (fewer free CUs than assumed) still ends.
+__device__ __forceinline__ void sweep_interval_barrier(uint32_t* __restrict__ counters, int slot,
+                                                       uint32_t expected, int32_t timeout) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t* broken = counters + kSweepBarrierSlots;
+    if (__hip_atomic_load(broken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+      uint32_t* ctr = counters + slot;
+      __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint64_t t0 = wall_clock64();
+      while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < expected) {
+        if (__hip_atomic_load(broken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+        if (wall_clock64() - t0 > (uint64_t)timeout) {
+          __hip_atomic_store(broken, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(16);
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// Pacing: a wavefront does not enter the next interval before `ticks` of the 100 MHz clock have
+// passed since it started.  Every wavefront follows the same schedule (the average number of
+// stream steps up to each interval boundary, times a fixed time per step), so all of them pass
+// over B at one pace without exchanging anything; one that is behind schedule never waits.  The
+// loop is bounded (the clock passes the deadline, and the iteration count is capped anyway).
+__device__ __forceinline__ void sweep_pace_until(uint64_t t0, float ticks) {
+  const uint64_t deadline = t0 + (uint64_t)ticks;
+  for (int i = 0; i < 2048; ++i) {
+    if (wall_clock64() >= deadline) break;
+    __builtin_amdgcn_s_sleep(8);
+  }
+}
+
+// sched[i] = average over the wavefronts of the first step of interval i (i = 0..n_intervals)
+__global__ __launch_bounds__(256) void sweep_sched_kernel(const int32_t* __restrict__ sync_off,
+                                                          int64_t n_waves, int32_t n_intervals,
+                                                          float* __restrict__ sched) {
+  __shared__ double red[256];
+  const int i = blockIdx.x;
+  double sum = 0.0;
+  for (int64_t w = threadIdx.x; w < n_waves; w += 256) sum += (double)sync_off[w * (kSweepMaxIntervals + 1) + i];
+  red[threadIdx.x] = sum;
+  __syncthreads();
+  for (int d = 128; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && i <= n_intervals) sched[i] = n_waves > 0 ? (float)(red[0] / (double)n_waves) : 0.f;
+}
+
+__global__ __launch_bounds__(256) void sweep_barrier_clear_kernel(uint32_t* __restrict__ counters, int n) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) counters[i] = 0u;
+  if (blockIdx.x == 0 && threadIdx.x == 0) counters[kSweepBarrierSlots] = 0u;
+}
 
 template <int FPL, int U, bool BUF>
 __global__ __launch_bounds__(256) void spmm_sweep_kernel(
@@ -237,7 +411,7 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
     const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ C,
     float* __restrict__ partial, const SweepDims d) {
   using vec = typename Vec<FPL>::T;
-  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][16 slots][64*FPL]
+  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][d.slots][64*FPL]
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t loff = lane * (FPL * 4);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -247,9 +421,8 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
       hdr->groups != 1)
     return;
   constexpr int kRow = 64 * FPL;  // floats per accumulator row
-  float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lane * FPL;
-#pragma unroll
-  for (int s = 0; s < kSweepSlots; ++s) *reinterpret_cast<vec*>(my + s * kRow) = vec(0.f);
+  float* __restrict__ my = lds_acc + (size_t)wave * d.slots * kRow + lane * FPL;
+  for (int s = 0; s < d.slots; ++s) *reinterpret_cast<vec*>(my + s * kRow) = vec(0.f);
 
   const int32_t base = wave_base[w];
   const int32_t len = wave_base[w + 1] - base;  // a multiple of U (padded when built)
@@ -283,7 +456,7 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
   }
 
 #pragma unroll 1
-  for (int s = 0; s < kSweepSlots; ++s) {
+  for (int s = 0; s < d.slots; ++s) {
     const int32_t tgt = piece_target[w * kSweepSlots + s];
     if (tgt == INT32_MIN) continue;
     vec r = *reinterpret_cast<const vec*>(my + s * kRow);
@@ -309,12 +482,13 @@ __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
     const uint32_t* __restrict__ code, const float* __restrict__ vals,
     const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
     const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ C,
-    float* __restrict__ partial, const SweepDims d) {
+    float* __restrict__ partial, const int32_t* __restrict__ sync_off,
+    uint32_t* __restrict__ barrier, const float* __restrict__ sched, const SweepDims d) {
   using vec = typename Vec<V>::T;
   constexpr int LG = 64 / R;             // lanes per group = lanes per row
   constexpr int kRow = LG * V;           // floats per row of this launch
-  constexpr int SL = kSweepSlots / R;    // slots per group
-  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][16 slots][kRow]
+  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][d.slots][kRow]
+  const int SL = d.slots / R;            // slots per group
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t gid = lane / LG, lig = lane % LG;
   const uint32_t loff = lig * (V * 4);
@@ -324,8 +498,7 @@ __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
   if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves ||
       hdr->groups != R)
     return;
-  float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lig * V;
-#pragma unroll
+  float* __restrict__ my = lds_acc + (size_t)wave * d.slots * kRow + lig * V;
   for (int ls = 0; ls < SL; ++ls) *reinterpret_cast<vec*>(my + (gid * SL + ls) * kRow) = vec(0.f);
 
   const int32_t base = wave_base[w];
@@ -333,60 +506,90 @@ __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
   const uint32_t* __restrict__ cw = code + base;
   const float* __restrict__ vw = vals + base;
   const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
+  // interval boundaries of this wavefront's stream (whole batches) and the barrier it shares
+  // with the workgroups of its cohort on its XCD
+  const bool with_barrier = d.n_intervals > 1;     // negative: same layout, no barriers
+  const int n_iv = d.n_intervals < 0 ? -d.n_intervals : d.n_intervals;
+  const int32_t* __restrict__ so = sync_off + w * (kSweepMaxIntervals + 1);
+  uint32_t expected = 0;
+  int bar_slot0 = 0;
+  if (with_barrier) {
+    const int64_t cohort = (int64_t)blockIdx.x / d.wg_per_cohort;
+    const int64_t first = cohort * d.wg_per_cohort;
+    int64_t last = first + d.wg_per_cohort;
+    if (last > (int64_t)gridDim.x) last = gridDim.x;
+    const int xg = (int)(blockIdx.x & 7);
+    // workgroups b in [first, last) with b mod 8 == xg (first is a multiple of 8)
+    expected = (uint32_t)((last - first - xg + 7) / 8) + (uint32_t)d.sync_test_extra;
+    bar_slot0 = (int)((cohort * 8 + xg) * n_iv);
+  }
+
+  const bool paced = d.pace_ticks > 0.f && n_iv > 1;
+  const uint64_t t_start = paced ? wall_clock64() : 0ull;
 
   vec acc = 0.f;
-  for (int32_t e = 0; e < steps; e += U) {
-    uint32_t c[U][R];
-    float v[U][R];
+  int32_t e = 0;
+  for (int iv = 0; iv < n_iv; ++iv) {
+    const int32_t e_end = iv + 1 < n_iv ? so[iv + 1] : steps;
+    for (; e < e_end; e += U) {
+      uint32_t c[U][R];
+      float v[U][R];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int g = 0; g < R; ++g) {
-        c[u][g] = cw[(e + u) * R + g];
-        v[u][g] = vw[(e + u) * R + g];
+        for (int g = 0; g < R; ++g) {
+          c[u][g] = cw[(e + u) * R + g];
+          v[u][g] = vw[(e + u) * R + g];
+        }
+      uint32_t mc[U];
+      float mv[U];
+      vec h[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        mc[u] = c[u][0];
+        mv[u] = v[u][0];
+        if constexpr (BUF) {
+          uint32_t off = (c[u][0] & kColMask) * d.row_bytes;
+#pragma unroll
+          for (int g = 1; g < R; ++g)
+            if (gid == (uint32_t)g) {
+              mc[u] = c[u][g];
+              mv[u] = v[u][g];
+              off = (c[u][g] & kColMask) * d.row_bytes;
+            }
+          off += loff;
+          if constexpr (V == 1) h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+          else if constexpr (V == 2) h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, 0));
+          else h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
+        } else {
+          const char* rowp = reinterpret_cast<const char*>(B + (int64_t)(c[u][0] & kColMask) * d.ldb);
+#pragma unroll
+          for (int g = 1; g < R; ++g)
+            if (gid == (uint32_t)g) {
+              mc[u] = c[u][g];
+              mv[u] = v[u][g];
+              rowp = reinterpret_cast<const char*>(B + (int64_t)(c[u][g] & kColMask) * d.ldb);
+            }
+          h[u] = *reinterpret_cast<const vec*>(rowp + loff);
+        }
       }
-    uint32_t mc[U];
-    float mv[U];
-    vec h[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      mc[u] = c[u][0];
-      mv[u] = v[u][0];
-      if constexpr (BUF) {
-        uint32_t off = (c[u][0] & kColMask) * d.row_bytes;
+      for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
 #pragma unroll
-        for (int g = 1; g < R; ++g)
-          if (gid == (uint32_t)g) {
-            mc[u] = c[u][g];
-            mv[u] = v[u][g];
-            off = (c[u][g] & kColMask) * d.row_bytes;
-          }
-        off += loff;
-        if constexpr (V == 1) h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
-        else if constexpr (V == 2) h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, 0));
-        else h[u] = __builtin_bit_cast(vec, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
-      } else {
-        const char* rowp = reinterpret_cast<const char*>(B + (int64_t)(c[u][0] & kColMask) * d.ldb);
-#pragma unroll
-        for (int g = 1; g < R; ++g)
-          if (gid == (uint32_t)g) {
-            mc[u] = c[u][g];
-            mv[u] = v[u][g];
-            rowp = reinterpret_cast<const char*>(B + (int64_t)(c[u][g] & kColMask) * d.ldb);
-          }
-        h[u] = *reinterpret_cast<const vec*>(rowp + loff);
+      for (int u = 0; u < U; ++u) {
+        acc += mv[u] * h[u];
+        if (mc[u] >> 31) {   // last entry of a (piece, slab) segment of this lane's group
+          vec* p = reinterpret_cast<vec*>(my + ((mc[u] >> kSweepColBits) & (kSweepSlots - 1)) * kRow);
+          *p += acc;
+          acc = 0.f;
+        }
       }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      acc += mv[u] * h[u];
-      if (mc[u] >> 31) {   // last entry of a (piece, slab) segment of this lane's group
-        vec* p = reinterpret_cast<vec*>(my + ((mc[u] >> kSweepColBits) & (kSweepSlots - 1)) * kRow);
-        *p += acc;
-        acc = 0.f;
-      }
+    // between two intervals: wait for the cohort (barrier mode) or hold the wavefront to the
+    // schedule (pacing); a wavefront with nothing in an interval still takes part
+    if (iv + 1 < n_iv) {
+      if (with_barrier) sweep_interval_barrier(barrier, bar_slot0 + iv, expected, d.sync_timeout_ticks);
+      else if (paced) sweep_pace_until(t_start, d.pace_ticks * sched[iv + 1]);
     }
   }
 
@@ -554,31 +757,24 @@ __global__ __launch_bounds__(256) void sweep_combine_kernel(
   }
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  return v ? atoi(v) : dflt;
-}
-
 struct Piece {
   int32_t size, row, j, p;
 };
 
 std::atomic<uint64_t> g_generation{1};
-thread_local SweepTuning g_tuning{0, 0};
 
 }  // namespace
-
-void sweep_set_tuning(SweepTuning t) { g_tuning = t; }
 
 // ---------------------------------------------------------------------------------------
 // host side of the preparation: classify rows, cut long rows into pieces, deal pieces to the
 // streams of the wavefronts (largest first, each to the shortest stream so far, so the streams
-// have nearly equal lengths), build the compacted short-row CSR.
+// have nearly equal lengths), build the compacted short-row CSR.  The streams themselves are
+// laid out by the three device passes above.
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
                   int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
-                  hipStream_t s, SweepPlanResult* out) {
+                  const sagnn_spmm_options& opt, hipStream_t s, SweepPlanResult* out) {
   out->use_sweep = false;
-  const int force = env_int("SAGNN_SWEEP", -1);  // 0: never, 1: whenever possible, -1: heuristic
+  const int force = opt.schedule == 1 ? 0 : (opt.schedule == 2 ? 1 : -1);
   if (force == 0 || nnz < 4096 || k <= 0 || k >= (1ll << kSweepColBits) || m <= 0) return SAGNN_OK;
   const int64_t b_bytes = k * (int64_t)f * 4;
   // worth it only if B is much larger than an L2 (the long-row share is checked below)
@@ -594,20 +790,20 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // many rows below it hold few entries and would only add accumulator slots); when the rows of
   // 16..63 entries hold a large share of the matrix (near-regular graphs, e.g. a partitioned
   // graph's row block) the threshold drops so that they are swept too.
-  int min_long = env_int("SAGNN_SWEEP_MINDEG", 0);
+  int min_long = opt.min_long;       // > 0: forced; < 0: used where the rule below would pick 64
   if (min_long <= 0) {
     int64_t mid = 0;
     for (int64_t r = 0; r < m; ++r) {
       const int64_t d = (int64_t)rp[r + 1] - rp[r];
       if (d >= kSweepMinLong && d < 64) mid += d;
     }
-    min_long = (mid * 4 >= nnz) ? kSweepMinLong : (g_tuning.min_long > 0 ? g_tuning.min_long : 64);
+    min_long = (mid * 4 >= nnz) ? kSweepMinLong : (min_long < 0 ? -min_long : 64);
   }
   if (min_long < kSweepMinLong) min_long = kSweepMinLong;
-  int piece_max = env_int("SAGNN_SWEEP_PIECE", g_tuning.piece > 0 ? g_tuning.piece : 4096);
+  int piece_max = opt.piece > 0 ? opt.piece : 4096;
   if (piece_max < 1024) piece_max = 1024;
   if (piece_max > 32768) piece_max = 32768;
-  const int64_t slab_bytes = (int64_t)env_int("SAGNN_SWEEP_SLAB_MB", 4) << 20;
+  const int64_t slab_bytes = opt.slab_kb < 0 ? 0 : (int64_t)(opt.slab_kb > 0 ? opt.slab_kb : 4096) << 10;
   int64_t S = slab_bytes >= (1 << 16) ? 8 * ceil_div(b_bytes, 8 * slab_bytes) : kSweepMaxSlabs;
   if (S < 8) S = 8;
   if (S > kSweepMaxSlabs) S = kSweepMaxSlabs;
@@ -623,8 +819,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // Narrow operands (f = 32, 16: rows of 128 / 64 bytes, 8 / 4 lanes each) exist only in the
   // grouped form, 8 / 16 rows per load.
   int64_t R = f == 128 ? 2 : (f == 64 ? 4 : (f == 32 ? 8 : (f == 16 ? 16 : 1)));
-  const int groups_env = env_int("SAGNN_SWEEP_GROUPS", 0);   // 1: never, 2: whenever possible
-  if (groups_env == 1 && f >= 64) R = 1;
+  if (opt.groups == 1 && f >= 64) R = 1;
   std::vector<Piece> pieces;
   int64_t long_entries = 0, short_rows = 0, short_entries = 0;
   bool has_empty = false;
@@ -644,7 +839,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     }
   }
   if (force != 1 && long_entries * 10 < nnz * 3) return SAGNN_OK;   // < 30 % of the entries
-  if (groups_env != 2 && long_entries < 8 * k) {
+  if (opt.groups != 2 && long_entries < 8 * k) {
     if (f < 64) return SAGNN_OK;   // no one-row-per-instruction form below 64: plain schedule
     R = 1;
   }
@@ -653,12 +848,20 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   std::vector<char> is_long((size_t)m, 0);
   for (const Piece& pc : pieces) is_long[(size_t)pc.row] = 1;
   const int64_t P = (int64_t)pieces.size();
-  // Pieces per wavefront: all kSweepSlots when there are plenty of pieces; fewer when that would
+  // Accumulator rows per wavefront.  A launch of width 128 with 16 rows per wavefront needs
+  // 32768 bytes of LDS per workgroup, of which a CU holds four, not five (measured; the LDS
+  // is handed out in units that make 5 x 32768 overshoot 160 KB).  14 rows (lane groups, 7 each)
+  // or 15 rows bring the fifth workgroup in, 20 wavefronts and 280 / 300 rows per CU instead
+  // of 16 and 256 -- measured slower free-running on the 2.45 M-vertex graph (5.4 against
+  // 4.5 ms: more wavefronts drift apart more) and equal under pacing, so it is an option only.
+  const bool has_128_slab = (f % 256) == 128 || (f % 256) == 192;
+  const int64_t slots = has_128_slab && opt.narrow_slots == 1 ? (R == 2 ? 14 : 15) : kSweepSlots;
+  // Pieces per wavefront: all slots when there are plenty of pieces; fewer when that would
   // leave the chip short of wavefronts (a row block of a partitioned graph has few long rows).
-  int64_t slots_used = ceil_div(P, (int64_t)env_int("SAGNN_SWEEP_MIN_WAVES", 8192));
+  int64_t slots_used = ceil_div(P, (int64_t)(opt.min_waves > 0 ? opt.min_waves : 8192));
   if (slots_used < R) slots_used = R;          // every lane group of a wavefront gets a piece
-  if (slots_used > kSweepSlots) slots_used = kSweepSlots;
-  if (ceil_div(P, slots_used) + 64 > L.max_waves - 1) slots_used = kSweepSlots;
+  if (slots_used > slots) slots_used = slots;
+  if (ceil_div(P, slots_used) + 64 > L.max_waves - 8) slots_used = slots;
   // Pieces are dealt window by window.  A window is a run of consecutive long rows holding a
   // few times as many pieces as the chip keeps resident at once (LDS-limited); inside a window
   // the pieces are sorted by size and dealt longest-first, so its wavefronts have nearly equal
@@ -667,15 +870,29 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // per generation on the 2.45 M-vertex R-MAT graph); a larger one whose row order carries
   // locality (a partitioned graph) keeps it, because a window only touches the part of B its
   // rows' neighbourhoods live in (2 M-vertex community-ordered graph: 13.9 -> 11.4 ms).
-  const int64_t lds_per_wg = 4ll * kSweepSlots * f * 4;
-  int64_t wg_per_cu = (160 * 1024) / lds_per_wg;
-  if (wg_per_cu > 8) wg_per_cu = 8;
+  const int64_t fw_max = f >= 256 ? 256 : (f >= 128 ? 128 : f);     // widest launch of a call
+  int64_t wg_per_cu = lds_resident_workgroups((size_t)(4ll * slots * fw_max * 4));
   if (wg_per_cu < 1) wg_per_cu = 1;
-  const int64_t resident_waves = 256 * wg_per_cu * 4;
+  int n_cus = 256;
+  {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n_cus = v;
+  }
+  const int64_t resident_waves = (int64_t)n_cus * wg_per_cu * 4;
   int64_t window = resident_waves * slots_used;              // pieces per window
   {
-    const int pct = env_int("SAGNN_SWEEP_WINDOW_PCT", 400);  // 0: one window (global dealing)
+    const int pct = opt.window_pct < 0 ? 0 : (opt.window_pct > 0 ? opt.window_pct : 400);
     window = pct <= 0 ? P : std::max<int64_t>(slots_used, window * pct / 100);
+  }
+  // Wavefronts in all: whole generations of resident wavefronts when there is more than one
+  // (the last generation then runs at the same occupancy, and under pacing at the same speed, as
+  // the others), else as few as the slots allow.
+  int64_t n_target_waves = ceil_div(P, slots_used);
+  if (n_target_waves > resident_waves) {
+    const int64_t up = round_up((size_t)n_target_waves, (size_t)resident_waves);
+    if (up + 64 <= L.max_waves - 8) n_target_waves = up;
   }
   std::vector<int64_t> win_wave0;                            // first wavefront of every window
   int64_t NW = 0;
@@ -692,16 +909,19 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     // the slots allow
     int64_t entries_w = 0;
     for (int64_t t = a; t < b; ++t) entries_w += pieces[(size_t)t].size;
-    const double target_len = (double)long_entries / (double)ceil_div(P, slots_used);
+    const double target_len = (double)long_entries / (double)n_target_waves;
     int64_t nw = (int64_t)((double)entries_w / target_len + 0.5);
-    nw = std::max(nw, ceil_div(b - a, (int64_t)kSweepSlots));
+    nw = std::max(nw, ceil_div(b - a, slots));
     nw = std::max<int64_t>(nw, 1);
     nw = std::min(nw, b - a);
     NW += nw;
   }
   win_wave0.push_back(NW);
-  if (NW > L.max_waves - 1) return SAGNN_OK;   // cannot happen with the bounds above; plain schedule
-  std::vector<int32_t> info((size_t)NW * kSweepSlots * 2, -1), target((size_t)NW * kSweepSlots, INT32_MIN);
+  // whole workgroups of four wavefronts (the last ones may own no piece): the kernels' workgroup
+  // barriers then never meet a wavefront that has left
+  const int64_t NW4 = (NW + 3) / 4 * 4;
+  if (NW4 > L.max_waves - 1) return SAGNN_OK;   // cannot happen with the bounds above; plain schedule
+  std::vector<int32_t> info((size_t)NW4 * kSweepSlots * 2, -1), target((size_t)NW4 * kSweepSlots, INT32_MIN);
   // multi-piece rows: partial slots in row order
   std::vector<int32_t> multi_row, multi_first;
   {
@@ -722,13 +942,13 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // smallest size class, which keeps the wavefronts in step from slab to slab.  With R lane
   // groups a wavefront carries R independent streams (group g owns slots g*16/R ..); the unit of
   // dealing is then the group stream.
-  const int64_t SL = kSweepSlots / R;           // slots per group stream
+  const int64_t SL = slots / R;                 // slots per group stream
   std::vector<int32_t> used((size_t)NW * R, 0);
   std::vector<int64_t> uload((size_t)NW * R, 0);
   using Load = std::pair<int64_t, int64_t>;   // (stream length, unit = wavefront * R + group)
   std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
   int64_t cur_win = -1;
-  const bool lpt = R > 1 || env_int("SAGNN_SWEEP_LPT", 1) != 0;
+  const bool lpt = R > 1 || opt.snake == 0;
   for (int64_t t = 0; t < P; ++t) {
     const int64_t win = t / window, tw = t - win * window;
     const int64_t nw = win_wave0[(size_t)win + 1] - win_wave0[(size_t)win];
@@ -763,25 +983,16 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
       target[g] = -(multi_first[q] + pc.j) - 1;
     }
   }
-  // A wavefront's R group streams are stored zipped (entry t of group g at R*t + g), each padded
-  // to the longest of them and to a multiple of the kernel's batch (8 steps)
-  std::vector<int32_t> wbase((size_t)NW + 1);
-  int64_t run = 0, unpadded = 0;
-  for (int64_t wv = 0; wv < NW; ++wv) {
-    wbase[(size_t)wv] = (int32_t)run;
-    int64_t longest = 0;
-    for (int64_t gi = 0; gi < R; ++gi) {
-      longest = std::max(longest, uload[(size_t)(wv * R + gi)]);
-      unpadded += uload[(size_t)(wv * R + gi)];
-    }
-    run += (longest + 7) / 8 * 8 * R;
-    if (run > 0x7FFFFFF0ll) return SAGNN_OK;
-  }
-  wbase[(size_t)NW] = (int32_t)run;
-  if (unpadded != long_entries) return SAGNN_EINVAL;
-  const int64_t stream_len = run;
-  const int64_t short_base = round_up((size_t)stream_len + 64, 256);
-  if (short_base + short_entries + kSpmmChunk > L.stream_cap) return SAGNN_OK;
+
+  // Interval barriers (lane-group kernels only): every `sync_slabs` slabs the workgroups of an
+  // XCD that run together wait for each other.  Decided here, laid out by the device passes.
+  // (the interval layout costs ~3 % of padding, so it is only made when something will use it)
+  int64_t sync_slabs = opt.sync_slabs < 0 ? 0 : (opt.sync_slabs > 0 ? opt.sync_slabs : 16);
+  if (opt.barriers != 1 && opt.pace_ps_per_step <= 0 && opt.sync_slabs <= 0) sync_slabs = 0;
+  if (R != 2 && R != 4) sync_slabs = 0;
+  if (sync_slabs > 0 && ceil_div(S, sync_slabs) > kSweepMaxIntervals) sync_slabs = ceil_div(S, kSweepMaxIntervals);
+  int64_t NI = sync_slabs > 0 ? ceil_div(S, sync_slabs) : 1;
+  if (NI <= 1) { NI = 1; sync_slabs = 0; }
 
   // short-row CSR
   std::vector<int32_t> rps((size_t)short_rows + 1), rmap((size_t)short_rows + 1);
@@ -799,7 +1010,6 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   };
   SAGNN_HIP(up(L.piece_info, info.data(), info.size() * 4));
   SAGNN_HIP(up(L.piece_target, target.data(), target.size() * 4));
-  SAGNN_HIP(up(L.wave_base, wbase.data(), wbase.size() * 4));
   SAGNN_HIP(up(L.multi_row, multi_row.data(), multi_row.size() * 4));
   SAGNN_HIP(up(L.multi_first, multi_first.data(), multi_first.size() * 4));
   SAGNN_HIP(up(L.rowptr_s, rps.data(), rps.size() * 4));
@@ -807,29 +1017,61 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
 
   // long rows must be column-sorted for the slab segmentation
   int32_t* d_flag = reinterpret_cast<int32_t*>(ws + L.carry);  // scratch until the first product
-  SAGNN_HIP(hipMemsetAsync(d_flag, 0, 4, s));
-  hipLaunchKernelGGL(sweep_check_sorted_kernel, dim3((unsigned)ceil_div(NW * kSweepSlots, 4)), dim3(256),
-                     0, s, d_rowptr, d_colidx, reinterpret_cast<const int32_t*>(ws + L.piece_info),
-                     NW * kSweepSlots, (uint32_t)(k - 1), d_flag);
+  hipLaunchKernelGGL(sweep_zero_flags_kernel, dim3(1), dim3(64), 0, s, d_flag);
   SAGNN_LAUNCH_CHECK();
-  int32_t unsorted = 0;
-  SAGNN_HIP(hipMemcpyAsync(&unsorted, d_flag, 4, hipMemcpyDeviceToHost, s));
-  SAGNN_HIP(hipStreamSynchronize(s));
-  if (unsorted) return SAGNN_OK;
+  hipLaunchKernelGGL(sweep_check_sorted_kernel, dim3((unsigned)ceil_div(NW4 * kSweepSlots, 4)), dim3(256),
+                     0, s, d_rowptr, d_colidx, reinterpret_cast<const int32_t*>(ws + L.piece_info),
+                     NW4 * kSweepSlots, (uint32_t)(k - 1), d_flag);
+  SAGNN_LAUNCH_CHECK();
 
   const uint32_t kmax = (uint32_t)(k - 1);
-  const size_t build_lds = sweep_build_lds_bytes(S);
+  const int32_t* d_info = reinterpret_cast<const int32_t*>(ws + L.piece_info);
+  int32_t* d_wave_base = reinterpret_cast<int32_t*>(ws + L.wave_base);
+  int32_t* d_wave_steps = reinterpret_cast<int32_t*>(ws + L.wave_steps);
+  int32_t* d_sync_off = reinterpret_cast<int32_t*>(ws + L.sync_off);
+  const size_t count_lds = sweep_count_lds_bytes(S), build_lds = sweep_build_lds_bytes(S);
+  SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_count_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)count_lds));
   SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_build_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)build_lds));
-  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW), dim3(kBuildThreads), build_lds, s, d_rowptr, d_colidx,
-                     d_val, reinterpret_cast<const int32_t*>(ws + L.piece_info),
-                     reinterpret_cast<const int32_t*>(ws + L.wave_base), (int32_t)S, (int32_t)width, kmax,
-                     (int32_t)env_int("SAGNN_SWEEP_STAGGER", 0), (int32_t)R,
-                     reinterpret_cast<uint32_t*>(ws + L.code), reinterpret_cast<float*>(ws + L.vals));
+  int64_t stream_len = 0, short_base = 0;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    hipLaunchKernelGGL(sweep_count_kernel, dim3((unsigned)NW4), dim3(kBuildThreads), count_lds, s, d_rowptr,
+                       d_colidx, d_info, (int32_t)S, (int32_t)width, kmax, (int32_t)R, (int32_t)SL, (int32_t)NI,
+                       (int32_t)sync_slabs, d_sync_off, d_wave_steps);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(sweep_scan_kernel, dim3(1), dim3(1024), 0, s, d_wave_steps, NW4, (int32_t)R,
+                       d_wave_base, d_flag + 1);
+    SAGNN_LAUNCH_CHECK();
+    int32_t h_flags[2] = {0, 0}, h_total = 0;
+    SAGNN_HIP(hipMemcpyAsync(h_flags, d_flag, 8, hipMemcpyDeviceToHost, s));
+    SAGNN_HIP(hipMemcpyAsync(&h_total, d_wave_base + NW4, 4, hipMemcpyDeviceToHost, s));
+    SAGNN_HIP(hipStreamSynchronize(s));    // also: the host vectors above have been consumed
+    if (h_flags[0]) return SAGNN_OK;       // unsorted long row or column out of range: plain schedule
+    stream_len = h_total;
+    short_base = (int64_t)round_up((size_t)stream_len + 64, 256);
+    const bool fits = !h_flags[1] && short_base + short_entries + kSpmmChunk <= L.stream_cap;
+    if (fits) break;
+    if (attempt == 1 || NI == 1) return SAGNN_OK;
+    NI = 1;                                // the interval padding did not fit: lay out without it
+    sync_slabs = 0;
+  }
+
+  hipLaunchKernelGGL(sweep_sched_kernel, dim3((unsigned)(NI + 1)), dim3(256), 0, s, d_sync_off, NW4, (int32_t)NI,
+                     reinterpret_cast<float*>(ws + L.sched));
+  SAGNN_LAUNCH_CHECK();
+  float mean_steps = 0.f;
+  SAGNN_HIP(hipMemcpyAsync(&mean_steps, reinterpret_cast<float*>(ws + L.sched) + NI, 4, hipMemcpyDeviceToHost, s));
+  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW4), dim3(kBuildThreads), build_lds, s, d_rowptr,
+                     d_colidx, d_val, d_info, d_wave_base, d_sync_off, (int32_t)S, (int32_t)width, kmax,
+                     (int32_t)R, (int32_t)SL, (int32_t)NI, (int32_t)sync_slabs, reinterpret_cast<uint32_t*>(ws + L.code),
+                     reinterpret_cast<float*>(ws + L.vals));
   SAGNN_LAUNCH_CHECK();
   // zero the gap between the long stream and the short entries (tail batches read into it)
-  SAGNN_HIP(hipMemsetAsync(ws + L.code + 4 * (size_t)stream_len, 0, 4 * (size_t)(short_base - stream_len), s));
-  SAGNN_HIP(hipMemsetAsync(ws + L.vals + 4 * (size_t)stream_len, 0, 4 * (size_t)(short_base - stream_len), s));
+  hipLaunchKernelGGL(sweep_zero_gap_kernel, dim3(1), dim3(256), 0, s,
+                     reinterpret_cast<uint32_t*>(ws + L.code) + stream_len,
+                     reinterpret_cast<float*>(ws + L.vals) + stream_len, (int32_t)(short_base - stream_len));
+  SAGNN_LAUNCH_CHECK();
   if (short_rows > 0) {
     hipLaunchKernelGGL(sweep_short_copy_kernel, dim3((unsigned)ceil_div(short_rows, 256)), dim3(256), 0, s,
                        d_rowptr, d_colidx, d_val, reinterpret_cast<const int32_t*>(ws + L.rowptr_s),
@@ -838,7 +1080,6 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
                        reinterpret_cast<float*>(ws + L.vals) + short_base);
     SAGNN_LAUNCH_CHECK();
   }
-  SAGNN_HIP(hipStreamSynchronize(s));  // host vectors are read by the copies above
 
   SpmmWsHeader& h = out->hdr;
   h = SpmmWsHeader{};
@@ -847,15 +1088,42 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   h.m = m; h.nnz = nnz; h.f = f; h.mode = 1;
   h.generation = g_generation.fetch_add(1);
   h.c_rows = short_rows; h.c_nnz = short_entries; h.c_nchunks = spmm_nchunks(short_entries);
-  h.n_waves = NW; h.n_long_entries = stream_len;   // padded length of the sweep streams
+  h.n_waves = NW4; h.n_long_entries = stream_len;   // padded length of the sweep streams
   h.n_multi_rows = (int64_t)multi_row.size(); h.n_multi_pieces = multi_first.back();
   h.n_slabs = (int32_t)S; h.slab_width = (int32_t)width;
   h.groups = (int32_t)R;
+  h.n_intervals = (int32_t)NI; h.sync_slabs = (int32_t)sync_slabs;
+  h.sync_timeout_ticks = (opt.sync_timeout_us > 0 ? opt.sync_timeout_us : 200) * 100;
+  h.sync_test_extra = opt.sync_test_extra > 0 ? opt.sync_test_extra : 0;
+  h.slots = (int32_t)slots;
+  h.barriers = opt.barriers == 1 && sync_slabs > 0 ? 1 : 0;
+  h.pace_ps_per_step = sync_slabs > 0 && !h.barriers ? opt.pace_ps_per_step : 0;
+  SAGNN_HIP(hipStreamSynchronize(s));     // mean_steps has arrived
+  out->mean_steps = mean_steps;
   out->use_sweep = true;
   return SAGNN_OK;
 }
 
 uint64_t spmm_next_generation() { return g_generation.fetch_add(1); }
+
+namespace {
+// workgroups of a kernel that are resident at once on the whole device, for the cohort size of
+// the interval barriers: CUs x workgroups per CU as the runtime reports them for this kernel
+// and its LDS size, rounded down to a multiple of 8 (one share per XCD).  0 if unknown.
+int resident_workgroups(const void* kern, size_t lds) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds) != hipSuccess) return 0;
+  // the runtime's figure is too high where the LDS is what limits (see lds_resident_workgroups):
+  // assuming too few resident workgroups only makes a cohort smaller, assuming too many would
+  // make every barrier run into its time limit
+  const int by_lds = lds_resident_workgroups(lds);
+  if (per_cu > by_lds) per_cu = by_lds;
+  const int64_t n = (int64_t)cus * per_cu / 8 * 8;
+  return n > 0 && n < (1 << 30) ? (int)n : 0;
+}
+}  // namespace
 
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
@@ -870,7 +1138,8 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
   const bool buf = buffer_addressable(kmax, ldb, fw, &sd.b_bytes);
   sd.row_bytes = (uint32_t)(ldb * 4);
   const unsigned blocks = (unsigned)ceil_div(d.n_waves, 4);
-  const size_t lds = (size_t)4 * kSweepSlots * fw * sizeof(float);
+  sd.slots = d.slots > 0 && d.slots <= kSweepSlots ? d.slots : kSweepSlots;
+  const size_t lds = (size_t)4 * sd.slots * fw * sizeof(float);
   auto go = [&](auto kern) -> int {
     if (lds > 48 * 1024)
       SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -885,6 +1154,42 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
     SAGNN_LAUNCH_CHECK();
     return SAGNN_OK;
   };
+  // lane-group kernels: walk the stream interval by interval, with a barrier of the XCD's
+  // resident workgroups in between when the schedule was laid out for it
+  auto go_group = [&](auto kern) -> int {
+    if (lds > 48 * 1024)
+      SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    uint32_t* barrier = reinterpret_cast<uint32_t*>(ws + L.barrier);
+    sd.n_intervals = d.n_intervals > 0 ? d.n_intervals : 1;
+    sd.sync_timeout_ticks = d.sync_timeout_ticks;
+    sd.sync_test_extra = d.sync_test_extra;
+    sd.wg_per_cohort = 0;
+    sd.pace_ticks = d.barriers ? 0.f : (float)d.pace_ps_per_step * 1e-4f;    // ps -> 10 ns ticks
+    if (d.barriers && d.sync_slabs > 0 && sd.n_intervals > 1 && (d.n_waves & 3) == 0) {
+      const int wpc = resident_workgroups(reinterpret_cast<const void*>(kern), lds);
+      const int64_t cohorts = wpc > 0 ? ceil_div((int64_t)blocks, wpc) : 0;
+      if (wpc >= 8 && cohorts * 8 * sd.n_intervals <= kSweepBarrierSlots) {
+        sd.wg_per_cohort = wpc;
+        const int n_ctr = (int)(cohorts * 8 * sd.n_intervals);
+        hipLaunchKernelGGL(sweep_barrier_clear_kernel, dim3((unsigned)ceil_div(n_ctr, 256)), dim3(256), 0, s,
+                           barrier, n_ctr);
+        SAGNN_LAUNCH_CHECK();
+      }
+    }
+    if (sd.wg_per_cohort == 0) sd.n_intervals = sd.n_intervals > 1 ? -sd.n_intervals : sd.n_intervals;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s,
+                       reinterpret_cast<const uint32_t*>(ws + L.code),
+                       reinterpret_cast<const float*>(ws + L.vals),
+                       reinterpret_cast<const int32_t*>(ws + L.wave_base),
+                       reinterpret_cast<const int32_t*>(ws + L.piece_target),
+                       reinterpret_cast<const SpmmWsHeader*>(ws + L.header), B + col0, C + col0,
+                       reinterpret_cast<float*>(ws + L.partial),
+                       reinterpret_cast<const int32_t*>(ws + L.sync_off), barrier,
+                       reinterpret_cast<const float*>(ws + L.sched), sd);
+    SAGNN_LAUNCH_CHECK();
+    return SAGNN_OK;
+  };
   if (d.groups == 16)    // prepared for f = 16: four lanes per row
     return fw == 16 ? (buf ? go(spmm_sweep_perm_kernel<16, true>) : go(spmm_sweep_perm_kernel<16, false>))
                     : SAGNN_EINVAL;
@@ -892,12 +1197,12 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
     return fw == 32 ? (buf ? go(spmm_sweep_perm_kernel<8, true>) : go(spmm_sweep_perm_kernel<8, false>))
                     : SAGNN_EINVAL;
   if (d.groups == 2) {   // prepared for f = 128: half a wavefront per row (or per half row at 64)
-    if (fw == 128) return buf ? go(spmm_sweep_group_kernel<4, 2, 8, true>) : go(spmm_sweep_group_kernel<4, 2, 8, false>);
-    if (fw == 64) return buf ? go(spmm_sweep_group_kernel<2, 2, 8, true>) : go(spmm_sweep_group_kernel<2, 2, 8, false>);
+    if (fw == 128) return buf ? go_group(spmm_sweep_group_kernel<4, 2, 8, true>) : go_group(spmm_sweep_group_kernel<4, 2, 8, false>);
+    if (fw == 64) return buf ? go_group(spmm_sweep_group_kernel<2, 2, 8, true>) : go_group(spmm_sweep_group_kernel<2, 2, 8, false>);
     return SAGNN_EINVAL;
   }
   if (d.groups == 4) {   // prepared for f = 64: a quarter wavefront per row
-    if (fw == 64) return buf ? go(spmm_sweep_group_kernel<4, 4, 8, true>) : go(spmm_sweep_group_kernel<4, 4, 8, false>);
+    if (fw == 64) return buf ? go_group(spmm_sweep_group_kernel<4, 4, 8, true>) : go_group(spmm_sweep_group_kernel<4, 4, 8, false>);
     return SAGNN_EINVAL;
   }
   if (fw == 256) return buf ? go(spmm_sweep_kernel<4, 8, true>) : go(spmm_sweep_kernel<4, 8, false>);

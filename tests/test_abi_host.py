@@ -60,7 +60,13 @@ def test_argument_validation_before_launch():
     assert L.spmm_csr_tallskinny(None, None, None, 0, 4, 0, None, 16, 16, None, 16, 0, None, 0, None) == 0
     assert L.spmm_csr_tallskinny(None, None, None, 4, 4, 4, None, 16, 18, None, 16, 0, None, 0, None) == -1
     assert L.spmm_csr_prepare(None, None, None, 4, 4, 4, 16, None, 0, None) == -1
-    assert L.spmm_csr_prepare_tuned(None, None, None, 4, 4, 4, 16, None, 0, None, 16, None, 16, None, None) == -1
+    assert L.spmm_csr_prepare_tuned(None, None, None, 4, 4, 4, 16, None, 0, None, 16, None, 16, None, None, None) == -1
+    assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, None, None) == -1
+    bad = sagnn.SpmmOptions()
+    bad.reserved[1] = 1                                   # reserved fields must be zero
+    import ctypes as _c
+    assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, _c.byref(bad), None) == -1
+    assert L.spmm_csr_release(None) == -1
     # plan: missing host arrays
     assert L.spmm_plan_needed_rows(None, None, 4, 4, 0, None, 1, None, 0, None, None, None, 0, 0, None) == -1
     # GEMM: unsupported sizes
@@ -72,6 +78,30 @@ def test_argument_validation_before_launch():
     assert L.spmm_split_workspace_bytes(100, 257, ctypes.byref(b)) == -1
     assert L.spmm_split_colblocks(None, None, None, 4, 0, None, 2, None, None, None, None, None, 0, None) == -1
     assert L.spmm_stage_loop(None, 1, 4, None, 4, 16, 16, None, None, 4, None, 16, 0, None, None) == -1
+
+
+def test_options_from_env_translation(monkeypatch):
+    """The library reads no environment; the binding turns the experiment variables into the
+    options struct (host only)."""
+    for k in list(os.environ):
+        if k.startswith("SAGNN_SWEEP"):
+            monkeypatch.delenv(k)
+    o = sagnn.options_from_env()
+    assert all(getattr(o, n) == 0 for n, _ in sagnn.SpmmOptions._fields_[:-1]) and not any(o.reserved)
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "0")
+    monkeypatch.setenv("SAGNN_SWEEP_LPT", "0")
+    monkeypatch.setenv("SAGNN_SWEEP_SYNC", "0")
+    monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+    o = sagnn.options_from_env()
+    assert (o.schedule, o.slab_kb, o.snake, o.sync_slabs, o.piece) == (2, -1, 1, -1, 1024)
+    monkeypatch.setenv("SAGNN_SWEEP", "0")
+    monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "2")
+    monkeypatch.setenv("SAGNN_SWEEP_SYNC", "8")
+    o = sagnn.options_from_env()
+    assert (o.schedule, o.slab_kb, o.sync_slabs) == (1, 2048, 8)
+    src = open(os.path.join(ROOT, "paper_2504_04673_amd", "csrc", "spmm_sweep.hip")).read()
+    assert "getenv" not in src and "getenv" not in open(os.path.join(ROOT, "paper_2504_04673_amd", "csrc", "spmm.hip")).read()
 
 
 def test_volume_stats_host_only():

@@ -648,3 +648,48 @@ def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     assert_close(Gp, np.where(Zprev > 0, gt, 0), gtabs, rtol, "bwd Gprev vs oracle GEMM of the library's S")
     yt, ytabs = oracle.gemm(H, Sg, bf16=bool(prec), transX=True, want_abs=True)
     assert_close(Y, yt, ytabs, rtol, "bwd Y vs oracle GEMM of the library's S")
+
+
+@pytest.mark.parametrize("f", [64, 128])
+def test_spmm_sweep_interval_barrier_gives_up_and_still_computes(f, force_sweep, monkeypatch):
+    """Barrier mode: the workgroups of the sweep wait for each other at interval boundaries, for a
+    bounded time.  Here every barrier is then told to expect more arrivals than there are
+    workgroups (a host-side test hook), so the first wait runs into its 20-microsecond limit, the
+    launch gives all barriers up and free-runs: every kernel still ends and the product is unchanged."""
+    rng = np.random.default_rng(9 + f)
+    m, n = 6000, 60_000
+    rowptr, colidx, val = random_csr(m, n, 25, rng, hubs=[(3, 9000), (7, 3000), (2500, 1024)])
+    B = synth.normal((n, f), f, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+
+    def run():
+        ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f)
+        assert ws.info()["mode"] == 1
+        out = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), ws=ws)
+        torch.cuda.synchronize()
+        return out, ws
+
+    monkeypatch.setenv("SAGNN_SWEEP_SYNC", "48")             # 384 slabs: 8 intervals
+    monkeypatch.setenv("SAGNN_SWEEP_BARRIERS", "1")
+    normal, ws = run()
+    assert ws.info()["barriers"] == 1 and ws.info()["intervals"] > 1 and not ws.barriers_gave_up()
+    assert_close(normal, ref, zabs, RTOL_SPMM, "with interval barriers")
+    monkeypatch.setenv("SAGNN_SWEEP_SYNC_TEST_EXTRA", "1000")
+    monkeypatch.setenv("SAGNN_SWEEP_SYNC_US", "20")
+    gave_up, ws = run()
+    assert ws.barriers_gave_up()
+    assert torch.equal(gave_up, normal)                       # same summation order either way
+    monkeypatch.delenv("SAGNN_SWEEP_SYNC_TEST_EXTRA")
+    monkeypatch.delenv("SAGNN_SWEEP_BARRIERS")
+    # pacing: every wavefront holds itself to a time schedule (here far slower than it could run,
+    # so every boundary really waits); same bits again
+    monkeypatch.setenv("SAGNN_SWEEP_PACE_PS", "2000000")
+    paced, ws = run()
+    assert ws.info()["pace_ps_per_step"] == 2000000 and ws.info()["barriers"] == 0
+    assert torch.equal(paced, normal)
+    monkeypatch.delenv("SAGNN_SWEEP_PACE_PS")                 # and without intervals at all (the default)
+    monkeypatch.delenv("SAGNN_SWEEP_SYNC")
+    plain, ws = run()
+    assert ws.info()["intervals"] == 1
+    assert_close(plain, ref, zabs, RTOL_SPMM, "without intervals")
