@@ -47,6 +47,20 @@ def parse_traffic(workload: str, f: int):
     return None
 
 
+def traffic_source(workload: str, f: int):
+    """Where roofline.traffic comes from: it is NOT measured in this run (counters need rocprofv3
+    around the process) but read from a committed summary; name it and the commit it was taken at."""
+    rel = os.path.join("profiles", f"spmm_{workload}_f{f}_traffic.txt")
+    path = os.path.join(ROOT, rel)
+    if not os.path.exists(path):
+        return None
+    commit = None
+    for line in open(path):
+        if line.startswith("taken_at_commit:"):
+            commit = line.split(":", 1)[1].strip()
+    return {"file": rel, "taken_at_commit": commit, "measured_in_this_run": False}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -236,6 +250,39 @@ def main():
         },
     }
 
+    out["roofline"]["traffic_source"] = traffic_source(wl.name, f)
+    # the layer as ONE kernel (T = A H kept on the chip; gcn_layer_fwd with d_T = NULL) against the
+    # two calls; reported, not part of `value`.  fp32 product where the fused form has it (W and a
+    # tile of T must fit the LDS), else bf16 operands on both sides of the comparison.
+    reps = max(args.steps // 2, 3)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    out["fused_layer"] = {"unsupported": f"f_in={f} f_out={f_out}"}
+    for prec, pname in ((sagnn.GEMM_FP32, "fp32"), (sagnn.GEMM_BF16, "bf16")):
+        fused = lambda: sagnn.gcn_layer_fwd(rp, plan.colidx_compact, va, Hn, W, act=sagnn.ACT_RELU, prec=prec,
+                                            want_t=False, want_z=False, out=(None, None, Ho))
+        try:
+            fused_ms = timed(fused)
+        except sagnn.SagnnError:
+            continue
+        gemm_p = timed(lambda: sagnn.dense_gemm_act(T, W, prec=prec, act=sagnn.ACT_RELU, want_z=False,
+                                                    want_act=True, out=(None, Ho)))
+        out["fused_layer"] = {"gemm_operands": pname, "fused_ms": round(fused_ms, 4),
+                              "split_ms": round(spmm_ms + gemm_p, 4), "split_gemm_ms": round(gemm_p, 4),
+                              "reps": reps,
+                              "note": "fused: row-range schedule, work balanced per tile of rows, T never in HBM; "
+                                      "split: prepared slab-sweep / nonzero-splitting product + dense transform"}
+        break
     if out["roofline"]["traffic"]:
         # rate at which the measured (counter) traffic of the profiled run moves at this run's time
         out["roofline"]["traffic_GBps"] = round(out["roofline"]["traffic"] / (spmm_ms * 1e-3) / 1e9, 1)

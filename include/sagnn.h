@@ -297,15 +297,33 @@ int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw,
  *   Z = T * W            (m x f_out, W is f_in x f_out row-major, ld = f_out)
  *   Hout = sigma(Z)      sigma = ReLU or identity
  *
- * A, H as in spmm_csr_tallskinny (H is k x f_in, ldh).  d_T is required; d_Z or d_Hout may
- * be NULL (not stored).  d_T, d_Z, d_Hout are dense with ld = f_in / f_out / f_out.
+ * A, H as in spmm_csr_tallskinny (H is k x f_in, ldh).  d_Z or d_Hout may be NULL (not
+ * stored).  d_T, d_Z, d_Hout are dense with ld = f_in / f_out / f_out.
  * d_ws: SpMM workspace prepared for (rowptr, m, nnz, f_in), or NULL.
+ *
+ * Two forms.  With d_T != NULL the layer is the sparse product (spmm_csr_tallskinny with its
+ * prepared schedule) followed by the dense transform, two kernels with T in HBM between them.
+ * With d_T == NULL (inference, or a backward pass that recomputes T) the layer runs as ONE
+ * kernel, gcn_layer_fwd_fused below: a workgroup computes whole rows of T for a tile of rows,
+ * keeps the tile in LDS beside W and multiplies it on the matrix cores, so T never reaches
+ * HBM (2 m f_in 4 bytes less traffic) and d_ws is not used.  The fused form exists for
+ * f_in in {64, 128, 256}, f_out <= 256 with W and one tile fitting the LDS (fp32: f_in * f_out
+ * <= 128 * 256; bfloat16: up to 256 x 256); other shapes return SAGNN_EINVAL when d_T is NULL.
+ * It balances work per tile of rows, not per entry: on matrices with rows of similar length it
+ * is the cheaper form, on power-law matrices the two-kernel form with the slab-sweep schedule
+ * is faster (rows longer than 2048 entries are shared by a workgroup's wavefronts, so they
+ * are correct but slow).  Same rounding bound as the two-kernel form.
+ * gcn_layer_fwd_fused may also be called directly, with d_T non-NULL to get T as a by-product.
  */
 int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                   int64_t m, int64_t k, int64_t nnz, const float* d_H, int64_t ldh,
                   int32_t f_in, const float* d_W, int32_t f_out, int32_t act,
                   int32_t gemm_prec, float* d_T, float* d_Z, float* d_Hout, void* d_ws,
                   size_t ws_bytes, void* stream);
+int gcn_layer_fwd_fused(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
+                        int64_t m, int64_t k, int64_t nnz, const float* d_H, int64_t ldh,
+                        int32_t f_in, const float* d_W, int32_t f_out, int32_t act,
+                        int32_t gemm_prec, float* d_T, float* d_Z, float* d_Hout, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Step 5: one GCN layer backward (Sec. 2.1 backward equations; Sec. 4.1 paragraphs on the

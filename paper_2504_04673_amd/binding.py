@@ -19,7 +19,7 @@ EXPORTS = [
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_plan_needed_rows_noalloc", "spmm_pack_rows",
     "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_opt", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
     "spmm_csr_release", "spmm_csr_tallskinny",
-    "dense_gemm_act", "gcn_layer_fwd", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
+    "dense_gemm_act", "gcn_layer_fwd", "gcn_layer_fwd_fused", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
     "spmm_transpose_workspace_bytes", "spmm_csr_transpose",
     "spmm_permute_workspace_bytes", "spmm_perm_from_labels", "spmm_csr_permute_symmetric",
@@ -129,6 +129,8 @@ def lib():
                                      vp, i64, vp]
         L.gcn_layer_fwd.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i32, i32, i32, vp,
                                     vp, vp, vp, sz, vp]
+        L.gcn_layer_fwd_fused.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i32, i32, i32, vp,
+                                          vp, vp, vp]
         L.gcn_bwd_workspace_bytes.argtypes = [i64, i32, i32, psz]
         L.gcn_layer_bwd.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i32, vp, vp, i32, vp, vp, vp,
                                     vp, sz, vp, sz, vp]
@@ -398,8 +400,10 @@ def dense_gemm_act(X, W, transW=False, prec=GEMM_FP32, act=ACT_IDENTITY, mask=No
 
 
 def gcn_layer_fwd(rowptr, colidx, val, H, W, act=ACT_RELU, prec=GEMM_FP32, ws: SpmmWorkspace = None,
-                  want_z=True, want_h=True, out=None):
-    """T = A H, Z = T W, Hout = sigma(Z).  Returns (T, Z, Hout)."""
+                  want_z=True, want_h=True, out=None, want_t=True, fused=False):
+    """T = A H, Z = T W, Hout = sigma(Z).  Returns (T, Z, Hout).  want_t=False: T is not stored
+    (returned as None) and the layer runs as one fused kernel; fused=True calls that kernel
+    directly and still returns T."""
     rowptr = _dev(rowptr, torch.int32, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     val = _dev(val, torch.float32, "val")
@@ -409,11 +413,16 @@ def gcn_layer_fwd(rowptr, colidx, val, H, W, act=ACT_RELU, prec=GEMM_FP32, ws: S
     k, f_in = H.shape
     f_out = W.shape[1]
     if out is None:
-        T = torch.empty((m, f_in), dtype=torch.float32, device=H.device)
+        T = torch.empty((m, f_in), dtype=torch.float32, device=H.device) if want_t else None
         Z = torch.empty((m, f_out), dtype=torch.float32, device=H.device) if want_z else None
         Ho = torch.empty((m, f_out), dtype=torch.float32, device=H.device) if want_h else None
     else:
         T, Z, Ho = out
+    if fused:
+        rc = lib().gcn_layer_fwd_fused(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(H), _ld(H),
+                                       f_in, _ptr(W), f_out, act, prec, _ptr(T), _ptr(Z), _ptr(Ho), _stream())
+        _check(rc, "gcn_layer_fwd_fused")
+        return T, Z, Ho
     rc = lib().gcn_layer_fwd(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, _ptr(H), _ld(H),
                              f_in, _ptr(W), f_out, act, prec, _ptr(T), _ptr(Z), _ptr(Ho),
                              _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0, _stream())

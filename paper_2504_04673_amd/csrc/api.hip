@@ -60,13 +60,25 @@ SAGNN_EXPORT int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx,
                                float* d_Z, float* d_Hout, void* d_ws, size_t ws_bytes,
                                void* stream) {
   using namespace sagnn;
-  if (!d_T || (!d_Z && !d_Hout) || !d_W) return SAGNN_EINVAL;
+  if ((!d_Z && !d_Hout) || !d_W) return SAGNN_EINVAL;
   hipStream_t s = (hipStream_t)stream;
+  if (!d_T)   // the caller does not want T: one kernel, the tile of T never leaves the chip
+    return launch_fused_layer(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_W, f_out, act,
+                              gemm_prec, nullptr, d_Z, d_Hout, s);
   int rc = launch_spmm(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_T, f_in, 0, d_ws,
                        ws_bytes, s);
   if (rc != SAGNN_OK) return rc;
   return launch_gemm(d_T, f_in, d_W, f_out, 0, m, f_in, f_out, gemm_prec, act, nullptr, 0, d_Z,
                      f_out, d_Hout, f_out, s);
+}
+
+SAGNN_EXPORT int gcn_layer_fwd_fused(const int32_t* d_rowptr, const int32_t* d_colidx,
+                                     const float* d_val, int64_t m, int64_t k, int64_t nnz,
+                                     const float* d_H, int64_t ldh, int32_t f_in, const float* d_W,
+                                     int32_t f_out, int32_t act, int32_t gemm_prec, float* d_T,
+                                     float* d_Z, float* d_Hout, void* stream) {
+  return sagnn::launch_fused_layer(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_W, f_out,
+                                   act, gemm_prec, d_T, d_Z, d_Hout, (hipStream_t)stream);
 }
 
 SAGNN_EXPORT int gcn_bwd_workspace_bytes(int64_t m, int32_t f_in, int32_t f_out, size_t* bytes) {

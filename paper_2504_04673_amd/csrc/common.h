@@ -175,6 +175,13 @@ int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_
                 const float* mask, int64_t ldmask, float* Z, int64_t ldz, float* A, int64_t lda,
                 hipStream_t s);
 
+// fused layer forward (fused.hip): T = A H stays on the chip; T may be NULL
+bool fused_layer_supported(int32_t f_in, int32_t f_out, int32_t prec);
+int launch_fused_layer(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
+                       int64_t k, int64_t nnz, const float* H, int64_t ldh, int32_t f_in,
+                       const float* W, int32_t f_out, int32_t act, int32_t prec, float* T, float* Z,
+                       float* Hout, hipStream_t s);
+
 int launch_gemm_tn(const float* X, int64_t ldx, const float* S, int64_t lds_, int64_t m,
                    int32_t fi, int32_t fo, int32_t prec, float* Y, void* yws, size_t yws_bytes,
                    hipStream_t s);

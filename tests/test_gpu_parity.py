@@ -693,3 +693,64 @@ def test_spmm_sweep_interval_barrier_gives_up_and_still_computes(f, force_sweep,
     plain, ws = run()
     assert ws.info()["intervals"] == 1
     assert_close(plain, ref, zabs, RTOL_SPMM, "without intervals")
+
+
+# ------------------------------------------------------------------------------------ fused layer
+
+@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 32), (1, 128, 100), (0, 128, 256),
+                                           (1, 64, 64), (1, 256, 36)])
+@pytest.mark.parametrize("graph", ["hubs_and_empty_rows", "sbm", "rmat"])
+def test_gcn_layer_fwd_fused(prec, fin, fout, graph, cfg1):
+    """The one-kernel layer (T = A H kept on the chip, then the dense transform on the matrix
+    cores) against the oracle's layer: without T (gcn_layer_fwd with d_T = NULL) and with T as a
+    by-product.  Rows longer than 2048 entries take the workgroup-shared path; m is not a
+    multiple of the tile height."""
+    rng = np.random.default_rng(fin + fout)
+    if graph == "hubs_and_empty_rows":
+        m, n = 4133, 9000
+        rowptr, colidx, val = random_csr(m, n, 20, rng, empty_frac=0.1,
+                                         hubs=[(5, 8000), (6, 2049), (7, 2048), (4132, 5000), (300, 300)], dup=True)
+    elif graph == "sbm":
+        g = synth.sbm_graph(6000, 16, 40, 2, 3)
+        rowptr, colidx, val, m, n = g.rowptr, g.colidx, g.val, g.m, g.n
+    else:
+        g = synth.rmat_graph(30_000, 1_500_000, 4)
+        rowptr, colidx, val, m, n = g.rowptr, g.colidx, g.val, g.m, g.n
+    H = synth.normal((n, fin), 1, synth.STREAM_H)
+    W = synth.normal((fin, fout), 1, synth.STREAM_W, scale=1 / np.sqrt(fin))
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1, bf16=bool(prec))
+    T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, want_t=False)
+    torch.cuda.synchronize()
+    assert T is None
+    assert_close(Z, o["Z"], o["Zabs"], rtol, "fused Z")
+    assert_close(Ho, o["H"], o["Zabs"], rtol, "fused H'")
+    assert torch.equal(Ho, torch.clamp_min(Z, 0))
+    T, Z2, _ = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_IDENTITY, prec=prec, fused=True,
+                                   want_h=False)
+    torch.cuda.synchronize()
+    assert_close(T, o["T"], o["Tabs"], RTOL_SPMM, "fused T")
+    assert torch.equal(Z2, Z)
+    zt, ztabs = oracle.gemm(T.cpu().numpy(), W, bf16=bool(prec), want_abs=True)
+    assert_close(Z, zt, ztabs, rtol, "fused Z vs oracle GEMM of the kernel's own T")
+
+
+def test_gcn_layer_fwd_fused_strided_h_and_unsupported_shapes():
+    rng = np.random.default_rng(2)
+    m, n, f = 1000, 2000, 128
+    rowptr, colidx, val = random_csr(m, n, 10, rng)
+    H = synth.normal((n, f), 1, synth.STREAM_H)
+    W = synth.normal((f, f), 1, synth.STREAM_W, scale=1 / np.sqrt(f))
+    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1)
+    wide = torch.full((n, f + 12), 9.0, device="cuda")
+    wide[:, :f] = dev(H)
+    _, Z, _ = sagnn.gcn_layer_fwd(dev(rowptr), dev(colidx), dev(val), wide[:, :f], dev(W), want_t=False)
+    torch.cuda.synchronize()
+    assert_close(Z, o["Z"], o["Zabs"], RTOL_GEMM_FP32, "fused, ldh > f")
+    for fin, fout, prec in ((256, 256, 0), (16, 16, 0), (192, 64, 1)):
+        Hs = dev(synth.normal((n, fin), 1, synth.STREAM_H))
+        Ws = dev(synth.normal((fin, fout), 1, synth.STREAM_W))
+        with pytest.raises(sagnn.SagnnError) as ei:
+            sagnn.gcn_layer_fwd(dev(rowptr), dev(colidx), dev(val), Hs, Ws, prec=prec, want_t=False)
+        assert ei.value.code == -1
