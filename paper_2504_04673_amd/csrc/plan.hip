@@ -414,6 +414,27 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(const uint64_t* __restri
   }
 }
 
+// Sparse membership (a few needed columns per word, e.g. a rank's share of a huge graph): one
+// thread per word walks the set bits; a wavefront per word would write a handful of ids with
+// 64 lanes.
+__global__ __launch_bounds__(kThreads) void emit_sparse_kernel(const uint64_t* __restrict__ bm,
+                                                               const int32_t* __restrict__ prefix,
+                                                               int64_t W, int64_t n,
+                                                               int32_t* __restrict__ needed) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x; w < W; w += stride) {
+    uint64_t word = bm[w];
+    if (word == 0ull) continue;
+    int64_t pos = prefix[w];
+    const int64_t base = w * 64;
+    while (word) {
+      const int b = __builtin_ctzll(word);
+      word &= word - 1ull;
+      if (base + b < n) needed[pos++] = (int32_t)(base + b);
+    }
+  }
+}
+
 __device__ __forceinline__ int32_t remap_one(int32_t c, int64_t n, const uint4* __restrict__ rank16) {
   if (c < 0 || c >= n) return -1;
   const uint4 t = rank16[c >> 6];
@@ -567,8 +588,12 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
   if (N > needed_cap) return SAGNN_ECAPACITY;
 
   if (N > 0) {
-    hipLaunchKernelGGL(emit_kernel, dim3(grid_for(w.W * 64)), dim3(kThreads), 0, s, w.bitmap,
-                       w.prefix, w.W, n, d_needed);
+    if (N * 8 < n)   // fewer than 8 needed columns per word on average
+      hipLaunchKernelGGL(emit_sparse_kernel, dim3(grid_for(w.W)), dim3(kThreads), 0, s, w.bitmap, w.prefix,
+                         w.W, n, d_needed);
+    else
+      hipLaunchKernelGGL(emit_kernel, dim3(grid_for(w.W * 64)), dim3(kThreads), 0, s, w.bitmap,
+                         w.prefix, w.W, n, d_needed);
     SAGNN_LAUNCH_CHECK();
   }
   if (d_colidx_compact && nnz > 0) {

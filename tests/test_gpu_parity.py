@@ -103,7 +103,8 @@ def test_plan_cfg1_all_blocks(cfg1):
 
 @pytest.mark.parametrize("m,n,nb,avg,seed", [(1, 1, 1, 1, 0), (50, 63, 3, 2, 1), (64, 64, 1, 3, 2),
                                              (1000, 65, 5, 1, 3), (3000, 100_003, 16, 9, 4),
-                                             (20000, 5_000_001, 7, 4, 5), (10, 1_000_000, 64, 0.3, 6)])
+                                             (20000, 5_000_001, 7, 4, 5), (10, 1_000_000, 64, 0.3, 6),
+                                             (30000, 20_000_003, 9, 6, 7), (5, 33_554_432, 3, 2, 8)])
 def test_plan_random_ragged(m, n, nb, avg, seed):
     rng = np.random.default_rng(seed)
     rowptr, colidx, _ = random_csr(m, n, avg, rng, dup=True)
