@@ -30,6 +30,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kCoopRow = 2048;   // rows longer than this are shared by the whole workgroup
 constexpr int kRunBlock = 128;   // entries per first-level sum
+constexpr int kCoopWaves = 8;    // wavefronts that share a long row (one partial row in LDS each)
 
 struct FusedArgs {
   const int32_t* rowptr; const int32_t* colidx; const float* val;
@@ -82,7 +83,7 @@ __device__ __forceinline__ typename Vec<FPL>::T row_sum(const FusedArgs& g, cons
   return tot + acc;
 }
 
-// U: gathers a wavefront keeps in flight (16 where the LDS only leaves room for 8 wavefronts)
+// U: gathers a wavefront keeps in flight (16 where the LDS only leaves room for one row tile per pass)
 template <int FPL, bool BF16, bool BUF, int U>
 __global__ __launch_bounds__(1024) void gcn_fused_kernel(
     // the read-only arrays as separate __restrict__ parameters: that is what lets the compiler
@@ -97,12 +98,13 @@ __global__ __launch_bounds__(1024) void gcn_fused_kernel(
   const int nwaves = nthreads >> 6;
   const int NB = g.nct * 32;                  // padded output width
   const int kdim = g.f_in;                    // 64 * FPL
-  // LDS: W slab | tile [rt*32][ldt] | partial rows of a shared long row [nwaves][f_in] | list
+  // LDS: W slab | tile [rt*32][ldt] | partial rows of a shared long row [<= 8][f_in] | list
   const size_t w_bytes = (size_t)kdim * NB * (BF16 ? 2 : 4);
   char* tile_raw = smem + w_bytes;
   const size_t tile_bytes = (size_t)g.rt * 32 * g.ldt * (BF16 ? 2 : 4);
   float* coop = reinterpret_cast<float*>(tile_raw + tile_bytes);
-  int32_t* longlist = reinterpret_cast<int32_t*>(coop + (size_t)nwaves * kdim);   // [0] = count, then local rows
+  const int ncoop = nwaves < kCoopWaves ? nwaves : kCoopWaves;
+  int32_t* longlist = reinterpret_cast<int32_t*>(coop + (size_t)ncoop * kdim);   // [0] = count, then local rows
 
   for (int idx = tid; idx < kdim * NB; idx += nthreads) {
     const int k = idx / NB, n = idx - k * NB;
@@ -170,12 +172,14 @@ __global__ __launch_bounds__(1024) void gcn_fused_kernel(
       int32_t b = rowptr[row], e = rowptr[row + 1];
       b = b < 0 ? 0 : b;
       e = e > g.nnz ? (int32_t)g.nnz : e;
-      const vec part = row_sum<FPL, BUF, U>(g, colidx, val, H, rs, b, e, wave, nwaves, loff);
-      *reinterpret_cast<vec*>(coop + (size_t)wave * kdim + lane * FPL) = part;
+      if (wave < ncoop) {
+        const vec part = row_sum<FPL, BUF, U>(g, colidx, val, H, rs, b, e, wave, ncoop, loff);
+        *reinterpret_cast<vec*>(coop + (size_t)wave * kdim + lane * FPL) = part;
+      }
       __syncthreads();
       if (wave == 0) {
         vec t = 0.f;
-        for (int w2 = 0; w2 < nwaves; ++w2) t += *reinterpret_cast<const vec*>(coop + (size_t)w2 * kdim + lane * FPL);
+        for (int w2 = 0; w2 < ncoop; ++w2) t += *reinterpret_cast<const vec*>(coop + (size_t)w2 * kdim + lane * FPL);
         if (g.T) *reinterpret_cast<vec*>(reinterpret_cast<char*>(g.T + row * g.f_in) + loff) = t;
         store_tile_row(lr, t);
       }
@@ -237,17 +241,18 @@ bool fused_plan(int32_t f_in, int32_t f_out, int32_t prec, int* rt_out, int* wav
   const int ldt = f_in + (bf16 ? 8 : 4);
   const size_t esz = bf16 ? 2 : 4;
   const size_t w_bytes = (size_t)f_in * nct * 32 * esz;
-  auto waves_for = [&](int r) { int w = r * nct; return w > 16 ? 16 : (w < 4 ? 4 : w); };
+  // Row tiles per pass: as many as the LDS holds beside W (at most 4).  Wavefronts: 16 whenever
+  // they fit (phase 1 is a latency-bound gather: the more rows in flight per CU the better; in
+  // phase 2 the wavefronts beyond the number of output tiles of a pass simply have no tile).
   auto lds_for = [&](int r) {
-    return w_bytes + (size_t)r * 32 * ldt * esz + (size_t)waves_for(r) * f_in * 4 + 4 * (size_t)(r * 32 + 4);
+    return w_bytes + (size_t)r * 32 * ldt * esz + (size_t)kCoopWaves * f_in * 4 + 4 * (size_t)(r * 32 + 4);
   };
-  // as many row tiles per pass as the LDS holds beside W (at most 4), as many wavefronts as
-  // there are output tiles per pass (at most 16, at least 4)
   int rt = 4;
   while (rt > 1 && lds_for(rt) > 156u * 1024u) --rt;
   if (lds_for(rt) > 156u * 1024u) return false;
+  const int waves = 16;
   *rt_out = rt;
-  *waves_out = waves_for(rt);
+  *waves_out = waves;
   *lds_out = lds_for(rt);
   return true;
 }
@@ -299,7 +304,7 @@ int launch_fused_layer(const int32_t* rowptr, const int32_t* colidx, const float
 #define SAGNN_FUSED_U(FPL_, U_)                                                                          \
   (bf16 ? (buf ? go(gcn_fused_kernel<FPL_, true, true, U_>) : go(gcn_fused_kernel<FPL_, true, false, U_>)) \
         : (buf ? go(gcn_fused_kernel<FPL_, false, true, U_>) : go(gcn_fused_kernel<FPL_, false, false, U_>)))
-#define SAGNN_FUSED(FPL_) (waves <= 8 ? SAGNN_FUSED_U(FPL_, 16) : SAGNN_FUSED_U(FPL_, 8))
+#define SAGNN_FUSED(FPL_) (rt == 1 ? SAGNN_FUSED_U(FPL_, 16) : SAGNN_FUSED_U(FPL_, 8))
   if (f_in == 64) return SAGNN_FUSED(1);
   if (f_in == 128) return SAGNN_FUSED(2);
   return SAGNN_FUSED(4);
