@@ -179,8 +179,9 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  * slab-sweep schedule was chosen, see spmm_csr_schedule_info; exactly the prepared f if that
  * was 32 or 16); part of it is scratch for
  * partial row sums, so two calls that share a workspace must not overlap in time.
- * spmm_csr_prepare() synchronises the stream (it plans on the host from a copy of rowptr) and
- * the library remembers a small host descriptor per prepared workspace address; passing a
+ * spmm_csr_prepare() plans on the device (row classification, cutting of long rows, dealing of
+ * the pieces to wavefronts, layout of the re-ordered copy); the host reads a few totals and
+ * flags back, which synchronises the stream three or four times.  The library remembers a small host descriptor per prepared workspace address; passing a
  * workspace that was not prepared in this process returns SAGNN_EINVAL.  If the workspace
  * memory was overwritten after preparation, C is unspecified (the kernels check a generation
  * tag and exit), but nothing faults.

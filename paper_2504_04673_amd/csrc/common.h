@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "sagnn.h"
 
 #define SAGNN_EXPORT extern "C" __attribute__((visibility("default")))
@@ -50,6 +52,7 @@ constexpr int kSweepMinLong = 16;           // smallest degree a "long" row can 
 // part of B.  A wavefront's stream is padded to a whole batch at every interval boundary.
 constexpr int kSweepMaxIntervals = 64;
 constexpr int kSweepBarrierSlots = 65536;   // arrival counters (cohort x XCD x interval)
+constexpr int kSweepMaxWindows = 2048;      // dealing windows of a matrix (11 bits of a sort key)
 
 struct SpmmWsHeader {       // first 256 bytes of the SpMM workspace (device copy)
   uint32_t magic;
@@ -78,7 +81,7 @@ static_assert(sizeof(SpmmWsHeader) <= 256, "header must fit its slot");
 // Fixed layout (a function of m, k, nnz, f only; every array has its worst-case size):
 struct SpmmWsLayout {
   size_t header, chunk_row, flags, rowptr_s, rowmap_s, code, vals, piece_info, piece_target,
-      wave_base, wave_steps, sync_off, barrier, sched, multi_row, multi_first, partial, carry, total;
+      wave_base, wave_steps, sync_off, barrier, sched, multi_row, multi_first, partial, carry, plan, total;
   int64_t max_chunks, max_pieces, max_waves, max_multi_rows, max_multi_pieces, stream_cap;
 };
 
@@ -117,6 +120,9 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   L.multi_first = take(sizeof(int32_t) * (size_t)(L.max_multi_rows + 1));
   L.partial = take(sizeof(float) * (size_t)L.max_multi_pieces * (size_t)f);
   L.carry = take(sizeof(float) * (size_t)L.max_chunks * (size_t)f);
+  // planner: totals, per-window arrays, tile sums of the five row scans (2048 rows per tile)
+  L.plan = take(256 + (size_t)kSweepMaxWindows * 8 + 3 * 4 * (size_t)(kSweepMaxWindows + 64) +
+                5 * sizeof(int32_t) * (size_t)(ceil_div(m, 2048) + 2));
   L.total = off;
   return L;
 }
@@ -166,9 +172,45 @@ struct SweepPlanResult {
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
                   int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
                   const sagnn_spmm_options& opt, hipStream_t s, SweepPlanResult* out);
+// device side of the planner (sweep_plan.hip); the scratch arrays live in the stream arrays of the
+// workspace, which are written last
+struct SweepRowTotals {
+  int64_t pieces, short_rows, short_entries, multi_rows, multi_pieces;
+  int32_t min_long;
+  bool has_empty, bad;
+};
+bool sweep_plan_fits(const SpmmWsLayout& L);
+// classify rows, build the short-row CSR, the list of split rows and the piece records; one
+// stream synchronisation (a 128-byte copy)
+int sweep_plan_rows(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t opt_min_long, int32_t piece_max,
+                    char* ws, const SpmmWsLayout& L, hipStream_t s, SweepRowTotals* out);
+// entries of the pieces of every window (only needed with several windows; synchronises)
+int sweep_plan_window_entries(char* ws, const SpmmWsLayout& L, int64_t P, int64_t window, int32_t nwin,
+                              hipStream_t s, std::vector<int64_t>* entries);
+// sort the pieces and deal them to the streams: fills piece_info / piece_target; synchronises
+// (it looks at a flag every few batches to see whether pieces are left); flags[2] of the carry
+// area stays 1 if pieces were left over
+int sweep_plan_deal(char* ws, const SpmmWsLayout& L, int64_t P, int64_t window, const int32_t* h_win_unit0,
+                    int32_t nwin, int64_t n_waves4, int32_t R, int32_t SL, bool snake, hipStream_t s);
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
                  int32_t accumulate, int32_t f_total, hipStream_t s);
+
+// Stable least-significant-digit radix sort of (key, payload) pairs on the device (stages.hip),
+// 8 bits per pass over key bits [0, bits).  With pay_in == NULL the payload is the index of the
+// pair.  The sorted pairs end up in w.keys[*result], w.pay[*result].  A workspace carved for n
+// pairs serves any smaller count.
+struct RadixWs {
+  uint32_t *keys[2], *pay[2];
+  int32_t* counts;     // [256][ntiles + 1]
+  int32_t* tilesum;    // [256][nscan + 1]
+  int64_t* digit_off;  // [257]
+  int64_t ntiles, nscan;
+  size_t bytes;
+};
+RadixWs carve_radix(void* base, int64_t n);   // base == NULL: sizes only
+int radix_sort_pairs(const uint32_t* keys_in, const uint32_t* pay_in, int64_t n, int bits, const RadixWs& w,
+                     hipStream_t s, int* result);
 
 int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_t transW,
                 int64_t m, int32_t kdim, int32_t nout, int32_t prec, int32_t act,

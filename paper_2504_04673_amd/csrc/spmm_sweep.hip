@@ -297,10 +297,6 @@ inline size_t sweep_build_lds_bytes(int64_t S) {
   return sizeof(int32_t) * (size_t)(kSweepSlots * (S + 1) + 3 * S * kSweepSlots);
 }
 
-__global__ void sweep_zero_flags_kernel(int32_t* __restrict__ flags) {
-  if (threadIdx.x < 4) flags[threadIdx.x] = 0;
-}
-
 __global__ __launch_bounds__(256) void sweep_zero_gap_kernel(uint32_t* __restrict__ code,
                                                             float* __restrict__ vals, int32_t n) {
   for (int i = threadIdx.x; i < n; i += 256) {
@@ -757,19 +753,16 @@ __global__ __launch_bounds__(256) void sweep_combine_kernel(
   }
 }
 
-struct Piece {
-  int32_t size, row, j, p;
-};
-
 std::atomic<uint64_t> g_generation{1};
 
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
-// host side of the preparation: classify rows, cut long rows into pieces, deal pieces to the
-// streams of the wavefronts (largest first, each to the shortest stream so far, so the streams
-// have nearly equal lengths), build the compacted short-row CSR.  The streams themselves are
-// laid out by the three device passes above.
+// host side of the preparation: the launch shape (lane groups, slots, windows, wavefronts per
+// window) is decided here from a handful of totals; classifying rows, cutting long rows into
+// pieces, dealing the pieces to the streams of the wavefronts (largest first, each to the
+// shortest stream so far, so the streams have nearly equal lengths) and the compacted short-row
+// CSR are device work (sweep_plan.hip), as is the layout of the streams (the passes above).
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,
                   int64_t k, int64_t nnz, int32_t f, char* ws, const SpmmWsLayout& L,
                   const sagnn_spmm_options& opt, hipStream_t s, SweepPlanResult* out) {
@@ -780,26 +773,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // worth it only if B is much larger than an L2 (the long-row share is checked below)
   if (force != 1 && (nnz < (1 << 20) || b_bytes <= (8ll << 20))) return SAGNN_OK;
 
-  std::vector<int32_t> rp((size_t)m + 1);
-  SAGNN_HIP(hipMemcpyAsync(rp.data(), d_rowptr, sizeof(int32_t) * (size_t)(m + 1),
-                           hipMemcpyDeviceToHost, s));
-  SAGNN_HIP(hipStreamSynchronize(s));
-  if (rp[0] != 0 || rp[m] != nnz) return SAGNN_OK;  // inconsistent: keep the plain schedule
-
-  // Rows with at least min_long entries go through the sweep.  64 suits power-law graphs (the
-  // many rows below it hold few entries and would only add accumulator slots); when the rows of
-  // 16..63 entries hold a large share of the matrix (near-regular graphs, e.g. a partitioned
-  // graph's row block) the threshold drops so that they are swept too.
-  int min_long = opt.min_long;       // > 0: forced; < 0: used where the rule below would pick 64
-  if (min_long <= 0) {
-    int64_t mid = 0;
-    for (int64_t r = 0; r < m; ++r) {
-      const int64_t d = (int64_t)rp[r + 1] - rp[r];
-      if (d >= kSweepMinLong && d < 64) mid += d;
-    }
-    min_long = (mid * 4 >= nnz) ? kSweepMinLong : (min_long < 0 ? -min_long : 64);
-  }
-  if (min_long < kSweepMinLong) min_long = kSweepMinLong;
+  if (!sweep_plan_fits(L)) return SAGNN_OK;
   int piece_max = opt.piece > 0 ? opt.piece : 4096;
   if (piece_max < 1024) piece_max = 1024;
   if (piece_max > 32768) piece_max = 32768;
@@ -808,6 +782,19 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   if (S < 8) S = 8;
   if (S > kSweepMaxSlabs) S = kSweepMaxSlabs;
   const int64_t width = ceil_div(k, S);
+
+  // Row classification, the short-row CSR, the list of split rows and one record per piece are
+  // made on the device (the long-row threshold is chosen there from the degree distribution);
+  // the host gets the totals.
+  SweepRowTotals tot{};
+  {
+    const int rc = sweep_plan_rows(d_rowptr, m, nnz, opt.min_long, piece_max, ws, L, s, &tot);
+    if (rc != SAGNN_OK) return rc;
+  }
+  if (tot.bad) return SAGNN_OK;   // not a CSR row pointer for this nnz: keep the plain schedule
+  const int64_t P = tot.pieces, short_rows = tot.short_rows, short_entries = tot.short_entries;
+  const int64_t long_entries = nnz - short_entries;
+  const bool has_empty = tot.has_empty;
 
   // Lane groups: at f = 128 half a wavefront, at f = 64 a quarter, moves a whole row of B with
   // 16 bytes per lane, so one load instruction serves 2 / 4 entries (the vector-memory issue
@@ -820,34 +807,14 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // grouped form, 8 / 16 rows per load.
   int64_t R = f == 128 ? 2 : (f == 64 ? 4 : (f == 32 ? 8 : (f == 16 ? 16 : 1)));
   if (opt.groups == 1 && f >= 64) R = 1;
-  std::vector<Piece> pieces;
-  int64_t long_entries = 0, short_rows = 0, short_entries = 0;
-  bool has_empty = false;
-  for (int64_t r = 0; r < m; ++r) {
-    const int64_t d = (int64_t)rp[r + 1] - rp[r];
-    if (d < 0) return SAGNN_OK;
-    if (d == 0) { has_empty = true; continue; }
-    if (d >= min_long) {
-      const int32_t p = (int32_t)ceil_div(d, piece_max);
-      if (p > 0x7FFF) return SAGNN_OK;
-      for (int32_t j = 0; j < p; ++j)
-        pieces.push_back({(int32_t)((d - j + p - 1) / p), (int32_t)r, j, p});
-      long_entries += d;
-    } else {
-      ++short_rows;
-      short_entries += d;
-    }
-  }
   if (force != 1 && long_entries * 10 < nnz * 3) return SAGNN_OK;   // < 30 % of the entries
   if (opt.groups != 2 && long_entries < 8 * k) {
     if (f < 64) return SAGNN_OK;   // no one-row-per-instruction form below 64: plain schedule
     R = 1;
   }
-  if (pieces.empty() || (int64_t)pieces.size() > L.max_pieces) return SAGNN_OK;
+  if (P <= 0 || P > L.max_pieces) return SAGNN_OK;
+  if (tot.multi_rows > L.max_multi_rows || tot.multi_pieces > L.max_multi_pieces) return SAGNN_OK;
 
-  std::vector<char> is_long((size_t)m, 0);
-  for (const Piece& pc : pieces) is_long[(size_t)pc.row] = 1;
-  const int64_t P = (int64_t)pieces.size();
   // Accumulator rows per wavefront.  A launch of width 128 with 16 rows per wavefront needs
   // 32768 bytes of LDS per workgroup, of which a CU holds four, not five (measured; the LDS
   // is handed out in units that make 5 x 32768 overshoot 160 KB).  14 rows (lane groups, 7 each)
@@ -886,6 +853,9 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     const int pct = opt.window_pct < 0 ? 0 : (opt.window_pct > 0 ? opt.window_pct : 400);
     window = pct <= 0 ? P : std::max<int64_t>(slots_used, window * pct / 100);
   }
+  if (window > P) window = P;
+  if (ceil_div(P, window) > kSweepMaxWindows) window = ceil_div(P, kSweepMaxWindows);
+  const int64_t nwin = ceil_div(P, window);
   // Wavefronts in all: whole generations of resident wavefronts when there is more than one
   // (the last generation then runs at the same occupancy, and under pacing at the same speed, as
   // the others), else as few as the slots allow.
@@ -894,94 +864,41 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     const int64_t up = round_up((size_t)n_target_waves, (size_t)resident_waves);
     if (up + 64 <= L.max_waves - 8) n_target_waves = up;
   }
-  std::vector<int64_t> win_wave0;                            // first wavefront of every window
+  std::vector<int64_t> win_entries(1, long_entries);
+  if (nwin > 1) {
+    const int rc = sweep_plan_window_entries(ws, L, P, window, (int32_t)nwin, s, &win_entries);
+    if (rc != SAGNN_OK) return rc;
+  }
+  // wavefronts of a window: as many as keep the stream length equal to the global average (equal
+  // lengths in ALL windows keep successive generations in step), but never fewer than the slots
+  // allow.  With R lane groups a wavefront carries R independent streams (group g owns slots
+  // g*SL ..); the unit of dealing is then the group stream.
+  const int64_t SL = slots / R;                 // slots per group stream
+  std::vector<int32_t> win_unit0((size_t)nwin + 1);   // first stream of every window
   int64_t NW = 0;
-  for (int64_t a = 0; a < P; a += window) {
-    const int64_t b = std::min(P, a + window);
-    std::sort(pieces.begin() + a, pieces.begin() + b, [](const Piece& x, const Piece& y) {
-      if (x.size != y.size) return x.size > y.size;
-      if (x.row != y.row) return x.row < y.row;
-      return x.j < y.j;
-    });
-    win_wave0.push_back(NW);
-    // wavefronts of this window: as many as keep the stream length equal to the global average
-    // (equal lengths in ALL windows keep successive generations in step), but never fewer than
-    // the slots allow
-    int64_t entries_w = 0;
-    for (int64_t t = a; t < b; ++t) entries_w += pieces[(size_t)t].size;
+  for (int64_t w = 0; w < nwin; ++w) {
+    const int64_t a = w * window, b = std::min(P, a + window);
     const double target_len = (double)long_entries / (double)n_target_waves;
-    int64_t nw = (int64_t)((double)entries_w / target_len + 0.5);
+    int64_t nw = (int64_t)((double)win_entries[(size_t)w] / target_len + 0.5);
     nw = std::max(nw, ceil_div(b - a, slots));
     nw = std::max<int64_t>(nw, 1);
     nw = std::min(nw, b - a);
+    win_unit0[(size_t)w] = (int32_t)(NW * R);
     NW += nw;
   }
-  win_wave0.push_back(NW);
+  win_unit0[(size_t)nwin] = (int32_t)(NW * R);
   // whole workgroups of four wavefronts (the last ones may own no piece): the kernels' workgroup
   // barriers then never meet a wavefront that has left
   const int64_t NW4 = (NW + 3) / 4 * 4;
   if (NW4 > L.max_waves - 1) return SAGNN_OK;   // cannot happen with the bounds above; plain schedule
-  std::vector<int32_t> info((size_t)NW4 * kSweepSlots * 2, -1), target((size_t)NW4 * kSweepSlots, INT32_MIN);
-  // multi-piece rows: partial slots in row order
-  std::vector<int32_t> multi_row, multi_first;
-  {
-    std::vector<std::pair<int32_t, int32_t>> mr;  // (row, p)
-    for (const Piece& pc : pieces)
-      if (pc.p > 1 && pc.j == 0) mr.push_back({pc.row, pc.p});
-    std::sort(mr.begin(), mr.end());
-    multi_first.push_back(0);
-    for (auto& e : mr) {
-      multi_row.push_back(e.first);
-      multi_first.push_back(multi_first.back() + e.second);
-    }
-  }
-  if ((int64_t)multi_row.size() > L.max_multi_rows || (int64_t)multi_first.back() > L.max_multi_pieces)
-    return SAGNN_OK;
   // Inside a window: largest piece first, each to the stream that is shortest so far and still
-  // has a free slot (ties: lowest index).  Streams come out equal to within a piece of the
-  // smallest size class, which keeps the wavefronts in step from slab to slab.  With R lane
-  // groups a wavefront carries R independent streams (group g owns slots g*16/R ..); the unit of
-  // dealing is then the group stream.
-  const int64_t SL = slots / R;                 // slots per group stream
-  std::vector<int32_t> used((size_t)NW * R, 0);
-  std::vector<int64_t> uload((size_t)NW * R, 0);
-  using Load = std::pair<int64_t, int64_t>;   // (stream length, unit = wavefront * R + group)
-  std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
-  int64_t cur_win = -1;
-  const bool lpt = R > 1 || opt.snake == 0;
-  for (int64_t t = 0; t < P; ++t) {
-    const int64_t win = t / window, tw = t - win * window;
-    const int64_t nw = win_wave0[(size_t)win + 1] - win_wave0[(size_t)win];
-    int64_t wv, slot;
-    if (lpt) {
-      if (win != cur_win) {
-        cur_win = win;
-        heap = decltype(heap)();
-        for (int64_t u = 0; u < nw * R; ++u) heap.push({0, win_wave0[(size_t)win] * R + u});
-      }
-      if (heap.empty()) return SAGNN_EINVAL;   // nw * kSweepSlots >= pieces of the window
-      const int64_t unit = heap.top().second;
-      heap.pop();
-      wv = unit / R;
-      slot = (unit % R) * SL + used[(size_t)unit]++;
-      uload[(size_t)unit] += pieces[(size_t)t].size;
-      if (used[(size_t)unit] < SL) heap.push({uload[(size_t)unit], unit});
-    } else {
-      slot = tw / nw;
-      const int64_t pos = tw % nw;
-      wv = win_wave0[(size_t)win] + ((slot & 1) ? nw - 1 - pos : pos);
-      uload[(size_t)wv] += pieces[(size_t)t].size;
-    }
-    const size_t g = (size_t)(wv * kSweepSlots + slot);
-    const Piece& pc = pieces[(size_t)t];
-    info[2 * g] = pc.row;
-    info[2 * g + 1] = (pc.j << 16) | pc.p;
-    if (pc.p == 1) {
-      target[g] = pc.row;
-    } else {
-      const size_t q = (size_t)(std::lower_bound(multi_row.begin(), multi_row.end(), pc.row) - multi_row.begin());
-      target[g] = -(multi_first[q] + pc.j) - 1;
-    }
+  // has a free slot.  Streams come out equal to within a piece of the smallest size class, which
+  // keeps the wavefronts in step from slab to slab.
+  {
+    const bool snake = R == 1 && opt.snake == 1;
+    const int rc = sweep_plan_deal(ws, L, P, window, win_unit0.data(), (int32_t)nwin, NW4, (int32_t)R,
+                                   (int32_t)SL, snake, s);
+    if (rc != SAGNN_OK) return rc;
   }
 
   // Interval barriers (lane-group kernels only): every `sync_slabs` slabs the workgroups of an
@@ -994,31 +911,8 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   int64_t NI = sync_slabs > 0 ? ceil_div(S, sync_slabs) : 1;
   if (NI <= 1) { NI = 1; sync_slabs = 0; }
 
-  // short-row CSR
-  std::vector<int32_t> rps((size_t)short_rows + 1), rmap((size_t)short_rows + 1);
-  {
-    int64_t i = 0, acc = 0;
-    for (int64_t r = 0; r < m; ++r) {
-      const int64_t d = (int64_t)rp[r + 1] - rp[r];
-      if (d > 0 && !is_long[(size_t)r]) { rps[(size_t)i] = (int32_t)acc; rmap[(size_t)i] = (int32_t)r; acc += d; ++i; }
-    }
-    rps[(size_t)short_rows] = (int32_t)acc;
-  }
-
-  auto up = [&](size_t off, const void* src, size_t bytes) {
-    return bytes ? hipMemcpyAsync(ws + off, src, bytes, hipMemcpyHostToDevice, s) : hipSuccess;
-  };
-  SAGNN_HIP(up(L.piece_info, info.data(), info.size() * 4));
-  SAGNN_HIP(up(L.piece_target, target.data(), target.size() * 4));
-  SAGNN_HIP(up(L.multi_row, multi_row.data(), multi_row.size() * 4));
-  SAGNN_HIP(up(L.multi_first, multi_first.data(), multi_first.size() * 4));
-  SAGNN_HIP(up(L.rowptr_s, rps.data(), rps.size() * 4));
-  SAGNN_HIP(up(L.rowmap_s, rmap.data(), rmap.size() * 4));
-
   // long rows must be column-sorted for the slab segmentation
-  int32_t* d_flag = reinterpret_cast<int32_t*>(ws + L.carry);  // scratch until the first product
-  hipLaunchKernelGGL(sweep_zero_flags_kernel, dim3(1), dim3(64), 0, s, d_flag);
-  SAGNN_LAUNCH_CHECK();
+  int32_t* d_flag = reinterpret_cast<int32_t*>(ws + L.carry);  // scratch until the first product; zeroed by the row pass
   hipLaunchKernelGGL(sweep_check_sorted_kernel, dim3((unsigned)ceil_div(NW4 * kSweepSlots, 4)), dim3(256),
                      0, s, d_rowptr, d_colidx, reinterpret_cast<const int32_t*>(ws + L.piece_info),
                      NW4 * kSweepSlots, (uint32_t)(k - 1), d_flag);
@@ -1043,11 +937,11 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     hipLaunchKernelGGL(sweep_scan_kernel, dim3(1), dim3(1024), 0, s, d_wave_steps, NW4, (int32_t)R,
                        d_wave_base, d_flag + 1);
     SAGNN_LAUNCH_CHECK();
-    int32_t h_flags[2] = {0, 0}, h_total = 0;
-    SAGNN_HIP(hipMemcpyAsync(h_flags, d_flag, 8, hipMemcpyDeviceToHost, s));
+    int32_t h_flags[4] = {0, 0, 0, 0}, h_total = 0;
+    SAGNN_HIP(hipMemcpyAsync(h_flags, d_flag, 16, hipMemcpyDeviceToHost, s));
     SAGNN_HIP(hipMemcpyAsync(&h_total, d_wave_base + NW4, 4, hipMemcpyDeviceToHost, s));
-    SAGNN_HIP(hipStreamSynchronize(s));    // also: the host vectors above have been consumed
-    if (h_flags[0]) return SAGNN_OK;       // unsorted long row or column out of range: plain schedule
+    SAGNN_HIP(hipStreamSynchronize(s));    // also: win_unit0 has been consumed
+    if (h_flags[0] || h_flags[2]) return SAGNN_OK;   // unsorted long row, column out of range, pieces left over: plain schedule
     stream_len = h_total;
     short_base = (int64_t)round_up((size_t)stream_len + 64, 256);
     const bool fits = !h_flags[1] && short_base + short_entries + kSpmmChunk <= L.stream_cap;
@@ -1089,7 +983,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   h.generation = g_generation.fetch_add(1);
   h.c_rows = short_rows; h.c_nnz = short_entries; h.c_nchunks = spmm_nchunks(short_entries);
   h.n_waves = NW4; h.n_long_entries = stream_len;   // padded length of the sweep streams
-  h.n_multi_rows = (int64_t)multi_row.size(); h.n_multi_pieces = multi_first.back();
+  h.n_multi_rows = tot.multi_rows; h.n_multi_pieces = tot.multi_pieces;
   h.n_slabs = (int32_t)S; h.slab_width = (int32_t)width;
   h.groups = (int32_t)R;
   h.n_intervals = (int32_t)NI; h.sync_slabs = (int32_t)sync_slabs;

@@ -196,6 +196,27 @@ __global__ __launch_bounds__(kThreads) void split_scan_tiles_kernel(int32_t* __r
   if (threadIdx.x == 0) ts[ntiles] = carry;
 }
 
+// The three scan steps in one launch for rows that fit one scan tile (m + 1 <= kScanTile): one
+// workgroup per block q scans its counts in place, total into element m and into ts[1] (ts laid
+// out with one tile per block, as split_offsets_kernel reads it).
+__global__ __launch_bounds__(kThreads) void split_scan_small_kernel(int32_t* __restrict__ rowptr_blk, int64_t m,
+                                                                    int32_t* __restrict__ tilesum) {
+  int32_t* __restrict__ a = rowptr_blk + (int64_t)blockIdx.x * (m + 1);
+  const int64_t i0 = (int64_t)threadIdx.x * 8;
+  int x[8], ex[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = (i0 + i < m) ? a[i0 + i] : 0;
+  const int total = tile_scan(x, ex);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    if (i0 + i < m) a[i0 + i] = ex[i];
+  if (threadIdx.x == 0) {
+    a[m] = total;
+    tilesum[(int64_t)blockIdx.x * 2] = 0;
+    tilesum[(int64_t)blockIdx.x * 2 + 1] = total;
+  }
+}
+
 // nnz_off[q] = sum of the totals of blocks < q (nb <= 256: one thread is enough)
 __global__ void split_offsets_kernel(const int32_t* __restrict__ tilesum, int64_t ntiles, int nb,
                                      int64_t* __restrict__ nnz_off) {
@@ -310,19 +331,19 @@ __global__ __launch_bounds__(kThreads) void transpose_gather_kernel(
   }
 }
 
-struct TransposeWs {
-  uint32_t *keys[2], *pay[2];
-  int32_t* counts;     // [256][ntiles + 1]
-  int32_t* tilesum;    // [256][nscan + 1]
-  int64_t* digit_off;  // [257]
-  int32_t* err;
-  int64_t ntiles, nscan;
-  size_t bytes;
-};
+unsigned wave_grid(int64_t rows) {
+  int64_t b = ceil_div(rows, kThreads / 64);
+  if (b > 256 * 64) b = 256 * 64;
+  if (b < 1) b = 1;
+  return (unsigned)b;
+}
 
-TransposeWs carve_transpose(void* base, int64_t nnz) {
-  TransposeWs w{};
-  w.ntiles = ceil_div(nnz > 0 ? nnz : 1, kSortTile);
+}  // namespace
+
+RadixWs carve_radix(void* base, int64_t n) {
+  RadixWs w{};
+  const int64_t cap = n > 0 ? n : 1;
+  w.ntiles = ceil_div(cap, kSortTile);
   w.nscan = ceil_div(w.ntiles + 1, kScanTile);
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -331,22 +352,67 @@ TransposeWs carve_transpose(void* base, int64_t nnz) {
     return p;
   };
   for (int i = 0; i < 2; ++i) {
-    w.keys[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)(nnz > 0 ? nnz : 1)));
-    w.pay[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)(nnz > 0 ? nnz : 1)));
+    w.keys[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)cap));
+    w.pay[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)cap));
   }
   w.counts = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(w.ntiles + 1)));
   w.tilesum = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(w.nscan + 1)));
   w.digit_off = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * 257));
-  w.err = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 4));
   w.bytes = off;
   return w;
 }
 
-unsigned wave_grid(int64_t rows) {
-  int64_t b = ceil_div(rows, kThreads / 64);
-  if (b > 256 * 64) b = 256 * 64;
-  if (b < 1) b = 1;
-  return (unsigned)b;
+int radix_sort_pairs(const uint32_t* keys_in, const uint32_t* pay_in, int64_t n, int bits, const RadixWs& w0,
+                     hipStream_t s, int* result) {
+  RadixWs w = w0;
+  w.ntiles = ceil_div(n > 0 ? n : 1, kSortTile);     // the workspace may have been carved for more
+  w.nscan = ceil_div(w.ntiles + 1, kScanTile);
+  if (w.ntiles > w0.ntiles || bits < 1 || bits > 32 || n < 0) return SAGNN_EINVAL;
+  const int passes = (bits + 7) / 8;
+  const dim3 sgrid((unsigned)w.nscan, 256u);
+  for (int pass = 0; pass < passes; ++pass) {
+    const uint32_t* kin = pass == 0 ? keys_in : w.keys[(pass - 1) & 1];
+    const uint32_t* pin = pass == 0 ? pay_in : w.pay[(pass - 1) & 1];
+    hipLaunchKernelGGL(radix_tile_kernel<false>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin, n,
+                       pass * 8, w.ntiles, w.counts, (const int64_t*)nullptr, (uint32_t*)nullptr,
+                       (uint32_t*)nullptr);
+    SAGNN_LAUNCH_CHECK();
+    if (w.ntiles + 1 <= kScanTile) {   // nscan == 1: the three scan steps as one launch
+      hipLaunchKernelGGL(split_scan_small_kernel, dim3(256), dim3(kThreads), 0, s, w.counts, w.ntiles, w.tilesum);
+      SAGNN_LAUNCH_CHECK();
+    } else {
+      hipLaunchKernelGGL(split_scan_kernel<0>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan, w.tilesum);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(split_scan_tiles_kernel, dim3(256), dim3(kThreads), 0, s, w.tilesum, w.nscan);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(split_scan_kernel<1>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan, w.tilesum);
+      SAGNN_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(64), 0, s, w.tilesum, w.nscan, 256, w.digit_off);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(radix_tile_kernel<true>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin, n,
+                       pass * 8, w.ntiles, w.counts, (const int64_t*)w.digit_off, w.keys[pass & 1],
+                       w.pay[pass & 1]);
+    SAGNN_LAUNCH_CHECK();
+  }
+  *result = (passes - 1) & 1;
+  return SAGNN_OK;
+}
+
+namespace {
+
+struct TransposeWs {
+  RadixWs r;
+  int32_t* err;
+  size_t bytes;
+};
+
+TransposeWs carve_transpose(void* base, int64_t nnz) {
+  TransposeWs w{};
+  w.r = carve_radix(base, nnz);
+  w.err = reinterpret_cast<int32_t*>(base ? static_cast<char*>(base) + w.r.bytes : nullptr);
+  w.bytes = w.r.bytes + 256;
+  return w;
 }
 
 }  // namespace
@@ -444,33 +510,11 @@ SAGNN_EXPORT int spmm_csr_transpose(const int32_t* d_rowptr, const int32_t* d_co
     SAGNN_LAUNCH_CHECK();
     int bits = 1;
     while (bits < 31 && (1ll << bits) < n) ++bits;
-    const int passes = (bits + 7) / 8;
-    const dim3 sgrid((unsigned)w.nscan, 256u);
-    for (int pass = 0; pass < passes; ++pass) {
-      const uint32_t* kin = pass == 0 ? reinterpret_cast<const uint32_t*>(d_colidx) : w.keys[(pass - 1) & 1];
-      const uint32_t* pin = pass == 0 ? nullptr : w.pay[(pass - 1) & 1];
-      uint32_t* kout = w.keys[pass & 1];
-      uint32_t* pout = w.pay[pass & 1];
-      hipLaunchKernelGGL(radix_tile_kernel<false>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin,
-                         nnz, pass * 8, w.ntiles, w.counts, (const int64_t*)nullptr, (uint32_t*)nullptr,
-                         (uint32_t*)nullptr);
-      SAGNN_LAUNCH_CHECK();
-      hipLaunchKernelGGL(split_scan_kernel<0>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan,
-                         w.tilesum);
-      SAGNN_LAUNCH_CHECK();
-      hipLaunchKernelGGL(split_scan_tiles_kernel, dim3(256), dim3(kThreads), 0, s, w.tilesum, w.nscan);
-      SAGNN_LAUNCH_CHECK();
-      hipLaunchKernelGGL(split_scan_kernel<1>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan,
-                         w.tilesum);
-      SAGNN_LAUNCH_CHECK();
-      hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(64), 0, s, w.tilesum, w.nscan, 256, w.digit_off);
-      SAGNN_LAUNCH_CHECK();
-      hipLaunchKernelGGL(radix_tile_kernel<true>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin,
-                         nnz, pass * 8, w.ntiles, w.counts, (const int64_t*)w.digit_off, kout, pout);
-      SAGNN_LAUNCH_CHECK();
-      sorted_keys = kout;
-      perm = pout;
-    }
+    int res = 0;
+    const int rc = radix_sort_pairs(reinterpret_cast<const uint32_t*>(d_colidx), nullptr, nnz, bits, w.r, s, &res);
+    if (rc != SAGNN_OK) return rc;
+    sorted_keys = w.r.keys[res];
+    perm = w.r.pay[res];
   }
   hipLaunchKernelGGL(transpose_rowptr_kernel, grid(n + 1), dim3(kThreads), 0, s, sorted_keys, nnz, n,
                      d_rowptr_t);
