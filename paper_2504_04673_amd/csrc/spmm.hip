@@ -22,7 +22,6 @@
 // remainder.
 #include <stdlib.h>
 
-#include <vector>
 
 #include "common.h"
 #include "rowload.h"
@@ -643,29 +642,17 @@ SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_
       // Rows without entries (e.g. one column block of a row block, Alg. 2) would make a chunk's
       // wavefront step over them one dependent load at a time.  Walk a row list without them
       // instead: the same compacted-CSR form the short rows of the sweep schedule use.
-      std::vector<int32_t> rp((size_t)m + 1);
-      SAGNN_HIP(hipMemcpyAsync(rp.data(), d_rowptr, sizeof(int32_t) * (size_t)(m + 1),
-                               hipMemcpyDeviceToHost, s));
-      SAGNN_HIP(hipStreamSynchronize(s));
-      std::vector<int32_t> rps, rmap;
-      bool ok = rp[0] == 0 && rp[(size_t)m] == nnz;
-      for (int64_t r = 0; ok && r < m; ++r) {
-        if (rp[(size_t)r + 1] < rp[(size_t)r]) ok = false;
-        else if (rp[(size_t)r + 1] > rp[(size_t)r]) { rps.push_back(rp[(size_t)r]); rmap.push_back((int32_t)r); }
-      }
-      if (ok) {   // (a malformed row pointer keeps the plain walk, which clamps everything)
-        rps.push_back((int32_t)nnz);
-        const int64_t rows_c = (int64_t)rmap.size();
-        SAGNN_HIP(hipMemcpyAsync(base + L.rowptr_s, rps.data(), sizeof(int32_t) * rps.size(),
-                                 hipMemcpyHostToDevice, s));
-        SAGNN_HIP(hipMemcpyAsync(base + L.rowmap_s, rmap.data(), sizeof(int32_t) * rmap.size(),
-                                 hipMemcpyHostToDevice, s));
-        rc = build_chunk_tables(reinterpret_cast<const int32_t*>(base + L.rowptr_s), rows_c, nnz,
+      // The row pass of the sweep planner with a threshold no row reaches makes exactly that list
+      // (every row with entries is "short").
+      SweepRowTotals t{};
+      rc = sweep_plan_rows(d_rowptr, m, nnz, 0x7FFFFFFF, 1024, base, L, s, &t);
+      if (rc != SAGNN_OK) return rc;
+      if (!t.bad && t.short_entries == nnz) {   // (a malformed row pointer keeps the plain walk, which clamps everything)
+        rc = build_chunk_tables(reinterpret_cast<const int32_t*>(base + L.rowptr_s), t.short_rows, nnz,
                                 reinterpret_cast<int32_t*>(base + L.chunk_row),
                                 reinterpret_cast<uint32_t*>(base + L.flags), d_has_empty, s);
         if (rc != SAGNN_OK) return rc;
-        SAGNN_HIP(hipStreamSynchronize(s));   // the host vectors are read by the copies above
-        h.c_rows = rows_c;
+        h.c_rows = t.short_rows;
       }
     }
   }

@@ -30,7 +30,6 @@
 #include <algorithm>
 #include <atomic>
 #include <functional>
-#include <queue>
 #include <vector>
 
 #include "common.h"
