@@ -260,7 +260,9 @@ int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx, con
  * interval (0 = one interval), [10] byte offset inside the workspace of a 32-bit flag that the
  * most recent product left at 1 if a barrier wait ran into its time limit (the product is
  * correct either way), [11] lane groups per wavefront, [12] pacing in picoseconds per stream
- * step (0 = none), [13] 1 if barriers are used, [14] accumulator rows per wavefront.
+ * step (0 = none), [13] 1 if barriers are used, [14] accumulator rows per wavefront,
+ * [15] steps (entries per lane group, padding included) of the longest wavefront stream; the
+ * average is [2] / ([1] * [11]).
  * SAGNN_EINVAL if the workspace is unknown. */
 int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info);
 /* Forget the host descriptor of a prepared workspace.  Call it before the workspace memory is

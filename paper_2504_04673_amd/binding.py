@@ -306,7 +306,7 @@ class SpmmWorkspace:
                "spmm_csr_schedule_info")
         keys = ("mode", "sweep_waves", "sweep_entries", "chunk_rows", "chunk_entries", "chunks",
                 "split_rows", "has_empty_rows", "intervals", "sync_slabs", "gave_up_offset", "groups",
-                "pace_ps_per_step", "barriers", "slots")
+                "pace_ps_per_step", "barriers", "slots", "longest_stream_steps")
         return dict(zip(keys, (int(x) for x in a)))
 
     def barriers_gave_up(self) -> bool:

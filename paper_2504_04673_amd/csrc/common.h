@@ -115,7 +115,7 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   L.wave_steps = take(sizeof(int32_t) * (size_t)(L.max_waves + 1));
   L.sync_off = take(sizeof(int32_t) * (size_t)L.max_waves * (kSweepMaxIntervals + 1));
   L.barrier = take(sizeof(uint32_t) * (size_t)(kSweepBarrierSlots + 64));
-  L.sched = take(sizeof(float) * (size_t)(kSweepMaxIntervals + 1));
+  L.sched = take(sizeof(float) * (size_t)(kSweepMaxIntervals + 2));
   L.multi_row = take(sizeof(int32_t) * (size_t)L.max_multi_rows);
   L.multi_first = take(sizeof(int32_t) * (size_t)(L.max_multi_rows + 1));
   L.partial = take(sizeof(float) * (size_t)L.max_multi_pieces * (size_t)f);
@@ -142,6 +142,7 @@ struct SpmmHostDesc {
   int32_t slots;
   int32_t barriers, pace_ps_per_step;
   float mean_steps;         // average stream steps per wavefront (the end of the pacing schedule)
+  float max_steps;          // steps of the longest stream
 };
 
 // Workgroups of `lds` bytes of LDS each that a CU really holds at once.  Measured on MI355X:
@@ -167,6 +168,7 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
 struct SweepPlanResult {
   bool use_sweep;
   float mean_steps;  // average stream steps per wavefront
+  float max_steps;   // steps of the longest stream
   SpmmWsHeader hdr;  // filled in for mode 1 (sweep part + short CSR sizes)
 };
 int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m,

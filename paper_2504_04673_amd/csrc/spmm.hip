@@ -670,6 +670,7 @@ SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_
   desc.slots = h.slots;
   desc.barriers = h.barriers; desc.pace_ps_per_step = h.pace_ps_per_step > 0 ? h.pace_ps_per_step : 0;
   desc.mean_steps = plan.mean_steps;
+  desc.max_steps = plan.max_steps;
   spmm_desc_put(d_ws, desc);
   return SAGNN_OK;
 }
@@ -834,7 +835,7 @@ SAGNN_EXPORT int spmm_csr_schedule_info(const void* d_ws, int64_t* h_info) {
   h_info[12] = d.mode == 1 ? d.pace_ps_per_step : 0;
   h_info[13] = d.mode == 1 ? d.barriers : 0;
   h_info[14] = d.mode == 1 ? d.slots : 0;
-  h_info[15] = 0;
+  h_info[15] = d.mode == 1 ? (int64_t)d.max_steps : 0;
   return SAGNN_OK;
 }
 

@@ -377,21 +377,31 @@ __device__ __forceinline__ void sweep_pace_until(uint64_t t0, float ticks) {
   }
 }
 
-// sched[i] = average over the wavefronts of the first step of interval i (i = 0..n_intervals)
+// sched[i] = average over the wavefronts of the first step of interval i (i = 0..n_intervals);
+// sched[n_intervals + 1] = the longest stream (steps), written by one more workgroup
 __global__ __launch_bounds__(256) void sweep_sched_kernel(const int32_t* __restrict__ sync_off,
                                                           int64_t n_waves, int32_t n_intervals,
                                                           float* __restrict__ sched) {
   __shared__ double red[256];
   const int i = blockIdx.x;
-  double sum = 0.0;
-  for (int64_t w = threadIdx.x; w < n_waves; w += 256) sum += (double)sync_off[w * (kSweepMaxIntervals + 1) + i];
-  red[threadIdx.x] = sum;
+  const bool want_max = i == n_intervals + 1;
+  const int col = want_max ? n_intervals : i;
+  double acc = 0.0;
+  for (int64_t w = threadIdx.x; w < n_waves; w += 256) {
+    const double v = (double)sync_off[w * (kSweepMaxIntervals + 1) + col];
+    acc = want_max ? (v > acc ? v : acc) : acc + v;
+  }
+  red[threadIdx.x] = acc;
   __syncthreads();
   for (int d = 128; d > 0; d >>= 1) {
-    if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+    if ((int)threadIdx.x < d) {
+      const double o = red[threadIdx.x + d];
+      red[threadIdx.x] = want_max ? (o > red[threadIdx.x] ? o : red[threadIdx.x]) : red[threadIdx.x] + o;
+    }
     __syncthreads();
   }
-  if (threadIdx.x == 0 && i <= n_intervals) sched[i] = n_waves > 0 ? (float)(red[0] / (double)n_waves) : 0.f;
+  if (threadIdx.x == 0 && i <= n_intervals + 1)
+    sched[i] = want_max ? (float)red[0] : (n_waves > 0 ? (float)(red[0] / (double)n_waves) : 0.f);
 }
 
 __global__ __launch_bounds__(256) void sweep_barrier_clear_kernel(uint32_t* __restrict__ counters, int n) {
@@ -950,11 +960,11 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
     sync_slabs = 0;
   }
 
-  hipLaunchKernelGGL(sweep_sched_kernel, dim3((unsigned)(NI + 1)), dim3(256), 0, s, d_sync_off, NW4, (int32_t)NI,
+  hipLaunchKernelGGL(sweep_sched_kernel, dim3((unsigned)(NI + 2)), dim3(256), 0, s, d_sync_off, NW4, (int32_t)NI,
                      reinterpret_cast<float*>(ws + L.sched));
   SAGNN_LAUNCH_CHECK();
-  float mean_steps = 0.f;
-  SAGNN_HIP(hipMemcpyAsync(&mean_steps, reinterpret_cast<float*>(ws + L.sched) + NI, 4, hipMemcpyDeviceToHost, s));
+  float steps[2] = {0.f, 0.f};   // mean, max over the wavefronts
+  SAGNN_HIP(hipMemcpyAsync(steps, reinterpret_cast<float*>(ws + L.sched) + NI, 8, hipMemcpyDeviceToHost, s));
   hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW4), dim3(kBuildThreads), build_lds, s, d_rowptr,
                      d_colidx, d_val, d_info, d_wave_base, d_sync_off, (int32_t)S, (int32_t)width, kmax,
                      (int32_t)R, (int32_t)SL, (int32_t)NI, (int32_t)sync_slabs, reinterpret_cast<uint32_t*>(ws + L.code),
@@ -991,8 +1001,9 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   h.slots = (int32_t)slots;
   h.barriers = opt.barriers == 1 && sync_slabs > 0 ? 1 : 0;
   h.pace_ps_per_step = sync_slabs > 0 && !h.barriers ? opt.pace_ps_per_step : 0;
-  SAGNN_HIP(hipStreamSynchronize(s));     // mean_steps has arrived
-  out->mean_steps = mean_steps;
+  SAGNN_HIP(hipStreamSynchronize(s));     // the step counts have arrived
+  out->mean_steps = steps[0];
+  out->max_steps = steps[1];
   out->use_sweep = true;
   return SAGNN_OK;
 }

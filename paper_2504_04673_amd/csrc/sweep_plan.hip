@@ -12,9 +12,10 @@
 //           accumulator slot.  The sequential rule is applied in batches: the next B pieces
 //           (B = half the window's streams) go, in order, to the B shortest streams with a free
 //           slot, found by sorting the streams by length.  On power-law graphs the stream
-//           lengths come out the same as with the piece-by-piece rule (the pieces of a batch have
-//           nearly equal sizes); whole rounds (B = all streams) do not: the first round hands out
-//           the large pieces and the later, much smaller ones cannot level them.
+//           lengths come out as with the piece-by-piece rule (the pieces of a batch have nearly
+//           equal sizes; where the slots per stream bind, the longest stream is about 1 % longer);
+//           whole rounds (B = all streams) do not: the first round hands out the large pieces and
+//           the later, much smaller ones cannot level them.
 // The host only sees five totals (one 128-byte copy) and, for matrices of several windows, the
 // entries per window.
 #include <algorithm>

@@ -271,6 +271,66 @@ def test_spmm_slab_sweep_planner_variants(variant, force_sweep, monkeypatch):
     assert_close(run_spmm(rowptr, colidx, val, B, True, C0=C0), ref2, zabs2, RTOL_SPMM, f"{variant} accumulate")
 
 
+@pytest.mark.parametrize("f", [128, 64, 256])
+def test_spmm_sweep_planner_balances_streams(f, monkeypatch):
+    """The device planner deals pieces longest-first to the shortest stream in batches; its longest
+    stream must be as short as the one of the sequential piece-by-piece rule, computed here with a
+    heap on the sizes the planner cuts (rows of >= 64 entries in pieces of <= 4096, strided).
+    Heavy-tailed degrees make the rule matter: dealing in whole rounds would leave the streams
+    that got the largest pieces first ~30 % longer than the average."""
+    import heapq
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "64")
+    monkeypatch.setenv("SAGNN_SWEEP_MIN_WAVES", "1")          # all 16 slots of a wavefront
+    rng = np.random.default_rng(9)
+    m, n = 30_000, 200_000
+    deg = np.minimum((64 / rng.random(m) ** 0.8).astype(np.int64), 30_000)   # heavy tail from 64 up
+    deg[rng.random(m) < 0.3] = 5                                              # some short rows
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    nnz = int(rowptr[-1])
+    colidx = np.empty(nnz, np.int32)
+    for r in range(m):
+        colidx[rowptr[r]:rowptr[r + 1]] = np.sort(rng.integers(0, n, size=deg[r]))
+    val = np.ones(nnz, np.float32)
+    ws = sagnn.spmm_csr_prepare(dev(rowptr), dev(colidx), dev(val), n, f)
+    info = ws.info()
+    assert info["mode"] == 1 and info["sweep_entries"] + info["chunk_entries"] == nnz
+    R = info["groups"]
+    sizes = []
+    for d in deg[deg >= 64]:
+        p = -(-int(d) // 4096)
+        sizes += [(int(d) - j + p - 1) // p for j in range(p)]
+    sizes.sort(reverse=True)
+    assert info["sweep_entries"] == sum(sizes)
+    n_waves = -(-len(sizes) // 16)        # as few wavefronts as the 16 slots allow (the launch rounds up to 4)
+    assert n_waves <= info["sweep_waves"] < n_waves + 4
+    units, per_unit = n_waves * R, 16 // R
+    heap = [(0, u) for u in range(units)]
+    used = [0] * units
+    longest = 0
+    for sz in sizes:
+        load, u = heapq.heappop(heap)
+        load += sz
+        used[u] += 1
+        longest = max(longest, load)
+        if used[u] < per_unit:
+            heapq.heappush(heap, (load, u))
+    # the library counts steps of wavefronts (the longer of a wavefront's group streams, in whole
+    # batches of 8): allow that rounding and 3 % on top
+    assert info["longest_stream_steps"] <= 1.03 * longest + 8, (info, longest, sum(sizes) / units)
+    # and the product is right
+    B = synth.normal((n, f), 5, synth.STREAM_H)
+    rows = rng.choice(m, size=200, replace=False)
+    got = sagnn.spmm_csr_tallskinny(dev(rowptr), dev(colidx), dev(val), dev(B), ws=ws)
+    torch.cuda.synchronize()
+    rows.sort()
+    sub_deg = deg[rows]
+    sub_rowptr = np.concatenate([[0], np.cumsum(sub_deg)]).astype(np.int32)
+    sub_idx = np.concatenate([np.arange(rowptr[r], rowptr[r + 1]) for r in rows])
+    ref, zabs = oracle.spmm(sub_rowptr, colidx[sub_idx], val[sub_idx], B, want_abs=True)
+    assert_close(got[torch.from_numpy(rows).cuda()], ref, zabs, RTOL_SPMM, f"balanced planner f={f}")
+
+
 def test_spmm_sweep_workspace_prepared_for_wider_f(force_sweep):
     """A workspace prepared for f = 128 (two lane groups) or 256 also serves narrower calls."""
     rng = np.random.default_rng(31)
