@@ -208,6 +208,7 @@ struct RadixWs {
   int32_t* tilesum;    // [256][nscan + 1]
   int64_t* digit_off;  // [257]
   int64_t ntiles, nscan;
+  int64_t cap;         // pairs the workspace was carved for
   size_t bytes;
 };
 RadixWs carve_radix(void* base, int64_t n);   // base == NULL: sizes only

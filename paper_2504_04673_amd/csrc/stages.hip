@@ -5,6 +5,8 @@
 // clarity: one wavefront per row, two passes (count, scatter) around a per-block scan of the
 // row counts.  Inside a row the stored order is kept, so splitting does not change the order
 // in which a block product sums its terms.
+#include <algorithm>
+
 #include "common.h"
 
 namespace sagnn {
@@ -217,14 +219,20 @@ __global__ __launch_bounds__(kThreads) void split_scan_small_kernel(int32_t* __r
   }
 }
 
-// nnz_off[q] = sum of the totals of blocks < q (nb <= 256: one thread is enough)
-__global__ void split_offsets_kernel(const int32_t* __restrict__ tilesum, int64_t ntiles, int nb,
-                                     int64_t* __restrict__ nnz_off) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+// nnz_off[q] = sum of the totals of blocks < q (nb <= 256; one workgroup of 256 threads: the
+// totals are fetched in parallel, the running sum is taken over LDS)
+__global__ __launch_bounds__(kThreads) void split_offsets_kernel(const int32_t* __restrict__ tilesum, int64_t ntiles,
+                                                                 int nb, int64_t* __restrict__ nnz_off) {
+  __shared__ int32_t tot[kMaxBlocks];
+  if (blockIdx.x != 0) return;
+  const int q = threadIdx.x;
+  tot[q] = q < nb ? tilesum[(int64_t)q * (ntiles + 1) + ntiles] : 0;
+  __syncthreads();
+  if (threadIdx.x != 0) return;
   int64_t run = 0;
-  for (int q = 0; q < nb; ++q) {
-    nnz_off[q] = run;
-    run += tilesum[(int64_t)q * (ntiles + 1) + ntiles];
+  for (int i = 0; i < nb; ++i) {
+    nnz_off[i] = run;
+    run += tot[i];
   }
   nnz_off[nb] = run;
 }
@@ -236,19 +244,20 @@ __global__ void split_offsets_kernel(const int32_t* __restrict__ tilesum, int64_
 // per (digit, tile), scan along the tiles of each digit, scatter with the tile-local stable
 // rank.  Stability makes the entries of a transposed row come out in the order of the rows
 // they came from (ascending), and keeps duplicates in their stored order.
-constexpr int kSortTile = 2048;
+constexpr int kSortTile = 2048;       // keys per wavefront and pass
+constexpr int kSortTileSmall = 256;   // for counts small enough that 2048-key tiles would leave the chip idle
 
 template <bool SCATTER>
 __global__ __launch_bounds__(kThreads) void radix_tile_kernel(
     const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ pay_in, int64_t nnz, int shift,
     int64_t ntiles, int32_t* __restrict__ counts, const int64_t* __restrict__ digit_off,
-    uint32_t* __restrict__ keys_out, uint32_t* __restrict__ pay_out) {
+    uint32_t* __restrict__ keys_out, uint32_t* __restrict__ pay_out, int tile) {
   const int lane = threadIdx.x & 63;
   const int64_t wave0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
   const int64_t nwaves = ((int64_t)gridDim.x * kThreads) >> 6;
   for (int64_t t = wave0; t < ntiles; t += nwaves) {
-    const int64_t b = t * kSortTile;
-    const int64_t e = b + kSortTile < nnz ? b + kSortTile : nnz;
+    const int64_t b = t * tile;
+    const int64_t e = b + tile < nnz ? b + tile : nnz;
     int32_t cnt[4] = {0, 0, 0, 0};
     for (int64_t base = b; base < e; base += 64) {
       const int64_t i = base + lane;
@@ -340,11 +349,20 @@ unsigned wave_grid(int64_t rows) {
 
 }  // namespace
 
+namespace {
+// keys per wavefront: small tiles while they still fit the one-launch scan (at most kScanTile - 1 tiles)
+inline int radix_tile(int64_t n) {
+  return n <= (int64_t)kSortTileSmall * (kScanTile - 1) ? kSortTileSmall : kSortTile;
+}
+}  // namespace
+
 RadixWs carve_radix(void* base, int64_t n) {
   RadixWs w{};
   const int64_t cap = n > 0 ? n : 1;
-  w.ntiles = ceil_div(cap, kSortTile);
+  w.ntiles = ceil_div(cap, radix_tile(cap));
   w.nscan = ceil_div(w.ntiles + 1, kScanTile);
+  // sized for the count that needs the most tiles among all counts <= cap
+  const int64_t max_tiles = std::max(w.ntiles, std::min<int64_t>(ceil_div(cap, kSortTileSmall), kScanTile - 1));
   size_t off = 0;
   auto take = [&](size_t bytes) {
     char* p = base ? static_cast<char*>(base) + off : nullptr;
@@ -355,9 +373,10 @@ RadixWs carve_radix(void* base, int64_t n) {
     w.keys[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)cap));
     w.pay[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)cap));
   }
-  w.counts = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(w.ntiles + 1)));
+  w.counts = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(max_tiles + 1)));
   w.tilesum = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 256 * (size_t)(w.nscan + 1)));
   w.digit_off = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * 257));
+  w.cap = cap;
   w.bytes = off;
   return w;
 }
@@ -365,9 +384,10 @@ RadixWs carve_radix(void* base, int64_t n) {
 int radix_sort_pairs(const uint32_t* keys_in, const uint32_t* pay_in, int64_t n, int bits, const RadixWs& w0,
                      hipStream_t s, int* result) {
   RadixWs w = w0;
-  w.ntiles = ceil_div(n > 0 ? n : 1, kSortTile);     // the workspace may have been carved for more
+  if (n < 0 || n > w0.cap || bits < 1 || bits > 32) return SAGNN_EINVAL;
+  const int tile = radix_tile(n > 0 ? n : 1);
+  w.ntiles = ceil_div(n > 0 ? n : 1, tile);          // the workspace may have been carved for more
   w.nscan = ceil_div(w.ntiles + 1, kScanTile);
-  if (w.ntiles > w0.ntiles || bits < 1 || bits > 32 || n < 0) return SAGNN_EINVAL;
   const int passes = (bits + 7) / 8;
   const dim3 sgrid((unsigned)w.nscan, 256u);
   for (int pass = 0; pass < passes; ++pass) {
@@ -375,7 +395,7 @@ int radix_sort_pairs(const uint32_t* keys_in, const uint32_t* pay_in, int64_t n,
     const uint32_t* pin = pass == 0 ? pay_in : w.pay[(pass - 1) & 1];
     hipLaunchKernelGGL(radix_tile_kernel<false>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin, n,
                        pass * 8, w.ntiles, w.counts, (const int64_t*)nullptr, (uint32_t*)nullptr,
-                       (uint32_t*)nullptr);
+                       (uint32_t*)nullptr, tile);
     SAGNN_LAUNCH_CHECK();
     if (w.ntiles + 1 <= kScanTile) {   // nscan == 1: the three scan steps as one launch
       hipLaunchKernelGGL(split_scan_small_kernel, dim3(256), dim3(kThreads), 0, s, w.counts, w.ntiles, w.tilesum);
@@ -388,11 +408,11 @@ int radix_sort_pairs(const uint32_t* keys_in, const uint32_t* pay_in, int64_t n,
       hipLaunchKernelGGL(split_scan_kernel<1>, sgrid, dim3(kThreads), 0, s, w.counts, w.ntiles, w.nscan, w.tilesum);
       SAGNN_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(64), 0, s, w.tilesum, w.nscan, 256, w.digit_off);
+    hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(kThreads), 0, s, w.tilesum, w.nscan, 256, w.digit_off);
     SAGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(radix_tile_kernel<true>, dim3(wave_grid(w.ntiles)), dim3(kThreads), 0, s, kin, pin, n,
                        pass * 8, w.ntiles, w.counts, (const int64_t*)w.digit_off, w.keys[pass & 1],
-                       w.pay[pass & 1]);
+                       w.pay[pass & 1], tile);
     SAGNN_LAUNCH_CHECK();
   }
   *result = (passes - 1) & 1;
@@ -460,7 +480,7 @@ SAGNN_EXPORT int spmm_split_colblocks(const int32_t* d_rowptr, const int32_t* d_
   hipLaunchKernelGGL(split_scan_kernel<1>, sgrid, dim3(kThreads), 0, s, d_rowptr_blk, m, w.ntiles,
                      w.tilesum);
   SAGNN_LAUNCH_CHECK();
-  hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(64), 0, s, w.tilesum, w.ntiles, (int)nb,
+  hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(kThreads), 0, s, w.tilesum, w.ntiles, (int)nb,
                      w.nnz_off);
   SAGNN_LAUNCH_CHECK();
   if (nnz > 0 && m > 0) {
