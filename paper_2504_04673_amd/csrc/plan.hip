@@ -166,13 +166,20 @@ __device__ __forceinline__ void lds_mark_one(int32_t c, int64_t n, int64_t c0, u
   }
 }
 
+// `spec` (may be NULL): the workgroups of the first column range also write the range-checked
+// copy of colidx that the remap is if every column turns out to be needed (a whole graph planned
+// as one block): the entries are in registers anyway, and the separate copy pass is then skipped.
+__device__ __forceinline__ int32_t identity_or_bad(int32_t c, int64_t n) { return (c < 0 || c >= n) ? -1 : c; }
+
 __global__ __launch_bounds__(kLdsThreads) void mark_lds_kernel(const int32_t* __restrict__ colidx,
                                                                int64_t nnz, int64_t n,
                                                                int32_t groups_per_pass,
                                                                uint32_t* __restrict__ part,
-                                                               int32_t* __restrict__ err, int aligned) {
+                                                               int32_t* __restrict__ err, int aligned,
+                                                               int32_t* __restrict__ spec) {
   extern __shared__ __attribute__((aligned(16))) uint32_t bits[];
   const int pass = blockIdx.x / groups_per_pass, share = blockIdx.x % groups_per_pass;
+  if (pass != 0) spec = nullptr;
   const int64_t c0 = (int64_t)pass * kLdsCols;
   uint4* b4 = reinterpret_cast<uint4*>(bits);
   for (int i = threadIdx.x; i < kLdsWords / 4; i += kLdsThreads) b4[i] = make_uint4(0u, 0u, 0u, 0u);
@@ -189,6 +196,13 @@ __global__ __launch_bounds__(kLdsThreads) void mark_lds_kernel(const int32_t* __
       int4 c[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) c[j] = c4[q + j * kLdsThreads];
+      if (spec) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          reinterpret_cast<int4*>(spec)[q + j * kLdsThreads] =
+              make_int4(identity_or_bad(c[j].x, n), identity_or_bad(c[j].y, n), identity_or_bad(c[j].z, n),
+                        identity_or_bad(c[j].w, n));
+      }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         lds_mark_one(c[j].x, n, c0, bits, err);
@@ -199,19 +213,29 @@ __global__ __launch_bounds__(kLdsThreads) void mark_lds_kernel(const int32_t* __
     }
     for (; q < q1; q += kLdsThreads) {
       const int4 c = c4[q];
+      if (spec)
+        reinterpret_cast<int4*>(spec)[q] = make_int4(identity_or_bad(c.x, n), identity_or_bad(c.y, n),
+                                                     identity_or_bad(c.z, n), identity_or_bad(c.w, n));
       lds_mark_one(c.x, n, c0, bits, err);
       lds_mark_one(c.y, n, c0, bits, err);
       lds_mark_one(c.z, n, c0, bits, err);
       lds_mark_one(c.w, n, c0, bits, err);
     }
     if (share == 0)
-      for (int64_t e = (quads << 2) + threadIdx.x; e < nnz; e += kLdsThreads)
-        lds_mark_one(colidx[e], n, c0, bits, err);
+      for (int64_t e = (quads << 2) + threadIdx.x; e < nnz; e += kLdsThreads) {
+        const int32_t c = colidx[e];
+        if (spec) spec[e] = identity_or_bad(c, n);
+        lds_mark_one(c, n, c0, bits, err);
+      }
   } else {
     const int64_t per = ceil_div_dev(nnz, groups_per_pass);
     const int64_t e0 = (int64_t)share * per;
     const int64_t e1 = e0 + per < nnz ? e0 + per : nnz;
-    for (int64_t e = e0 + threadIdx.x; e < e1; e += kLdsThreads) lds_mark_one(colidx[e], n, c0, bits, err);
+    for (int64_t e = e0 + threadIdx.x; e < e1; e += kLdsThreads) {
+      const int32_t c = colidx[e];
+      if (spec) spec[e] = identity_or_bad(c, n);
+      lds_mark_one(c, n, c0, bits, err);
+    }
   }
   __syncthreads();
   // only the words that cover columns below n are ever read back
@@ -549,15 +573,19 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
   }
   const bool oblivious = (flags & SAGNN_PLAN_OBLIVIOUS) != 0;
   const bool lds_mark = !oblivious && w.part != nullptr;
+  bool speculated = false;   // the marking pass has already written the identity remap
   if (lds_mark) {
     const int passes = (int)ceil_div(n, kLdsCols);
     const int groups_per_pass = kLdsGroups / passes;
     const size_t lds = sizeof(uint32_t) * (size_t)kLdsWords;
     SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mark_lds_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    // dense enough that every column is probably needed: write the identity remap on the way
+    speculated = d_colidx_compact && !oblivious && nnz >= 8 * n;
+    const bool al = aligned16(d_colidx) && (!speculated || aligned16(d_colidx_compact));
     hipLaunchKernelGGL(mark_lds_kernel, dim3((unsigned)(passes * groups_per_pass)), dim3(kLdsThreads),
-                       lds, s, d_colidx, nnz, n, (int32_t)groups_per_pass, w.part, w.err,
-                       aligned16(d_colidx) ? 1 : 0);
+                       lds, s, d_colidx, nnz, n, (int32_t)groups_per_pass, w.part, w.err, al ? 1 : 0,
+                       speculated ? d_colidx_compact : (int32_t*)nullptr);
     SAGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(merge_kernel, dim3((unsigned)ceil_div(w.W, 16)), dim3(kThreads), 0, s, w.part,
                        (int32_t)groups_per_pass, w.W, n, w.bitmap);
@@ -608,6 +636,8 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
   }
   if (d_colidx_compact && nnz > 0) {
     const int al = (aligned16(d_colidx) && aligned16(d_colidx_compact)) ? 1 : 0;
+    if (N == n && speculated)
+      return SAGNN_OK;
     if (N == n)
       hipLaunchKernelGGL(remap_identity_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx,
                          nnz, n, d_colidx_compact, al);

@@ -114,11 +114,16 @@ def test_plan_random_ragged(m, n, nb, avg, seed):
 
 
 @pytest.mark.parametrize("n,nnz,misalign", [(1_000_000, 4_300_000, 0), (1_245_185, 4_200_003, 1),
-                                            (2_700_001, 4_500_001, 3), (4_980_736, 4_194_304, 0)])
+                                            (2_700_001, 4_500_001, 3), (4_980_736, 4_194_304, 0),
+                                            (500_000, 4_300_000, 0), (100_000, 4_300_003, 0),
+                                            (100_001, 4_300_001, 1)])
 def test_plan_large_entry_counts_lds_marking(n, nnz, misalign):
     """Entry counts above 2^22 with at most ~5 M columns take the LDS-bitmap marking path
     (1 to 4 column ranges); the column array is also given at a 4-byte-but-not-16-byte aligned
-    address.  Power-law-like columns (squared uniform) plus the last column of every range."""
+    address.  Power-law-like columns (squared uniform) plus the last column of every range.
+    With eight or more entries per column the marking pass also writes the identity remap in
+    advance: the 500 k-column case leaves columns unused (the advance copy must be replaced by
+    the real remap), the 100 k-column cases use every column (it is the result)."""
     rng = np.random.default_rng(n % 97)
     m = 5000
     cols = (rng.random(nnz) ** 2 * n).astype(np.int64)
@@ -137,6 +142,10 @@ def test_plan_large_entry_counts_lds_marking(n, nnz, misalign):
     assert np.array_equal(plan.blk_off, blk_off)
     assert np.array_equal(plan.needed.cpu().numpy(), needed)
     assert np.array_equal(plan.colidx_compact.cpu().numpy(), compact)
+    if n == 500_000:
+        assert plan.N < n
+    if n in (100_000, 100_001):
+        assert plan.N == n
     ci[12345] = n                                           # out of range: validation must see it
     with pytest.raises(sagnn.SagnnError) as ei:
         sagnn.spmm_plan_needed_rows(dev(rowptr), ci, n, colblk, validate=True)
