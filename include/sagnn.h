@@ -223,7 +223,12 @@ typedef struct sagnn_spmm_options {
                               (16 rows need 32768 bytes of LDS per workgroup and 5 x 32768 do not
                               fit).  Measured slower on the free-running sweep (more wavefronts
                               thrash the L2 more) and equal under pacing; off unless asked for     */
-  int32_t reserved[2];     /* must be 0 */
+  int32_t slab_width;      /* widest column slab of B one launch covers: 0 = 256; 128 = operands wider
+                              than 128 are processed as 128-wide slabs by the kernels that fetch two
+                              rows of B per load (faster on the 2.45 M-vertex power-law graph at
+                              f = 256, slower on the community-ordered one; the measured choice of
+                              spmm_csr_prepare_tuned tries it)                                       */
+  int32_t reserved[1];     /* must be 0 */
 } sagnn_spmm_options;
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
 int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
@@ -243,6 +248,8 @@ int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_colidx, const
  * preparations and thirty products; synchronises the stream.  When the plain
  * schedule is chosen there is nothing to vary and the call equals spmm_csr_prepare().  Every
  * variant computes the same product up to rounding order.
+ * For operands wider than 128 two more variants take B as 128-wide column slabs (indices 5 and 6;
+ * slab_width of sagnn_spmm_options).
  * h_choice (host, 4 values, may be NULL): piece length and long-row threshold of the variant
  * kept (0 = default), its best time in microseconds, its index.  h_opt (may be NULL): options
  * every variant starts from (see sagnn_spmm_options below).

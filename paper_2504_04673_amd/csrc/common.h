@@ -75,6 +75,7 @@ struct SpmmWsHeader {       // first 256 bytes of the SpMM workspace (device cop
   int32_t slots;            // accumulator rows (pieces) per wavefront actually used, <= kSweepSlots
   int32_t barriers;         // 1: barriers at interval boundaries
   int32_t pace_ps_per_step; // pacing asked for at prepare time (0: none)
+  int32_t max_slab;         // widest column slab of B per launch (256 or 128)
 };
 static_assert(sizeof(SpmmWsHeader) <= 256, "header must fit its slot");
 
@@ -141,6 +142,7 @@ struct SpmmHostDesc {
   int32_t n_intervals, sync_slabs, wg_per_cohort, sync_timeout_ticks, sync_test_extra;
   int32_t slots;
   int32_t barriers, pace_ps_per_step;
+  int32_t max_slab;         // widest column slab of B per launch (256, or 128 for the lane-group kernels at wider f)
   float mean_steps;         // average stream steps per wavefront (the end of the pacing schedule)
   float max_steps;          // steps of the longest stream
 };

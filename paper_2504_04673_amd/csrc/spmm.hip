@@ -537,6 +537,7 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
   }
 
   const int64_t blocks = ceil_div(d.nchunks, kWavesPerBlock);
+  const int32_t max_slab = desc.mode == 1 && desc.max_slab == 128 ? 128 : 256;
   // column slabs: 256 / 128 / 64 wide through the wide kernels, the rest through the narrow one
   int32_t col0 = 0;
   while (col0 < f) {
@@ -544,7 +545,7 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
     SpmmPtrs sp = p;
     SpmmDims sd = d;
     sp.B = B + col0; sp.C = C + col0; sp.carry = p.carry + col0;
-    sd.f = rest >= 256 ? 256 : (rest >= 128 ? 128 : (rest >= 64 ? 64 : rest));
+    sd.f = rest >= 256 && max_slab >= 256 ? 256 : (rest >= 128 ? 128 : (rest >= 64 ? 64 : rest));
     const bool buf = buffer_addressable(d.kmax, ldb, sd.f, &sd.b_bytes);
     sd.row_bytes = (uint32_t)(ldb * 4);
     if (desc.mode == 1) {
@@ -600,8 +601,8 @@ SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_
   using namespace sagnn;
   sagnn_spmm_options opt{};
   if (h_opt) opt = *h_opt;
-  for (int i = 0; i < 2; ++i)
-    if (opt.reserved[i] != 0) return SAGNN_EINVAL;
+  if (opt.reserved[0] != 0 || (opt.slab_width != 0 && opt.slab_width != 128 && opt.slab_width != 256))
+    return SAGNN_EINVAL;
   if (m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || m > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll ||
       k > 0x7FFFFFFFll)
     return SAGNN_EINVAL;
@@ -668,6 +669,7 @@ SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_
   desc.n_intervals = h.n_intervals; desc.sync_slabs = h.sync_slabs; desc.wg_per_cohort = h.wg_per_cohort;
   desc.sync_timeout_ticks = h.sync_timeout_ticks; desc.sync_test_extra = h.sync_test_extra;
   desc.slots = h.slots;
+  desc.max_slab = h.max_slab > 0 ? h.max_slab : 256;
   desc.barriers = h.barriers; desc.pace_ps_per_step = h.pace_ps_per_step > 0 ? h.pace_ps_per_step : 0;
   desc.mean_steps = plan.mean_steps;
   desc.max_steps = plan.max_steps;
@@ -690,9 +692,11 @@ SAGNN_EXPORT int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* 
   if (!d_B || !d_C || ldb < f || ldc < f) return SAGNN_EINVAL;
   hipStream_t s = (hipStream_t)stream;
   // (piece, long-row threshold) variants of the slab-sweep plan; {0, 0} is spmm_csr_prepare's own
-  struct Cand { int piece, min_long; };
-  static const Cand cand[] = {{0, 0}, {4608, 0}, {3584, 0}, {0, 96}, {4608, 96}};
-  const int n_cand = (int)(sizeof(cand) / sizeof(cand[0]));
+  struct Cand { int piece, min_long, slab; };
+  static const Cand cand[] = {{0, 0, 0}, {4608, 0, 0}, {3584, 0, 0}, {0, 96, 0}, {4608, 96, 0},
+                              {0, 0, 128}, {4608, 0, 128}};
+  // the 128-wide-slab variants only exist for operands wider than 128
+  const int n_cand = (f > 128 && (f & 63) == 0 && !(h_opt && h_opt->slab_width != 0)) ? 7 : 5;
   // a variant only replaces choices the planner would make by itself: where it picks the
   // lower long-row threshold (near-regular matrices) the candidate threshold is not forced
   auto options_of = [&](int c) {
@@ -700,6 +704,7 @@ SAGNN_EXPORT int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* 
     if (h_opt) o = *h_opt;
     if (cand[c].piece > 0) o.piece = cand[c].piece;
     if (cand[c].min_long > 0) o.min_long = -cand[c].min_long;   // negative: "where you would pick 64"
+    if (cand[c].slab > 0) o.slab_width = cand[c].slab;
     return o;
   };
   int best = -1, last = -1;
@@ -761,7 +766,7 @@ SAGNN_EXPORT int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* 
       if (spmm_desc_get(d_ws, &desc) && desc.mode == 1 && desc.n_intervals > 1 && desc.mean_steps > 0.f) {
         int dev = 0, cus = 256;
         if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const int32_t fw = f >= 256 ? 256 : (f >= 128 ? 128 : f);
+        const int32_t fw = desc.max_slab == 128 && f > 128 ? 128 : (f >= 256 ? 256 : (f >= 128 ? 128 : f));
         const int64_t resident = (int64_t)cus * lds_resident_workgroups((size_t)4 * desc.slots * fw * 4) * 4;
         const double gens = (double)ceil_div(desc.n_waves, resident > 0 ? resident : 1);
         const double ps_hi = (double)best_ms * 1e9 / (gens * (double)desc.mean_steps);

@@ -814,7 +814,10 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // the average number of swept entries per row of B.
   // Narrow operands (f = 32, 16: rows of 128 / 64 bytes, 8 / 4 lanes each) exist only in the
   // grouped form, 8 / 16 rows per load.
-  int64_t R = f == 128 ? 2 : (f == 64 ? 4 : (f == 32 ? 8 : (f == 16 ? 16 : 1)));
+  // Wider operands (multiples of 64 above 128) can be taken as 128-wide slabs by the two-group
+  // kernels (a last slab of 64 is served by the same streams): an option, see sagnn_spmm_options.
+  const bool narrow_slabs = opt.slab_width == 128 && f > 128 && (f & 63) == 0 && opt.groups != 1;
+  int64_t R = (f == 128 || narrow_slabs) ? 2 : (f == 64 ? 4 : (f == 32 ? 8 : (f == 16 ? 16 : 1)));
   if (opt.groups == 1 && f >= 64) R = 1;
   if (force != 1 && long_entries * 10 < nnz * 3) return SAGNN_OK;   // < 30 % of the entries
   if (opt.groups != 2 && long_entries < 8 * k) {
@@ -830,7 +833,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // or 15 rows bring the fifth workgroup in, 20 wavefronts and 280 / 300 rows per CU instead
   // of 16 and 256 -- measured slower free-running on the 2.45 M-vertex graph (5.4 against
   // 4.5 ms: more wavefronts drift apart more) and equal under pacing, so it is an option only.
-  const bool has_128_slab = (f % 256) == 128 || (f % 256) == 192;
+  const bool has_128_slab = narrow_slabs || (f % 256) == 128 || (f % 256) == 192;
   const int64_t slots = has_128_slab && opt.narrow_slots == 1 ? (R == 2 ? 14 : 15) : kSweepSlots;
   // Pieces per wavefront: all slots when there are plenty of pieces; fewer when that would
   // leave the chip short of wavefronts (a row block of a partitioned graph has few long rows).
@@ -846,7 +849,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // per generation on the 2.45 M-vertex R-MAT graph); a larger one whose row order carries
   // locality (a partitioned graph) keeps it, because a window only touches the part of B its
   // rows' neighbourhoods live in (2 M-vertex community-ordered graph: 13.9 -> 11.4 ms).
-  const int64_t fw_max = f >= 256 ? 256 : (f >= 128 ? 128 : f);     // widest launch of a call
+  const int64_t fw_max = narrow_slabs ? 128 : (f >= 256 ? 256 : (f >= 128 ? 128 : f));   // widest launch of a call
   int64_t wg_per_cu = lds_resident_workgroups((size_t)(4ll * slots * fw_max * 4));
   if (wg_per_cu < 1) wg_per_cu = 1;
   int n_cus = 256;
@@ -1001,6 +1004,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   h.slots = (int32_t)slots;
   h.barriers = opt.barriers == 1 && sync_slabs > 0 ? 1 : 0;
   h.pace_ps_per_step = sync_slabs > 0 && !h.barriers ? opt.pace_ps_per_step : 0;
+  h.max_slab = narrow_slabs && R == 2 ? 128 : 256;
   SAGNN_HIP(hipStreamSynchronize(s));     // the step counts have arrived
   out->mean_steps = steps[0];
   out->max_steps = steps[1];

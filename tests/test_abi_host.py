@@ -63,7 +63,7 @@ def test_argument_validation_before_launch():
     assert L.spmm_csr_prepare_tuned(None, None, None, 4, 4, 4, 16, None, 0, None, 16, None, 16, None, None, None) == -1
     assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, None, None) == -1
     bad = sagnn.SpmmOptions()
-    bad.reserved[1] = 1                                   # reserved fields must be zero
+    bad.reserved[0] = 1                                   # reserved fields must be zero
     import ctypes as _c
     assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, _c.byref(bad), None) == -1
     assert L.spmm_csr_release(None) == -1

@@ -340,6 +340,37 @@ def test_spmm_sweep_planner_balances_streams(f, monkeypatch):
     assert_close(got[torch.from_numpy(rows).cuda()], ref, zabs, RTOL_SPMM, f"balanced planner f={f}")
 
 
+@pytest.mark.parametrize("f", [192, 256, 320])
+def test_spmm_sweep_wide_operand_as_128_wide_slabs(f, force_sweep, monkeypatch):
+    """Operands wider than 128 taken as 128-wide column slabs (plus a 64-wide rest) by the kernels
+    that fetch two rows of B per load: same product."""
+    monkeypatch.setenv("SAGNN_SWEEP_SLAB_WIDTH", "128")
+    rng = np.random.default_rng(f + 1)
+    m, n = 6001, 40_000
+    rowptr, colidx, val = random_csr(m, n, 25, rng, empty_frac=0.1,
+                                     hubs=[(4, 7000), (9, 2049), (3000, 1024), (6000, 33)])
+    B = synth.normal((n, f), f, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f)
+    info = ws.info()
+    assert info["mode"] == 1 and info["groups"] == 2
+    got = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got, ref, zabs, RTOL_SPMM, f"128-wide slabs f={f}")
+    C0 = synth.normal((m, f), f + 2, synth.STREAM_G)
+    ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
+    got2 = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), C=dev(C0), accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got2, ref2, zabs2, RTOL_SPMM, f"128-wide slabs accumulate f={f}")
+    # a narrower call on the same workspace (the streams serve 128- and 64-wide launches)
+    B64 = synth.normal((n, 64), 3, synth.STREAM_H)
+    ref3, zabs3 = oracle.spmm(rowptr, colidx, val, B64, want_abs=True)
+    got3 = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B64), ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got3, ref3, zabs3, RTOL_SPMM, f"128-wide slabs prepared {f}, called 64")
+
+
 def test_spmm_sweep_workspace_prepared_for_wider_f(force_sweep):
     """A workspace prepared for f = 128 (two lane groups) or 256 also serves narrower calls."""
     rng = np.random.default_rng(31)
