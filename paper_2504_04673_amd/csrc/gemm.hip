@@ -170,13 +170,35 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
       float* zp = g.Z ? g.Z + row0 * g.ldz + col0 : nullptr;
       float* ap = g.A ? g.A + row0 * g.lda + col0 : nullptr;
       const bool relu = g.act == SAGNN_ACT_RELU;
+      if (mk) {
+        // the mask is applied in a pass of its own: between the stores below its loads would each
+        // have to wait for the store before them (the arrays may alias as far as the compiler
+        // knows), one memory round trip per element
+        // and its loads are issued a batch at a time (16 to 32 in flight) ahead of their uses
+        constexpr int VB = NT >= 8 ? 2 : 4;
+#pragma unroll
+        for (int v0 = 0; v0 < 16; v0 += VB) {
+          float mv[VB][NT];
+#pragma unroll
+          for (int dv = 0; dv < VB; ++dv) {
+            const int64_t dr = ((v0 + dv) >> 2) * 8 + ((v0 + dv) & 3);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) mv[dv][nt] = mk[dr * g.ldmask + nt * 32];
+          }
+          __builtin_amdgcn_sched_barrier(0);   // keep the batch of loads together, ahead of the selects
+#pragma unroll
+          for (int dv = 0; dv < VB; ++dv)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              if (!(mv[dv][nt] > 0.f)) acc[nt][v0 + dv] = 0.f;
+        }
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t dr = (v >> 2) * 8 + (v & 3);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          float z = acc[nt][v];
-          if (mk && !(mk[dr * g.ldmask + nt * 32] > 0.f)) z = 0.f;
+          const float z = acc[nt][v];
           if (zp) zp[dr * g.ldz + nt * 32] = z;
           if (ap) ap[dr * g.lda + nt * 32] = relu ? (z > 0.f ? z : 0.f) : z;
         }
