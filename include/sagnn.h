@@ -321,7 +321,7 @@ int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw,
  * <= 128 * 256; bfloat16: up to 256 x 256); other shapes return SAGNN_EINVAL when d_T is NULL.
  * It balances work per tile of rows, not per entry: on matrices with rows of similar length it
  * is the cheaper form, on power-law matrices the two-kernel form with the slab-sweep schedule
- * is faster (rows longer than 2048 entries are shared by a workgroup's wavefronts, so they
+ * is faster (rows longer than 512 entries are shared by a workgroup's wavefronts, so they
  * are correct but slow).  Same rounding bound as the two-kernel form.
  * gcn_layer_fwd_fused may also be called directly, with d_T non-NULL to get T as a by-product.
  */

@@ -28,7 +28,7 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kCoopRow = 2048;   // rows longer than this are shared by the whole workgroup
+constexpr int kCoopRow = 512;    // rows longer than this are shared by the wavefronts of the workgroup
 constexpr int kRunBlock = 128;   // entries per first-level sum
 constexpr int kCoopWaves = 8;    // wavefronts that share a long row (one partial row in LDS each)
 
@@ -133,10 +133,19 @@ __global__ __launch_bounds__(1024) void gcn_fused_kernel(
 
   for (int64_t pass = blockIdx.x; pass < npasses; pass += gridDim.x) {
     const int64_t row0 = pass * rows_per_pass;
-    if (tid == 0) longlist[0] = 0;
+    if (tid == 0) {
+      longlist[0] = 0;
+      longlist[rows_per_pass + 2] = 0;   // next local row to hand out
+    }
     __syncthreads();                 // W staged (first pass); previous pass's tile consumed
-    // ---- phase 1: T rows of this pass
-    for (int lr = wave; lr < rows_per_pass; lr += nwaves) {
+    // ---- phase 1: T rows of this pass.  A wavefront takes the next row when it is done with its
+    // last one (rows differ in length by orders of magnitude on power-law graphs; every row is
+    // still summed by one wavefront in a fixed order, so the result does not depend on who took it)
+    for (;;) {
+      int lr = 0;
+      if (lane == 0) lr = atomicAdd(&longlist[rows_per_pass + 2], 1);
+      lr = __builtin_amdgcn_readfirstlane(lr);
+      if (lr >= rows_per_pass) break;
       const int64_t row = row0 + lr;
       vec t = 0.f;
       bool is_long = false;

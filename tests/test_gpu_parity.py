@@ -804,13 +804,13 @@ def test_spmm_sweep_interval_barrier_gives_up_and_still_computes(f, force_sweep,
 def test_gcn_layer_fwd_fused(prec, fin, fout, graph, cfg1):
     """The one-kernel layer (T = A H kept on the chip, then the dense transform on the matrix
     cores) against the oracle's layer: without T (gcn_layer_fwd with d_T = NULL) and with T as a
-    by-product.  Rows longer than 2048 entries take the workgroup-shared path; m is not a
+    by-product.  Rows longer than 512 entries take the workgroup-shared path; m is not a
     multiple of the tile height."""
     rng = np.random.default_rng(fin + fout)
     if graph == "hubs_and_empty_rows":
         m, n = 4133, 9000
         rowptr, colidx, val = random_csr(m, n, 20, rng, empty_frac=0.1,
-                                         hubs=[(5, 8000), (6, 2049), (7, 2048), (4132, 5000), (300, 300)], dup=True)
+                                         hubs=[(5, 8000), (6, 513), (7, 512), (4132, 5000), (300, 300), (301, 2049)], dup=True)
     elif graph == "sbm":
         g = synth.sbm_graph(6000, 16, 40, 2, 3)
         rowptr, colidx, val, m, n = g.rowptr, g.colidx, g.val, g.m, g.n
