@@ -166,7 +166,10 @@ __global__ __launch_bounds__(kT) void plan_rows_kernel(
   block_scan5(s, ex, tot);
   if (!EMIT) {
     if (too_many) atomicAdd(&stat[ST_BAD], 1ull);
-    if (threadIdx.x < 5) tilesum[(int64_t)threadIdx.x * (ntiles + 1) + blockIdx.x] = tot[threadIdx.x];
+    if (threadIdx.x == 0) {
+#pragma unroll
+      for (int c = 0; c < 5; ++c) tilesum[(int64_t)c * (ntiles + 1) + blockIdx.x] = tot[c];
+    }
     return;
   }
   int64_t run[5];
@@ -348,11 +351,26 @@ __global__ __launch_bounds__(kT) void deal_keys_kernel(DealDims d, const int32_t
   }
 }
 
+// first[w] = first position of window w in the sorted stream keys (several windows only)
+__global__ __launch_bounds__(kT) void deal_first_kernel(DealDims d, const uint32_t* __restrict__ skeys,
+                                                        int32_t* __restrict__ first) {
+  const int w = blockIdx.x * kT + threadIdx.x;
+  if (w >= d.nwin) return;
+  const uint32_t wkey = (uint32_t)w << 20;
+  int64_t lo = 0, hi = d.U;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (skeys[mid] < wkey) lo = mid + 1; else hi = mid;
+  }
+  first[w] = (int32_t)lo;
+}
+
 // position i of the sorted streams: the rank-th shortest open stream of its window takes the
 // rank-th largest piece the window has left, for rank < B = half the window's streams
 __global__ __launch_bounds__(kT) void deal_assign_kernel(DealDims d, const int32_t* __restrict__ win_unit0,
                                                          const uint32_t* __restrict__ skeys,
                                                          const uint32_t* __restrict__ sunit,
+                                                         const int32_t* __restrict__ first,
                                                          const uint32_t* __restrict__ piece_order, PieceArrays pa,
                                                          int32_t* __restrict__ load, int32_t* __restrict__ used,
                                                          const int32_t* __restrict__ done,
@@ -364,13 +382,7 @@ __global__ __launch_bounds__(kT) void deal_assign_kernel(DealDims d, const int32
   if (key == kFullUnit) return;
   const int32_t w = (int32_t)(key >> 20);
   if (w >= d.nwin) return;
-  const uint32_t wkey = (uint32_t)w << 20;
-  int64_t lo = 0, hi = i;            // first position whose key is >= wkey
-  while (lo < hi) {
-    const int64_t mid = (lo + hi) >> 1;
-    if (skeys[mid] < wkey) lo = mid + 1; else hi = mid;
-  }
-  const int64_t rank = i - lo;
+  const int64_t rank = i - (d.nwin > 1 ? (int64_t)first[w] : 0);
   const int64_t units_w = (int64_t)win_unit0[w + 1] - win_unit0[w];
   const int64_t B = units_w / 2 > 0 ? units_w / 2 : 1;
   const int64_t left = window_pieces(d, w) - done[w];
@@ -598,8 +610,14 @@ int sweep_plan_deal(char* ws, const SpmmWsLayout& L, int64_t P, int64_t window, 
     SAGNN_LAUNCH_CHECK();
     rc = radix_sort_pairs(sc.unit_keys, nullptr, U, nwin > 1 ? 20 + wbits : 24, sc.radix, s, &res);
     if (rc != SAGNN_OK) return rc;
+    int32_t* first = reinterpret_cast<int32_t*>(sm.win_entries);   // the window sums have been read back
+    if (nwin > 1) {
+      hipLaunchKernelGGL(deal_first_kernel, dim3((unsigned)ceil_div(nwin, kT)), dim3(kT), 0, s, d,
+                         sc.radix.keys[res], first);
+      SAGNN_LAUNCH_CHECK();
+    }
     hipLaunchKernelGGL(deal_assign_kernel, dim3((unsigned)ceil_div(U, kT)), dim3(kT), 0, s, d, sm.win_unit0,
-                       sc.radix.keys[res], sc.radix.pay[res], piece_order, sc.pa, sc.load, sc.used, sm.done,
+                       sc.radix.keys[res], sc.radix.pay[res], first, piece_order, sc.pa, sc.load, sc.used, sm.done,
                        sm.assigned, info, target);
     SAGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(deal_advance_kernel, dim3((unsigned)ceil_div(nwin, kT)), dim3(kT), 0, s, sm.done, sm.assigned,
