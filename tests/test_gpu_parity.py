@@ -837,6 +837,36 @@ def test_gcn_layer_fwd_fused(prec, fin, fout, graph, cfg1):
     assert_close(Z, zt, ztabs, rtol, "fused Z vs oracle GEMM of the kernel's own T")
 
 
+def test_gcn_layer_fwd_fused_degenerate_shapes():
+    """No entries at all (every row of T is zero, so Z = 0 and H' = 0), a single row, and a
+    matrix of one long row that the wavefronts of a workgroup share."""
+    f = 128
+    W = synth.normal((f, f), 2, synth.STREAM_W, scale=1 / np.sqrt(f))
+    H = synth.normal((300, f), 2, synth.STREAM_H)
+    empty = torch.zeros(0, dtype=torch.int32, device="cuda")
+    rp = dev(np.zeros(8, np.int32))                       # 7 rows, no entries
+    T, Z, Ho = sagnn.gcn_layer_fwd(rp, empty, torch.zeros(0, device="cuda"), dev(H), dev(W), want_t=False)
+    torch.cuda.synchronize()
+    assert T is None and Z.shape == (7, f) and not Z.any().item() and not Ho.any().item()
+    for deg in (1, 299):                                  # one row; 299 > none of the thresholds, then a shared row below
+        rowptr = np.array([0, deg], np.int32)
+        colidx = np.arange(deg, dtype=np.int32)
+        val = synth.normal((deg,), deg, synth.STREAM_G).astype(np.float32)
+        o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1)
+        _, Z, Ho = sagnn.gcn_layer_fwd(dev(rowptr), dev(colidx), dev(val), dev(H), dev(W), want_t=False)
+        torch.cuda.synchronize()
+        assert_close(Z, o["Z"], o["Zabs"], RTOL_GEMM_FP32, f"fused one row of {deg}")
+        assert_close(Ho, o["H"], o["Zabs"], RTOL_GEMM_FP32, f"fused one row of {deg} H'")
+    rng = np.random.default_rng(4)
+    cols = np.sort(rng.integers(0, 300, size=3000)).astype(np.int32)      # one row of 3000 entries (duplicates summed)
+    rowptr = np.array([0, 3000], np.int32)
+    val = rng.standard_normal(3000).astype(np.float32)
+    o = oracle.gcn_layer_fwd(rowptr, cols, val, H, W, act=1)
+    _, Z, Ho = sagnn.gcn_layer_fwd(dev(rowptr), dev(cols), dev(val), dev(H), dev(W), want_t=False)
+    torch.cuda.synchronize()
+    assert_close(Z, o["Z"], o["Zabs"], RTOL_GEMM_FP32, "fused one shared row")
+
+
 def test_gcn_layer_fwd_fused_strided_h_and_unsupported_shapes():
     rng = np.random.default_rng(2)
     m, n, f = 1000, 2000, 128
