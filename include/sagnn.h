@@ -209,8 +209,10 @@ typedef struct sagnn_spmm_options {
   int32_t pace_ps_per_step;/* pacing: a wavefront does not start interval i before its own start
                               time + this many picoseconds x the average number of stream steps
                               up to i, so that all wavefronts pass the slabs at one pace and an
-                              XCD's L2 has to hold one part of B at a time.  0 = none (plain
-                              prepare) / measured (spmm_csr_prepare_tuned); -1 = never            */
+                              XCD's L2 has to hold one part of B at a time.  0 or -1 = none;
+                              -2 = spmm_csr_prepare_tuned searches the pace after choosing the plan
+                              variant (about seventy more products) and keeps it only if it is
+                              more than 1.5 % faster                                               */
   int32_t barriers;        /* 1: instead of pacing, the workgroups of an XCD that run together
                               wait for each other at every interval boundary (bounded wait).
                               Kept for experiments: it moves less data than pacing and is slower */
