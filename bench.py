@@ -291,6 +291,26 @@ def main():
                               "reps": reps,
                               "note": "fused: row-range schedule, work balanced per tile of rows, T never in HBM; "
                                       "split: prepared slab-sweep / nonzero-splitting product + dense transform"}
+        # the sweep with the dense transform as its epilogue, where the prepared schedule allows it;
+        # if this run's schedule does not (lane groups), a one-row-per-instruction schedule is prepared for it
+        try:
+            ws_e, own = ws, False
+            if sagnn.gcn_layer_fwd_form(ws_e, f, f_out, prec) != 2 and f in (64, 128, 256):
+                o = sagnn.options_from_env()
+                o.groups = 1
+                ws_e, own = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, va, N, f, options=o), True
+            if sagnn.gcn_layer_fwd_form(ws_e, f, f_out, prec) == 2:
+                ep = timed(lambda: sagnn.gcn_layer_fwd(rp, plan.colidx_compact, va, Hn, W, act=sagnn.ACT_RELU,
+                                                       prec=prec, ws=ws_e, want_t=False, want_z=False,
+                                                       out=(None, None, Ho)))
+                out["fused_layer"]["sweep_epilogue_ms"] = round(ep, 4)
+                if own:
+                    plain = timed(lambda: sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, va, Hn, C=T, ws=ws_e))
+                    out["fused_layer"]["sweep_epilogue_schedule_spmm_ms"] = round(plain, 4)
+            if own:
+                ws_e.release()
+        except sagnn.SagnnError as e:
+            out["fused_layer"]["sweep_epilogue_error"] = str(e)
         break
     if out["roofline"]["traffic"]:
         # rate at which the measured (counter) traffic of the profiled run moves at this run's time
@@ -397,6 +417,23 @@ def train_step_bench(args, sagnn, workloads, torch, np, dev, kw):
     ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
     ph = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(6)] for e in marks])
     med = np.median(ph, axis=0)
+    # the two forward layers as gcn_layer_fwd without T (the backward pass does not use it): where the
+    # prepared schedule allows it the sweep ends with the dense transform (outside the timed steps)
+    fwd_fused = None
+    if sagnn.gcn_layer_fwd_form(ws, f, f, BF) == 2:
+        def fwd():
+            sagnn.gcn_layer_fwd(rp, ci, va, H0, W1, act=sagnn.ACT_RELU, prec=BF, ws=ws, want_t=False, out=(None, Z1, H1))
+            sagnn.gcn_layer_fwd(rp, ci, va, H1, W2, act=sagnn.ACT_IDENTITY, prec=BF, ws=ws, want_t=False,
+                                want_h=False, out=(None, Z2, None))
+        fwd()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(3):
+            fwd()
+        b.record()
+        torch.cuda.synchronize()
+        fwd_fused = a.elapsed_time(b) / 3
     mdl = workloads.byte_models(m, m, nnz, m, f, f)
     tn_bytes = 2 * m * f * 4 + f * f * 4
     step_bytes = 4 * mdl["spmm_bytes"] + 3 * mdl["gemm_bytes"] + 2 * tn_bytes
@@ -420,6 +457,8 @@ def train_step_bench(args, sagnn, workloads, torch, np, dev, kw):
                      "gather_delivery_GBps": round(mdl["spmm_gather_bytes"] / (spmm_ms * 1e-3) / 1e9, 1)},
         "stages": {"median_ms": {k: round(float(v), 4) for k, v in zip(
             ("fwd1_spmm", "fwd1_gemm_relu", "fwd2_spmm", "fwd2_gemm", "bwd2_layer", "bwd1_layer"), med)},
+            "fwd_two_layers_split_ms": round(float(med[:4].sum()), 4),
+            "fwd_two_layers_sweep_epilogue_ms": None if fwd_fused is None else round(fwd_fused, 4),
             "step_TFLOPs": round(step_flops / (ms_per_step * 1e-3) / 1e12, 2),
             "fwd_gemm_TFLOPs": round(mdl["gemm_flops"] / (float(med[1]) * 1e-3) / 1e12, 2)},
     }

@@ -325,6 +325,13 @@ int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw,
  * is the cheaper form, on power-law matrices the two-kernel form with the slab-sweep schedule
  * is faster (rows longer than 512 entries are shared by a workgroup's wavefronts, so they
  * are correct but slow).  Same rounding bound as the two-kernel form.
+ * With d_T == NULL and a workspace that was prepared for the one-row-per-instruction slab sweep
+ * (spmm_csr_schedule_info: schedule 1, lane groups 1; f_in 64, 128 or 256 in one column slab)
+ * whose wavefronts finish all but at most 4096 rows (rows outside the sweep and rows cut into
+ * several pieces are the exceptions; a partitioned graph's blocks have none), the sweep kernel
+ * itself ends with the dense transform: a workgroup's 64 finished rows of A H are multiplied by
+ * W on the matrix cores straight out of LDS, the few other rows go through a small kernel.
+ * gcn_layer_fwd_form() tells which form a call would take.
  * gcn_layer_fwd_fused may also be called directly, with d_T non-NULL to get T as a by-product.
  */
 int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
@@ -332,6 +339,10 @@ int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
                   int32_t f_in, const float* d_W, int32_t f_out, int32_t act,
                   int32_t gemm_prec, float* d_T, float* d_Z, float* d_Hout, void* d_ws,
                   size_t ws_bytes, void* stream);
+/* Host query: *h_form = 2 if gcn_layer_fwd(d_T = NULL) with this prepared workspace (may be NULL)
+ * and these widths runs as the slab sweep with the dense transform as its epilogue, 1 if it
+ * runs as the row-range kernel, 0 if neither supports the shape. */
+int gcn_layer_fwd_form(const void* d_ws, int32_t f_in, int32_t f_out, int32_t gemm_prec, int32_t* h_form);
 int gcn_layer_fwd_fused(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                         int64_t m, int64_t k, int64_t nnz, const float* d_H, int64_t ldh,
                         int32_t f_in, const float* d_W, int32_t f_out, int32_t act,

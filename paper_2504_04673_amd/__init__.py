@@ -8,7 +8,7 @@ library is missing or no GPU is present, calls raise.
 from .binding import (  # noqa: F401
     SagnnError, lib, lib_path, Plan, SpmmWorkspace, SpmmOptions, options_from_env, plan_buffers,
     spmm_plan_needed_rows, spmm_plan_needed_rows_noalloc, spmm_pack_rows, spmm_csr_prepare, spmm_csr_prepare_tuned, spmm_csr_tallskinny,
-    dense_gemm_act, gcn_layer_fwd, gcn_layer_bwd,
+    dense_gemm_act, gcn_layer_fwd, gcn_layer_fwd_form, gcn_layer_bwd,
     ColBlocks, spmm_split_colblocks, spmm_stage_loop, spmm_volume_stats, spmm_csr_transpose,
     spmm_perm_from_labels, spmm_csr_permute_symmetric,
     ACT_IDENTITY, ACT_RELU, GEMM_FP32, GEMM_BF16, PLAN_VALIDATE, PLAN_OBLIVIOUS,

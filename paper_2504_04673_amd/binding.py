@@ -19,7 +19,7 @@ EXPORTS = [
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_plan_needed_rows_noalloc", "spmm_pack_rows",
     "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_opt", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
     "spmm_csr_release", "spmm_csr_tallskinny",
-    "dense_gemm_act", "gcn_layer_fwd", "gcn_layer_fwd_fused", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
+    "dense_gemm_act", "gcn_layer_fwd", "gcn_layer_fwd_fused", "gcn_layer_fwd_form", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
     "spmm_transpose_workspace_bytes", "spmm_csr_transpose",
     "spmm_permute_workspace_bytes", "spmm_perm_from_labels", "spmm_csr_permute_symmetric",
@@ -131,6 +131,7 @@ def lib():
                                     vp, vp, vp, sz, vp]
         L.gcn_layer_fwd_fused.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, i32, vp, i32, i32, i32, vp,
                                           vp, vp, vp]
+        L.gcn_layer_fwd_form.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_int32)]
         L.gcn_bwd_workspace_bytes.argtypes = [i64, i32, i32, psz]
         L.gcn_layer_bwd.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i32, vp, vp, i32, vp, vp, vp,
                                     vp, sz, vp, sz, vp]
@@ -428,6 +429,15 @@ def gcn_layer_fwd(rowptr, colidx, val, H, W, act=ACT_RELU, prec=GEMM_FP32, ws: S
                              _ptr(ws.buf) if ws else None, ws.buf.numel() if ws else 0, _stream())
     _check(rc, "gcn_layer_fwd")
     return T, Z, Ho
+
+
+def gcn_layer_fwd_form(ws: SpmmWorkspace, f_in: int, f_out: int, prec=GEMM_FP32) -> int:
+    """Which form gcn_layer_fwd(want_t=False) takes: 2 sweep with the dense transform as epilogue,
+    1 row-range kernel, 0 unsupported shape."""
+    form = ctypes.c_int32(0)
+    _check(lib().gcn_layer_fwd_form(_ptr(ws.buf) if ws else None, f_in, f_out, prec, ctypes.byref(form)),
+           "gcn_layer_fwd_form")
+    return form.value
 
 
 def gcn_layer_bwd(rowptr, colidx, val, G, W, Zprev, Hprev, prec=GEMM_FP32, ws: SpmmWorkspace = None,

@@ -62,9 +62,17 @@ SAGNN_EXPORT int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx,
   using namespace sagnn;
   if ((!d_Z && !d_Hout) || !d_W) return SAGNN_EINVAL;
   hipStream_t s = (hipStream_t)stream;
-  if (!d_T)   // the caller does not want T: one kernel, the tile of T never leaves the chip
+  if (!d_T) {   // the caller does not want T: the rows of T never leave the chip
+    if (d_ws) {
+      // a workspace prepared for the one-row-per-instruction sweep whose wavefronts finish (nearly)
+      // all rows: the sweep itself ends with the dense transform
+      const int rc = launch_fused_sweep_layer(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_W, f_out,
+                                              act, gemm_prec, nullptr, d_Z, d_Hout, d_ws, ws_bytes, s);
+      if (rc != 1) return rc;
+    }
     return launch_fused_layer(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_W, f_out, act,
                               gemm_prec, nullptr, d_Z, d_Hout, s);
+  }
   int rc = launch_spmm(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_T, f_in, 0, d_ws,
                        ws_bytes, s);
   if (rc != SAGNN_OK) return rc;
@@ -79,6 +87,15 @@ SAGNN_EXPORT int gcn_layer_fwd_fused(const int32_t* d_rowptr, const int32_t* d_c
                                      float* d_Z, float* d_Hout, void* stream) {
   return sagnn::launch_fused_layer(d_rowptr, d_colidx, d_val, m, k, nnz, d_H, ldh, f_in, d_W, f_out,
                                    act, gemm_prec, d_T, d_Z, d_Hout, (hipStream_t)stream);
+}
+
+SAGNN_EXPORT int gcn_layer_fwd_form(const void* d_ws, int32_t f_in, int32_t f_out, int32_t gemm_prec,
+                                    int32_t* h_form) {
+  using namespace sagnn;
+  if (!h_form) return SAGNN_EINVAL;
+  if (d_ws && fused_sweep_layer_applicable(d_ws, f_in, f_out)) *h_form = 2;
+  else *h_form = fused_layer_supported(f_in, f_out, gemm_prec) ? 1 : 0;
+  return SAGNN_OK;
 }
 
 SAGNN_EXPORT int gcn_bwd_workspace_bytes(int64_t m, int32_t f_in, int32_t f_out, size_t* bytes) {

@@ -82,7 +82,7 @@ static_assert(sizeof(SpmmWsHeader) <= 256, "header must fit its slot");
 // Fixed layout (a function of m, k, nnz, f only; every array has its worst-case size):
 struct SpmmWsLayout {
   size_t header, chunk_row, flags, rowptr_s, rowmap_s, code, vals, piece_info, piece_target,
-      wave_base, wave_steps, sync_off, barrier, sched, multi_row, multi_first, partial, carry, plan, total;
+      wave_base, wave_steps, sync_off, barrier, sched, multi_row, multi_first, partial, carry, plan, wpack, total;
   int64_t max_chunks, max_pieces, max_waves, max_multi_rows, max_multi_pieces, stream_cap;
 };
 
@@ -124,6 +124,8 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   // planner: totals, per-window arrays, tile sums of the five row scans (2048 rows per tile)
   L.plan = take(256 + (size_t)kSweepMaxWindows * 8 + 3 * 4 * (size_t)(kSweepMaxWindows + 64) +
                 5 * sizeof(int32_t) * (size_t)(ceil_div(m, 2048) + 2));
+  // W of a fused layer call packed for the bfloat16 matrix instructions (at most 256 x 256)
+  L.wpack = take(256 * 256 * 2);
   L.total = off;
   return L;
 }
@@ -196,6 +198,22 @@ int sweep_plan_window_entries(char* ws, const SpmmWsLayout& L, int64_t P, int64_
 // area stays 1 if pieces were left over
 int sweep_plan_deal(char* ws, const SpmmWsLayout& L, int64_t P, int64_t window, const int32_t* h_win_unit0,
                     int32_t nwin, int64_t n_waves4, int32_t R, int32_t SL, bool snake, hipStream_t s);
+// the sweep with the dense transform of a GCN layer as its epilogue (spmm_sweep.hip)
+struct SweepFusedArgs {
+  const float* W;        // f_in x f_out, row-major
+  const void* Wp;        // bfloat16 product: W packed for the matrix cores (set by the launcher)
+  float *Z, *Hout, *T;   // m x f_out, m x f_out, m x f_in; each may be NULL (not both Z and Hout)
+  int32_t f_out, act;
+};
+int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B, int64_t ldb,
+                       int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t bf16, hipStream_t s);
+// the layer through that kernel plus a small kernel for the rows it leaves out (spmm.hip);
+// returns 1 if the workspace / shapes do not allow it (the caller then uses another form)
+bool fused_sweep_layer_applicable(const void* ws, int32_t f_in, int32_t f_out);
+int launch_fused_sweep_layer(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
+                             int64_t k, int64_t nnz, const float* H, int64_t ldh, int32_t f_in,
+                             const float* W, int32_t f_out, int32_t act, int32_t prec, float* T, float* Z,
+                             float* Hout, void* ws, size_t ws_bytes, hipStream_t s);
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
                  int32_t accumulate, int32_t f_total, hipStream_t s);

@@ -584,6 +584,139 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
   return SAGNN_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// The layer with the dense transform as the epilogue of the slab sweep (spmm_sweep_fused_kernel)
+// covers the rows that one wavefront of the sweep finishes.  The others -- rows outside the sweep
+// (short rows) and rows cut into several pieces -- are few where this form is used and go
+// through this kernel: one wavefront per row computes the row of T (a gather over the row's
+// entries, or the sum of the row's partial rows in a fixed order), puts it into LDS and
+// multiplies it by W, 64 output columns at a time.
+namespace {
+constexpr int64_t kFusedLeftoverMax = 4096;   // rows; above that the row-range kernel serves the layer
+
+template <int FPL, bool BF16>
+__global__ __launch_bounds__(256) void layer_leftover_kernel(
+    const int32_t* __restrict__ rowptr_s, const int32_t* __restrict__ rowmap_s,
+    const int32_t* __restrict__ colidx_s, const float* __restrict__ val_s, int64_t n_short, int64_t nnz_s,
+    const int32_t* __restrict__ multi_row, const int32_t* __restrict__ multi_first, int64_t n_multi,
+    const float* __restrict__ partial, const SpmmWsHeader* __restrict__ hdr, uint64_t generation,
+    const float* __restrict__ B, int64_t ldb, uint32_t kmax, const SweepFusedArgs fa) {
+  using vec = typename Vec<FPL>::T;
+  constexpr int kRow = 64 * FPL;
+  __shared__ float trow[4][kRow];
+  if (hdr->magic != kSpmmMagic || hdr->generation != generation) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 4 + wave;
+  int64_t row = -1;
+  vec t = 0.f;
+  if (i < n_short) {
+    row = rowmap_s[i];
+    int32_t b = rowptr_s[i], e = rowptr_s[i + 1];
+    b = b < 0 ? 0 : b;
+    e = e > nnz_s ? (int32_t)nnz_s : e;
+    for (int32_t q = b; q < e; ++q) {
+      const uint32_t cc = (uint32_t)colidx_s[q];
+      const uint32_t c = cc > kmax ? kmax : cc;
+      t += val_s[q] * *reinterpret_cast<const vec*>(B + (int64_t)c * ldb + lane * FPL);
+    }
+  } else if (i < n_short + n_multi) {
+    const int64_t q = i - n_short;
+    row = multi_row[q];
+    for (int32_t j = multi_first[q]; j < multi_first[q + 1]; ++j)
+      t += *reinterpret_cast<const vec*>(partial + (int64_t)j * kRow + lane * FPL);
+  }
+  if (row >= 0 && fa.T) *reinterpret_cast<vec*>(fa.T + row * kRow + lane * FPL) = t;
+  if constexpr (FPL == 1) {
+    trow[wave][lane] = BF16 ? (float)(__bf16)t : t;
+  } else {
+#pragma unroll
+    for (int c = 0; c < FPL; ++c) trow[wave][lane * FPL + c] = BF16 ? (float)(__bf16)t[c] : t[c];
+  }
+  __syncthreads();
+  if (row < 0) return;
+  for (int col = lane; col < fa.f_out; col += 64) {
+    float z = 0.f;
+    for (int k = 0; k < kRow; ++k) {
+      const float w = fa.W[(int64_t)k * fa.f_out + col];
+      z += trow[wave][k] * (BF16 ? (float)(__bf16)w : w);
+    }
+    if (fa.Z) fa.Z[row * fa.f_out + col] = z;
+    if (fa.Hout) fa.Hout[row * fa.f_out + col] = fa.act == SAGNN_ACT_RELU ? (z > 0.f ? z : 0.f) : z;
+  }
+}
+}  // namespace
+
+bool fused_sweep_layer_applicable(const void* ws, int32_t f_in, int32_t f_out) {
+  SpmmHostDesc desc{};
+  if (!ws || !spmm_desc_get(ws, &desc)) return false;
+  if (desc.mode != 1 || desc.groups != 1 || desc.slots != kSweepSlots || desc.n_waves <= 0 || (desc.n_waves & 3))
+    return false;
+  if (!(f_in == 64 || f_in == 128 || f_in == 256) || f_in > desc.f || f_in > desc.max_slab) return false;
+  if (f_out <= 0 || (f_out & 3) || f_out > 256) return false;
+  return desc.c_rows + desc.n_multi_rows <= kFusedLeftoverMax;
+}
+
+int launch_fused_sweep_layer(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
+                             int64_t k, int64_t nnz, const float* H, int64_t ldh, int32_t f_in,
+                             const float* W, int32_t f_out, int32_t act, int32_t prec, float* T, float* Z,
+                             float* Hout, void* ws, size_t ws_bytes, hipStream_t s) {
+  (void)colidx; (void)val;   // the prepared workspace holds its own copy of the entries
+  SpmmHostDesc desc{};
+  if (!fused_sweep_layer_applicable(ws, f_in, f_out) || !spmm_desc_get(ws, &desc)) return 1;
+  if (desc.m != m || desc.nnz != nnz) return SAGNN_EINVAL;
+  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
+  if (act != SAGNN_ACT_IDENTITY && act != SAGNN_ACT_RELU) return SAGNN_EINVAL;
+  if (nnz > 0 && k < desc.k) return SAGNN_EINVAL;
+  if (!rowptr || !H || !W || (!Z && !Hout) || ldh < f_in || (ldh & 3) || !aligned16(H)) return SAGNN_EINVAL;
+  const SpmmWsLayout L = spmm_ws_layout(m, nnz, desc.f);
+  if (ws_bytes < L.total) return SAGNN_ECAPACITY;
+  char* base = reinterpret_cast<char*>(ws);
+  const SpmmWsHeader* hdr = reinterpret_cast<const SpmmWsHeader*>(base + L.header);
+  const uint32_t kmax = k > 0 ? (uint32_t)(k - 1) : 0u;
+  const bool bf16 = prec == SAGNN_GEMM_BF16;
+
+  if (desc.has_empty_rows) {   // a row without entries: T = 0, so Z = 0 and sigma(0) = 0
+    SpmmPtrs p{};
+    p.rowptr = rowptr; p.hdr = hdr;
+    SpmmDims d{};
+    d.m = m; d.generation = desc.generation;
+    float* outs[3] = {Z, Hout, T};
+    const int32_t widths[3] = {f_out, f_out, f_in};
+    for (int o = 0; o < 3; ++o) {
+      if (!outs[o]) continue;
+      p.C = outs[o];
+      d.ldc = widths[o];
+      launch_waves(spmm_zero_empty_kernel, capped_grid(ceil_div(m, kWavesPerBlock)), p, d, s, widths[o]);
+      SAGNN_LAUNCH_CHECK();
+    }
+  }
+  SweepFusedArgs fa{};
+  fa.W = W; fa.Z = Z; fa.Hout = Hout; fa.T = T; fa.f_out = f_out; fa.act = act;
+  int rc = sweep_launch_fused(desc, L, base, H, ldh, f_in, kmax, fa, bf16 ? 1 : 0, s);
+  if (rc != SAGNN_OK) return rc;
+  const int64_t left = desc.c_rows + desc.n_multi_rows;
+  if (left > 0) {
+    const int64_t short_base = (int64_t)round_up((size_t)desc.sweep_stream_len + 64, 256);
+    auto go = [&](auto kern) -> int {
+      hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(left, 4)), dim3(256), 0, s,
+                         reinterpret_cast<const int32_t*>(base + L.rowptr_s),
+                         reinterpret_cast<const int32_t*>(base + L.rowmap_s),
+                         reinterpret_cast<const int32_t*>(base + L.code) + short_base,
+                         reinterpret_cast<const float*>(base + L.vals) + short_base, desc.c_rows, desc.c_nnz,
+                         reinterpret_cast<const int32_t*>(base + L.multi_row),
+                         reinterpret_cast<const int32_t*>(base + L.multi_first), desc.n_multi_rows,
+                         reinterpret_cast<const float*>(base + L.partial), hdr, desc.generation, H, ldh, kmax, fa);
+      SAGNN_LAUNCH_CHECK();
+      return SAGNN_OK;
+    };
+    if (f_in == 256) rc = bf16 ? go(layer_leftover_kernel<4, true>) : go(layer_leftover_kernel<4, false>);
+    else if (f_in == 128) rc = bf16 ? go(layer_leftover_kernel<2, true>) : go(layer_leftover_kernel<2, false>);
+    else rc = bf16 ? go(layer_leftover_kernel<1, true>) : go(layer_leftover_kernel<1, false>);
+    if (rc != SAGNN_OK) return rc;
+  }
+  return SAGNN_OK;
+}
+
 }  // namespace sagnn
 
 SAGNN_EXPORT int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes) {

@@ -476,6 +476,187 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
   }
 }
 
+// The sweep with the layer's dense transform as its epilogue (Alg. 1: the SpMM statement followed
+// by GEMM and the activation): when a workgroup's four wavefronts have walked their streams, its
+// LDS holds 64 finished rows of T = A H (4 x 16 accumulator rows), which is two 32-row operand
+// tiles of the matrix cores.  Wavefront (rt, half) multiplies row tile rt by the 32-column tiles
+// half, half + 2, .. of W, read from global memory (W is small and stays in L2), and stores the
+// rows of Z / sigma(Z) at the rows the pieces belong to.  Rows that are cut into several pieces
+// (their partial rows go to `partial` as usual) and rows outside the sweep are left to a
+// separate small kernel.  T itself goes to memory only if the caller wants it.
+typedef float sweep_floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 sweep_bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int FPL, int U, bool BUF, bool BF16>
+__global__ __launch_bounds__(256) void spmm_sweep_fused_kernel(
+    const uint32_t* __restrict__ code, const float* __restrict__ vals,
+    const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
+    const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ partial,
+    const SweepDims d, const SweepFusedArgs fa) {
+  using vec = typename Vec<FPL>::T;
+  extern __shared__ __attribute__((aligned(16))) float lds_acc[];  // [4 waves][16][64*FPL]
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t loff = lane * (FPL * 4);
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+  // (the launch has whole workgroups: n_waves is a multiple of 4, checked by the launcher)
+  if (hdr->magic != kSpmmMagic || hdr->generation != d.generation || hdr->n_waves != d.n_waves ||
+      hdr->groups != 1)
+    return;
+  constexpr int kRow = 64 * FPL;  // floats per accumulator row = f_in
+  float* __restrict__ my = lds_acc + (size_t)wave * kSweepSlots * kRow + lane * FPL;
+  for (int s = 0; s < kSweepSlots; ++s) *reinterpret_cast<vec*>(my + s * kRow) = vec(0.f);
+
+  const int32_t base = wave_base[w];
+  const int32_t len = wave_base[w + 1] - base;  // a multiple of U (padded when built)
+  const uint32_t* __restrict__ cw = code + base;
+  const float* __restrict__ vw = vals + base;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(B, d.b_bytes);
+
+  vec acc = 0.f;
+  for (int32_t e = 0; e < len; e += U) {
+    uint32_t c[U];
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      c[u] = cw[e + u];
+      v[u] = vw[e + u];
+    }
+    vec h[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) h[u] = load_row<FPL, BUF>(rs, B, c[u] & kColMask, loff, d.row_bytes, d.ldb);
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" : "+v"(h[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc += v[u] * h[u];
+      if (c[u] >> 31) {
+        vec* p = reinterpret_cast<vec*>(my + ((c[u] >> kSweepColBits) & (kSweepSlots - 1)) * kRow);
+        *p += acc;
+        acc = 0.f;
+      }
+    }
+  }
+
+  // pieces of split rows to `partial`; T rows to memory if wanted
+#pragma unroll 1
+  for (int s = 0; s < kSweepSlots; ++s) {
+    const int32_t tgt = piece_target[w * kSweepSlots + s];
+    if (tgt == INT32_MIN) continue;
+    const vec r = *reinterpret_cast<const vec*>(my + s * kRow);
+    if (tgt >= 0) {
+      if (fa.T) *reinterpret_cast<vec*>(reinterpret_cast<char*>(fa.T + (int64_t)tgt * kRow) + loff) = r;
+    } else {
+      const int64_t pi = -(int64_t)tgt - 1;
+      *reinterpret_cast<vec*>(reinterpret_cast<char*>(partial + pi * d.f_total + d.col0) + loff) = r;
+    }
+  }
+  __syncthreads();
+
+  // ---- dense transform of the workgroup's 64 rows
+  const int r = lane & 31, h = lane >> 5;
+  const int rt = wave & 1;
+  const int nct = (fa.f_out + 31) >> 5;
+  // rows of the output this lane holds in a 32 x 32 accumulator tile: 8 * (v / 4) + 4 * h + v % 4
+  int32_t tg[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int tr = rt * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+    tg[v] = piece_target[((int64_t)blockIdx.x * 4 + (tr >> 4)) * kSweepSlots + (tr & 15)];
+  }
+  const float* __restrict__ trow = lds_acc + (size_t)(rt * 32 + r) * kRow;
+  // this wavefront's column tiles: ct0, ct0 + 2, ..  (at most 4 of the at most 8).  k runs in the
+  // outer loop so that a row piece of T is read from LDS once for all of them, and the operands
+  // of W for the next k group are requested before the matrix instructions of this one.
+  const int ct0 = wave >> 1;
+  const int nmy = nct > ct0 ? (nct - ct0 + 1) >> 1 : 0;
+  sweep_floatx16 z[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) z[q][v] = 0.f;
+  if constexpr (BF16) {
+    // W as packed by sweep_pack_w_kernel: [k / 8][NB] vectors of 8 bfloat16 (zero beyond f_out)
+    const sweep_bf16x8* __restrict__ Wp = reinterpret_cast<const sweep_bf16x8*>(fa.Wp);
+    const int NB = nct * 32;
+    constexpr int J = kRow / 16;
+    sweep_bf16x8 cur[4], nxt[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (q < nmy) cur[q] = Wp[(int64_t)h * NB + (ct0 + 2 * q) * 32 + r];
+    for (int j = 0; j < J; ++j) {
+      if (j + 1 < J) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (q < nmy) nxt[q] = Wp[(int64_t)(2 * (j + 1) + h) * NB + (ct0 + 2 * q) * 32 + r];
+      }
+      const float4 x0 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h);
+      const float4 x1 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h + 4);
+      sweep_bf16x8 a;
+      a[0] = (__bf16)x0.x; a[1] = (__bf16)x0.y; a[2] = (__bf16)x0.z; a[3] = (__bf16)x0.w;
+      a[4] = (__bf16)x1.x; a[5] = (__bf16)x1.y; a[6] = (__bf16)x1.z; a[7] = (__bf16)x1.w;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (q < nmy) z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, cur[q], z[q], 0, 0, 0);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+    }
+  } else {
+    constexpr int J = kRow / 8;
+    float cur[4][4], nxt[4][4];
+    auto wload = [&](int j, float (&dst)[4][4]) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = (ct0 + 2 * q) * 32 + r;
+        const bool ok = q < nmy && col < fa.f_out;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dst[q][i] = ok ? fa.W[(int64_t)(8 * j + 4 * h + i) * fa.f_out + col] : 0.f;
+      }
+    };
+    wload(0, cur);
+    for (int j = 0; j < J; ++j) {
+      if (j + 1 < J) wload(j + 1, nxt);
+      const float4 x = *reinterpret_cast<const float4*>(trow + 8 * j + 4 * h);
+      const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q < nmy) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) z[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[i], cur[q][i], z[q], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) cur[q][i] = nxt[q][i];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int col = (ct0 + 2 * q) * 32 + r;
+    if (q >= nmy || col >= fa.f_out) continue;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (tg[v] < 0) continue;               // unused slot, or a piece of a split row
+      const float zz = z[q][v];
+      if (fa.Z) fa.Z[(int64_t)tg[v] * fa.f_out + col] = zz;
+      if (fa.Hout) fa.Hout[(int64_t)tg[v] * fa.f_out + col] = fa.act == SAGNN_ACT_RELU ? (zz > 0.f ? zz : 0.f) : zz;
+    }
+  }
+}
+
+// W (f_in x f_out, row-major fp32) -> [f_in / 8][NB] vectors of 8 bfloat16 (k fastest), NB = f_out
+// rounded up to 32, zero beyond f_out: one 16-byte load then gives a lane its matrix-core operand
+__global__ __launch_bounds__(256) void sweep_pack_w_kernel(const float* __restrict__ W, int32_t f_in, int32_t f_out,
+                                                           int32_t NB, __bf16* __restrict__ Wp) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;     // one (k / 8, n) vector per thread
+  if (idx >= (f_in / 8) * NB) return;
+  const int kg = idx / NB, n = idx - kg * NB;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    Wp[(int64_t)idx * 8 + i] = (__bf16)(n < f_out ? W[(int64_t)(kg * 8 + i) * f_out + n] : 0.f);
+}
+
 // Lane-group variant: the wavefront carries R independent streams (zipped in memory), lane
 // group g = lanes [g*64/R, (g+1)*64/R) walks stream g.  A group's 64/R lanes move one whole row
 // of B with V floats (16 bytes at V = 4) per lane, so one load instruction serves R entries.
@@ -1117,6 +1298,51 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
   if (fw == 128) return buf ? go(spmm_sweep_kernel<2, 8, true>) : go(spmm_sweep_kernel<2, 8, false>);
   if (fw == 64) return buf ? go(spmm_sweep_kernel<1, 8, true>) : go(spmm_sweep_kernel<1, 8, false>);
   return SAGNN_EINVAL;
+}
+
+int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B, int64_t ldb,
+                       int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t bf16, hipStream_t s) {
+  if (d.n_waves <= 0 || (d.n_waves & 3) || d.groups != 1 || d.slots != kSweepSlots) return SAGNN_EINVAL;
+  if (!(f_in == 64 || f_in == 128 || f_in == 256) || fa.f_out <= 0 || fa.f_out > 256 || !fa.W) return SAGNN_EINVAL;
+  SweepDims sd{};
+  sd.n_waves = d.n_waves; sd.ldb = ldb; sd.ldc = f_in; sd.f_total = f_in;
+  sd.generation = d.generation; sd.col0 = 0; sd.accumulate = 0; sd.slots = kSweepSlots;
+  sd.b_bytes = 0;
+  const bool buf = buffer_addressable(kmax, ldb, f_in, &sd.b_bytes);
+  sd.row_bytes = (uint32_t)(ldb * 4);
+  const unsigned blocks = (unsigned)(d.n_waves / 4);
+  const size_t lds = (size_t)4 * kSweepSlots * f_in * sizeof(float);
+  SweepFusedArgs fb = fa;
+  fb.Wp = nullptr;
+  if (bf16) {
+    const int32_t NB = (fa.f_out + 31) / 32 * 32;
+    __bf16* wp = reinterpret_cast<__bf16*>(ws + L.wpack);
+    hipLaunchKernelGGL(sweep_pack_w_kernel, dim3((unsigned)ceil_div((int64_t)(f_in / 8) * NB, 256)), dim3(256), 0, s,
+                       fa.W, f_in, fa.f_out, NB, wp);
+    SAGNN_LAUNCH_CHECK();
+    fb.Wp = wp;
+  }
+  auto go = [&](auto kern) -> int {
+    if (lds > 48 * 1024)
+      SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s,
+                       reinterpret_cast<const uint32_t*>(ws + L.code),
+                       reinterpret_cast<const float*>(ws + L.vals),
+                       reinterpret_cast<const int32_t*>(ws + L.wave_base),
+                       reinterpret_cast<const int32_t*>(ws + L.piece_target),
+                       reinterpret_cast<const SpmmWsHeader*>(ws + L.header), B,
+                       reinterpret_cast<float*>(ws + L.partial), sd, fb);
+    SAGNN_LAUNCH_CHECK();
+    return SAGNN_OK;
+  };
+#define SAGNN_SWF(FPL_)                                                                                  \
+  (bf16 ? (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, true>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, true>)) \
+        : (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, false>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, false>)))
+  if (f_in == 256) return SAGNN_SWF(4);
+  if (f_in == 128) return SAGNN_SWF(2);
+  return SAGNN_SWF(1);
+#undef SAGNN_SWF
 }
 
 int sweep_combine(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, float* C, int64_t ldc,

@@ -216,8 +216,21 @@ def test_cfg5_reordering_and_two_layer_training_step():
         ws = sagnn.spmm_csr_prepare(rp, plan.colidx_compact, v, plan.N, f)
         Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
         torch.cuda.synchronize()
-        check_spmm_full(gb, Z, wl.H, f"cfg5 block {name}")
-        del Hd, Hn, Z
+        tfull, tfabs, _ = check_spmm_full(gb, Z, wl.H, f"cfg5 block {name}")
+        # the layer on this block without T: every row of a partitioned graph's block is swept by
+        # one wavefront, so the sweep kernel itself ends with the dense transform
+        assert sagnn.gcn_layer_fwd_form(ws, f, f, sagnn.GEMM_BF16) == 2
+        rows = pick_rows(gb, 400, 9)
+        sel = torch.from_numpy(rows).cuda()
+        Wd = dev(wl.W)
+        _, Zl, Hl = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, Wd, act=sagnn.ACT_RELU,
+                                        prec=sagnn.GEMM_BF16, ws=ws, want_t=False)
+        torch.cuda.synchronize()
+        zref, zabs = oracle.gemm(tfull[rows], wl.W, bf16=True, Xabs=tfabs[rows], want_abs=True)
+        assert_close(Zl[sel], zref, zabs, RTOL_BF16, f"cfg5 block {name} layer Z (sweep epilogue)")
+        assert_close(Hl[sel], np.maximum(zref, 0), zabs, RTOL_BF16, f"cfg5 block {name} layer H'")
+        assert torch.isfinite(Zl).all().item() and torch.equal(Hl, torch.clamp_min(Zl, 0))
+        del Hd, Hn, Z, Zl, Hl, tfull, tfabs
     # the same "before -> after" step done by the library on the device: renumber the randomly
     # ordered graph by its community labels (the partitioner's output), permute it symmetrically,
     # plan rank 0's block of the result (Sec. 5: the reordering is what shrinks NnzCols)

@@ -837,6 +837,57 @@ def test_gcn_layer_fwd_fused(prec, fin, fout, graph, cfg1):
     assert_close(Z, zt, ztabs, rtol, "fused Z vs oracle GEMM of the kernel's own T")
 
 
+@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 36), (1, 128, 100), (1, 256, 64)])
+@pytest.mark.parametrize("graph", ["regular_all_rows_swept", "with_split_short_and_empty_rows"])
+def test_gcn_layer_fwd_sweep_epilogue(prec, fin, fout, graph, monkeypatch):
+    """The layer with d_T = NULL on a workspace prepared for the one-row-per-instruction sweep: the
+    sweep kernel ends with the dense transform (form 2).  A near-regular graph whose rows are all
+    swept, and one with rows cut into pieces, rows outside the sweep and empty rows (the small
+    kernel for the rows the sweep does not finish)."""
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "1")
+    monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
+    monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+    rng = np.random.default_rng(fin * 3 + fout)
+    if graph == "regular_all_rows_swept":
+        g = synth.sbm_graph(6000, 16, 40, 2, 5)
+        rowptr, colidx, val, m, n = g.rowptr, g.colidx, g.val, g.m, g.n
+    else:
+        m, n = 5003, 12000
+        rowptr, colidx, val = random_csr(m, n, 30, rng, empty_frac=0.05,
+                                         hubs=[(7, 5000), (8, 1025), (4000, 3), (4001, 15), (5002, 2100)])
+    H = synth.normal((n, fin), 3, synth.STREAM_H)
+    W = synth.normal((fin, fout), 3, synth.STREAM_W, scale=1 / np.sqrt(fin))
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    ws = sagnn.spmm_csr_prepare(rp, ci, v, n, fin)
+    info = ws.info()
+    assert info["mode"] == 1 and info["groups"] == 1
+    assert sagnn.gcn_layer_fwd_form(ws, fin, fout, prec) == 2
+    if graph != "regular_all_rows_swept":
+        assert info["split_rows"] >= 3 and info["chunk_rows"] > 0 and info["has_empty_rows"] == 1
+    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1, bf16=bool(prec))
+    Z0 = torch.full((m, fout), float("nan"), device="cuda")
+    H0 = torch.full((m, fout), float("nan"), device="cuda")
+    T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws,
+                                   want_t=False, out=(None, Z0, H0))
+    torch.cuda.synchronize()
+    assert T is None
+    assert_close(Z, o["Z"], o["Zabs"], rtol, "sweep epilogue Z")          # every row written (no NaN left)
+    assert_close(Ho, o["H"], o["Zabs"], rtol, "sweep epilogue H'")
+    assert torch.equal(Ho, torch.clamp_min(Z, 0))
+    # only H' wanted, identity activation
+    _, Zn, Hi = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_IDENTITY, prec=prec, ws=ws,
+                                    want_t=False, want_z=False)
+    torch.cuda.synchronize()
+    assert Zn is None and torch.equal(Hi, Z)
+    # a workspace with lane groups keeps the row-range form
+    monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "2")
+    if fin in (64, 128):
+        ws2 = sagnn.spmm_csr_prepare(rp, ci, v, n, fin)
+        assert ws2.info()["groups"] > 1 and sagnn.gcn_layer_fwd_form(ws2, fin, fout, prec) == 1
+
+
 def test_gcn_layer_fwd_fused_degenerate_shapes():
     """No entries at all (every row of T is zero, so Z = 0 and H' = 0), a single row, and a
     matrix of one long row that the wavefronts of a workgroup share."""
