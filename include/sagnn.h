@@ -325,9 +325,9 @@ int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw,
  * is the cheaper form, on power-law matrices the two-kernel form with the slab-sweep schedule
  * is faster (rows longer than 512 entries are shared by a workgroup's wavefronts, so they
  * are correct but slow).  Same rounding bound as the two-kernel form.
- * With d_T == NULL and a workspace that was prepared for the one-row-per-instruction slab sweep
- * (spmm_csr_schedule_info: schedule 1, lane groups 1; f_in 64, 128 or 256 in one column slab)
- * whose wavefronts finish all but at most 4096 rows (rows outside the sweep and rows cut into
+ * With d_T == NULL and a workspace that was prepared for the slab sweep (spmm_csr_schedule_info:
+ * schedule 1; f_in 64, 128 or 256 covered by one launch of the prepared kernels: 256 needs lane
+ * groups 1, 128 lane groups 1 or 2, 64 any) whose wavefronts finish all but at most 4096 rows (rows outside the sweep and rows cut into
  * several pieces are the exceptions; a partitioned graph's blocks have none), the sweep kernel
  * itself ends with the dense transform: a workgroup's 64 finished rows of A H are multiplied by
  * W on the matrix cores straight out of LDS, the few other rows go through a small kernel.

@@ -214,9 +214,11 @@ int launch_fused_sweep_layer(const int32_t* rowptr, const int32_t* colidx, const
                              int64_t k, int64_t nnz, const float* H, int64_t ldh, int32_t f_in,
                              const float* W, int32_t f_out, int32_t act, int32_t prec, float* T, float* Z,
                              float* Hout, void* ws, size_t ws_bytes, hipStream_t s);
+// `fused` / `fuse` (lane-group schedules only): the layer form, see SweepFusedArgs
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
-                 int32_t accumulate, int32_t f_total, hipStream_t s);
+                 int32_t accumulate, int32_t f_total, hipStream_t s,
+                 const SweepFusedArgs* fused = nullptr, int32_t fuse = 0);
 
 // Stable least-significant-digit radix sort of (key, payload) pairs on the device (stages.hip),
 // 8 bits per pass over key bits [0, bits).  With pay_in == NULL the payload is the index of the

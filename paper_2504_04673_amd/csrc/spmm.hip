@@ -649,9 +649,10 @@ __global__ __launch_bounds__(256) void layer_leftover_kernel(
 bool fused_sweep_layer_applicable(const void* ws, int32_t f_in, int32_t f_out) {
   SpmmHostDesc desc{};
   if (!ws || !spmm_desc_get(ws, &desc)) return false;
-  if (desc.mode != 1 || desc.groups != 1 || desc.slots != kSweepSlots || desc.n_waves <= 0 || (desc.n_waves & 3))
-    return false;
+  if (desc.mode != 1 || desc.slots != kSweepSlots || desc.n_waves <= 0 || (desc.n_waves & 3)) return false;
   if (!(f_in == 64 || f_in == 128 || f_in == 256) || f_in > desc.f || f_in > desc.max_slab) return false;
+  // the launch must cover the whole width of T with one kernel of the prepared schedule
+  if (desc.groups == 2 ? f_in > 128 : (desc.groups == 4 ? f_in != 64 : desc.groups != 1)) return false;
   if (f_out <= 0 || (f_out & 3) || f_out > 256) return false;
   return desc.c_rows + desc.n_multi_rows <= kFusedLeftoverMax;
 }

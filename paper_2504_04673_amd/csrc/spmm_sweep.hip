@@ -487,6 +487,114 @@ __global__ __launch_bounds__(256) void spmm_sweep_kernel(
 typedef float sweep_floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 sweep_bf16x8 __attribute__((ext_vector_type(8)));
 
+// Dense transform of a sweep workgroup's 64 finished rows of T (LDS, [4 waves][16 slots][KROW]):
+// wavefront (rt, half) multiplies row tile rt by the 32-column tiles half, half + 2, .. of W and
+// stores the rows of Z / sigma(Z) at the rows the pieces belong to (slots that hold a piece of a
+// split row, or nothing, are skipped).  Called by all four wavefronts after a workgroup barrier.
+template <int KROW, bool BF16, int QT>
+__device__ __forceinline__ void sweep_dense_epilogue(const float* __restrict__ lds_acc,
+                                                     const int32_t* __restrict__ piece_target,
+                                                     const SweepFusedArgs& fa, int wave, int lane) {
+  constexpr int kRow = KROW;
+  const int r = lane & 31, h = lane >> 5;
+  const int rt = wave & 1;
+  const int nct = (fa.f_out + 31) >> 5;
+  // rows of the output this lane holds in a 32 x 32 accumulator tile: 8 * (v / 4) + 4 * h + v % 4
+  int32_t tg[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int tr = rt * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
+    tg[v] = piece_target[((int64_t)blockIdx.x * 4 + (tr >> 4)) * kSweepSlots + (tr & 15)];
+  }
+  const float* __restrict__ trow = lds_acc + (size_t)(rt * 32 + r) * kRow;
+  // this wavefront's column tiles: ct_first, ct_first + 2, ..  (at most 4 of the at most 8).  k runs
+  // in the outer loop so that a row piece of T is read from LDS once for the tiles of a pass, and the
+  // operands of W for the next k group are requested before the matrix instructions of this one;
+  // QT of them per pass over k (the accumulators of a pass live in registers: 16 per tile).
+  const int ct_first = wave >> 1;
+  const int nmine = nct > ct_first ? (nct - ct_first + 1) >> 1 : 0;
+#pragma unroll 1
+  for (int q0 = 0; q0 < nmine; q0 += QT) {
+    const int ct0 = ct_first + 2 * q0;
+    const int nmy = nmine - q0 < QT ? nmine - q0 : QT;
+    sweep_floatx16 z[QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) z[q][v] = 0.f;
+    if constexpr (BF16) {
+      // W as packed by sweep_pack_w_kernel: [k / 8][NB] vectors of 8 bfloat16 (zero beyond f_out)
+      const sweep_bf16x8* __restrict__ Wp = reinterpret_cast<const sweep_bf16x8*>(fa.Wp);
+      const int NB = nct * 32;
+      constexpr int J = kRow / 16;
+      sweep_bf16x8 cur[QT], nxt[QT];
+#pragma unroll
+      for (int q = 0; q < QT; ++q)
+        if (q < nmy) cur[q] = Wp[(int64_t)h * NB + (ct0 + 2 * q) * 32 + r];
+#pragma unroll 1
+      for (int j = 0; j < J; ++j) {
+        if (j + 1 < J) {
+#pragma unroll
+          for (int q = 0; q < QT; ++q)
+            if (q < nmy) nxt[q] = Wp[(int64_t)(2 * (j + 1) + h) * NB + (ct0 + 2 * q) * 32 + r];
+        }
+        const float4 x0 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h);
+        const float4 x1 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h + 4);
+        sweep_bf16x8 a;
+        a[0] = (__bf16)x0.x; a[1] = (__bf16)x0.y; a[2] = (__bf16)x0.z; a[3] = (__bf16)x0.w;
+        a[4] = (__bf16)x1.x; a[5] = (__bf16)x1.y; a[6] = (__bf16)x1.z; a[7] = (__bf16)x1.w;
+#pragma unroll
+        for (int q = 0; q < QT; ++q)
+          if (q < nmy) z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, cur[q], z[q], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < QT; ++q) cur[q] = nxt[q];
+      }
+    } else {
+      constexpr int J = kRow / 8;
+      float cur[QT][4], nxt[QT][4];
+      auto wload = [&](int j, float (&dst)[QT][4]) {
+#pragma unroll
+        for (int q = 0; q < QT; ++q) {
+          const int col = (ct0 + 2 * q) * 32 + r;
+          const bool ok = q < nmy && col < fa.f_out;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dst[q][i] = ok ? fa.W[(int64_t)(8 * j + 4 * h + i) * fa.f_out + col] : 0.f;
+        }
+      };
+      wload(0, cur);
+#pragma unroll 1
+      for (int j = 0; j < J; ++j) {
+        if (j + 1 < J) wload(j + 1, nxt);
+        const float4 x = *reinterpret_cast<const float4*>(trow + 8 * j + 4 * h);
+        const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int q = 0; q < QT; ++q) {
+          if (q < nmy) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) z[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[i], cur[q][i], z[q], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < QT; ++q)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) cur[q][i] = nxt[q][i];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int col = (ct0 + 2 * q) * 32 + r;
+      if (q >= nmy || col >= fa.f_out) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        if (tg[v] < 0) continue;               // unused slot, or a piece of a split row
+        const float zz = z[q][v];
+        if (fa.Z) fa.Z[(int64_t)tg[v] * fa.f_out + col] = zz;
+        if (fa.Hout) fa.Hout[(int64_t)tg[v] * fa.f_out + col] = fa.act == SAGNN_ACT_RELU ? (zz > 0.f ? zz : 0.f) : zz;
+      }
+    }
+  }
+}
+
 template <int FPL, int U, bool BUF, bool BF16>
 __global__ __launch_bounds__(256) void spmm_sweep_fused_kernel(
     const uint32_t* __restrict__ code, const float* __restrict__ vals,
@@ -553,96 +661,8 @@ __global__ __launch_bounds__(256) void spmm_sweep_fused_kernel(
   }
   __syncthreads();
 
-  // ---- dense transform of the workgroup's 64 rows
-  const int r = lane & 31, h = lane >> 5;
-  const int rt = wave & 1;
-  const int nct = (fa.f_out + 31) >> 5;
-  // rows of the output this lane holds in a 32 x 32 accumulator tile: 8 * (v / 4) + 4 * h + v % 4
-  int32_t tg[16];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int tr = rt * 32 + (v >> 2) * 8 + h * 4 + (v & 3);
-    tg[v] = piece_target[((int64_t)blockIdx.x * 4 + (tr >> 4)) * kSweepSlots + (tr & 15)];
-  }
-  const float* __restrict__ trow = lds_acc + (size_t)(rt * 32 + r) * kRow;
-  // this wavefront's column tiles: ct0, ct0 + 2, ..  (at most 4 of the at most 8).  k runs in the
-  // outer loop so that a row piece of T is read from LDS once for all of them, and the operands
-  // of W for the next k group are requested before the matrix instructions of this one.
-  const int ct0 = wave >> 1;
-  const int nmy = nct > ct0 ? (nct - ct0 + 1) >> 1 : 0;
-  sweep_floatx16 z[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) z[q][v] = 0.f;
-  if constexpr (BF16) {
-    // W as packed by sweep_pack_w_kernel: [k / 8][NB] vectors of 8 bfloat16 (zero beyond f_out)
-    const sweep_bf16x8* __restrict__ Wp = reinterpret_cast<const sweep_bf16x8*>(fa.Wp);
-    const int NB = nct * 32;
-    constexpr int J = kRow / 16;
-    sweep_bf16x8 cur[4], nxt[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (q < nmy) cur[q] = Wp[(int64_t)h * NB + (ct0 + 2 * q) * 32 + r];
-    for (int j = 0; j < J; ++j) {
-      if (j + 1 < J) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (q < nmy) nxt[q] = Wp[(int64_t)(2 * (j + 1) + h) * NB + (ct0 + 2 * q) * 32 + r];
-      }
-      const float4 x0 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h);
-      const float4 x1 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h + 4);
-      sweep_bf16x8 a;
-      a[0] = (__bf16)x0.x; a[1] = (__bf16)x0.y; a[2] = (__bf16)x0.z; a[3] = (__bf16)x0.w;
-      a[4] = (__bf16)x1.x; a[5] = (__bf16)x1.y; a[6] = (__bf16)x1.z; a[7] = (__bf16)x1.w;
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (q < nmy) z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, cur[q], z[q], 0, 0, 0);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
-    }
-  } else {
-    constexpr int J = kRow / 8;
-    float cur[4][4], nxt[4][4];
-    auto wload = [&](int j, float (&dst)[4][4]) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = (ct0 + 2 * q) * 32 + r;
-        const bool ok = q < nmy && col < fa.f_out;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) dst[q][i] = ok ? fa.W[(int64_t)(8 * j + 4 * h + i) * fa.f_out + col] : 0.f;
-      }
-    };
-    wload(0, cur);
-    for (int j = 0; j < J; ++j) {
-      if (j + 1 < J) wload(j + 1, nxt);
-      const float4 x = *reinterpret_cast<const float4*>(trow + 8 * j + 4 * h);
-      const float xs[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (q < nmy) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) z[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[i], cur[q][i], z[q], 0, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) cur[q][i] = nxt[q][i];
-    }
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int col = (ct0 + 2 * q) * 32 + r;
-    if (q >= nmy || col >= fa.f_out) continue;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (tg[v] < 0) continue;               // unused slot, or a piece of a split row
-      const float zz = z[q][v];
-      if (fa.Z) fa.Z[(int64_t)tg[v] * fa.f_out + col] = zz;
-      if (fa.Hout) fa.Hout[(int64_t)tg[v] * fa.f_out + col] = fa.act == SAGNN_ACT_RELU ? (zz > 0.f ? zz : 0.f) : zz;
-    }
-  }
+  // tiles per pass: 4 at f = 256 (the LDS already limits a CU to two workgroups), 1 below
+  sweep_dense_epilogue<kRow, BF16, (FPL == 4 ? 4 : 1)>(lds_acc, piece_target, fa, wave, (int)lane);
 }
 
 // W (f_in x f_out, row-major fp32) -> [f_in / 8][NB] vectors of 8 bfloat16 (k fastest), NB = f_out
@@ -663,13 +683,17 @@ __global__ __launch_bounds__(256) void sweep_pack_w_kernel(const float* __restri
 // Column ids and values still arrive by scalar loads; a lane picks its group's pair with
 // selects (the row offset is multiplied on the scalar side first).  Flushes are per group:
 // lanes of other groups are masked off by the divergent branch.
-template <int V, int R, int U, bool BUF>
+// FUSE: 0 the product alone; 1 / 2 the layer form: the kernel ends with the dense transform of the
+// workgroup's rows (fp32 / bfloat16 operands, see sweep_dense_epilogue) instead of storing T (C is
+// then only written if the caller wants T as a by-product: fa.T).
+template <int V, int R, int U, bool BUF, int FUSE = 0>
 __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
     const uint32_t* __restrict__ code, const float* __restrict__ vals,
     const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
     const SpmmWsHeader* __restrict__ hdr, const float* __restrict__ B, float* __restrict__ C,
     float* __restrict__ partial, const int32_t* __restrict__ sync_off,
-    uint32_t* __restrict__ barrier, const float* __restrict__ sched, const SweepDims d) {
+    uint32_t* __restrict__ barrier, const float* __restrict__ sched, const SweepDims d,
+    const SweepFusedArgs fa) {
   using vec = typename Vec<V>::T;
   constexpr int LG = 64 / R;             // lanes per group = lanes per row
   constexpr int kRow = LG * V;           // floats per row of this launch
@@ -786,13 +810,23 @@ __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
     if (tgt == INT32_MIN) continue;
     vec r = *reinterpret_cast<const vec*>(my + slot * kRow);
     if (tgt >= 0) {
-      vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)tgt * d.ldc) + loff);
-      if (d.accumulate) r += *p;
-      *p = r;
+      if constexpr (FUSE != 0) {
+        if (fa.T) *reinterpret_cast<vec*>(reinterpret_cast<char*>(fa.T + (int64_t)tgt * kRow) + loff) = r;
+      } else {
+        vec* p = reinterpret_cast<vec*>(reinterpret_cast<char*>(C + (int64_t)tgt * d.ldc) + loff);
+        if (d.accumulate) r += *p;
+        *p = r;
+      }
     } else {
       const int64_t pi = -(int64_t)tgt - 1;
       *reinterpret_cast<vec*>(reinterpret_cast<char*>(partial + pi * d.f_total + d.col0) + loff) = r;
     }
+  }
+  if constexpr (FUSE != 0) {
+    // (whole workgroups: the launcher only takes this form when n_waves is a multiple of 4 and
+    // every wavefront owns 16 slots)
+    __syncthreads();
+    sweep_dense_epilogue<kRow, FUSE == 2, 1>(lds_acc, piece_target, fa, wave, (int)lane);
   }
 }
 
@@ -1214,10 +1248,22 @@ int resident_workgroups(const void* kern, size_t lds) {
 }
 }  // namespace
 
+namespace {
+// lane-group kernels: fuse = 0 product, 1 / 2 layer form with fp32 / bfloat16 operands
+template <int V, int R, bool BUF>
+auto group_kernel_of(int fuse) {
+  if (fuse == 1) return &spmm_sweep_group_kernel<V, R, 8, BUF, 1>;
+  if (fuse == 2) return &spmm_sweep_group_kernel<V, R, 8, BUF, 2>;
+  return &spmm_sweep_group_kernel<V, R, 8, BUF, 0>;
+}
+}  // namespace
+
 int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B,
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
-                 int32_t accumulate, int32_t f_total, hipStream_t s) {
+                 int32_t accumulate, int32_t f_total, hipStream_t s, const SweepFusedArgs* fused, int32_t fuse) {
   if (d.n_waves <= 0) return SAGNN_OK;
+  const SweepFusedArgs fa = fused ? *fused : SweepFusedArgs{};
+  if (!fused) fuse = 0;
   SweepDims sd{};
   sd.n_waves = d.n_waves; sd.ldb = ldb; sd.ldc = ldc; sd.f_total = f_total;
   sd.generation = d.generation; sd.col0 = col0; sd.accumulate = accumulate;
@@ -1275,10 +1321,11 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
                        reinterpret_cast<const SpmmWsHeader*>(ws + L.header), B + col0, C + col0,
                        reinterpret_cast<float*>(ws + L.partial),
                        reinterpret_cast<const int32_t*>(ws + L.sync_off), barrier,
-                       reinterpret_cast<const float*>(ws + L.sched), sd);
+                       reinterpret_cast<const float*>(ws + L.sched), sd, fa);
     SAGNN_LAUNCH_CHECK();
     return SAGNN_OK;
   };
+  if (fuse != 0 && d.groups != 2 && d.groups != 4) return SAGNN_EINVAL;   // (groups == 1: sweep_launch_fused)
   if (d.groups == 16)    // prepared for f = 16: four lanes per row
     return fw == 16 ? (buf ? go(spmm_sweep_perm_kernel<16, true>) : go(spmm_sweep_perm_kernel<16, false>))
                     : SAGNN_EINVAL;
@@ -1286,12 +1333,12 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
     return fw == 32 ? (buf ? go(spmm_sweep_perm_kernel<8, true>) : go(spmm_sweep_perm_kernel<8, false>))
                     : SAGNN_EINVAL;
   if (d.groups == 2) {   // prepared for f = 128: half a wavefront per row (or per half row at 64)
-    if (fw == 128) return buf ? go_group(spmm_sweep_group_kernel<4, 2, 8, true>) : go_group(spmm_sweep_group_kernel<4, 2, 8, false>);
-    if (fw == 64) return buf ? go_group(spmm_sweep_group_kernel<2, 2, 8, true>) : go_group(spmm_sweep_group_kernel<2, 2, 8, false>);
+    if (fw == 128) return buf ? go_group(group_kernel_of<4, 2, true>(fuse)) : go_group(group_kernel_of<4, 2, false>(fuse));
+    if (fw == 64) return buf ? go_group(group_kernel_of<2, 2, true>(fuse)) : go_group(group_kernel_of<2, 2, false>(fuse));
     return SAGNN_EINVAL;
   }
   if (d.groups == 4) {   // prepared for f = 64: a quarter wavefront per row
-    if (fw == 64) return buf ? go_group(spmm_sweep_group_kernel<4, 4, 8, true>) : go_group(spmm_sweep_group_kernel<4, 4, 8, false>);
+    if (fw == 64) return buf ? go_group(group_kernel_of<4, 4, true>(fuse)) : go_group(group_kernel_of<4, 4, false>(fuse));
     return SAGNN_EINVAL;
   }
   if (fw == 256) return buf ? go(spmm_sweep_kernel<4, 8, true>) : go(spmm_sweep_kernel<4, 8, false>);
@@ -1302,8 +1349,23 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
 
 int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B, int64_t ldb,
                        int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t bf16, hipStream_t s) {
-  if (d.n_waves <= 0 || (d.n_waves & 3) || d.groups != 1 || d.slots != kSweepSlots) return SAGNN_EINVAL;
+  if (d.n_waves <= 0 || (d.n_waves & 3) || d.slots != kSweepSlots) return SAGNN_EINVAL;
   if (!(f_in == 64 || f_in == 128 || f_in == 256) || fa.f_out <= 0 || fa.f_out > 256 || !fa.W) return SAGNN_EINVAL;
+  if (d.groups == 2 || d.groups == 4) {
+    // lane-group schedules: the same kernels as the product, with the dense transform compiled in
+    SweepFusedArgs fg = fa;
+    fg.Wp = nullptr;
+    if (bf16) {
+      const int32_t NB = (fa.f_out + 31) / 32 * 32;
+      __bf16* wp = reinterpret_cast<__bf16*>(ws + L.wpack);
+      hipLaunchKernelGGL(sweep_pack_w_kernel, dim3((unsigned)ceil_div((int64_t)(f_in / 8) * NB, 256)), dim3(256), 0, s,
+                         fa.W, f_in, fa.f_out, NB, wp);
+      SAGNN_LAUNCH_CHECK();
+      fg.Wp = wp;
+    }
+    return sweep_launch(d, L, ws, B, ldb, 0, f_in, kmax, nullptr, f_in, 0, f_in, s, &fg, bf16 ? 2 : 1);
+  }
+  if (d.groups != 1) return SAGNN_EINVAL;
   SweepDims sd{};
   sd.n_waves = d.n_waves; sd.ldb = ldb; sd.ldc = f_in; sd.f_total = f_in;
   sd.generation = d.generation; sd.col0 = 0; sd.accumulate = 0; sd.slots = kSweepSlots;

@@ -881,11 +881,31 @@ def test_gcn_layer_fwd_sweep_epilogue(prec, fin, fout, graph, monkeypatch):
                                     want_t=False, want_z=False)
     torch.cuda.synchronize()
     assert Zn is None and torch.equal(Hi, Z)
-    # a workspace with lane groups keeps the row-range form
+    # the schedules with lane groups (two / four rows of H per load) end with the same transform
     monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "2")
     if fin in (64, 128):
         ws2 = sagnn.spmm_csr_prepare(rp, ci, v, n, fin)
-        assert ws2.info()["groups"] > 1 and sagnn.gcn_layer_fwd_form(ws2, fin, fout, prec) == 1
+        assert ws2.info()["groups"] == (2 if fin == 128 else 4)
+        assert sagnn.gcn_layer_fwd_form(ws2, fin, fout, prec) == 2
+        Z0.fill_(float("nan"))
+        H0.fill_(float("nan"))
+        _, Zg, Hg = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws2,
+                                        want_t=False, out=(None, Z0, H0))
+        torch.cuda.synchronize()
+        assert_close(Zg, o["Z"], o["Zabs"], rtol, "sweep epilogue, lane groups, Z")
+        assert_close(Hg, o["H"], o["Zabs"], rtol, "sweep epilogue, lane groups, H'")
+    if fin == 64:
+        # a workspace prepared for 128 columns (two lane groups) serves a 64-wide layer
+        ws3 = sagnn.spmm_csr_prepare(rp, ci, v, n, 128)
+        assert ws3.info()["groups"] == 2 and sagnn.gcn_layer_fwd_form(ws3, 64, fout, prec) == 2
+        Z0.fill_(float("nan"))
+        _, Zw, _ = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws3,
+                                       want_t=False, want_h=False, out=(None, Z0, None))
+        torch.cuda.synchronize()
+        assert_close(Zw, o["Z"], o["Zabs"], rtol, "sweep epilogue, prepared 128 called 64")
+    # a workspace of the 256-wide schedule cannot serve... nothing: every width has a form; an
+    # unprepared call (no workspace) takes the row-range kernel
+    assert sagnn.gcn_layer_fwd_form(None, fin, fout, prec) == 1
 
 
 def test_gcn_layer_fwd_fused_degenerate_shapes():
