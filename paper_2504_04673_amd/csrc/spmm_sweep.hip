@@ -372,7 +372,7 @@ __device__ __forceinline__ void sweep_interval_barrier(uint32_t* __restrict__ co
 __device__ __forceinline__ void sweep_pace_until(uint64_t t0, float ticks) {
   const uint64_t deadline = t0 + (uint64_t)ticks;
   for (int i = 0; i < 2048; ++i) {
-    if (wall_clock64() >= deadline) break;
+    if ((uint64_t)wall_clock64() >= deadline) break;
     __builtin_amdgcn_s_sleep(8);
   }
 }
