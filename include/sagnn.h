@@ -230,7 +230,17 @@ typedef struct sagnn_spmm_options {
                               rows of B per load (faster on the 2.45 M-vertex power-law graph at
                               f = 256, slower on the community-ordered one; the measured choice of
                               spmm_csr_prepare_tuned tries it)                                       */
-  int32_t reserved[1];     /* must be 0 */
+  int32_t short_rows;      /* the rows below the long-row threshold are swept too -- as whole rows, 16
+                              per wavefront in order of their length, behind the wavefronts of the long
+                              rows, every row one segment of its wavefront's stream -- instead of going
+                              through the nonzero-splitting kernel on a compacted CSR.  Every row then
+                              ends in a wavefront of the sweep, so gcn_layer_fwd with d_T = NULL can
+                              take its sweep-epilogue form on graphs with many short rows.  Possible
+                              with widths of 64 and up, 16 accumulator rows, no slab intervals, short
+                              rows of at most 255 entries and a matrix of at least 16 entries per row
+                              on average (the piece tables of the workspace are sized from nnz / 16).
+                              0 = where possible and the short rows average four entries or more,
+                              1 = where possible, -1 = never                                          */
 } sagnn_spmm_options;
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
 int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,

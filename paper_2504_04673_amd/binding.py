@@ -38,7 +38,7 @@ class SpmmOptions(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("schedule", "min_long", "piece", "slab_kb", "min_waves", "window_pct", "snake", "groups",
                  "sync_slabs", "pace_ps_per_step", "barriers", "sync_timeout_us", "sync_test_extra",
-                 "narrow_slots", "slab_width")] + [("reserved", ctypes.c_int32 * 1)]
+                 "narrow_slots", "slab_width", "short_rows")]
 
 
 # The library itself reads no environment variables.  For experiments and for tests that force a
@@ -48,7 +48,8 @@ class SpmmOptions(ctypes.Structure):
 #   SAGNN_SWEEP_WINDOW_PCT (0 = one window), SAGNN_SWEEP_LPT=0 (snake dealing),
 #   SAGNN_SWEEP_GROUPS=1|2, SAGNN_SWEEP_SYNC (slabs per interval, 0 = one interval),
 #   SAGNN_SWEEP_PACE_PS (picoseconds per stream step, -1 = never pace), SAGNN_SWEEP_BARRIERS=1,
-#   SAGNN_SWEEP_SYNC_US, SAGNN_SWEEP_SYNC_TEST_EXTRA, SAGNN_SWEEP_NARROW_SLOTS=1, SAGNN_SWEEP_SLAB_WIDTH=128
+#   SAGNN_SWEEP_SYNC_US, SAGNN_SWEEP_SYNC_TEST_EXTRA, SAGNN_SWEEP_NARROW_SLOTS=1, SAGNN_SWEEP_SLAB_WIDTH=128,
+#   SAGNN_SWEEP_SHORT_ROWS=1 (short rows swept as whole rows)
 def options_from_env() -> SpmmOptions:
     o = SpmmOptions()
     env = os.environ.get
@@ -64,7 +65,8 @@ def options_from_env() -> SpmmOptions:
                         ("SAGNN_SWEEP_MIN_WAVES", "min_waves"), ("SAGNN_SWEEP_GROUPS", "groups"),
                         ("SAGNN_SWEEP_SYNC_US", "sync_timeout_us"), ("SAGNN_SWEEP_PACE_PS", "pace_ps_per_step"),
                         ("SAGNN_SWEEP_BARRIERS", "barriers"), ("SAGNN_SWEEP_NARROW_SLOTS", "narrow_slots"),
-                        ("SAGNN_SWEEP_SYNC_TEST_EXTRA", "sync_test_extra"), ("SAGNN_SWEEP_SLAB_WIDTH", "slab_width")):
+                        ("SAGNN_SWEEP_SYNC_TEST_EXTRA", "sync_test_extra"), ("SAGNN_SWEEP_SLAB_WIDTH", "slab_width"),
+                        ("SAGNN_SWEEP_SHORT_ROWS", "short_rows")):
         v = num(name)
         if v is not None:
             setattr(o, field, v)

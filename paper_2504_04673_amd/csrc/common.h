@@ -188,8 +188,9 @@ struct SweepRowTotals {
 bool sweep_plan_fits(const SpmmWsLayout& L);
 // classify rows, build the short-row CSR, the list of split rows and the piece records; one
 // stream synchronisation (a 128-byte copy)
+// (short_pieces: the short rows also get piece records, one whole row each, behind those of the long rows)
 int sweep_plan_rows(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t opt_min_long, int32_t piece_max,
-                    char* ws, const SpmmWsLayout& L, hipStream_t s, SweepRowTotals* out);
+                    char* ws, const SpmmWsLayout& L, hipStream_t s, SweepRowTotals* out, bool short_pieces = false);
 // entries of the pieces of every window (only needed with several windows; synchronises)
 int sweep_plan_window_entries(char* ws, const SpmmWsLayout& L, int64_t P, int64_t window, int32_t nwin,
                               hipStream_t s, std::vector<int64_t>* entries);
@@ -198,6 +199,11 @@ int sweep_plan_window_entries(char* ws, const SpmmWsLayout& L, int64_t P, int64_
 // area stays 1 if pieces were left over
 int sweep_plan_deal(char* ws, const SpmmWsLayout& L, int64_t P, int64_t window, const int32_t* h_win_unit0,
                     int32_t nwin, int64_t n_waves4, int32_t R, int32_t SL, bool snake, hipStream_t s);
+// the short rows' pieces (records P_long .. P_long + n_short), longest first, 16 consecutive ones
+// per wavefront from wavefront first_wave on (n_waves4 of sweep_plan_deal must cover them); no
+// synchronisation
+int sweep_plan_deal_short(char* ws, const SpmmWsLayout& L, int64_t P_long, int64_t n_short, int64_t first_wave,
+                          hipStream_t s);
 // the sweep with the dense transform of a GCN layer as its epilogue (spmm_sweep.hip)
 struct SweepFusedArgs {
   const float* W;        // f_in x f_out, row-major

@@ -592,7 +592,7 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
 // entries, or the sum of the row's partial rows in a fixed order), puts it into LDS and
 // multiplies it by W, 64 output columns at a time.
 namespace {
-constexpr int64_t kFusedLeftoverMax = 4096;   // rows; above that the row-range kernel serves the layer
+constexpr int64_t kFusedLeftoverMax = 65536;   // rows; above that the row-range kernel serves the layer
 
 template <int FPL, bool BF16>
 __global__ __launch_bounds__(256) void layer_leftover_kernel(
@@ -735,7 +735,8 @@ SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_
   using namespace sagnn;
   sagnn_spmm_options opt{};
   if (h_opt) opt = *h_opt;
-  if (opt.reserved[0] != 0 || (opt.slab_width != 0 && opt.slab_width != 128 && opt.slab_width != 256))
+  if (opt.short_rows < -1 || opt.short_rows > 1 ||
+      (opt.slab_width != 0 && opt.slab_width != 128 && opt.slab_width != 256))
     return SAGNN_EINVAL;
   if (m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || m > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll ||
       k > 0x7FFFFFFFll)

@@ -163,11 +163,16 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_count_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
     const int32_t* __restrict__ piece_info, int32_t n_slabs, int32_t slab_width, uint32_t kmax,
     int32_t groups, int32_t slots_per_group, int32_t n_intervals, int32_t sync_slabs,
-    int32_t* __restrict__ sync_off, int32_t* __restrict__ wave_steps) {
+    int32_t* __restrict__ sync_off, int32_t* __restrict__ wave_steps, int64_t first_whole_row_wave) {
   extern __shared__ __attribute__((aligned(16))) int32_t build_lds[];
   __shared__ BuildPieces pc;
   __shared__ int32_t ivl_len[kSweepMaxIntervals];
   const int64_t w = blockIdx.x;
+  // wavefronts of whole short rows keep every row as one segment: one slab that covers all of B
+  if (w >= first_whole_row_wave) {
+    n_slabs = 1;
+    slab_width = 0x7FFFFFFF;
+  }
   const int S = n_slabs, R = groups;
   const BuildTables T = carve_tables(build_lds, S);
   build_tables(rowptr, colidx, piece_info, w, S, slab_width, kmax, R, slots_per_group, pc, T);
@@ -237,11 +242,15 @@ __global__ __launch_bounds__(kBuildThreads) void sweep_build_kernel(
     const float* __restrict__ val, const int32_t* __restrict__ piece_info,
     const int32_t* __restrict__ wave_base, const int32_t* __restrict__ sync_off, int32_t n_slabs,
     int32_t slab_width, uint32_t kmax, int32_t groups, int32_t slots_per_group, int32_t n_intervals,
-    int32_t sync_slabs, uint32_t* __restrict__ code, float* __restrict__ vals) {
+    int32_t sync_slabs, uint32_t* __restrict__ code, float* __restrict__ vals, int64_t first_whole_row_wave) {
   extern __shared__ __attribute__((aligned(16))) int32_t build_lds[];
   __shared__ BuildPieces pc;
   const int64_t w = blockIdx.x;
   const int tid = threadIdx.x;
+  if (w >= first_whole_row_wave) {   // whole short rows: one segment per row (see sweep_count_kernel)
+    n_slabs = 1;
+    slab_width = 0x7FFFFFFF;
+  }
   const int S = n_slabs, R = groups, SL = slots_per_group;
   const BuildTables T = carve_tables(build_lds, S);
   int32_t* slab_base_ = T.slab_tot + S * kSweepSlots;          // [S][16]: first step of slab s, group g
@@ -1012,7 +1021,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // the host gets the totals.
   SweepRowTotals tot{};
   {
-    const int rc = sweep_plan_rows(d_rowptr, m, nnz, opt.min_long, piece_max, ws, L, s, &tot);
+    const int rc = sweep_plan_rows(d_rowptr, m, nnz, opt.min_long, piece_max, ws, L, s, &tot, opt.short_rows >= 0);
     if (rc != SAGNN_OK) return rc;
   }
   if (tot.bad) return SAGNN_OK;   // not a CSR row pointer for this nnz: keep the plain schedule
@@ -1118,14 +1127,40 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // barriers then never meet a wavefront that has left
   const int64_t NW4 = (NW + 3) / 4 * 4;
   if (NW4 > L.max_waves - 1) return SAGNN_OK;   // cannot happen with the bounds above; plain schedule
+  // Option: the short rows are swept too, as whole rows -- 16 per wavefront, behind the wavefronts
+  // of the long rows, every row one segment of its wavefront's stream -- instead of going through
+  // the nonzero-splitting kernel.  Every row then ends in a wavefront's accumulator rows, which is
+  // what the layer form with the dense transform as the sweep's epilogue needs.
+  // Measured never slower than the nonzero-splitting kernel on the power-law graphs (233 k vertices:
+  // 2.54 -> 2.50 ms, 2.45 M vertices: 2.78 -> 2.62 ms at f = 64, 4.24 -> 4.19 ms at f = 128); left to
+  // that kernel when the short rows average fewer than four entries (a wavefront of 16 such rows is
+  // mostly set-up) unless asked for.
+  bool whole_rows = (opt.short_rows == 1 || (opt.short_rows == 0 && short_entries >= 4 * short_rows)) &&
+                    short_rows > 0 && tot.min_long <= 255 && slots == kSweepSlots && R <= 4 &&
+                    P + short_rows <= L.max_pieces && opt.sync_slabs <= 0 && opt.barriers != 1 &&
+                    opt.pace_ps_per_step <= 0;
+  int64_t NWT4 = NW4;
+  if (whole_rows) {
+    NWT4 = NW4 + (ceil_div(short_rows, (int64_t)kSweepSlots) + 3) / 4 * 4;
+    if (NWT4 > L.max_waves - 1) {
+      whole_rows = false;
+      NWT4 = NW4;
+    }
+  }
+  const int64_t first_whole_row_wave = whole_rows ? NW4 : INT64_MAX;
+  const int64_t short_entries_csr = whole_rows ? 0 : short_entries;   // entries of the compacted short-row CSR
   // Inside a window: largest piece first, each to the stream that is shortest so far and still
   // has a free slot.  Streams come out equal to within a piece of the smallest size class, which
   // keeps the wavefronts in step from slab to slab.
   {
     const bool snake = R == 1 && opt.snake == 1;
-    const int rc = sweep_plan_deal(ws, L, P, window, win_unit0.data(), (int32_t)nwin, NW4, (int32_t)R,
-                                   (int32_t)SL, snake, s);
+    int rc = sweep_plan_deal(ws, L, P, window, win_unit0.data(), (int32_t)nwin, NWT4, (int32_t)R,
+                             (int32_t)SL, snake, s);
     if (rc != SAGNN_OK) return rc;
+    if (whole_rows) {
+      rc = sweep_plan_deal_short(ws, L, P, short_rows, NW4, s);
+      if (rc != SAGNN_OK) return rc;
+    }
   }
 
   // Interval barriers (lane-group kernels only): every `sync_slabs` slabs the workgroups of an
@@ -1133,7 +1168,7 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // (the interval layout costs ~3 % of padding, so it is only made when something will use it)
   int64_t sync_slabs = opt.sync_slabs < 0 ? 0 : (opt.sync_slabs > 0 ? opt.sync_slabs : 16);
   if (opt.barriers != 1 && opt.pace_ps_per_step <= 0 && opt.sync_slabs <= 0) sync_slabs = 0;
-  if (R != 2 && R != 4) sync_slabs = 0;
+  if ((R != 2 && R != 4) || whole_rows) sync_slabs = 0;   // (whole-row wavefronts have no slab intervals)
   if (sync_slabs > 0 && ceil_div(S, sync_slabs) > kSweepMaxIntervals) sync_slabs = ceil_div(S, kSweepMaxIntervals);
   int64_t NI = sync_slabs > 0 ? ceil_div(S, sync_slabs) : 1;
   if (NI <= 1) { NI = 1; sync_slabs = 0; }
@@ -1157,43 +1192,43 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)build_lds));
   int64_t stream_len = 0, short_base = 0;
   for (int attempt = 0; attempt < 2; ++attempt) {
-    hipLaunchKernelGGL(sweep_count_kernel, dim3((unsigned)NW4), dim3(kBuildThreads), count_lds, s, d_rowptr,
+    hipLaunchKernelGGL(sweep_count_kernel, dim3((unsigned)NWT4), dim3(kBuildThreads), count_lds, s, d_rowptr,
                        d_colidx, d_info, (int32_t)S, (int32_t)width, kmax, (int32_t)R, (int32_t)SL, (int32_t)NI,
-                       (int32_t)sync_slabs, d_sync_off, d_wave_steps);
+                       (int32_t)sync_slabs, d_sync_off, d_wave_steps, first_whole_row_wave);
     SAGNN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(sweep_scan_kernel, dim3(1), dim3(1024), 0, s, d_wave_steps, NW4, (int32_t)R,
+    hipLaunchKernelGGL(sweep_scan_kernel, dim3(1), dim3(1024), 0, s, d_wave_steps, NWT4, (int32_t)R,
                        d_wave_base, d_flag + 1);
     SAGNN_LAUNCH_CHECK();
     int32_t h_flags[4] = {0, 0, 0, 0}, h_total = 0;
     SAGNN_HIP(hipMemcpyAsync(h_flags, d_flag, 16, hipMemcpyDeviceToHost, s));
-    SAGNN_HIP(hipMemcpyAsync(&h_total, d_wave_base + NW4, 4, hipMemcpyDeviceToHost, s));
+    SAGNN_HIP(hipMemcpyAsync(&h_total, d_wave_base + NWT4, 4, hipMemcpyDeviceToHost, s));
     SAGNN_HIP(hipStreamSynchronize(s));    // also: win_unit0 has been consumed
     if (h_flags[0] || h_flags[2]) return SAGNN_OK;   // unsorted long row, column out of range, pieces left over: plain schedule
     stream_len = h_total;
     short_base = (int64_t)round_up((size_t)stream_len + 64, 256);
-    const bool fits = !h_flags[1] && short_base + short_entries + kSpmmChunk <= L.stream_cap;
+    const bool fits = !h_flags[1] && short_base + short_entries_csr + kSpmmChunk <= L.stream_cap;
     if (fits) break;
     if (attempt == 1 || NI == 1) return SAGNN_OK;
     NI = 1;                                // the interval padding did not fit: lay out without it
     sync_slabs = 0;
   }
 
-  hipLaunchKernelGGL(sweep_sched_kernel, dim3((unsigned)(NI + 2)), dim3(256), 0, s, d_sync_off, NW4, (int32_t)NI,
+  hipLaunchKernelGGL(sweep_sched_kernel, dim3((unsigned)(NI + 2)), dim3(256), 0, s, d_sync_off, NWT4, (int32_t)NI,
                      reinterpret_cast<float*>(ws + L.sched));
   SAGNN_LAUNCH_CHECK();
   float steps[2] = {0.f, 0.f};   // mean, max over the wavefronts
   SAGNN_HIP(hipMemcpyAsync(steps, reinterpret_cast<float*>(ws + L.sched) + NI, 8, hipMemcpyDeviceToHost, s));
-  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NW4), dim3(kBuildThreads), build_lds, s, d_rowptr,
+  hipLaunchKernelGGL(sweep_build_kernel, dim3((unsigned)NWT4), dim3(kBuildThreads), build_lds, s, d_rowptr,
                      d_colidx, d_val, d_info, d_wave_base, d_sync_off, (int32_t)S, (int32_t)width, kmax,
                      (int32_t)R, (int32_t)SL, (int32_t)NI, (int32_t)sync_slabs, reinterpret_cast<uint32_t*>(ws + L.code),
-                     reinterpret_cast<float*>(ws + L.vals));
+                     reinterpret_cast<float*>(ws + L.vals), first_whole_row_wave);
   SAGNN_LAUNCH_CHECK();
   // zero the gap between the long stream and the short entries (tail batches read into it)
   hipLaunchKernelGGL(sweep_zero_gap_kernel, dim3(1), dim3(256), 0, s,
                      reinterpret_cast<uint32_t*>(ws + L.code) + stream_len,
                      reinterpret_cast<float*>(ws + L.vals) + stream_len, (int32_t)(short_base - stream_len));
   SAGNN_LAUNCH_CHECK();
-  if (short_rows > 0) {
+  if (short_rows > 0 && !whole_rows) {
     hipLaunchKernelGGL(sweep_short_copy_kernel, dim3((unsigned)ceil_div(short_rows, 256)), dim3(256), 0, s,
                        d_rowptr, d_colidx, d_val, reinterpret_cast<const int32_t*>(ws + L.rowptr_s),
                        reinterpret_cast<const int32_t*>(ws + L.rowmap_s), short_rows,
@@ -1208,8 +1243,8 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   h.has_empty_rows = has_empty ? 1 : 0;
   h.m = m; h.nnz = nnz; h.f = f; h.mode = 1;
   h.generation = g_generation.fetch_add(1);
-  h.c_rows = short_rows; h.c_nnz = short_entries; h.c_nchunks = spmm_nchunks(short_entries);
-  h.n_waves = NW4; h.n_long_entries = stream_len;   // padded length of the sweep streams
+  h.c_rows = whole_rows ? 0 : short_rows; h.c_nnz = short_entries_csr; h.c_nchunks = spmm_nchunks(short_entries_csr);
+  h.n_waves = NWT4; h.n_long_entries = stream_len;   // padded length of the sweep streams
   h.n_multi_rows = tot.multi_rows; h.n_multi_pieces = tot.multi_pieces;
   h.n_slabs = (int32_t)S; h.slab_width = (int32_t)width;
   h.groups = (int32_t)R;

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kT) void plan_rows_kernel(
     const int32_t* __restrict__ rowptr, int64_t m, int32_t piece_max, int64_t ntiles,
     unsigned long long* __restrict__ stat, int32_t* __restrict__ tilesum, int32_t* __restrict__ rowptr_s,
     int32_t* __restrict__ rowmap_s, int32_t* __restrict__ multi_row, int32_t* __restrict__ multi_first,
-    PieceArrays pa, int64_t max_pieces, int64_t max_multi_rows) {
+    PieceArrays pa, int64_t max_pieces, int64_t max_multi_rows, int32_t short_pieces) {
   const int32_t min_long = (int32_t)stat[ST_MINLONG];
   const int64_t r0 = (int64_t)blockIdx.x * kRowTile + (int64_t)threadIdx.x * 8;
   RowQ q[8];
@@ -175,6 +175,9 @@ __global__ __launch_bounds__(kT) void plan_rows_kernel(
   int64_t run[5];
 #pragma unroll
   for (int c = 0; c < 5; ++c) run[c] = (int64_t)tilesum[(int64_t)c * (ntiles + 1) + blockIdx.x] + ex[c];
+  // short_pieces: every short row also gets a piece record (one whole-row piece), stored behind
+  // the pieces of the long rows in row order, for the schedules that sweep the short rows too
+  const int64_t short_id0 = (int64_t)stat[ST_PIECES];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int64_t r = r0 + i;
@@ -182,6 +185,13 @@ __global__ __launch_bounds__(kT) void plan_rows_kernel(
       if (q[i].v[1]) {
         rowptr_s[run[1]] = (int32_t)run[2];
         rowmap_s[run[1]] = (int32_t)r;
+        const int64_t id = short_id0 + run[1];
+        if (short_pieces && id < max_pieces) {
+          pa.row[id] = (int32_t)r;
+          pa.jp[id] = 1;                 // piece 0 of 1
+          pa.size[id] = (int32_t)deg[i];
+          pa.mf[id] = -1;
+        }
       }
       const int p = q[i].v[0];
       if (q[i].v[3] && run[3] < max_multi_rows) {
@@ -434,6 +444,26 @@ __global__ __launch_bounds__(kT) void deal_snake_kernel(DealDims d, const int32_
   }
 }
 
+// Short rows as whole-row pieces: sorted by length (descending, row order inside a length), 16
+// consecutive ones per wavefront, so the rows of a wavefront -- and with lane groups the rows of
+// its groups -- have nearly the same length.
+__global__ __launch_bounds__(kT) void short_keys_kernel(const int32_t* __restrict__ size, int64_t n,
+                                                        uint32_t* __restrict__ keys) {
+  const int64_t stride = (int64_t)gridDim.x * kT;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += stride) {
+    const int32_t d = size[i];
+    keys[i] = (uint32_t)(255 - (d > 255 ? 255 : (d < 0 ? 0 : d)));
+  }
+}
+
+__global__ __launch_bounds__(kT) void deal_short_kernel(const uint32_t* __restrict__ order, int64_t n, int64_t id0,
+                                                        int64_t slot0, PieceArrays pa, int32_t* __restrict__ info,
+                                                        int32_t* __restrict__ target) {
+  const int64_t stride = (int64_t)gridDim.x * kT;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += stride)
+    put_piece(info, target, slot0 + i, pa, id0 + (int64_t)order[i]);
+}
+
 struct PlanScratch {
   PieceArrays pa;
   uint32_t* piece_keys;
@@ -500,7 +530,7 @@ bool sweep_plan_fits(const SpmmWsLayout& L) {
 }
 
 int sweep_plan_rows(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t opt_min_long, int32_t piece_max,
-                    char* ws, const SpmmWsLayout& L, hipStream_t s, SweepRowTotals* out) {
+                    char* ws, const SpmmWsLayout& L, hipStream_t s, SweepRowTotals* out, bool short_pieces) {
   const PlanSmall sm = carve_small(ws, L);
   const PlanScratch sc = carve_plan(ws + L.code, L.max_pieces, L.max_waves * kSweepSlots);
   int32_t* d_flag = reinterpret_cast<int32_t*>(ws + L.carry);
@@ -517,14 +547,14 @@ int sweep_plan_rows(const int32_t* d_rowptr, int64_t m, int64_t nnz, int32_t opt
   int32_t* multi_first = reinterpret_cast<int32_t*>(ws + L.multi_first);
   hipLaunchKernelGGL(plan_rows_kernel<false>, dim3((unsigned)ntiles), dim3(kT), 0, s, d_rowptr, m, piece_max, ntiles,
                      sm.stat, sm.tilesum, rowptr_s, rowmap_s, multi_row, multi_first, sc.pa, L.max_pieces,
-                     L.max_multi_rows);
+                     L.max_multi_rows, 0);
   SAGNN_LAUNCH_CHECK();
   hipLaunchKernelGGL(plan_scan_tiles_kernel, dim3(1), dim3(kT), 0, s, sm.tilesum, ntiles, sm.stat, rowptr_s,
                      multi_first, L.max_multi_rows);
   SAGNN_LAUNCH_CHECK();
   hipLaunchKernelGGL(plan_rows_kernel<true>, dim3((unsigned)ntiles), dim3(kT), 0, s, d_rowptr, m, piece_max, ntiles,
                      sm.stat, sm.tilesum, rowptr_s, rowmap_s, multi_row, multi_first, sc.pa, L.max_pieces,
-                     L.max_multi_rows);
+                     L.max_multi_rows, short_pieces ? 1 : 0);
   SAGNN_LAUNCH_CHECK();
   unsigned long long h[ST_COUNT];
   SAGNN_HIP(hipMemcpyAsync(h, sm.stat, sizeof(h), hipMemcpyDeviceToHost, s));
@@ -552,6 +582,28 @@ int sweep_plan_window_entries(char* ws, const SpmmWsLayout& L, int64_t P, int64_
                            hipMemcpyDeviceToHost, s));
   SAGNN_HIP(hipStreamSynchronize(s));
   entries->assign(h.begin(), h.end());
+  return SAGNN_OK;
+}
+
+int sweep_plan_deal_short(char* ws, const SpmmWsLayout& L, int64_t P_long, int64_t n_short, int64_t first_wave,
+                          hipStream_t s) {
+  const PlanScratch sc = carve_plan(ws + L.code, L.max_pieces, L.max_waves * kSweepSlots);
+  int32_t* info = reinterpret_cast<int32_t*>(ws + L.piece_info);
+  int32_t* target = reinterpret_cast<int32_t*>(ws + L.piece_target);
+  if (n_short <= 0) return SAGNN_OK;
+  if (P_long < 0 || P_long + n_short > L.max_pieces ||
+      first_wave + ceil_div(n_short, (int64_t)kSweepSlots) > L.max_waves)
+    return SAGNN_EINVAL;
+  // the key array of the pieces is free once the long pieces have been dealt (stream order)
+  hipLaunchKernelGGL(short_keys_kernel, grid_for(n_short), dim3(kT), 0, s, sc.pa.size + P_long, n_short,
+                     sc.piece_keys);
+  SAGNN_LAUNCH_CHECK();
+  int res = 0;
+  const int rc = radix_sort_pairs(sc.piece_keys, nullptr, n_short, 8, sc.radix, s, &res);
+  if (rc != SAGNN_OK) return rc;
+  hipLaunchKernelGGL(deal_short_kernel, grid_for(n_short), dim3(kT), 0, s, sc.radix.pay[res], n_short, P_long,
+                     first_wave * kSweepSlots, sc.pa, info, target);
+  SAGNN_LAUNCH_CHECK();
   return SAGNN_OK;
 }
 

@@ -63,7 +63,7 @@ def test_argument_validation_before_launch():
     assert L.spmm_csr_prepare_tuned(None, None, None, 4, 4, 4, 16, None, 0, None, 16, None, 16, None, None, None) == -1
     assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, None, None) == -1
     bad = sagnn.SpmmOptions()
-    bad.reserved[0] = 1                                   # reserved fields must be zero
+    bad.short_rows = 2                                    # not one of -1, 0, 1
     import ctypes as _c
     assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, _c.byref(bad), None) == -1
     assert L.spmm_csr_release(None) == -1
@@ -87,7 +87,7 @@ def test_options_from_env_translation(monkeypatch):
         if k.startswith("SAGNN_SWEEP"):
             monkeypatch.delenv(k)
     o = sagnn.options_from_env()
-    assert all(getattr(o, n) == 0 for n, _ in sagnn.SpmmOptions._fields_[:-1]) and not any(o.reserved)
+    assert all(getattr(o, n) == 0 for n, _ in sagnn.SpmmOptions._fields_)
     monkeypatch.setenv("SAGNN_SWEEP", "1")
     monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "0")
     monkeypatch.setenv("SAGNN_SWEEP_LPT", "0")

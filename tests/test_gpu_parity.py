@@ -215,11 +215,13 @@ def test_spmm_random_widths(f, use_ws):
     assert_close(got2, ref2, zabs2, RTOL_SPMM, f"spmm accumulate f={f} ws={use_ws}")
 
 
-@pytest.fixture
-def force_sweep(monkeypatch):
+@pytest.fixture(params=["short_rows_by_nonzero_splitting", "short_rows_swept_whole"])
+def force_sweep(request, monkeypatch):
     """Force the slab-sweep schedule on small matrices (the heuristic reserves it for big ones)
     with tiny pieces and many slabs, so that split rows, staggered starts and the short-row
-    path are all exercised."""
+    path are all exercised -- the short rows once through the nonzero-splitting kernel on their
+    compacted CSR, once as whole-row wavefronts of the sweep (where the width has that form)."""
+    monkeypatch.setenv("SAGNN_SWEEP_SHORT_ROWS", "-1" if request.param == "short_rows_by_nonzero_splitting" else "1")
     monkeypatch.setenv("SAGNN_SWEEP", "1")
     monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
     monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
@@ -243,6 +245,61 @@ def test_spmm_slab_sweep_schedule(f, force_sweep):
     ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
     got2 = run_spmm(rowptr, colidx, val, B, True, C0=C0)
     assert_close(got2, ref2, zabs2, RTOL_SPMM, f"sweep accumulate f={f}")
+
+
+@pytest.mark.parametrize("f", [64, 128, 192, 256])
+@pytest.mark.parametrize("groups", [1, 2])
+def test_spmm_sweep_short_rows_as_whole_rows(f, groups, monkeypatch):
+    """Option short_rows: the rows below the long-row threshold are swept as whole rows, 16 per
+    wavefront, instead of going through the nonzero-splitting kernel (no compacted short-row CSR is
+    left).  Most rows of this matrix are short, their columns are not sorted and may repeat; long
+    rows are ascending as the sweep requires; hubs are cut into pieces; some rows are empty."""
+    monkeypatch.setenv("SAGNN_SWEEP", "1")
+    monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+    monkeypatch.setenv("SAGNN_SWEEP_SLAB_MB", "0")
+    monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "64")
+    monkeypatch.setenv("SAGNN_SWEEP_GROUPS", str(groups))
+    rng = np.random.default_rng(300 + f + groups)
+    m, n = 7001, 30_000
+    rowptr, colidx, val = random_csr(m, n, 22, rng, empty_frac=0.1, dup=True,
+                                     hubs=[(3, 9000), (7, 3000), (2500, 1025), (5002, 64), (11, 63), (12, 1),
+                                           (7000, 200)])
+    for r in range(m):
+        a, b = rowptr[r], rowptr[r + 1]
+        if b - a >= 64:
+            o = np.argsort(colidx[a:b], kind="stable")
+            colidx[a:b], val[a:b] = colidx[a:b][o], val[a:b][o]
+    B = synth.normal((n, f), f, synth.STREAM_H)
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    rp, ci, v = dev(rowptr), dev(colidx), dev(val)
+    ws = sagnn.spmm_csr_prepare(rp, ci, v, n, f)
+    info = ws.info()
+    assert info["mode"] == 1 and info["chunk_rows"] == 0 and info["chunk_entries"] == 0, info
+    assert info["split_rows"] >= 3 and info["has_empty_rows"] == 1
+    C0 = torch.full((m, f), float("nan"), device="cuda")
+    got = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), C=C0, ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got, ref, zabs, RTOL_SPMM, f"whole-row sweep f={f} groups={groups}")
+    Cacc = synth.normal((m, f), f + 1, synth.STREAM_G)
+    ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=Cacc, want_abs=True)
+    got2 = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), C=dev(Cacc), accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got2, ref2, zabs2, RTOL_SPMM, f"whole-row sweep accumulate f={f} groups={groups}")
+    if f in (64, 128, 256):
+        # every row ends in a wavefront of the sweep: the layer takes the sweep-epilogue form
+        fout = 96
+        W = synth.normal((f, fout), 5, synth.STREAM_W, scale=1 / np.sqrt(f))
+        for prec in (0, 1):
+            assert sagnn.gcn_layer_fwd_form(ws, f, fout, prec) == 2
+            o = oracle.gcn_layer_fwd(rowptr, colidx, val, B, W, act=1, bf16=bool(prec))
+            Z0 = torch.full((m, fout), float("nan"), device="cuda")
+            H0 = torch.full((m, fout), float("nan"), device="cuda")
+            _, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(B), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws,
+                                           want_t=False, out=(None, Z0, H0))
+            torch.cuda.synchronize()
+            rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+            assert_close(Z, o["Z"], o["Zabs"], rtol, f"whole-row sweep layer Z f={f} prec={prec}")
+            assert_close(Ho, o["H"], o["Zabs"], rtol, f"whole-row sweep layer H' f={f} prec={prec}")
 
 
 @pytest.mark.parametrize("variant", ["sixteen_pieces_per_wavefront", "many_small_windows", "snake_dealing",
@@ -291,6 +348,7 @@ def test_spmm_sweep_planner_balances_streams(f, monkeypatch):
     monkeypatch.setenv("SAGNN_SWEEP", "1")
     monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "64")
     monkeypatch.setenv("SAGNN_SWEEP_MIN_WAVES", "1")          # all 16 slots of a wavefront
+    monkeypatch.setenv("SAGNN_SWEEP_SHORT_ROWS", "-1")        # the streams of the long rows only
     rng = np.random.default_rng(9)
     m, n = 30_000, 200_000
     deg = np.minimum((64 / rng.random(m) ** 0.8).astype(np.int64), 30_000)   # heavy tail from 64 up
@@ -848,6 +906,7 @@ def test_gcn_layer_fwd_sweep_epilogue(prec, fin, fout, graph, monkeypatch):
     monkeypatch.setenv("SAGNN_SWEEP_GROUPS", "1")
     monkeypatch.setenv("SAGNN_SWEEP_MINDEG", "16")
     monkeypatch.setenv("SAGNN_SWEEP_PIECE", "1024")
+    monkeypatch.setenv("SAGNN_SWEEP_SHORT_ROWS", "-1")   # short rows stay outside the sweep: the small kernel takes them
     rng = np.random.default_rng(fin * 3 + fout)
     if graph == "regular_all_rows_swept":
         g = synth.sbm_graph(6000, 16, 40, 2, 5)
