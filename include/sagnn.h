@@ -173,6 +173,9 @@ int spmm_pack_rows(const float* d_H, int64_t n, int64_t ldh, int32_t f, const in
  *     At f = 128 and f = 64 the re-ordered copy is laid out for kernels that fetch two / four
  *     rows of B per load instruction, which a later call must match: a workspace prepared for
  *     f = 128 serves calls with f = 128 or 64, one prepared for f = 64 only f = 64.
+ *     The short rows are swept as well, as whole rows in wavefronts of their own, where the
+ *     matrix allows it (short_rows of sagnn_spmm_options); otherwise they go through the first
+ *     schedule on a compacted copy.
  * The workspace then holds a private copy of colidx/val: call spmm_csr_prepare() again if
  * they change.  d_ws must be passed unchanged to every spmm_csr_tallskinny() call with the
  * same (rowptr, colidx, val, m, k, nnz) and f <= the prepared f (a multiple of 64 if the
@@ -272,7 +275,8 @@ int spmm_csr_prepare_tuned(const int32_t* d_rowptr, const int32_t* d_colidx, con
                            int64_t ldc, int32_t* h_choice, const sagnn_spmm_options* h_opt,
                            void* stream);
 /* What spmm_csr_prepare() decided for a workspace (host query, no GPU work).  h_info[16]:
- * [0] schedule (0 nonzero splitting, 1 slab sweep + nonzero splitting for short rows),
+ * [0] schedule (0 nonzero splitting, 1 slab sweep, with nonzero splitting for the short rows
+ *     unless they are swept too: then [3] = [4] = [5] = 0),
  * [1] wavefront streams of the sweep, [2] entries in them, [3] rows, [4] entries and
  * [5] chunks of the nonzero-splitting part, [6] rows cut into several pieces,
  * [7] 1 if the matrix has empty rows, [8] barrier intervals of the sweep, [9] slabs per
@@ -337,8 +341,10 @@ int dense_gemm_act(const float* d_X, int64_t ldx, const float* d_W, int64_t ldw,
  * are correct but slow).  Same rounding bound as the two-kernel form.
  * With d_T == NULL and a workspace that was prepared for the slab sweep (spmm_csr_schedule_info:
  * schedule 1; f_in 64, 128 or 256 covered by one launch of the prepared kernels: 256 needs lane
- * groups 1, 128 lane groups 1 or 2, 64 any) whose wavefronts finish all but at most 4096 rows (rows outside the sweep and rows cut into
- * several pieces are the exceptions; a partitioned graph's blocks have none), the sweep kernel
+ * groups 1, 128 lane groups 1 or 2, 64 any) whose wavefronts finish all but at most 65536 rows
+ * (rows outside the sweep and rows cut into several pieces are the exceptions; a partitioned
+ * graph's blocks have none, a power-law graph whose short rows are swept as whole rows --
+ * short_rows of sagnn_spmm_options, the default where possible -- a few thousand), the sweep kernel
  * itself ends with the dense transform: a workgroup's 64 finished rows of A H are multiplied by
  * W on the matrix cores straight out of LDS, the few other rows go through a small kernel.
  * gcn_layer_fwd_form() tells which form a call would take.

@@ -17,8 +17,10 @@
 // (Starting the XCDs at different slabs was measured to be slower: it defeats that sharing.)
 // Per-piece accumulators live in LDS (a wavefront adds its register accumulator to the piece's
 // LDS row whenever a (piece, slab) segment ends), so nothing is spilled to HBM between slabs.
-// Pieces of a split row are summed in a fixed order by a small second kernel.  Short rows go
-// through the nonzero-splitting kernels of spmm.hip on a compacted CSR.
+// Pieces of a split row are summed in a fixed order by a small second kernel.  Short rows are
+// swept as whole rows -- 16 per wavefront, each one segment, in wavefronts of their own -- where
+// the matrix allows it, else they go through the nonzero-splitting kernels of spmm.hip on a
+// compacted CSR.
 //
 // The entry stream of a wavefront is stored in the workspace as (code, value) pairs sorted by
 // (slab, piece): code = column | piece_slot << 27 | segment_end << 31.  At f = 128 / 64 a
