@@ -307,6 +307,17 @@ def main():
                 if own:
                     plain = timed(lambda: sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, va, Hn, C=T, ws=ws_e))
                     out["fused_layer"]["sweep_epilogue_schedule_spmm_ms"] = round(plain, 4)
+            if prec == sagnn.GEMM_FP32 and sagnn.gcn_layer_fwd_form(ws_e, f, f_out, sagnn.GEMM_BF16) == 2:
+                # the same comparison with bfloat16 operands on the matrix cores (the epilogue's matrix
+                # instructions are what it adds to a workgroup's time, and they are 8x shorter)
+                ep16 = timed(lambda: sagnn.gcn_layer_fwd(rp, plan.colidx_compact, va, Hn, W, act=sagnn.ACT_RELU,
+                                                         prec=sagnn.GEMM_BF16, ws=ws_e, want_t=False, want_z=False,
+                                                         out=(None, None, Ho)))
+                g16 = timed(lambda: sagnn.dense_gemm_act(T, W, prec=sagnn.GEMM_BF16, act=sagnn.ACT_RELU,
+                                                         want_z=False, want_act=True, out=(None, Ho)))
+                out["fused_layer"]["bf16_operands"] = {"sweep_epilogue_ms": round(ep16, 4),
+                                                       "split_ms": round(spmm_ms + g16, 4),
+                                                       "split_gemm_ms": round(g16, 4)}
             if own:
                 ws_e.release()
         except sagnn.SagnnError as e:
