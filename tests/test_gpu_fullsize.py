@@ -105,6 +105,15 @@ def test_cfg2_full_path():
     # the dense stage alone, on the library's own T (scale |T| |W|)
     zt, ztabs = oracle.gemm(T[sel].cpu().numpy(), W, want_abs=True)
     assert_close(Z[sel], zt, ztabs, RTOL_GEMM, "cfg2 Z vs oracle GEMM of the library's T")
+    # the layer without T: the short rows of this graph are swept as whole rows, so the sweep kernel
+    # itself ends with the dense transform
+    assert ws.info()["chunk_rows"] == 0 and sagnn.gcn_layer_fwd_form(ws, f, W.shape[1], sagnn.GEMM_FP32) == 2
+    _, Z2, H2 = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, dev(W), act=sagnn.ACT_RELU, ws=ws, want_t=False)
+    torch.cuda.synchronize()
+    assert_close(Z2[sel], zref, zabs, RTOL_GEMM, "cfg2 Z (sweep epilogue)")
+    assert_close(H2[sel], np.maximum(zref, 0), zabs, RTOL_GEMM, "cfg2 H' (sweep epilogue)")
+    assert torch.isfinite(Z2).all().item() and torch.equal(H2, torch.clamp_min(Z2, 0))
+    del Z2, H2
     check_eigenvector(g, f, ws, rp, plan.colidx_compact, v)
 
 
@@ -121,9 +130,27 @@ def test_cfg3_width_sweep():
         Hn = sagnn.spmm_pack_rows(dev(H), plan.needed)
         Z = sagnn.spmm_csr_tallskinny(rp, plan.colidx_compact, v, Hn, ws=ws)
         torch.cuda.synchronize()
-        check_spmm_full(g, Z, H, f"cfg3 f={f}")
+        tfull, tfabs, _ = check_spmm_full(g, Z, H, f"cfg3 f={f}")
         check_eigenvector(g, f, ws, rp, plan.colidx_compact, v)
-        del Hn, Z, ws
+        if f == 128:
+            # the schedule the benchmark times: 2.26 M short rows swept as whole rows behind the pieces
+            # of the long ones, and on it the layer without T (the sweep ends with the dense transform)
+            info = ws.info()
+            assert info["mode"] == 1 and info["chunk_rows"] == 0 and info["sweep_entries"] == g.nnz
+            Wf = np.ascontiguousarray(wl.W[:f, :f])
+            rows = pick_rows(g, 1500, 4)
+            sel = torch.from_numpy(rows).cuda()
+            for prec, rtol in ((sagnn.GEMM_FP32, RTOL_GEMM), (sagnn.GEMM_BF16, RTOL_BF16)):
+                assert sagnn.gcn_layer_fwd_form(ws, f, f, prec) == 2
+                _, Zl, Hl = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, dev(Wf), act=sagnn.ACT_RELU,
+                                                prec=prec, ws=ws, want_t=False)
+                torch.cuda.synchronize()
+                zref, zabs = oracle.gemm(tfull[rows], Wf, bf16=bool(prec), Xabs=tfabs[rows], want_abs=True)
+                assert_close(Zl[sel], zref, zabs, rtol, f"cfg3 layer Z (sweep epilogue, prec {prec})")
+                assert_close(Hl[sel], np.maximum(zref, 0), zabs, rtol, f"cfg3 layer H' (sweep epilogue, prec {prec})")
+                assert torch.isfinite(Zl).all().item() and torch.equal(Hl, torch.clamp_min(Zl, 0))
+                del Zl, Hl
+        del Hn, Z, ws, tfull, tfabs
 
 
 # ------------------------------------------------------------------------------------------ cfg4
