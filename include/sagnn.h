@@ -239,11 +239,9 @@ typedef struct sagnn_spmm_options {
                               through the nonzero-splitting kernel on a compacted CSR.  Every row then
                               ends in a wavefront of the sweep, so gcn_layer_fwd with d_T = NULL can
                               take its sweep-epilogue form on graphs with many short rows.  Possible
-                              with widths of 64 and up, 16 accumulator rows, no slab intervals, short
-                              rows of at most 255 entries and a matrix of at least 16 entries per row
-                              on average (the piece tables of the workspace are sized from nnz / 16).
-                              0 = where possible and the short rows average four entries or more,
-                              1 = where possible, -1 = never                                          */
+                              with widths of 64 and up, 16 accumulator rows, no slab intervals and
+                              short rows of at most 255 entries.
+                              0 or 1 = where possible, -1 = never                                     */
 } sagnn_spmm_options;
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
 int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,

@@ -91,16 +91,21 @@ inline int64_t spmm_nchunks(int64_t nnz) { return ceil_div(nnz, kSpmmChunk); }
 inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   SpmmWsLayout L{};
   L.max_chunks = spmm_nchunks(nnz) + 1;
-  // every long row has >= kSweepMinLong entries; splitting adds at most nnz/1024 pieces
-  L.max_pieces = nnz / kSweepMinLong + nnz / 1024 + kSweepSlots;
-  L.max_waves = ceil_div(L.max_pieces, kSweepSlots) + 1;
+  // every long row has >= kSweepMinLong entries; splitting adds at most nnz/1024 pieces; every
+  // short row may become a piece of its own (whole-row wavefronts behind those of the long rows)
+  const int64_t long_pieces = nnz / kSweepMinLong + nnz / 1024 + kSweepSlots;
+  const int64_t long_waves = ceil_div(long_pieces, kSweepSlots) + 1;
+  const int64_t short_waves = ceil_div(m, kSweepSlots) + 4;
+  L.max_pieces = long_pieces + m;
+  L.max_waves = long_waves + short_waves;
   L.max_multi_rows = nnz / 1024 + 1;
   L.max_multi_pieces = 2 * (nnz / 1024) + 2;
   // sweep streams + gap + short CSR entries + padding.  A wavefront's stream is padded to the
   // batch of 8 steps at every interval boundary; with lane groups (up to 4 zipped streams per
   // wavefront) also to the longest of its group streams inside every interval.  If a pattern
-  // needs more than this, the planner lays the streams out as one interval.
-  L.stream_cap = nnz + nnz / 4 + 256 * L.max_waves + 4 * kSpmmChunk;
+  // needs more than this, the planner lays the streams out as one interval.  A whole-row
+  // wavefront has one interval: at most 8 steps of padding for each of its up to 4 group streams.
+  L.stream_cap = nnz + nnz / 4 + 256 * long_waves + 32 * short_waves + 4 * kSpmmChunk;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   L.header = take(256);

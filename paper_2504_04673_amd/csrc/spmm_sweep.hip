@@ -1134,10 +1134,9 @@ int sweep_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
   // the nonzero-splitting kernel.  Every row then ends in a wavefront's accumulator rows, which is
   // what the layer form with the dense transform as the sweep's epilogue needs.
   // Measured never slower than the nonzero-splitting kernel on the power-law graphs (233 k vertices:
-  // 2.54 -> 2.50 ms, 2.45 M vertices: 2.78 -> 2.62 ms at f = 64, 4.24 -> 4.19 ms at f = 128); left to
-  // that kernel when the short rows average fewer than four entries (a wavefront of 16 such rows is
-  // mostly set-up) unless asked for.
-  bool whole_rows = (opt.short_rows == 1 || (opt.short_rows == 0 && short_entries >= 4 * short_rows)) &&
+  // 2.54 -> 2.50 ms, 2.45 M vertices: 2.78 -> 2.62 ms at f = 64, 4.24 -> 4.19 ms at f = 128), also
+  // when the short rows are very short (2 M rows of which 92 % hold one entry each: 3.50 -> 3.38 ms).
+  bool whole_rows = opt.short_rows >= 0 &&
                     short_rows > 0 && tot.min_long <= 255 && slots == kSweepSlots && R <= 4 &&
                     P + short_rows <= L.max_pieces && opt.sync_slabs <= 0 && opt.barriers != 1 &&
                     opt.pace_ps_per_step <= 0;

@@ -188,6 +188,19 @@ def test_cfg4_rank_share():
     ucols, inv = np.unique(sci, return_inverse=True)
     ref, zabs = oracle.spmm(srp, inv.astype(np.int32), sv, wl.H_rows(ucols.astype(np.int32)), want_abs=True)
     assert_close(Z[torch.from_numpy(rows).cuda()], ref, zabs, RTOL_SPMM, "cfg4 Z")
+    # the layer without T on the same schedule (1.69 M rows of 3.6 entries swept as whole rows):
+    # sampled rows against the oracle's GEMM of the oracle's rows of T
+    info = ws.info()
+    assert info["mode"] == 1 and info["chunk_rows"] == 0 and sagnn.gcn_layer_fwd_form(ws, f, f, sagnn.GEMM_FP32) == 2
+    sel = torch.from_numpy(rows).cuda()
+    Wl = synth.normal((f, f), 4, synth.STREAM_W, scale=1 / np.sqrt(f))
+    _, Zl, Hl = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, dev(Wl), act=sagnn.ACT_RELU, ws=ws, want_t=False)
+    torch.cuda.synchronize()
+    zref, zabs_l = oracle.gemm(ref, Wl, Xabs=zabs, want_abs=True)
+    assert_close(Zl[sel], zref, zabs_l, RTOL_GEMM, "cfg4 layer Z (sweep epilogue)")
+    assert_close(Hl[sel], np.maximum(zref, 0), zabs_l, RTOL_GEMM, "cfg4 layer H' (sweep epilogue)")
+    assert torch.isfinite(Zl).all().item() and torch.equal(Hl, torch.clamp_min(Zl, 0))
+    del Zl, Hl
     # per-pair volumes (what the all-to-allv of the 1D algorithm would carry) are consistent
     counts = np.diff(plan.blk_off)
     assert counts.sum() == N and counts[0] >= g.m       # the diagonal block holds the self loops
