@@ -234,7 +234,8 @@ def main():
             "cfg5": "SBM 2M vertices, rank-0 block of 16, ordered by community",
         }[wl.name] + f", m={m} n={n} nnz={nnz} N_needed={N} f={f} f_out={f_out} nb={nb}",
             "step": ("" if args.no_plan else "plan+") + "pack+spmm+gemm_relu", "seed": 0,
-            "spmm_schedule": dict(ws.info(), tuned=ws.choice, barriers_gave_up=ws.barriers_gave_up(), prepare_ms=prepare_ms),
+            "spmm_schedule": dict(ws.info(), tuned=ws.choice, barriers_gave_up=ws.barriers_gave_up(), prepare_ms=prepare_ms,
+                                  dense_tiles=ws.tile_info()),
             "scale": args.scale},
         "roofline": {
             "kernel": "spmm_csr_tallskinny (all kernels of one call: slab-sweep + nonzero-splitting "

@@ -242,8 +242,38 @@ typedef struct sagnn_spmm_options {
                               with widths of 64 and up, 16 accumulator rows, no slab intervals and
                               short rows of at most 255 entries.
                               0 or 1 = where possible, -1 = never                                     */
+  int32_t dense_tiles;     /* 1: the tiles of A that are dense enough to re-use staged rows of the dense
+                              operand are taken out of the matrix and multiplied by a kernel that keeps
+                              those rows in LDS (see "dense tiles" below); needs a workspace sized by
+                              spmm_csr_workspace_bytes_opt with the same setting and f = 64, 128 or 256
+                              (other widths: ignored).  0 or -1 = no.  Measured slower than the slab
+                              sweep on the power-law graphs it was built for (see below); kept as an
+                              option                                                                  */
+  int32_t tile_reuse_x10;  /* a tile is kept when it holds at least this many entries per column, in
+                              tenths (0 = 25, i.e. every staged row is used 2.5 times on average)     */
 } sagnn_spmm_options;
 int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, size_t* bytes);
+/* Workspace size for a preparation with the given options: spmm_csr_workspace_bytes() plus, with
+ * dense_tiles = 1, the tile region.  h_opt may be NULL.
+ *
+ * Dense tiles (high-degree graphs such as the 233 k-vertex one with ~490 entries per row): rows of A
+ * are ranked by their number of entries, columns by the number of entries that reference them; the
+ * first 131,072 rows and 65,536 columns form tiles of 512 rows x (16384 / f) columns (256 rows at
+ * f = 256).  A tile with at least tile_reuse_x10 / 10 entries per column is multiplied by a kernel
+ * that stages the tile's rows of the dense operand (64 KB) in LDS, double-buffered, while the 16
+ * wavefronts of a workgroup keep the sums of the tile's rows in registers; the sums of a row group's
+ * work items are added to C in a fixed order by a second kernel (reproducible, no floating-point
+ * atomics).  All other entries stay in a rest CSR (stored in the tile region, rows still ascending)
+ * that is prepared and multiplied like any other matrix.  If no tile qualifies the preparation is
+ * the plain one.  The tile region holds the rest CSR, the tile entry streams and the partial sums:
+ * about 28 bytes per entry of A.  gcn_layer_fwd with d_T = NULL uses its row-range form on such a
+ * workspace (rows with entries in tiles are not finished by one wavefront). */
+int spmm_csr_workspace_bytes_opt(int64_t m, int64_t k, int64_t nnz, int32_t f,
+                                 const sagnn_spmm_options* h_opt, size_t* bytes);
+/* What a preparation with dense_tiles = 1 decided (host query).  h_info[6]: [0] 1 if tiles are in
+ * use, [1] entries in kept tiles, [2] kept tiles, [3] work items, [4] ranked rows, [5] entries of
+ * the rest CSR.  SAGNN_EINVAL if the workspace is unknown. */
+int spmm_csr_tile_info(const void* d_ws, int64_t* h_info);
 int spmm_csr_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                      int64_t m, int64_t k, int64_t nnz, int32_t f, void* d_ws, size_t ws_bytes,
                      void* stream);

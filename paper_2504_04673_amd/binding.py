@@ -17,7 +17,7 @@ PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
     "spmm_plan_workspace_bytes", "spmm_plan_needed_rows", "spmm_plan_needed_rows_noalloc", "spmm_pack_rows",
-    "spmm_csr_workspace_bytes", "spmm_csr_prepare", "spmm_csr_prepare_opt", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
+    "spmm_csr_workspace_bytes", "spmm_csr_workspace_bytes_opt", "spmm_csr_tile_info", "spmm_csr_prepare", "spmm_csr_prepare_opt", "spmm_csr_prepare_tuned", "spmm_csr_schedule_info",
     "spmm_csr_release", "spmm_csr_tallskinny",
     "dense_gemm_act", "gcn_layer_fwd", "gcn_layer_fwd_fused", "gcn_layer_fwd_form", "gcn_bwd_workspace_bytes", "gcn_layer_bwd",
     "spmm_split_workspace_bytes", "spmm_split_colblocks", "spmm_stage_loop", "spmm_volume_stats",
@@ -38,7 +38,7 @@ class SpmmOptions(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("schedule", "min_long", "piece", "slab_kb", "min_waves", "window_pct", "snake", "groups",
                  "sync_slabs", "pace_ps_per_step", "barriers", "sync_timeout_us", "sync_test_extra",
-                 "narrow_slots", "slab_width", "short_rows")]
+                 "narrow_slots", "slab_width", "short_rows", "dense_tiles", "tile_reuse_x10")]
 
 
 # The library itself reads no environment variables.  For experiments and for tests that force a
@@ -49,7 +49,8 @@ class SpmmOptions(ctypes.Structure):
 #   SAGNN_SWEEP_GROUPS=1|2, SAGNN_SWEEP_SYNC (slabs per interval, 0 = one interval),
 #   SAGNN_SWEEP_PACE_PS (picoseconds per stream step, -1 = never pace), SAGNN_SWEEP_BARRIERS=1,
 #   SAGNN_SWEEP_SYNC_US, SAGNN_SWEEP_SYNC_TEST_EXTRA, SAGNN_SWEEP_NARROW_SLOTS=1, SAGNN_SWEEP_SLAB_WIDTH=128,
-#   SAGNN_SWEEP_SHORT_ROWS=1 (short rows swept as whole rows)
+#   SAGNN_SWEEP_SHORT_ROWS=1 (short rows swept as whole rows),
+#   SAGNN_TILES=1|-1 (dense tiles out of LDS: always / never), SAGNN_TILE_REUSE_X10
 def options_from_env() -> SpmmOptions:
     o = SpmmOptions()
     env = os.environ.get
@@ -66,7 +67,8 @@ def options_from_env() -> SpmmOptions:
                         ("SAGNN_SWEEP_SYNC_US", "sync_timeout_us"), ("SAGNN_SWEEP_PACE_PS", "pace_ps_per_step"),
                         ("SAGNN_SWEEP_BARRIERS", "barriers"), ("SAGNN_SWEEP_NARROW_SLOTS", "narrow_slots"),
                         ("SAGNN_SWEEP_SYNC_TEST_EXTRA", "sync_test_extra"), ("SAGNN_SWEEP_SLAB_WIDTH", "slab_width"),
-                        ("SAGNN_SWEEP_SHORT_ROWS", "short_rows")):
+                        ("SAGNN_SWEEP_SHORT_ROWS", "short_rows"), ("SAGNN_TILES", "dense_tiles"),
+                        ("SAGNN_TILE_REUSE_X10", "tile_reuse_x10")):
         v = num(name)
         if v is not None:
             setattr(o, field, v)
@@ -120,6 +122,8 @@ def lib():
         L.spmm_plan_needed_rows_noalloc.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64, vp, vp, u32, vp]
         L.spmm_pack_rows.argtypes = [vp, i64, i64, i32, vp, i64, vp, i64, vp]
         L.spmm_csr_workspace_bytes.argtypes = [i64, i64, i32, psz]
+        L.spmm_csr_workspace_bytes_opt.argtypes = [i64, i64, i64, i32, vp, psz]
+        L.spmm_csr_tile_info.argtypes = [vp, vp]
         L.spmm_csr_prepare.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
         L.spmm_csr_prepare_opt.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, vp]
         L.spmm_csr_prepare_tuned.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp, i64, vp, i64, vp, vp, vp]
@@ -312,6 +316,13 @@ class SpmmWorkspace:
                 "pace_ps_per_step", "barriers", "slots", "longest_stream_steps")
         return dict(zip(keys, (int(x) for x in a)))
 
+    def tile_info(self) -> dict:
+        """What a preparation with dense tiles decided (see spmm_csr_tile_info)."""
+        a = np.zeros(6, dtype=np.int64)
+        _check(lib().spmm_csr_tile_info(_ptr(self.buf), a.ctypes.data_as(ctypes.c_void_p)), "spmm_csr_tile_info")
+        keys = ("tiles", "tile_entries", "kept_tiles", "items", "ranked_rows", "rest_entries")
+        return dict(zip(keys, (int(x) for x in a)))
+
     def barriers_gave_up(self) -> bool:
         """True if a barrier wait of the most recent product hit its time limit (synchronises)."""
         off = self.info()["gave_up_offset"]
@@ -327,9 +338,10 @@ def spmm_csr_prepare(rowptr, colidx, val, k: int, f: int, options: SpmmOptions =
     m, nnz = rowptr.numel() - 1, colidx.numel()
     L = lib()
     wsb = ctypes.c_size_t(0)
-    _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
-    buf = _ws(wsb.value, rowptr.device)
     opt = options if options is not None else options_from_env()
+    _check(L.spmm_csr_workspace_bytes_opt(m, k, nnz, f, ctypes.byref(opt), ctypes.byref(wsb)),
+           "spmm_csr_workspace_bytes_opt")
+    buf = _ws(wsb.value, rowptr.device)
     _check(L.spmm_csr_prepare_opt(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
                                   buf.numel(), ctypes.byref(opt), _stream()), "spmm_csr_prepare_opt")
     return SpmmWorkspace(buf, m, nnz, f, None, int(k))
@@ -349,10 +361,11 @@ def spmm_csr_prepare_tuned(rowptr, colidx, val, B, C=None, options: SpmmOptions 
     _dev(C, torch.float32, "C")
     L = lib()
     wsb = ctypes.c_size_t(0)
-    _check(L.spmm_csr_workspace_bytes(m, nnz, f, ctypes.byref(wsb)), "spmm_csr_workspace_bytes")
+    opt = options if options is not None else options_from_env()
+    _check(L.spmm_csr_workspace_bytes_opt(m, k, nnz, f, ctypes.byref(opt), ctypes.byref(wsb)),
+           "spmm_csr_workspace_bytes_opt")
     buf = _ws(wsb.value, rowptr.device)
     choice = np.zeros(4, dtype=np.int32)
-    opt = options if options is not None else options_from_env()
     _check(L.spmm_csr_prepare_tuned(_ptr(rowptr), _ptr(colidx), _ptr(val), m, k, nnz, f, _ptr(buf),
                                     buf.numel(), _ptr(B), B.stride(0), _ptr(C), C.stride(0),
                                     choice.ctypes.data_as(ctypes.c_void_p), ctypes.byref(opt), _stream()),

@@ -11,7 +11,7 @@ INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB = os.path.join(_HERE, "libsagnn.so")
 OBJDIR = os.path.join(_HERE, "_build")
 SOURCES = ["api.hip", "pack.hip", "plan.hip", "spmm.hip", "spmm_sweep.hip", "gemm.hip", "stages.hip",
-           "fused.hip", "permute.hip", "sweep_plan.hip"]
+           "fused.hip", "permute.hip", "sweep_plan.hip", "tiles.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "rowload.h"), os.path.join(INCLUDE, "sagnn.h")]
 
 HIPCC_FLAGS = [

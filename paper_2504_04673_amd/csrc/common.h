@@ -152,6 +152,11 @@ struct SpmmHostDesc {
   int32_t max_slab;         // widest column slab of B per launch (256, or 128 for the lane-group kernels at wider f)
   float mean_steps;         // average stream steps per wavefront (the end of the pacing schedule)
   float max_steps;          // steps of the longest stream
+  // dense-tile schedule (tiles.hip): when tiles != 0 everything above describes the rest CSR
+  // stored in the tile region behind the plain workspace, nnz included; full_nnz is the caller's
+  int32_t tiles;
+  int64_t full_nnz, tile_count, tile_items, tile_entries, tile_rows;
+  uint64_t tile_generation;
 };
 
 // Workgroups of `lds` bytes of LDS each that a CU really holds at once.  Measured on MI355X:
@@ -230,6 +235,28 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
                  int64_t ldb, int32_t col0, int32_t fw, uint32_t kmax, float* C, int64_t ldc,
                  int32_t accumulate, int32_t f_total, hipStream_t s,
                  const SweepFusedArgs* fused = nullptr, int32_t fuse = 0);
+
+// Dense-tile schedule (tiles.hip): the tiles of A that are dense enough to re-use staged rows of
+// the dense operand are multiplied out of LDS, the rest of A goes through the other schedules.
+constexpr int64_t kTileMaxRows = 131072;   // ranked rows / columns that can form tiles
+constexpr int64_t kTileMaxCols = 65536;
+constexpr int64_t kTileItemEntries = 32768;   // entries of a work item (several tiles of one row group)
+struct TileGeom { int fpl, rpw, rg, tc; };    // floats per lane, rows per wavefront, rows per group, columns per tile
+bool tile_geom(int32_t f, TileGeom* g);       // false: no tile kernel for this width
+struct TileWsLayout {   // the tile region (a function of m, k, nnz, f; worst-case sizes)
+  size_t header, rowrank, colrank, hubrow, hubcol, tilecnt, tileslot, ts_chunk, ts_item, item_g, item_ts0,
+      item_nch, group_item0, cnt16, roff16, wstart, ent, partial, rest_rowptr, rest_col, rest_val, keys, colcnt,
+      err, radix, total;
+  int64_t kr, kc, ng, nc, max_ts, max_items;
+};
+TileWsLayout tile_ws_layout(int64_t m, int64_t k, int64_t nnz, int32_t f);
+struct TilePlan { int64_t n_ts, n_items, entries, rest_nnz, rows; };
+int tile_prepare(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val, int64_t m, int64_t k,
+                 int64_t nnz, int32_t f, char* base, const TileWsLayout& L, int32_t reuse_x10, uint64_t generation,
+                 hipStream_t s, TilePlan* out);
+// C += (kept tiles of A) * B
+int tile_launch(const TilePlan& p, uint64_t generation, char* base, const TileWsLayout& L, const float* B,
+                int64_t ldb, uint32_t kmax, int32_t f, int64_t m, float* C, int64_t ldc, hipStream_t s);
 
 // Stable least-significant-digit radix sort of (key, payload) pairs on the device (stages.hip),
 // 8 bits per pass over key bits [0, bits).  With pay_in == NULL the payload is the index of the

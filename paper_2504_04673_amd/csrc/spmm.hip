@@ -472,9 +472,21 @@ uint64_t spmm_next_generation();
 int sweep_combine(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, float* C, int64_t ldc,
                   int32_t f_total, int32_t accumulate, hipStream_t s);
 
+namespace {
+int launch_spmm_body(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
+                     int64_t k, int64_t nnz, const float* B, int64_t ldb, int32_t f, float* C,
+                     int64_t ldc, int32_t accumulate, void* ws, size_t ws_bytes, hipStream_t s, bool inner);
+}
 int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
                 int64_t k, int64_t nnz, const float* B, int64_t ldb, int32_t f, float* C,
                 int64_t ldc, int32_t accumulate, void* ws, size_t ws_bytes, hipStream_t s) {
+  return launch_spmm_body(rowptr, colidx, val, m, k, nnz, B, ldb, f, C, ldc, accumulate, ws, ws_bytes, s, false);
+}
+namespace {
+// inner: the call is the rest-CSR part of a workspace prepared with dense tiles
+int launch_spmm_body(const int32_t* rowptr, const int32_t* colidx, const float* val, int64_t m,
+                     int64_t k, int64_t nnz, const float* B, int64_t ldb, int32_t f, float* C,
+                     int64_t ldc, int32_t accumulate, void* ws, size_t ws_bytes, hipStream_t s, bool inner) {
   if (m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || ldb < f || ldc < f || (ldb & 3) ||
       (ldc & 3) || m > 0x7FFFFFFFll || k > 0x7FFFFFFFll || nnz > 0x7FFFFFFFll)
     return SAGNN_EINVAL;
@@ -501,6 +513,24 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
 
   SpmmHostDesc desc{};
   if (!spmm_desc_get(ws, &desc)) return SAGNN_EINVAL;        // never prepared in this process
+  if (desc.tiles && !inner) {
+    // dense tiles: the rest CSR (stored behind the plain workspace) through the schedule prepared
+    // for it, then C += tiles * B out of LDS
+    if (desc.m != m || desc.full_nnz != nnz || desc.f != f || k < desc.k) return SAGNN_EINVAL;
+    const size_t plain = round_up(spmm_ws_bytes(m, desc.full_nnz, desc.f), 256);
+    const TileWsLayout TL = tile_ws_layout(m, desc.k, desc.full_nnz, desc.f);
+    if (ws_bytes < plain + TL.total) return SAGNN_ECAPACITY;
+    char* tb = reinterpret_cast<char*>(ws) + plain;
+    int rc = launch_spmm_body(reinterpret_cast<const int32_t*>(tb + TL.rest_rowptr),
+                              reinterpret_cast<const int32_t*>(tb + TL.rest_col),
+                              reinterpret_cast<const float*>(tb + TL.rest_val), m, k, desc.nnz, B, ldb, f, C, ldc,
+                              accumulate, ws, plain, s, true);
+    if (rc != SAGNN_OK) return rc;
+    TilePlan tp{};
+    tp.n_ts = desc.tile_count; tp.n_items = desc.tile_items; tp.entries = desc.tile_entries;
+    tp.rest_nnz = desc.nnz; tp.rows = desc.tile_rows;
+    return tile_launch(tp, desc.tile_generation, tb, TL, B, ldb, d.kmax, f, m, C, ldc, s);
+  }
   if (desc.m != m || desc.nnz != nnz || desc.f < f) return SAGNN_EINVAL;
   // the re-ordered entry streams hold column ids checked against the k of the preparation: an
   // operand with fewer rows would be read out of range
@@ -583,6 +613,7 @@ int launch_spmm(const int32_t* rowptr, const int32_t* colidx, const float* val, 
   }
   return SAGNN_OK;
 }
+}  // namespace
 
 // ------------------------------------------------------------------------------------------
 // The layer with the dense transform as the epilogue of the slab sweep (spmm_sweep_fused_kernel)
@@ -649,6 +680,7 @@ __global__ __launch_bounds__(256) void layer_leftover_kernel(
 bool fused_sweep_layer_applicable(const void* ws, int32_t f_in, int32_t f_out) {
   SpmmHostDesc desc{};
   if (!ws || !spmm_desc_get(ws, &desc)) return false;
+  if (desc.tiles) return false;   // rows with entries in dense tiles are not finished by the sweep
   if (desc.mode != 1 || desc.slots != kSweepSlots || desc.n_waves <= 0 || (desc.n_waves & 3)) return false;
   if (!(f_in == 64 || f_in == 128 || f_in == 256) || f_in > desc.f || f_in > desc.max_slab) return false;
   // the launch must cover the whole width of T with one kernel of the prepared schedule
@@ -728,6 +760,33 @@ SAGNN_EXPORT int spmm_csr_workspace_bytes(int64_t m, int64_t nnz, int32_t f, siz
   return SAGNN_OK;
 }
 
+SAGNN_EXPORT int spmm_csr_workspace_bytes_opt(int64_t m, int64_t k, int64_t nnz, int32_t f,
+                                              const sagnn_spmm_options* h_opt, size_t* bytes) {
+  using namespace sagnn;
+  if (!bytes || m < 0 || k < 0 || nnz < 0 || f <= 0 || (f & 3) || nnz > 0x7FFFFFFFll || m > 0x7FFFFFFFll ||
+      k > 0x7FFFFFFFll)
+    return SAGNN_EINVAL;
+  size_t b = spmm_ws_bytes(m, nnz, f);
+  TileGeom g{};
+  if (h_opt && h_opt->dense_tiles == 1 && tile_geom(f, &g)) b = round_up(b, 256) + tile_ws_layout(m, k, nnz, f).total;
+  *bytes = b;
+  return SAGNN_OK;
+}
+
+SAGNN_EXPORT int spmm_csr_tile_info(const void* d_ws, int64_t* h_info) {
+  using namespace sagnn;
+  if (!d_ws || !h_info) return SAGNN_EINVAL;
+  SpmmHostDesc d{};
+  if (!spmm_desc_get(d_ws, &d)) return SAGNN_EINVAL;
+  h_info[0] = d.tiles;
+  h_info[1] = d.tiles ? d.tile_entries : 0;
+  h_info[2] = d.tiles ? d.tile_count : 0;
+  h_info[3] = d.tiles ? d.tile_items : 0;
+  h_info[4] = d.tiles ? d.tile_rows : 0;
+  h_info[5] = d.tiles ? d.nnz : 0;
+  return SAGNN_OK;
+}
+
 SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_colidx,
                                       const float* d_val, int64_t m, int64_t k, int64_t nnz, int32_t f,
                                       void* d_ws, size_t ws_bytes, const sagnn_spmm_options* h_opt,
@@ -747,6 +806,38 @@ SAGNN_EXPORT int spmm_csr_prepare_opt(const int32_t* d_rowptr, const int32_t* d_
   if (ws_bytes < L.total) return SAGNN_ECAPACITY;
   hipStream_t s = (hipStream_t)stream;
   char* base = reinterpret_cast<char*>(d_ws);
+  if (opt.dense_tiles < -1 || opt.dense_tiles > 1 || opt.tile_reuse_x10 < 0) return SAGNN_EINVAL;
+  TileGeom tg{};
+  if (opt.dense_tiles == 1 && tile_geom(f, &tg) && m > 0 && k > 0 && nnz > 0) {
+    // dense tiles: split A into the kept tiles and a rest CSR (both in the tile region behind the
+    // plain workspace), then prepare the rest like any other matrix
+    const size_t plain = round_up(L.total, 256);
+    const TileWsLayout TL = tile_ws_layout(m, k, nnz, f);
+    if (ws_bytes < plain + TL.total) return SAGNN_ECAPACITY;
+    TilePlan tp{};
+    const uint64_t gen = spmm_next_generation();
+    int rc = tile_prepare(d_rowptr, d_colidx, d_val, m, k, nnz, f, base + plain, TL, opt.tile_reuse_x10, gen, s, &tp);
+    if (rc != SAGNN_OK) return rc;
+    if (tp.n_ts > 0) {
+      sagnn_spmm_options inner_opt = opt;
+      inner_opt.dense_tiles = -1;
+      char* tb = base + plain;
+      rc = spmm_csr_prepare_opt(reinterpret_cast<const int32_t*>(tb + TL.rest_rowptr),
+                                reinterpret_cast<const int32_t*>(tb + TL.rest_col),
+                                reinterpret_cast<const float*>(tb + TL.rest_val), m, k, tp.rest_nnz, f, d_ws, plain,
+                                &inner_opt, stream);
+      if (rc != SAGNN_OK) return rc;
+      SpmmHostDesc desc{};
+      if (!spmm_desc_get(d_ws, &desc)) return SAGNN_EINVAL;
+      desc.tiles = 1;
+      desc.full_nnz = nnz;
+      desc.tile_count = tp.n_ts; desc.tile_items = tp.n_items; desc.tile_entries = tp.entries;
+      desc.tile_rows = tp.rows; desc.tile_generation = gen;
+      spmm_desc_put(d_ws, desc);
+      return SAGNN_OK;
+    }
+    // no tile is dense enough: the plain preparation below
+  }
   int32_t* d_has_empty = reinterpret_cast<int32_t*>(base + L.carry);  // scratch until the first product
 
   SweepPlanResult plan{};

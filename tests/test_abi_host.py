@@ -43,6 +43,16 @@ def test_workspace_queries():
     assert L.spmm_csr_workspace_bytes(10, 1000, 128, ctypes.byref(b)) == 0
     assert b.value >= 4 * 128 * 4
     assert L.spmm_csr_workspace_bytes(10, 1000, 6, ctypes.byref(b)) == -1
+    plain = b.value
+    assert L.spmm_csr_workspace_bytes_opt(10, 20, 1000, 128, None, ctypes.byref(b)) == 0 and b.value == plain
+    tiles = sagnn.SpmmOptions()
+    tiles.dense_tiles = 1
+    # the tile region holds the rest CSR (8 bytes per entry) and the tile streams (8 bytes per entry)
+    assert L.spmm_csr_workspace_bytes_opt(10, 20, 1000, 128, ctypes.byref(tiles), ctypes.byref(b)) == 0
+    assert b.value >= plain + 16 * 1000
+    assert L.spmm_csr_workspace_bytes_opt(10, 20, 1000, 100, ctypes.byref(tiles), ctypes.byref(b)) == 0  # no tile kernel at this width
+    assert L.spmm_csr_workspace_bytes_opt(10, -1, 1000, 128, None, ctypes.byref(b)) == -1
+    assert L.spmm_csr_workspace_bytes_opt(10, 20, 1000, 128, None, None) == -1
     assert L.gcn_bwd_workspace_bytes(1000, 256, 256, ctypes.byref(b)) == 0 and b.value >= 256 * 256 * 4
     assert L.gcn_bwd_workspace_bytes(1000, 102, 256, ctypes.byref(b)) == -1
     assert L.gcn_bwd_workspace_bytes(1000, 16, 260, ctypes.byref(b)) == -1
@@ -66,7 +76,15 @@ def test_argument_validation_before_launch():
     bad.short_rows = 2                                    # not one of -1, 0, 1
     import ctypes as _c
     assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, _c.byref(bad), None) == -1
+    bad = sagnn.SpmmOptions()
+    bad.dense_tiles = 2                                   # not one of -1, 0, 1
+    assert L.spmm_csr_prepare_opt(None, None, None, 4, 4, 4, 16, None, 0, _c.byref(bad), None) == -1
     assert L.spmm_csr_release(None) == -1
+    assert L.spmm_csr_tile_info(None, None) == -1
+    import numpy as _np
+    info = _np.zeros(6, dtype=_np.int64)
+    never_prepared = _c.c_void_p(0x1000)
+    assert L.spmm_csr_tile_info(never_prepared, info.ctypes.data_as(_c.c_void_p)) == -1
     # plan: missing host arrays
     assert L.spmm_plan_needed_rows(None, None, 4, 4, 0, None, 1, None, 0, None, None, None, 0, 0, None) == -1
     # GEMM: unsupported sizes
@@ -84,7 +102,7 @@ def test_options_from_env_translation(monkeypatch):
     """The library reads no environment; the binding turns the experiment variables into the
     options struct (host only)."""
     for k in list(os.environ):
-        if k.startswith("SAGNN_SWEEP"):
+        if k.startswith("SAGNN_SWEEP") or k.startswith("SAGNN_TILE"):
             monkeypatch.delenv(k)
     o = sagnn.options_from_env()
     assert all(getattr(o, n) == 0 for n, _ in sagnn.SpmmOptions._fields_)
@@ -100,7 +118,12 @@ def test_options_from_env_translation(monkeypatch):
     monkeypatch.setenv("SAGNN_SWEEP_SYNC", "8")
     o = sagnn.options_from_env()
     assert (o.schedule, o.slab_kb, o.sync_slabs) == (1, 2048, 8)
+    monkeypatch.setenv("SAGNN_TILES", "1")
+    monkeypatch.setenv("SAGNN_TILE_REUSE_X10", "40")
+    o = sagnn.options_from_env()
+    assert (o.dense_tiles, o.tile_reuse_x10) == (1, 40)
     src = open(os.path.join(ROOT, "paper_2504_04673_amd", "csrc", "spmm_sweep.hip")).read()
+    assert "getenv" not in open(os.path.join(ROOT, "paper_2504_04673_amd", "csrc", "tiles.hip")).read()
     assert "getenv" not in src and "getenv" not in open(os.path.join(ROOT, "paper_2504_04673_amd", "csrc", "spmm.hip")).read()
 
 
