@@ -142,3 +142,19 @@ def test_spmm_dense_tiles_layer_falls_back_to_split_or_row_range_form(monkeypatc
     _, Z2, _ = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), ws=ws, want_t=False)
     torch.cuda.synchronize()
     assert_close(Z2, ref["Z"], ref["Zabs"], 2e-5, "layer Z with tiles, T not stored")
+
+
+def test_spmm_dense_tiles_full_size_cfg2(monkeypatch):
+    """The configuration the dense tiles were built for, at full size: the whole product against the
+    oracle, and the eigenvector closed form A sqrt(d) = sqrt(d) (all terms positive, per-column
+    scales), on the launch configuration that profiles/ holds the counters of."""
+    from paper_2504_04673_amd import workloads
+    from tests.test_gpu_fullsize import check_eigenvector, check_spmm_full
+    wl = workloads.cfg2()
+    g, f = wl.g, 128
+    rp, ci, v, ws, ti = _prepare_tiles(g.rowptr, g.colidx, g.val, g.n, f, monkeypatch)
+    assert ti["tile_entries"] > 0.8 * g.nnz and ws.info()["mode"] == 1, (ti, ws.info())
+    Z = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(wl.H), ws=ws)
+    torch.cuda.synchronize()
+    check_spmm_full(g, Z, wl.H, "cfg2 with dense tiles")
+    check_eigenvector(g, f, ws, rp, ci, v)
