@@ -158,3 +158,29 @@ def test_spmm_dense_tiles_full_size_cfg2(monkeypatch):
     torch.cuda.synchronize()
     check_spmm_full(g, Z, wl.H, "cfg2 with dense tiles")
     check_eigenvector(g, f, ws, rp, ci, v)
+
+
+@pytest.mark.parametrize("m,k", [(40, 50), (513, 129), (1, 300), (600, 1)])
+def test_spmm_dense_tiles_ragged_small_shapes(m, k, monkeypatch):
+    """Fully dense small matrices whose last row group and last column chunk are partial (one row,
+    one column): every entry lands in a kept tile or, below 256 entries per tile, in the rest."""
+    monkeypatch.setenv("SAGNN_SWEEP", "0")
+    f = 128
+    rng = np.random.default_rng(m * 1000 + k)
+    rowptr = (np.arange(m + 1, dtype=np.int64) * k).astype(np.int32)
+    colidx = np.tile(np.arange(k, dtype=np.int32), m)
+    val = rng.standard_normal(m * k).astype(np.float32)
+    B = synth.normal((k, f), 21, synth.STREAM_H)
+    rp, ci, v, ws, ti = _prepare_tiles(rowptr, colidx, val, k, f, monkeypatch, expect=False)
+    # a tile (512 rows x 128 columns here) is kept from 320 entries on
+    fullest = min(m, 512) * min(k, 128)
+    assert ti["tiles"] == (1 if fullest >= 320 else 0), ti
+    ref, zabs = oracle.spmm(rowptr, colidx, val, B, want_abs=True)
+    C0 = synth.normal((m, f), 22, synth.STREAM_G)
+    got = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got, ref, zabs, RTOL_SPMM, f"dense {m}x{k}")
+    ref2, zabs2 = oracle.spmm(rowptr, colidx, val, B, C=C0, want_abs=True)
+    got2 = sagnn.spmm_csr_tallskinny(rp, ci, v, dev(B), C=dev(C0), accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    assert_close(got2, ref2, zabs2, RTOL_SPMM, f"dense {m}x{k} accumulate")
