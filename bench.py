@@ -6,7 +6,7 @@ A step is one pass of the whole path over one synthetic batch, every stage throu
 (the last two are exactly what gcn_layer_fwd chains; they are called separately here so that
 HIP events can bracket the SpMM inside the timed region).
 
-Prints ONE JSON line (see README / DESIGN for the fields).  Default workload: configuration 3
+Prints ONE JSON line (metric, value, roofline, cpu_baseline, stages, ...).  Default workload: configuration 3
 (R-MAT, 2.45 M vertices, ~124 M stored entries) at f = 128, the headline case of the metric.
 """
 from __future__ import annotations
