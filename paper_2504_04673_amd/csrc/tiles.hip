@@ -301,14 +301,13 @@ __global__ __launch_bounds__(kT) void tile_copy_rows_kernel(const int32_t* __res
 struct TileArgs {
   const TileHeader* hdr;
   uint64_t generation;
-  const int32_t *item_g, *item_ts0, *item_nch, *ts_chunk, *hubcol, *wstart;
+  const int32_t *item_ts0, *item_nch, *ts_chunk, *hubcol, *wstart;
   const uint16_t* cnt16;
   const uint2* ent;
   float* partial;
   const float* B;
   int64_t ldb;
   uint32_t kmax;
-  int32_t n_items;
   int32_t ent_cap;   // entries the array holds (>= 1)
 };
 
@@ -676,12 +675,12 @@ int tile_launch(const TilePlan& p, uint64_t generation, char* base, const TileWs
   TileArgs a{};
   a.hdr = reinterpret_cast<const TileHeader*>(base + L.header);
   a.generation = generation;
-  a.item_g = P32(L.item_g); a.item_ts0 = P32(L.item_ts0); a.item_nch = P32(L.item_nch);
+  a.item_ts0 = P32(L.item_ts0); a.item_nch = P32(L.item_nch);
   a.ts_chunk = P32(L.ts_chunk); a.hubcol = P32(L.hubcol); a.wstart = P32(L.wstart);
   a.cnt16 = reinterpret_cast<const uint16_t*>(base + L.cnt16);
   a.ent = reinterpret_cast<const uint2*>(base + L.ent);
   a.partial = reinterpret_cast<float*>(base + L.partial);
-  a.B = B; a.ldb = ldb; a.kmax = kmax; a.n_items = (int32_t)p.n_items;
+  a.B = B; a.ldb = ldb; a.kmax = kmax;
   a.ent_cap = (int32_t)std::max<int64_t>(p.entries, 1);
   const size_t lds = 2 * (size_t)kTileBuf + (size_t)kTileWaves * 128 * sizeof(uint2);   // tiles + entry rings
   auto go = [&](auto kern, auto comb) -> int {
