@@ -41,6 +41,21 @@ inline bool lds_mark_eligible(int64_t n, int64_t nnz) {
   return nnz >= kLdsMinNnz && n > 0 && n <= kLdsMaxPasses * kLdsCols;
 }
 
+// Wider column ranges: the entries are first partitioned by column range (count, offsets, scatter:
+// streaming passes over colidx with LDS counters), then every range is marked from its own bucket
+// by one workgroup whose LDS holds one flag BYTE per column (plain stores: LDS atomics run at about
+// one lane per five clocks, a bit per column would cost more than the byte flags in memory do) and
+// which turns the bytes into the range's membership words itself.  Byte flags in memory cost one
+// cache-line fill per entry; this costs three streaming passes.
+constexpr int64_t kBktCols = 155648;                // columns per range: 152 KB of flag bytes, a multiple of 64
+constexpr int kBktMaxRanges = 2048;
+constexpr int kBktGroups = 256;                     // workgroups of the partition passes
+constexpr int kBktThreads = 1024;                   // their size: 16 wavefronts keep enough loads in flight
+inline int64_t bucket_ranges(int64_t n) { return ceil_div(n > 0 ? n : 1, kBktCols); }
+inline bool bucket_mark_eligible(int64_t n, int64_t nnz) {
+  return nnz >= kLdsMinNnz && n > kLdsMaxPasses * kLdsCols && bucket_ranges(n) <= kBktMaxRanges;
+}
+
 struct PlanWs {
   uint8_t* flag;      // n bytes (rounded up to 64W)
   uint64_t* bitmap;   // W words
@@ -51,6 +66,9 @@ struct PlanWs {
   int64_t* blkoff;    // nb + 1
   int32_t* err;       // 4 counters
   uint32_t* part;     // LDS marking only: kLdsGroups private bitmaps of kLdsWords words
+  int32_t* bkt_cols;  // bucketed marking only: the column ids partitioned by range (nnz)
+  int32_t* bkt_cnt;   // bucketed marking only: [ranges][kBktGroups] counts, then offsets inside the range
+  int32_t* bkt_start; // bucketed marking only: first entry of every range (+ total)
   int64_t W, nblk;
   size_t bytes;
 };
@@ -73,9 +91,14 @@ PlanWs carve(void* base, int64_t n, int32_t nb, int64_t nnz) {
   w.colblk = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
   w.blkoff = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
   w.err = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 4));
+  const bool bucketed = bucket_mark_eligible(n, nnz);
   w.part = lds_mark_eligible(n, nnz)
                ? reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)kLdsGroups * kLdsWords))
                : nullptr;
+  w.bkt_cols = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)nnz)) : nullptr;
+  w.bkt_cnt = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(bucket_ranges(n) * kBktGroups)))
+                       : nullptr;
+  w.bkt_start = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(bucket_ranges(n) + 1))) : nullptr;
   w.bytes = off;
   return w;
 }
@@ -243,6 +266,182 @@ __global__ __launch_bounds__(kLdsThreads) void mark_lds_kernel(const int32_t* __
   const int used4 = cols_here > 0 ? (int)((cols_here + 127) >> 7) : 0;
   uint4* __restrict__ out = reinterpret_cast<uint4*>(part + (size_t)blockIdx.x * kLdsWords);
   for (int i = threadIdx.x; i < used4; i += kLdsThreads) out[i] = b4[i];
+}
+
+// --- bucketed marking ------------------------------------------------------------------------
+// entries of workgroup g: [g * per, (g + 1) * per); cnt[b * kBktGroups + g] = its entries in range b
+//
+// Columns are ascending inside a row, so neighbouring lanes often fall into the same range (about
+// 13 of 64 lanes share one on an R-MAT block) and their LDS atomics on one counter would run one
+// after the other.  A run of equal ranges in adjacent lanes is therefore counted by its first lane
+// alone: heads = lanes whose lower neighbour differs, the run's length comes from the ballot of heads.
+struct LaneRun {
+  int head;    // first lane of this lane's run
+  int len;     // length of the run (meaningful in its first lane)
+  bool first;
+};
+__device__ __forceinline__ LaneRun lane_run(int32_t b, int lane) {
+  const int32_t prev = __shfl_up(b, 1, 64);
+  LaneRun r;
+  r.first = lane == 0 || prev != b;
+  const uint64_t heads = __ballot(r.first);
+  r.head = 63 - __clzll((long long)(heads & (~0ull >> (63 - lane))));
+  const uint64_t above = lane == 63 ? 0ull : heads >> (lane + 1);
+  r.len = above ? __ffsll((long long)above) : 64 - lane;
+  return r;
+}
+
+// per workgroup: how many of its entries fall into every range (out-of-range columns are flagged and left out)
+__global__ __launch_bounds__(kBktThreads) void bucket_count_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
+                                                                int64_t n, int32_t nbk, int32_t* __restrict__ cnt,
+                                                                int32_t* __restrict__ err) {
+  __shared__ int32_t h[kBktMaxRanges];
+  for (int b = threadIdx.x; b < nbk; b += kBktThreads) h[b] = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  const int64_t per = ceil_div_dev(nnz, kBktGroups);
+  const int64_t e0 = (int64_t)blockIdx.x * per, e1 = e0 + per < nnz ? e0 + per : nnz;
+  // eight independent loads per thread in flight; the trip count is the same for every lane (ballots inside)
+  for (int64_t base = e0; base < e1; base += 8 * kBktThreads) {
+    const int64_t e = base + threadIdx.x;
+    int32_t c[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = e + j * kBktThreads < e1 ? colidx[e + j * kBktThreads] : 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int32_t b = -1;                                    // past the end or out of range: no bucket
+      if (e + j * kBktThreads < e1) {
+        if (c[j] < 0 || c[j] >= n) err[1] = 1;
+        else b = (int32_t)((uint32_t)c[j] / (uint32_t)kBktCols);
+      }
+      const LaneRun r = lane_run(b, lane);
+      if (r.first && b >= 0) atomicAdd(&h[b], r.len);
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < nbk; b += kBktThreads) cnt[(int64_t)b * kBktGroups + blockIdx.x] = h[b];
+}
+
+// one workgroup per range: the counts of the kBktGroups workgroups become offsets inside the
+// range, the range's total goes to tot[range]
+__global__ __launch_bounds__(kBktGroups) void bucket_within_kernel(int32_t* __restrict__ cnt, int32_t* __restrict__ tot) {
+  __shared__ int32_t wsum[kBktGroups / 64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int32_t* __restrict__ c = cnt + (int64_t)blockIdx.x * kBktGroups;
+  const int32_t v = c[threadIdx.x];
+  int32_t inc = v;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int32_t t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  int32_t before = 0;
+  for (int j = 0; j < w; ++j) before += wsum[j];
+  c[threadIdx.x] = before + inc - v;
+  if (threadIdx.x == kBktGroups - 1) tot[blockIdx.x] = before + inc;
+}
+
+// exclusive scan in place of the range totals (nbk <= kBktMaxRanges), grand total to a[nbk]; one workgroup
+__global__ __launch_bounds__(1024) void bucket_starts_kernel(int32_t* __restrict__ a, int32_t nbk) {
+  __shared__ int32_t wsum[16];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int i0 = threadIdx.x * 2;
+  const int32_t v0 = i0 < nbk ? a[i0] : 0, v1 = i0 + 1 < nbk ? a[i0 + 1] : 0;
+  int32_t inc = v0 + v1;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int32_t t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  int32_t before = 0;
+  for (int j = 0; j < w; ++j) before += wsum[j];
+  const int32_t excl = before + inc - v0 - v1;
+  __syncthreads();
+  if (i0 < nbk) a[i0] = excl;
+  if (i0 + 1 < nbk) a[i0 + 1] = excl + v0;
+  if (threadIdx.x == 1023) a[nbk] = before + inc;
+}
+
+// every workgroup places its entries behind its own offset of every range; a run of adjacent lanes
+// with one range takes its places with one atomic and writes them side by side
+__global__ __launch_bounds__(kBktThreads) void bucket_scatter_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
+                                                                  int64_t n, int32_t nbk,
+                                                                  const int32_t* __restrict__ within,
+                                                                  const int32_t* __restrict__ start,
+                                                                  int32_t* __restrict__ cols) {
+  __shared__ int32_t off[kBktMaxRanges];
+  for (int b = threadIdx.x; b < nbk; b += kBktThreads) off[b] = start[b] + within[(int64_t)b * kBktGroups + blockIdx.x];
+  __syncthreads();
+  const int lane = threadIdx.x & 63;
+  const int64_t per = ceil_div_dev(nnz, kBktGroups);
+  const int64_t e0 = (int64_t)blockIdx.x * per, e1 = e0 + per < nnz ? e0 + per : nnz;
+  for (int64_t base = e0; base < e1; base += 8 * kBktThreads) {
+    const int64_t e = base + threadIdx.x;
+    int32_t c[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = e + j * kBktThreads < e1 ? colidx[e + j * kBktThreads] : -1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int32_t b = (c[j] < 0 || c[j] >= n) ? -1 : (int32_t)((uint32_t)c[j] / (uint32_t)kBktCols);
+      const LaneRun r = lane_run(b, lane);
+      int32_t first_pos = 0;
+      if (r.first && b >= 0) first_pos = atomicAdd(&off[b], r.len);
+      const int32_t pos = __shfl(first_pos, r.head, 64) + (lane - r.head);
+      // (the order inside a bucket does not matter: the marks are a set)
+      if (b >= 0 && pos >= 0 && pos < nnz) cols[pos] = c[j];
+    }
+  }
+}
+
+// one workgroup per range: flag bytes in LDS from the range's bucket, then the range's membership
+// words (kBktCols / 64 of them, the last range fewer) straight into the bitmap
+__global__ __launch_bounds__(kLdsThreads) void mark_bucket_kernel(const int32_t* __restrict__ cols,
+                                                                  const int32_t* __restrict__ start, int64_t nnz,
+                                                                  int64_t n, int64_t W, uint64_t* __restrict__ bm) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t bits[];
+  uint8_t* flag = reinterpret_cast<uint8_t*>(bits);
+  const int range = blockIdx.x;
+  const int64_t c0 = (int64_t)range * kBktCols;
+  uint4* b4 = reinterpret_cast<uint4*>(bits);
+  for (int i = threadIdx.x; i < (int)(kBktCols / 16); i += kLdsThreads) b4[i] = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();
+  int64_t e0 = start[range], e1 = start[range + 1];
+  e0 = e0 < 0 ? 0 : e0;
+  e1 = e1 > nnz ? nnz : e1;
+  for (int64_t e = e0 + threadIdx.x; e < e1; e += 8 * kLdsThreads) {
+    int32_t c[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = e + j * kLdsThreads < e1 ? cols[e + j * kLdsThreads] : -1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int64_t rel = (int64_t)c[j] - c0;
+      if (c[j] >= 0 && rel >= 0 && rel < kBktCols) flag[rel] = 1;
+    }
+  }
+  __syncthreads();
+  // 64 flag bytes -> one word: a lane squeezes its 8 bytes into 8 bits, eight lanes make a word
+  const int64_t w0 = c0 >> 6;
+  const int words_here = (int)((W - w0 < kBktCols / 64) ? (W - w0) : (kBktCols / 64));
+  const uint2* f8 = reinterpret_cast<const uint2*>(bits);
+  for (int i = threadIdx.x; i < words_here * 8; i += kLdsThreads) {
+    const uint2 t = f8[i];
+    // bytes are 0 or 1: gather bit 0 of every byte
+    const uint32_t lo = ((t.x & 0x01010101u) * 0x01020408u) >> 24;
+    const uint32_t hi = ((t.y & 0x01010101u) * 0x01020408u) >> 24;
+    uint64_t piece = (uint64_t)((lo & 0xFu) | ((hi & 0xFu) << 4)) << ((i & 7) * 8);
+    // combine the eight lanes of a word (consecutive lanes)
+    piece |= __shfl_xor(piece, 1, 64);
+    piece |= __shfl_xor(piece, 2, 64);
+    piece |= __shfl_xor(piece, 4, 64);
+    if ((i & 7) == 0) {
+      const int64_t wi = w0 + (i >> 3);
+      const int64_t col = wi * 64;
+      if (n - col < 64) piece &= (1ull << (n - col)) - 1ull;
+      bm[wi] = piece;
+    }
+  }
 }
 
 // Membership words from the private bitmaps.  A workgroup owns 16 consecutive 64-bit words;
@@ -563,8 +762,10 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
 
   SAGNN_HIP(hipMemcpyAsync(w.colblk, h_colblk, sizeof(int64_t) * (size_t)(nb + 1),
                            hipMemcpyHostToDevice, s));
-  hipLaunchKernelGGL(clear_kernel, dim3(grid_for(w.W * 4)), dim3(kThreads), 0, s,
-                     reinterpret_cast<uint4*>(w.flag), w.W * 4, w.err);
+  // (the bucketed marking does not use the flag bytes: only the error counters are cleared then)
+  const int64_t clear16 = ((flags & SAGNN_PLAN_OBLIVIOUS) == 0 && w.bkt_cols != nullptr) ? 0 : w.W * 4;
+  hipLaunchKernelGGL(clear_kernel, dim3(grid_for(clear16)), dim3(kThreads), 0, s,
+                     reinterpret_cast<uint4*>(w.flag), clear16, w.err);
   SAGNN_LAUNCH_CHECK();
   if (flags & SAGNN_PLAN_VALIDATE) {
     hipLaunchKernelGGL(validate_rowptr_kernel, dim3(grid_for(m)), dim3(kThreads), 0, s, d_rowptr,
@@ -572,9 +773,31 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
     SAGNN_LAUNCH_CHECK();
   }
   const bool oblivious = (flags & SAGNN_PLAN_OBLIVIOUS) != 0;
-  const bool lds_mark = !oblivious && w.part != nullptr;
+  const bool bucket_mark = !oblivious && w.bkt_cols != nullptr;
+  const bool lds_mark = !oblivious && !bucket_mark && w.part != nullptr;
   bool speculated = false;   // the marking pass has already written the identity remap
-  if (lds_mark) {
+  if (bucket_mark) {
+    const int32_t nbk = (int32_t)bucket_ranges(n);
+    const size_t lds = (size_t)kBktCols;
+    hipLaunchKernelGGL(bucket_count_kernel, dim3(kBktGroups), dim3(kBktThreads), 0, s, d_colidx, nnz, n, nbk, w.bkt_cnt,
+                       w.err);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bucket_within_kernel, dim3((unsigned)nbk), dim3(kBktGroups), 0, s, w.bkt_cnt, w.bkt_start);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bucket_starts_kernel, dim3(1), dim3(1024), 0, s, w.bkt_start, nbk);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bucket_scatter_kernel, dim3(kBktGroups), dim3(kBktThreads), 0, s, d_colidx, nnz, n, nbk,
+                       w.bkt_cnt, w.bkt_start, w.bkt_cols);
+    SAGNN_LAUNCH_CHECK();
+    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mark_bucket_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(mark_bucket_kernel, dim3((unsigned)nbk), dim3(kLdsThreads), lds, s, w.bkt_cols, w.bkt_start,
+                       nnz, n, w.W, w.bitmap);
+    SAGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(count_kernel, dim3((unsigned)w.nblk), dim3(kThreads), 0, s, w.bitmap, w.W,
+                       w.blocksum);
+    SAGNN_LAUNCH_CHECK();
+  } else if (lds_mark) {
     const int passes = (int)ceil_div(n, kLdsCols);
     const int groups_per_pass = kLdsGroups / passes;
     const size_t lds = sizeof(uint32_t) * (size_t)kLdsWords;

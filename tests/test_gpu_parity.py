@@ -116,10 +116,15 @@ def test_plan_random_ragged(m, n, nb, avg, seed):
 @pytest.mark.parametrize("n,nnz,misalign", [(1_000_000, 4_300_000, 0), (1_245_185, 4_200_003, 1),
                                             (2_700_001, 4_500_001, 3), (4_980_736, 4_194_304, 0),
                                             (500_000, 4_300_000, 0), (100_000, 4_300_003, 0),
-                                            (100_001, 4_300_001, 1)])
+                                            (100_001, 4_300_001, 1),
+                                            # wider than four LDS ranges: entries partitioned by range first
+                                            (4_980_737, 4_200_000, 0), (6_225_921, 4_300_003, 1),
+                                            (20_000_003, 4_500_001, 3), (111_059_956, 5_000_000, 0),
+                                            (318_767_104, 4_194_304, 0)])
 def test_plan_large_entry_counts_lds_marking(n, nnz, misalign):
     """Entry counts above 2^22 with at most ~5 M columns take the LDS-bitmap marking path
-    (1 to 4 column ranges); the column array is also given at a 4-byte-but-not-16-byte aligned
+    (1 to 4 column ranges); beyond that, up to 2048 ranges of 155,648 columns (318.8 M columns), the
+    entries are partitioned by range first and every range is marked from its bucket; the column array is also given at a 4-byte-but-not-16-byte aligned
     address.  Power-law-like columns (squared uniform) plus the last column of every range.
     With eight or more entries per column the marking pass also writes the identity remap in
     advance: the 500 k-column case leaves columns unused (the advance copy must be replaced by
@@ -129,6 +134,15 @@ def test_plan_large_entry_counts_lds_marking(n, nnz, misalign):
     cols = (rng.random(nnz) ** 2 * n).astype(np.int64)
     cols[:8] = [0, n - 1, min(n - 1, 1_245_183), min(n - 1, 1_245_184), min(n - 1, 2_490_367),
                 min(n - 1, 2_490_368), min(n - 1, 3_735_552), n // 2]
+    if n > 4_980_736:
+        # first and last column of the ranges around the middle and at the end; a uniform share so that
+        # the far ranges are not empty
+        r = 1_245_184
+        mid, last = (n // 2) // r, (n - 1) // r
+        edge = [mid * r - 1, mid * r, mid * r + r - 1, last * r - 1, last * r, n - 2, 155_647, 155_648,
+                (n - 1) // 155_648 * 155_648 - 1, (n - 1) // 155_648 * 155_648]
+        cols[8:8 + len(edge)] = [min(max(c, 0), n - 1) for c in edge]
+        cols[100:100 + nnz // 4] = rng.integers(0, n, size=nnz // 4)
     cuts = np.sort(rng.integers(0, nnz + 1, size=m - 1))
     rowptr = np.array([0, *cuts, nnz], dtype=np.int32)
     colidx = cols.astype(np.int32)
@@ -147,6 +161,10 @@ def test_plan_large_entry_counts_lds_marking(n, nnz, misalign):
     if n in (100_000, 100_001):
         assert plan.N == n
     ci[12345] = n                                           # out of range: validation must see it
+    with pytest.raises(sagnn.SagnnError) as ei:
+        sagnn.spmm_plan_needed_rows(dev(rowptr), ci, n, colblk, validate=True)
+    assert ei.value.code == -3
+    ci[12345] = -2                                          # negative: likewise
     with pytest.raises(sagnn.SagnnError) as ei:
         sagnn.spmm_plan_needed_rows(dev(rowptr), ci, n, colblk, validate=True)
     assert ei.value.code == -3
