@@ -319,6 +319,17 @@ def main():
                 out["fused_layer"]["bf16_operands"] = {"sweep_epilogue_ms": round(ep16, 4),
                                                        "split_ms": round(spmm_ms + g16, 4),
                                                        "split_gemm_ms": round(g16, 4)}
+            if prec == sagnn.GEMM_FP32:
+                # fp32 operands as three bfloat16 terms each (six matrix-core products, fp32 accuracy)
+                gx3 = timed(lambda: sagnn.dense_gemm_act(T, W, prec=sagnn.GEMM_FP32_BF16X3, act=sagnn.ACT_RELU,
+                                                         want_z=False, want_act=True, out=(None, Ho)))
+                out["fused_layer"]["fp32_as_3_bf16_terms"] = {"split_ms": round(spmm_ms + gx3, 4),
+                                                              "split_gemm_ms": round(gx3, 4)}
+                if sagnn.gcn_layer_fwd_form(ws_e, f, f_out, sagnn.GEMM_FP32_BF16X3) == 2:
+                    epx3 = timed(lambda: sagnn.gcn_layer_fwd(rp, plan.colidx_compact, va, Hn, W, act=sagnn.ACT_RELU,
+                                                             prec=sagnn.GEMM_FP32_BF16X3, ws=ws_e, want_t=False,
+                                                             want_z=False, out=(None, None, Ho)))
+                    out["fused_layer"]["fp32_as_3_bf16_terms"]["sweep_epilogue_ms"] = round(epx3, 4)
             if own:
                 ws_e.release()
         except sagnn.SagnnError as e:

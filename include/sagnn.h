@@ -62,6 +62,17 @@ enum {
 
 #define SAGNN_GEMM_FP32 0 /* fp32 operands, fp32 MFMA                          */
 #define SAGNN_GEMM_BF16 1 /* operands rounded to bfloat16 (RNE), fp32 accumulate */
+#define SAGNN_GEMM_FP32_BF16X3 2 /* fp32 operands (finite, below 2^127), each split exactly into three
+                                   bfloat16 terms (round to nearest, remainder, remainder); the six
+                                   products down to 2^-16 of the leading one run on the bfloat16
+                                   matrix cores with fp32 accumulation.  The dropped products are below
+                                   2^-23 |x||w|: the accuracy of SAGNN_GEMM_FP32, results not bit-equal
+                                   to it.  dense_gemm_act, gcn_layer_fwd (with d_T given, or through a
+                                   workspace whose sweep ends with the dense transform) and the
+                                   G-gradient of gcn_layer_bwd run it; the weight gradient then uses
+                                   SAGNN_GEMM_FP32; the row-range one-kernel layer
+                                   (gcn_layer_fwd_fused, gcn_layer_fwd without d_T and without such a
+                                   workspace) returns SAGNN_EINVAL */
 
 /* Text for an error code (static string). */
 const char* sagnn_strerror(int code);
@@ -333,7 +344,7 @@ int spmm_csr_tallskinny(const int32_t* d_rowptr, const int32_t* d_colidx, const 
  *
  *   transW = 0: W is kdim x nout (ldw);  transW = 1: W is nout x kdim (ldw), used as W^T
  *   X is m x kdim (ldx), Z is m x nout (ldz)
- *   prec: SAGNN_GEMM_FP32 or SAGNN_GEMM_BF16
+ *   prec: SAGNN_GEMM_FP32, SAGNN_GEMM_BF16 or SAGNN_GEMM_FP32_BF16X3
  *   d_Z   (may be NULL) receives the product
  *   d_act (may be NULL) receives ReLU(product) when act = SAGNN_ACT_RELU, else the product
  *   d_mask (may be NULL, m x nout, ldmask): the product is zeroed where d_mask <= 0

@@ -11,7 +11,7 @@ import torch
 from . import build as _build
 
 ACT_IDENTITY, ACT_RELU = 0, 1
-GEMM_FP32, GEMM_BF16 = 0, 1
+GEMM_FP32, GEMM_BF16, GEMM_FP32_BF16X3 = 0, 1, 2
 PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
 
 EXPORTS = [

@@ -129,8 +129,9 @@ inline SpmmWsLayout spmm_ws_layout(int64_t m, int64_t nnz, int32_t f) {
   // planner: totals, per-window arrays, tile sums of the five row scans (2048 rows per tile)
   L.plan = take(256 + (size_t)kSweepMaxWindows * 8 + 3 * 4 * (size_t)(kSweepMaxWindows + 64) +
                 5 * sizeof(int32_t) * (size_t)(ceil_div(m, 2048) + 2));
-  // W of a fused layer call packed for the bfloat16 matrix instructions (at most 256 x 256)
-  L.wpack = take(256 * 256 * 2);
+  // W of a fused layer call packed for the bfloat16 matrix instructions (at most 256 x 256, up to
+  // three terms per element)
+  L.wpack = take(3 * 256 * 256 * 2);
   L.total = off;
   return L;
 }
@@ -217,12 +218,12 @@ int sweep_plan_deal_short(char* ws, const SpmmWsLayout& L, int64_t P_long, int64
 // the sweep with the dense transform of a GCN layer as its epilogue (spmm_sweep.hip)
 struct SweepFusedArgs {
   const float* W;        // f_in x f_out, row-major
-  const void* Wp;        // bfloat16 product: W packed for the matrix cores (set by the launcher)
+  const void* Wp;        // bfloat16 products: W packed for the matrix cores (set by the launcher)
   float *Z, *Hout, *T;   // m x f_out, m x f_out, m x f_in; each may be NULL (not both Z and Hout)
   int32_t f_out, act;
 };
 int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B, int64_t ldb,
-                       int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t bf16, hipStream_t s);
+                       int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t mode, hipStream_t s);
 // the layer through that kernel plus a small kernel for the rows it leaves out (spmm.hip);
 // returns 1 if the workspace / shapes do not allow it (the caller then uses another form)
 bool fused_sweep_layer_applicable(const void* ws, int32_t f_in, int32_t f_out);

@@ -43,30 +43,48 @@ struct GemmArgs {
   int32_t n0;  // first output column of this launch's slab
 };
 
+// Split mode: a finite fp32 number x is the exact sum of three bfloat16 numbers: t1 = x rounded to
+// nearest, t2 = (x - t1) rounded, t3 = x - t1 - t2, which needs no rounding (8 + 8 + 8 significant
+// bits); both subtractions are exact, |t2| <= 2^-8 |x| and |t3| <= 2^-16 |x|.
+__device__ __forceinline__ void split3(float x, __bf16& t1, __bf16& t2, __bf16& t3) {
+  t1 = (__bf16)x;
+  const float r = x - (float)t1;
+  t2 = (__bf16)r;
+  t3 = (__bf16)(r - (float)t2);
+}
+
 // ------------------------------------------------------------------------------------------
 // KPAD: kdim is not a multiple of 32, loads of X are guarded against the real k extent.
 // NG > 0: the k loop has exactly NG groups of 32 and is fully unrolled.  In straight-line code the
 // compiler counts outstanding loads exactly; around a loop back-edge it waits for ALL of them,
 // which would make the prefetch of the next group useless.
-template <int NT, bool BF16, int WAVES, bool KPAD, int NG>
+template <int NT, int PREC, int WAVES, bool KPAD, int NG>
 __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int NB = NT * 32;
+  constexpr bool BF16 = PREC == SAGNN_GEMM_BF16;
+  constexpr bool SPLIT = PREC == SAGNN_GEMM_FP32_BF16X3;
   const int tid = threadIdx.x;
   const int kreal = g.kdim;                  // any multiple of 4
   const int kdim = (kreal + 31) & ~31;       // the k loop runs over the zero-padded extent
 
-  // stage the W slab: fp32 as Ws[k][n]; bf16 packed as Ws[k/8][n][k%8]; zero outside W
+  // stage the W slab: fp32 as Ws[k][n]; bf16 packed as Ws[k/8][n][k%8] (split mode: three such
+  // planes, one per term); zero outside W
   for (int idx = tid; idx < kdim * NB; idx += WAVES * 64) {
     const int k = idx / NB, n = idx - k * NB;
     const int col = g.n0 + n;
     float w = 0.f;
     if (col < g.nout && k < kreal)
       w = g.transW ? g.W[(int64_t)col * g.ldw + k] : g.W[(int64_t)k * g.ldw + col];
-    if (BF16)
+    if (SPLIT) {
+      __bf16* Wp = reinterpret_cast<__bf16*>(smem);
+      const int at = ((k >> 3) * NB + n) * 8 + (k & 7);
+      split3(w, Wp[at], Wp[kdim * NB + at], Wp[2 * kdim * NB + at]);
+    } else if (BF16) {
       reinterpret_cast<__bf16*>(smem)[((k >> 3) * NB + n) * 8 + (k & 7)] = (__bf16)w;
-    else
+    } else {
       reinterpret_cast<float*>(smem)[k * NB + n] = w;
+    }
   }
   __syncthreads();
 
@@ -90,7 +108,59 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
 
     // The k loop runs in groups of JB steps; the A-operand loads of the next group are issued
     // before the MFMAs of the current one, so HBM latency hides behind matrix-core work.
-    if (BF16) {
+    if (SPLIT) {
+      const bf16x8* __restrict__ Ws = reinterpret_cast<const bf16x8*>(smem);
+      const int plane = (kdim >> 3) * NB;      // bf16x8 elements per term plane
+      constexpr int JB = 2;
+      const int ngroups = NG > 0 ? NG : kdim / (16 * JB);
+      float4 cur[JB][2], nxt[JB][2];
+#pragma unroll
+      for (int q = 0; q < JB; ++q) {
+        cur[q][0] = ldx4(16 * q + 8 * h);
+        cur[q][1] = ldx4(16 * q + 8 * h + 4);
+      }
+#pragma unroll
+      for (int gi = 0; gi < (NG > 0 ? NG : ngroups); ++gi) {
+        if (gi + 1 < ngroups) {
+#pragma unroll
+          for (int q = 0; q < JB; ++q) {
+            nxt[q][0] = ldx4(16 * ((gi + 1) * JB + q) + 8 * h);
+            nxt[q][1] = ldx4(16 * ((gi + 1) * JB + q) + 8 * h + 4);
+          }
+        }
+        if constexpr (NG > 0) __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of this group's MFMAs
+#pragma unroll
+        for (int q = 0; q < JB; ++q) {
+          const int j = gi * JB + q;
+          const float xs[8] = {cur[q][0].x, cur[q][0].y, cur[q][0].z, cur[q][0].w,
+                               cur[q][1].x, cur[q][1].y, cur[q][1].z, cur[q][1].w};
+          bf16x8 a1, a2, a3;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            __bf16 t1, t2, t3;
+            split3(xs[i], t1, t2, t3);
+            a1[i] = t1; a2[i] = t2; a3[i] = t3;
+          }
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const int at = (2 * j + h) * NB + nt * 32 + r;
+            const bf16x8 b1 = Ws[at], b2 = Ws[plane + at], b3 = Ws[2 * plane + at];
+            // the six products down to 2^-16 of the leading one, smallest first
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, b1, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b3, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b2, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, b1, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b2, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[nt], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < JB; ++q) {
+          cur[q][0] = nxt[q][0];
+          cur[q][1] = nxt[q][1];
+        }
+      }
+    } else if (BF16) {
       const bf16x8* __restrict__ Ws = reinterpret_cast<const bf16x8*>(smem);
       constexpr int JB = 2;
       const int ngroups = NG > 0 ? NG : kdim / (16 * JB);
@@ -222,12 +292,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_nn_kernel(const GemmArgs g) {
   }
 }
 
-template <int NT, bool BF16, int WAVES>
+template <int NT, int PREC, int WAVES>
 int launch_nn_waves(const GemmArgs& g, size_t lds, hipStream_t s) {
-  void (*kern)(const GemmArgs) = gemm_nn_kernel<NT, BF16, WAVES, false, 0>;
-  if (g.kdim & 31) kern = gemm_nn_kernel<NT, BF16, WAVES, true, 0>;
-  else if (g.kdim == 128) kern = gemm_nn_kernel<NT, BF16, WAVES, false, 4>;
-  else if (g.kdim == 256) kern = gemm_nn_kernel<NT, BF16, WAVES, false, 8>;
+  void (*kern)(const GemmArgs) = gemm_nn_kernel<NT, PREC, WAVES, false, 0>;
+  if (g.kdim & 31) kern = gemm_nn_kernel<NT, PREC, WAVES, true, 0>;
+  else if (g.kdim == 128) kern = gemm_nn_kernel<NT, PREC, WAVES, false, 4>;
+  else if (g.kdim == 256) kern = gemm_nn_kernel<NT, PREC, WAVES, false, 8>;
   SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int64_t ntiles = (g.m + 31) / 32;
@@ -240,14 +310,20 @@ int launch_nn_waves(const GemmArgs& g, size_t lds, hipStream_t s) {
   return SAGNN_OK;
 }
 
-template <int NT, bool BF16>
+// bytes of LDS the W slab of NT*32 columns takes (split mode: three bfloat16 planes)
+inline size_t nn_slab_bytes(int32_t kdim, int nt, int prec) {
+  const size_t elems = (size_t)((kdim + 31) & ~31) * nt * 32;
+  return prec == SAGNN_GEMM_FP32 ? elems * 4 : (prec == SAGNN_GEMM_BF16 ? elems * 2 : elems * 6);
+}
+
+template <int NT, int PREC>
 int launch_nn(const GemmArgs& g, hipStream_t s) {
-  const size_t lds = (size_t)((g.kdim + 31) & ~31) * NT * 32 * (BF16 ? 2 : 4);
+  const size_t lds = nn_slab_bytes(g.kdim, NT, PREC);
   if (lds > 160 * 1024) return SAGNN_EINVAL;
   // fp32: 4 wavefronts per workgroup, two workgroups per CU while the W slab allows it; when the
   // slab is so large that only one workgroup fits a CU, 8 wavefronts keep two per SIMD
-  if (BF16 || lds > 80 * 1024) return launch_nn_waves<NT, BF16, 8>(g, lds, s);
-  return launch_nn_waves<NT, BF16, 4>(g, lds, s);
+  if (PREC != SAGNN_GEMM_FP32 || lds > 80 * 1024) return launch_nn_waves<NT, PREC, 8>(g, lds, s);
+  return launch_nn_waves<NT, PREC, 4>(g, lds, s);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -437,7 +513,7 @@ int launch_gemm_tn(const float* X, int64_t ldx, const float* S, int64_t lds_, in
   if (m < 0 || fi <= 0 || fo <= 0 || (fi & 3) || (fo & 3) || fi > 256 || fo > 256 ||
       ldx < fi || lds_ < fo || (ldx & 3) || (lds_ & 3))
     return SAGNN_EINVAL;
-  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
+  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16 && prec != SAGNN_GEMM_FP32_BF16X3) return SAGNN_EINVAL;
   if (!Y || !yws || !aligned16(yws)) return SAGNN_EINVAL;
   if (m > 0 && (!X || !S || !aligned16(X) || !aligned16(S))) return SAGNN_EINVAL;
   if (yws_bytes < gemm_tn_ws_bytes(m, fi, fo)) return SAGNN_ECAPACITY;
@@ -471,7 +547,7 @@ int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_
                 hipStream_t s) {
   if (m < 0 || kdim <= 0 || nout <= 0 || (kdim & 3) || (nout & 3) || kdim > 256 || nout > 256)
     return SAGNN_EINVAL;
-  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
+  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16 && prec != SAGNN_GEMM_FP32_BF16X3) return SAGNN_EINVAL;
   if (act != SAGNN_ACT_IDENTITY && act != SAGNN_ACT_RELU) return SAGNN_EINVAL;
   if (transW != 0 && transW != 1) return SAGNN_EINVAL;
   if (ldx < kdim || (ldx & 3) || ldw < (transW ? kdim : nout)) return SAGNN_EINVAL;
@@ -488,18 +564,32 @@ int launch_gemm(const float* X, int64_t ldx, const float* W, int64_t ldw, int32_
   if (prec == SAGNN_GEMM_BF16) {
     g.n0 = 0;
     const int tiles = (nout + 31) / 32;
-    if (tiles <= 1) return launch_nn<1, true>(g, s);
-    if (tiles <= 2) return launch_nn<2, true>(g, s);
-    if (tiles <= 4) return launch_nn<4, true>(g, s);
-    return launch_nn<8, true>(g, s);
+    if (tiles <= 1) return launch_nn<1, SAGNN_GEMM_BF16>(g, s);
+    if (tiles <= 2) return launch_nn<2, SAGNN_GEMM_BF16>(g, s);
+    if (tiles <= 4) return launch_nn<4, SAGNN_GEMM_BF16>(g, s);
+    return launch_nn<8, SAGNN_GEMM_BF16>(g, s);
+  }
+  if (prec == SAGNN_GEMM_FP32_BF16X3) {
+    // the widest column slab whose three planes fit the LDS: 128 columns up to k = 128, 64 beyond
+    const int32_t slab = nn_slab_bytes(kdim, 4, prec) <= 160 * 1024 ? 128 : 64;
+    for (int32_t n0 = 0; n0 < nout; n0 += slab) {
+      g.n0 = n0;
+      const int tiles = ((nout - n0 < slab ? nout - n0 : slab) + 31) / 32;
+      int rc;
+      if (tiles <= 1) rc = launch_nn<1, SAGNN_GEMM_FP32_BF16X3>(g, s);
+      else if (tiles <= 2) rc = launch_nn<2, SAGNN_GEMM_FP32_BF16X3>(g, s);
+      else rc = launch_nn<4, SAGNN_GEMM_FP32_BF16X3>(g, s);
+      if (rc != SAGNN_OK) return rc;
+    }
+    return SAGNN_OK;
   }
   for (int32_t n0 = 0; n0 < nout; n0 += 128) {
     g.n0 = n0;
     const int tiles = ((nout - n0 < 128 ? nout - n0 : 128) + 31) / 32;
     int rc;
-    if (tiles <= 1) rc = launch_nn<1, false>(g, s);
-    else if (tiles <= 2) rc = launch_nn<2, false>(g, s);
-    else rc = launch_nn<4, false>(g, s);
+    if (tiles <= 1) rc = launch_nn<1, SAGNN_GEMM_FP32>(g, s);
+    else if (tiles <= 2) rc = launch_nn<2, SAGNN_GEMM_FP32>(g, s);
+    else rc = launch_nn<4, SAGNN_GEMM_FP32>(g, s);
     if (rc != SAGNN_OK) return rc;
   }
   return SAGNN_OK;

@@ -697,7 +697,7 @@ int launch_fused_sweep_layer(const int32_t* rowptr, const int32_t* colidx, const
   SpmmHostDesc desc{};
   if (!fused_sweep_layer_applicable(ws, f_in, f_out) || !spmm_desc_get(ws, &desc)) return 1;
   if (desc.m != m || desc.nnz != nnz) return SAGNN_EINVAL;
-  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16) return SAGNN_EINVAL;
+  if (prec != SAGNN_GEMM_FP32 && prec != SAGNN_GEMM_BF16 && prec != SAGNN_GEMM_FP32_BF16X3) return SAGNN_EINVAL;
   if (act != SAGNN_ACT_IDENTITY && act != SAGNN_ACT_RELU) return SAGNN_EINVAL;
   if (nnz > 0 && k < desc.k) return SAGNN_EINVAL;
   if (!rowptr || !H || !W || (!Z && !Hout) || ldh < f_in || (ldh & 3) || !aligned16(H)) return SAGNN_EINVAL;
@@ -706,7 +706,7 @@ int launch_fused_sweep_layer(const int32_t* rowptr, const int32_t* colidx, const
   char* base = reinterpret_cast<char*>(ws);
   const SpmmWsHeader* hdr = reinterpret_cast<const SpmmWsHeader*>(base + L.header);
   const uint32_t kmax = k > 0 ? (uint32_t)(k - 1) : 0u;
-  const bool bf16 = prec == SAGNN_GEMM_BF16;
+  const bool bf16 = prec == SAGNN_GEMM_BF16;   // (the few rows left to the small kernel: three-term mode uses fp32 there)
 
   if (desc.has_empty_rows) {   // a row without entries: T = 0, so Z = 0 and sigma(0) = 0
     SpmmPtrs p{};
@@ -725,7 +725,7 @@ int launch_fused_sweep_layer(const int32_t* rowptr, const int32_t* colidx, const
   }
   SweepFusedArgs fa{};
   fa.W = W; fa.Z = Z; fa.Hout = Hout; fa.T = T; fa.f_out = f_out; fa.act = act;
-  int rc = sweep_launch_fused(desc, L, base, H, ldh, f_in, kmax, fa, bf16 ? 1 : 0, s);
+  int rc = sweep_launch_fused(desc, L, base, H, ldh, f_in, kmax, fa, prec, s);   // (operand modes are numbered like prec)
   if (rc != SAGNN_OK) return rc;
   const int64_t left = desc.c_rows + desc.n_multi_rows;
   if (left > 0) {

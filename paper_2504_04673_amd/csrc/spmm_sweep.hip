@@ -502,7 +502,17 @@ typedef __bf16 sweep_bf16x8 __attribute__((ext_vector_type(8)));
 // wavefront (rt, half) multiplies row tile rt by the 32-column tiles half, half + 2, .. of W and
 // stores the rows of Z / sigma(Z) at the rows the pieces belong to (slots that hold a piece of a
 // split row, or nothing, are skipped).  Called by all four wavefronts after a workgroup barrier.
-template <int KROW, bool BF16, int QT>
+// MODE: the matrix-core operands, numbered like SAGNN_GEMM_*: 0 fp32, 1 rounded to bfloat16, 2 fp32
+// as the exact sum of three bfloat16 terms with the six products down to 2^-16 of the leading one.
+// |t2| <= 2^-8 |x| and |t3| <= 2^-16 |x|; both subtractions are exact.
+__device__ __forceinline__ void sweep_split3(float x, __bf16& t1, __bf16& t2, __bf16& t3) {
+  t1 = (__bf16)x;
+  const float r = x - (float)t1;
+  t2 = (__bf16)r;
+  t3 = (__bf16)(r - (float)t2);
+}
+
+template <int KROW, int MODE, int QT>
 __device__ __forceinline__ void sweep_dense_epilogue(const float* __restrict__ lds_acc,
                                                      const int32_t* __restrict__ piece_target,
                                                      const SweepFusedArgs& fa, int wave, int lane) {
@@ -533,7 +543,56 @@ __device__ __forceinline__ void sweep_dense_epilogue(const float* __restrict__ l
     for (int q = 0; q < QT; ++q)
 #pragma unroll
       for (int v = 0; v < 16; ++v) z[q][v] = 0.f;
-    if constexpr (BF16) {
+    if constexpr (MODE == 2) {
+      // W as packed by sweep_pack_w_kernel with three planes: term t of W at Wp + t * (kRow / 8) * NB
+      const sweep_bf16x8* __restrict__ Wp = reinterpret_cast<const sweep_bf16x8*>(fa.Wp);
+      const int NB = nct * 32;
+      const int64_t plane = (int64_t)(kRow / 8) * NB;
+      constexpr int J = kRow / 16;
+      sweep_bf16x8 cur[QT][3], nxt[QT][3];
+#pragma unroll
+      for (int q = 0; q < QT; ++q)
+        if (q < nmy) {
+#pragma unroll
+          for (int t = 0; t < 3; ++t) cur[q][t] = Wp[t * plane + (int64_t)h * NB + (ct0 + 2 * q) * 32 + r];
+        }
+#pragma unroll 1
+      for (int j = 0; j < J; ++j) {
+        if (j + 1 < J) {
+#pragma unroll
+          for (int q = 0; q < QT; ++q)
+            if (q < nmy) {
+#pragma unroll
+              for (int t = 0; t < 3; ++t)
+                nxt[q][t] = Wp[t * plane + (int64_t)(2 * (j + 1) + h) * NB + (ct0 + 2 * q) * 32 + r];
+            }
+        }
+        const float4 x0 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h);
+        const float4 x1 = *reinterpret_cast<const float4*>(trow + 16 * j + 8 * h + 4);
+        const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+        sweep_bf16x8 a1, a2, a3;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          __bf16 t1, t2, t3;
+          sweep_split3(xs[i], t1, t2, t3);
+          a1[i] = t1; a2[i] = t2; a3[i] = t3;
+        }
+#pragma unroll
+        for (int q = 0; q < QT; ++q)
+          if (q < nmy) {
+            z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a3, cur[q][0], z[q], 0, 0, 0);
+            z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, cur[q][2], z[q], 0, 0, 0);
+            z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, cur[q][1], z[q], 0, 0, 0);
+            z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, cur[q][0], z[q], 0, 0, 0);
+            z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, cur[q][1], z[q], 0, 0, 0);
+            z[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, cur[q][0], z[q], 0, 0, 0);
+          }
+#pragma unroll
+        for (int q = 0; q < QT; ++q)
+#pragma unroll
+          for (int t = 0; t < 3; ++t) cur[q][t] = nxt[q][t];
+      }
+    } else if constexpr (MODE == 1) {
       // W as packed by sweep_pack_w_kernel: [k / 8][NB] vectors of 8 bfloat16 (zero beyond f_out)
       const sweep_bf16x8* __restrict__ Wp = reinterpret_cast<const sweep_bf16x8*>(fa.Wp);
       const int NB = nct * 32;
@@ -606,7 +665,7 @@ __device__ __forceinline__ void sweep_dense_epilogue(const float* __restrict__ l
   }
 }
 
-template <int FPL, int U, bool BUF, bool BF16>
+template <int FPL, int U, bool BUF, int MODE>
 __global__ __launch_bounds__(256) void spmm_sweep_fused_kernel(
     const uint32_t* __restrict__ code, const float* __restrict__ vals,
     const int32_t* __restrict__ wave_base, const int32_t* __restrict__ piece_target,
@@ -672,20 +731,28 @@ __global__ __launch_bounds__(256) void spmm_sweep_fused_kernel(
   }
   __syncthreads();
 
-  // tiles per pass: 4 at f = 256 (the LDS already limits a CU to two workgroups), 1 below
-  sweep_dense_epilogue<kRow, BF16, (FPL == 4 ? 4 : 1)>(lds_acc, piece_target, fa, wave, (int)lane);
+  // tiles per pass: 4 at f = 256 (the LDS already limits a CU to two workgroups; 2 with three operand
+  // terms per tile in registers), 1 below
+  sweep_dense_epilogue<kRow, MODE, (FPL == 4 ? (MODE == 2 ? 2 : 4) : 1)>(lds_acc, piece_target, fa, wave, (int)lane);
 }
 
 // W (f_in x f_out, row-major fp32) -> [f_in / 8][NB] vectors of 8 bfloat16 (k fastest), NB = f_out
 // rounded up to 32, zero beyond f_out: one 16-byte load then gives a lane its matrix-core operand
+// planes = 3: the three bfloat16 terms of every element, one plane of that layout per term
 __global__ __launch_bounds__(256) void sweep_pack_w_kernel(const float* __restrict__ W, int32_t f_in, int32_t f_out,
-                                                           int32_t NB, __bf16* __restrict__ Wp) {
+                                                           int32_t NB, __bf16* __restrict__ Wp, int32_t planes) {
   const int idx = blockIdx.x * 256 + threadIdx.x;     // one (k / 8, n) vector per thread
   if (idx >= (f_in / 8) * NB) return;
   const int kg = idx / NB, n = idx - kg * NB;
+  const int64_t plane = (int64_t)(f_in / 8) * NB * 8;
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
-    Wp[(int64_t)idx * 8 + i] = (__bf16)(n < f_out ? W[(int64_t)(kg * 8 + i) * f_out + n] : 0.f);
+  for (int i = 0; i < 8; ++i) {
+    const float w = n < f_out ? W[(int64_t)(kg * 8 + i) * f_out + n] : 0.f;
+    if (planes == 3)
+      sweep_split3(w, Wp[(int64_t)idx * 8 + i], Wp[plane + (int64_t)idx * 8 + i], Wp[2 * plane + (int64_t)idx * 8 + i]);
+    else
+      Wp[(int64_t)idx * 8 + i] = (__bf16)w;
+  }
 }
 
 // Lane-group variant: the wavefront carries R independent streams (zipped in memory), lane
@@ -694,8 +761,8 @@ __global__ __launch_bounds__(256) void sweep_pack_w_kernel(const float* __restri
 // Column ids and values still arrive by scalar loads; a lane picks its group's pair with
 // selects (the row offset is multiplied on the scalar side first).  Flushes are per group:
 // lanes of other groups are masked off by the divergent branch.
-// FUSE: 0 the product alone; 1 / 2 the layer form: the kernel ends with the dense transform of the
-// workgroup's rows (fp32 / bfloat16 operands, see sweep_dense_epilogue) instead of storing T (C is
+// FUSE: 0 the product alone; 1 / 2 / 3 the layer form: the kernel ends with the dense transform of the
+// workgroup's rows (fp32 / bfloat16 / three-term operands, see sweep_dense_epilogue) instead of storing T (C is
 // then only written if the caller wants T as a by-product: fa.T).
 template <int V, int R, int U, bool BUF, int FUSE = 0>
 __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
@@ -837,7 +904,7 @@ __global__ __launch_bounds__(256) void spmm_sweep_group_kernel(
     // (whole workgroups: the launcher only takes this form when n_waves is a multiple of 4 and
     // every wavefront owns 16 slots)
     __syncthreads();
-    sweep_dense_epilogue<kRow, FUSE == 2, 1>(lds_acc, piece_target, fa, wave, (int)lane);
+    sweep_dense_epilogue<kRow, FUSE - 1, 1>(lds_acc, piece_target, fa, wave, (int)lane);
   }
 }
 
@@ -1285,11 +1352,12 @@ int resident_workgroups(const void* kern, size_t lds) {
 }  // namespace
 
 namespace {
-// lane-group kernels: fuse = 0 product, 1 / 2 layer form with fp32 / bfloat16 operands
+// lane-group kernels: fuse = 0 product, 1 / 2 / 3 layer form with fp32 / bfloat16 / three-term operands
 template <int V, int R, bool BUF>
 auto group_kernel_of(int fuse) {
   if (fuse == 1) return &spmm_sweep_group_kernel<V, R, 8, BUF, 1>;
   if (fuse == 2) return &spmm_sweep_group_kernel<V, R, 8, BUF, 2>;
+  if (fuse == 3) return &spmm_sweep_group_kernel<V, R, 8, BUF, 3>;
   return &spmm_sweep_group_kernel<V, R, 8, BUF, 0>;
 }
 }  // namespace
@@ -1384,22 +1452,23 @@ int sweep_launch(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const f
 }
 
 int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, const float* B, int64_t ldb,
-                       int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t bf16, hipStream_t s) {
+                       int32_t f_in, uint32_t kmax, const SweepFusedArgs& fa, int32_t mode, hipStream_t s) {
   if (d.n_waves <= 0 || (d.n_waves & 3) || d.slots != kSweepSlots) return SAGNN_EINVAL;
+  if (mode < 0 || mode > 2) return SAGNN_EINVAL;
   if (!(f_in == 64 || f_in == 128 || f_in == 256) || fa.f_out <= 0 || fa.f_out > 256 || !fa.W) return SAGNN_EINVAL;
   if (d.groups == 2 || d.groups == 4) {
     // lane-group schedules: the same kernels as the product, with the dense transform compiled in
     SweepFusedArgs fg = fa;
     fg.Wp = nullptr;
-    if (bf16) {
+    if (mode != 0) {
       const int32_t NB = (fa.f_out + 31) / 32 * 32;
       __bf16* wp = reinterpret_cast<__bf16*>(ws + L.wpack);
       hipLaunchKernelGGL(sweep_pack_w_kernel, dim3((unsigned)ceil_div((int64_t)(f_in / 8) * NB, 256)), dim3(256), 0, s,
-                         fa.W, f_in, fa.f_out, NB, wp);
+                         fa.W, f_in, fa.f_out, NB, wp, mode == 2 ? 3 : 1);
       SAGNN_LAUNCH_CHECK();
       fg.Wp = wp;
     }
-    return sweep_launch(d, L, ws, B, ldb, 0, f_in, kmax, nullptr, f_in, 0, f_in, s, &fg, bf16 ? 2 : 1);
+    return sweep_launch(d, L, ws, B, ldb, 0, f_in, kmax, nullptr, f_in, 0, f_in, s, &fg, mode + 1);
   }
   if (d.groups != 1) return SAGNN_EINVAL;
   SweepDims sd{};
@@ -1412,11 +1481,11 @@ int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, c
   const size_t lds = (size_t)4 * kSweepSlots * f_in * sizeof(float);
   SweepFusedArgs fb = fa;
   fb.Wp = nullptr;
-  if (bf16) {
+  if (mode != 0) {
     const int32_t NB = (fa.f_out + 31) / 32 * 32;
     __bf16* wp = reinterpret_cast<__bf16*>(ws + L.wpack);
     hipLaunchKernelGGL(sweep_pack_w_kernel, dim3((unsigned)ceil_div((int64_t)(f_in / 8) * NB, 256)), dim3(256), 0, s,
-                       fa.W, f_in, fa.f_out, NB, wp);
+                       fa.W, f_in, fa.f_out, NB, wp, mode == 2 ? 3 : 1);
     SAGNN_LAUNCH_CHECK();
     fb.Wp = wp;
   }
@@ -1434,9 +1503,10 @@ int sweep_launch_fused(const SpmmHostDesc& d, const SpmmWsLayout& L, char* ws, c
     SAGNN_LAUNCH_CHECK();
     return SAGNN_OK;
   };
-#define SAGNN_SWF(FPL_)                                                                                  \
-  (bf16 ? (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, true>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, true>)) \
-        : (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, false>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, false>)))
+#define SAGNN_SWF(FPL_)                                                                                      \
+  (mode == 2 ? (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, 2>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, 2>))   \
+   : mode == 1 ? (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, 1>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, 1>)) \
+               : (buf ? go(spmm_sweep_fused_kernel<FPL_, 8, true, 0>) : go(spmm_sweep_fused_kernel<FPL_, 8, false, 0>)))
   if (f_in == 256) return SAGNN_SWF(4);
   if (f_in == 128) return SAGNN_SWF(2);
   return SAGNN_SWF(1);

@@ -145,7 +145,7 @@ def test_cfg3_width_sweep():
                 _, Zl, Hl = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, dev(Wf), act=sagnn.ACT_RELU,
                                                 prec=prec, ws=ws, want_t=False)
                 torch.cuda.synchronize()
-                zref, zabs = oracle.gemm(tfull[rows], Wf, bf16=bool(prec), Xabs=tfabs[rows], want_abs=True)
+                zref, zabs = oracle.gemm(tfull[rows], Wf, bf16=(prec == 1), Xabs=tfabs[rows], want_abs=True)
                 assert_close(Zl[sel], zref, zabs, rtol, f"cfg3 layer Z (sweep epilogue, prec {prec})")
                 assert_close(Hl[sel], np.maximum(zref, 0), zabs, rtol, f"cfg3 layer H' (sweep epilogue, prec {prec})")
                 assert torch.isfinite(Zl).all().item() and torch.equal(Hl, torch.clamp_min(Zl, 0))

@@ -307,15 +307,15 @@ def test_spmm_sweep_short_rows_as_whole_rows(f, groups, monkeypatch):
         # every row ends in a wavefront of the sweep: the layer takes the sweep-epilogue form
         fout = 96
         W = synth.normal((f, fout), 5, synth.STREAM_W, scale=1 / np.sqrt(f))
-        for prec in (0, 1):
+        for prec in (0, 1, 2):
             assert sagnn.gcn_layer_fwd_form(ws, f, fout, prec) == 2
-            o = oracle.gcn_layer_fwd(rowptr, colidx, val, B, W, act=1, bf16=bool(prec))
+            o = oracle.gcn_layer_fwd(rowptr, colidx, val, B, W, act=1, bf16=(prec == 1))
             Z0 = torch.full((m, fout), float("nan"), device="cuda")
             H0 = torch.full((m, fout), float("nan"), device="cuda")
             _, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(B), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws,
                                            want_t=False, out=(None, Z0, H0))
             torch.cuda.synchronize()
-            rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+            rtol = RTOL_BF16 if prec == 1 else RTOL_GEMM_FP32
             assert_close(Z, o["Z"], o["Zabs"], rtol, f"whole-row sweep layer Z f={f} prec={prec}")
             assert_close(Ho, o["H"], o["Zabs"], rtol, f"whole-row sweep layer H' f={f} prec={prec}")
 
@@ -760,7 +760,7 @@ def test_spmm_small_rmat(f):
 
 @pytest.mark.parametrize("m,k,n", [(1, 32, 32), (31, 64, 96), (33, 128, 128), (1000, 160, 256), (4097, 256, 64),
                                    (77, 16, 16), (500, 20, 100), (129, 100, 44), (64, 4, 4)])
-@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("prec", [0, 1, 2])
 @pytest.mark.parametrize("transW", [False, True])
 def test_dense_gemm(m, k, n, prec, transW):
     X = synth.normal((m, k), m, synth.STREAM_H)
@@ -768,8 +768,8 @@ def test_dense_gemm(m, k, n, prec, transW):
     if prec == 1:
         X.reshape(-1)[:4] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 2.0 ** -8 + 2.0 ** -20][:min(4, X.size)]
     mask = synth.normal((m, n), n, synth.STREAM_G)
-    ref, zabs = oracle.gemm(X, W, bf16=bool(prec), transW=transW, want_abs=True)
-    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
+    ref, zabs = oracle.gemm(X, W, bf16=(prec == 1), transW=transW, want_abs=True)
+    rtol = RTOL_BF16 if prec == 1 else RTOL_GEMM_FP32
     Z, A = sagnn.dense_gemm_act(dev(X), dev(W), transW=transW, prec=prec, act=sagnn.ACT_RELU, want_z=True, want_act=True)
     torch.cuda.synchronize()
     assert_close(Z, ref, zabs, rtol, "gemm Z")
@@ -778,6 +778,37 @@ def test_dense_gemm(m, k, n, prec, transW):
     torch.cuda.synchronize()
     assert_close(Zm, np.where(mask > 0, ref, 0), zabs, rtol, "gemm masked")
     assert torch.equal(Zm == 0, (dev(mask) <= 0) | (Z == 0))
+
+
+@pytest.mark.parametrize("k,n", [(128, 128), (256, 256), (100, 44)])
+def test_bf16x3_gemm_has_the_accuracy_of_the_fp32_gemm(k, n):
+    """fp32 operands as three bfloat16 terms, six products: every operand bit takes part, so the
+    result must be as close to the fp64 oracle as the fp32 matrix-core product is (both accumulate
+    in fp32), and far inside the fp32 tolerance.  Operands with all 24 significant bits set, of both
+    signs, very small and very large magnitudes, and zeros: a term lost in the split, a wrong pairing
+    of the terms or a rounding that does not sum back to the operand shows at 2^-9 .. 2^-17."""
+    m = 777
+    X = synth.normal((m, k), 5, synth.STREAM_H)
+    W = synth.normal((k, n), 5, synth.STREAM_W, scale=1 / np.sqrt(k))
+    X[0, :] = np.float32(1.0) + np.float32(2.0 ** -23) * np.arange(1, 2 * k, 2, dtype=np.float32)   # dense low bits
+    X[1, :] = -(np.float32(2.0) - np.float32(2.0 ** -23))                                              # all ones
+    X[2, :] = X[2, :] * np.float32(1e-30)
+    X[3, :] = X[3, :] * np.float32(1e30)
+    X[4, :] = 0
+    X[5, ::2] = np.float32(1.0 + 2.0 ** -8 + 2.0 ** -16)      # a tie at the first rounding, low bits behind it
+    W[:, 0] = np.float32(1.0) - np.float32(2.0 ** -24)
+    W[:, 1] = np.float32(-3.0) * (np.float32(1.0) + np.float32(2.0 ** -23))
+    ref, zabs = oracle.gemm(X, W, want_abs=True)
+    Z32, _ = sagnn.dense_gemm_act(dev(X), dev(W), prec=0)
+    Zs, _ = sagnn.dense_gemm_act(dev(X), dev(W), prec=2)
+    torch.cuda.synchronize()
+    assert_close(Zs, ref, zabs, RTOL_GEMM_FP32, "bf16x3 gemm")
+    scale = np.where(zabs > 0, zabs, 1.0)
+    e32 = float(np.max(np.abs(Z32.cpu().numpy().astype(np.float64) - ref) / scale))
+    es = float(np.max(np.abs(Zs.cpu().numpy().astype(np.float64) - ref) / scale))
+    assert es <= max(2 * e32, 2e-7), (es, e32)
+    assert es < 2e-6
+    assert bool((Zs[4] == 0).all())
 
 
 def test_bf16_gemm_is_tight_against_bf16_rounded_oracle():
@@ -791,7 +822,8 @@ def test_bf16_gemm_is_tight_against_bf16_rounded_oracle():
     assert_close(Z, ref, zabs, 2e-5, "bf16 gemm vs bf16-rounded oracle")
 
 
-@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 32), (0, 16, 16), (1, 48, 20)])
+@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 32), (0, 16, 16), (1, 48, 20),
+                                           (2, 128, 128), (2, 256, 256), (2, 48, 20)])
 def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     g = synth.sbm_graph(6000, 16, 40, 2, 3)
     H = synth.normal((g.n, fin), 1, synth.STREAM_H)
@@ -800,8 +832,8 @@ def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     rp, ci, v = csr_dev(g)
     ws_in = sagnn.spmm_csr_prepare(rp, ci, v, g.n, fin)
     ws_out = sagnn.spmm_csr_prepare(rp, ci, v, g.n, fout)
-    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
-    o = oracle.gcn_layer_fwd(g.rowptr, g.colidx, g.val, H, W, act=1, bf16=bool(prec))
+    rtol = RTOL_BF16 if prec == 1 else RTOL_GEMM_FP32
+    o = oracle.gcn_layer_fwd(g.rowptr, g.colidx, g.val, H, W, act=1, bf16=(prec == 1))
     T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws_in)
     torch.cuda.synchronize()
     assert_close(T, o["T"], o["Tabs"], RTOL_SPMM, "layer T")
@@ -810,20 +842,20 @@ def test_gcn_layer_fwd_bwd_small(prec, fin, fout):
     # the dense stage by itself, on the very T the library produced: scale |T| |W| (no slack
     # inherited from the sparse product's sum of magnitudes)
     Tg = T.cpu().numpy()
-    zt, ztabs = oracle.gemm(Tg, W, bf16=bool(prec), want_abs=True)
+    zt, ztabs = oracle.gemm(Tg, W, bf16=(prec == 1), want_abs=True)
     assert_close(Z, zt, ztabs, rtol, "layer Z vs oracle GEMM of the library's T")
     # backward of this layer with the oracle's own Z / inputs as given data
     Zprev = synth.normal((g.n, fin), 2, synth.STREAM_G)
-    ob = oracle.gcn_layer_bwd(g.rowptr, g.colidx, g.val, G, W, Zprev, H, bf16=bool(prec))
+    ob = oracle.gcn_layer_bwd(g.rowptr, g.colidx, g.val, G, W, Zprev, H, bf16=(prec == 1))
     S, Gp, Y = sagnn.gcn_layer_bwd(rp, ci, v, dev(G), dev(W), dev(Zprev), dev(H), prec=prec, ws=ws_out)
     torch.cuda.synchronize()
     assert_close(S, ob["S"], ob["Sabs"], RTOL_SPMM, "bwd S")
     assert_close(Gp, ob["Gprev"], ob["Gabs"], rtol, "bwd Gprev")
     assert_close(Y, ob["Y"], ob["Yabs"], rtol, "bwd Y")
     Sg = S.cpu().numpy()
-    gt, gtabs = oracle.gemm(Sg, W, bf16=bool(prec), transW=True, want_abs=True)
+    gt, gtabs = oracle.gemm(Sg, W, bf16=(prec == 1), transW=True, want_abs=True)
     assert_close(Gp, np.where(Zprev > 0, gt, 0), gtabs, rtol, "bwd Gprev vs oracle GEMM of the library's S")
-    yt, ytabs = oracle.gemm(H, Sg, bf16=bool(prec), transX=True, want_abs=True)
+    yt, ytabs = oracle.gemm(H, Sg, bf16=(prec == 1), transX=True, want_abs=True)
     assert_close(Y, yt, ytabs, rtol, "bwd Y vs oracle GEMM of the library's S")
 
 
@@ -896,8 +928,8 @@ def test_gcn_layer_fwd_fused(prec, fin, fout, graph, cfg1):
     H = synth.normal((n, fin), 1, synth.STREAM_H)
     W = synth.normal((fin, fout), 1, synth.STREAM_W, scale=1 / np.sqrt(fin))
     rp, ci, v = dev(rowptr), dev(colidx), dev(val)
-    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
-    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1, bf16=bool(prec))
+    rtol = RTOL_BF16 if prec == 1 else RTOL_GEMM_FP32
+    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1, bf16=(prec == 1))
     T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, want_t=False)
     torch.cuda.synchronize()
     assert T is None
@@ -909,11 +941,12 @@ def test_gcn_layer_fwd_fused(prec, fin, fout, graph, cfg1):
     torch.cuda.synchronize()
     assert_close(T, o["T"], o["Tabs"], RTOL_SPMM, "fused T")
     assert torch.equal(Z2, Z)
-    zt, ztabs = oracle.gemm(T.cpu().numpy(), W, bf16=bool(prec), want_abs=True)
+    zt, ztabs = oracle.gemm(T.cpu().numpy(), W, bf16=(prec == 1), want_abs=True)
     assert_close(Z, zt, ztabs, rtol, "fused Z vs oracle GEMM of the kernel's own T")
 
 
-@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 36), (1, 128, 100), (1, 256, 64)])
+@pytest.mark.parametrize("prec,fin,fout", [(0, 128, 128), (1, 256, 256), (0, 64, 36), (1, 128, 100), (1, 256, 64),
+                                           (2, 128, 128), (2, 256, 256), (2, 64, 36), (2, 128, 100)])
 @pytest.mark.parametrize("graph", ["regular_all_rows_swept", "with_split_short_and_empty_rows"])
 def test_gcn_layer_fwd_sweep_epilogue(prec, fin, fout, graph, monkeypatch):
     """The layer with d_T = NULL on a workspace prepared for the one-row-per-instruction sweep: the
@@ -942,8 +975,8 @@ def test_gcn_layer_fwd_sweep_epilogue(prec, fin, fout, graph, monkeypatch):
     assert sagnn.gcn_layer_fwd_form(ws, fin, fout, prec) == 2
     if graph != "regular_all_rows_swept":
         assert info["split_rows"] >= 3 and info["chunk_rows"] > 0 and info["has_empty_rows"] == 1
-    rtol = RTOL_BF16 if prec else RTOL_GEMM_FP32
-    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1, bf16=bool(prec))
+    rtol = RTOL_BF16 if prec == 1 else RTOL_GEMM_FP32
+    o = oracle.gcn_layer_fwd(rowptr, colidx, val, H, W, act=1, bf16=(prec == 1))
     Z0 = torch.full((m, fout), float("nan"), device="cuda")
     H0 = torch.full((m, fout), float("nan"), device="cuda")
     T, Z, Ho = sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, ws=ws,
@@ -982,7 +1015,11 @@ def test_gcn_layer_fwd_sweep_epilogue(prec, fin, fout, graph, monkeypatch):
         assert_close(Zw, o["Z"], o["Zabs"], rtol, "sweep epilogue, prepared 128 called 64")
     # a workspace of the 256-wide schedule cannot serve... nothing: every width has a form; an
     # unprepared call (no workspace) takes the row-range kernel
-    assert sagnn.gcn_layer_fwd_form(None, fin, fout, prec) == 1
+    # (the row-range kernel has no three-term form: such a call is an error, not a silent fp32 product)
+    assert sagnn.gcn_layer_fwd_form(None, fin, fout, prec) == (0 if prec == 2 else 1)
+    if prec == 2:
+        with pytest.raises(sagnn.SagnnError):
+            sagnn.gcn_layer_fwd(rp, ci, v, dev(H), dev(W), act=sagnn.ACT_RELU, prec=prec, want_t=False)
 
 
 def test_gcn_layer_fwd_fused_degenerate_shapes():
