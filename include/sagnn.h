@@ -56,6 +56,7 @@ enum {
 
 #define SAGNN_PLAN_VALIDATE 1u  /* flags bit 0 of spmm_plan_needed_rows */
 #define SAGNN_PLAN_OBLIVIOUS 2u /* flags bit 1: plan of the sparsity-oblivious algorithm   */
+#define SAGNN_PLAN_MULTIPASS 4u /* flags bit 2: never take the one-launch path of small blocks */
 
 #define SAGNN_ACT_IDENTITY 0
 #define SAGNN_ACT_RELU 1
@@ -107,6 +108,11 @@ int sagnn_version(void);
  * its whole block row of H): every column of [0,n) is "needed", so d_needed = 0..n-1,
  * h_blk_off = h_colblk and d_colidx_compact = d_colidx.  Same kernels downstream; it exists so
  * that both algorithms can be measured on one harness.
+ *
+ * Small blocks (n <= 262,144 columns, m <= 262,144 rows, nnz <= 65,536, nb <= 16, not oblivious) are
+ * planned by one workgroup in one launch with one copy back (the launch-latency regime: the general
+ * path is ten launches and three copies); SAGNN_PLAN_MULTIPASS switches that off.  Results are the
+ * same either way.
  *
  * Workspace: spmm_plan_workspace_bytes(); contents are scratch.  Its size is a few bytes per
  * column plus, for wide blocks with many entries (n above about 5 M columns and nnz >= 2^22),

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     dense_gemm_act, gcn_layer_fwd, gcn_layer_fwd_form, gcn_layer_bwd,
     ColBlocks, spmm_split_colblocks, spmm_stage_loop, spmm_volume_stats, spmm_csr_transpose,
     spmm_perm_from_labels, spmm_csr_permute_symmetric,
-    ACT_IDENTITY, ACT_RELU, GEMM_FP32, GEMM_BF16, GEMM_FP32_BF16X3, PLAN_VALIDATE, PLAN_OBLIVIOUS,
+    ACT_IDENTITY, ACT_RELU, GEMM_FP32, GEMM_BF16, GEMM_FP32_BF16X3, PLAN_VALIDATE, PLAN_OBLIVIOUS, PLAN_MULTIPASS,
 )

@@ -12,7 +12,7 @@ from . import build as _build
 
 ACT_IDENTITY, ACT_RELU = 0, 1
 GEMM_FP32, GEMM_BF16, GEMM_FP32_BF16X3 = 0, 1, 2
-PLAN_VALIDATE, PLAN_OBLIVIOUS = 1, 2
+PLAN_VALIDATE, PLAN_OBLIVIOUS, PLAN_MULTIPASS = 1, 2, 4
 
 EXPORTS = [
     "sagnn_strerror", "sagnn_last_hip_error", "sagnn_version",
@@ -210,11 +210,20 @@ class Plan:
         return int(self.blk_off[-1])
 
 
+def _plan_flags(validate, oblivious, multipass):
+    if multipass is None:
+        multipass = os.environ.get("SAGNN_PLAN_MULTIPASS", "0") not in ("", "0")
+    return ((PLAN_VALIDATE if validate else 0) | (PLAN_OBLIVIOUS if oblivious else 0) |
+            (PLAN_MULTIPASS if multipass else 0))
+
+
 def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, validate=False,
-                          needed_cap=None, bufs=None, oblivious=False) -> Plan:
+                          needed_cap=None, bufs=None, oblivious=False, multipass=None) -> Plan:
     """NnzCols of every column block (Sec. 4.1).  Outputs are torch tensors; `needed` is sized
     min(n, nnz) unless needed_cap is given.  `bufs` = (ws, needed, compact) reuses buffers of an
-    earlier call (see plan_buffers) so that a repeated call allocates nothing."""
+    earlier call (see plan_buffers) so that a repeated call allocates nothing.  `multipass=True`
+    (default: the environment variable SAGNN_PLAN_MULTIPASS) keeps small blocks off the one-launch
+    path."""
     rowptr = _dev(rowptr, torch.int32, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     m, nnz = rowptr.numel() - 1, colidx.numel()
@@ -229,16 +238,14 @@ def spmm_plan_needed_rows(rowptr, colidx, n: int, colblk, want_compact=True, val
     rc = L.spmm_plan_needed_rows(_ptr(rowptr), _ptr(colidx), m, n, nnz,
                                  colblk.ctypes.data_as(ctypes.c_void_p), nb, _ptr(needed), cap,
                                  blk_off.ctypes.data_as(ctypes.c_void_p), _ptr(compact), _ptr(ws),
-                                 ws.numel(),
-                                 (PLAN_VALIDATE if validate else 0) | (PLAN_OBLIVIOUS if oblivious else 0),
-                                 _stream())
+                                 ws.numel(), _plan_flags(validate, oblivious, multipass), _stream())
     _check(rc, "spmm_plan_needed_rows")
     N = int(blk_off[-1])
     return Plan(needed[:N], blk_off, compact[:nnz] if compact is not None else None)
 
 
 def spmm_plan_needed_rows_noalloc(rowptr, colidx, n: int, colblk, needed, compact=None, validate=False,
-                                  oblivious=False) -> Plan:
+                                  oblivious=False, multipass=None) -> Plan:
     """spmm_plan_needed_rows without a workspace: the library's fixed per-GPU scratch array is
     used and nothing is allocated, here or in the library.  `needed` (int32, capacity = its
     length) and `compact` (int32, nnz entries, or None) are the caller's output buffers."""
@@ -254,7 +261,7 @@ def spmm_plan_needed_rows_noalloc(rowptr, colidx, n: int, colblk, needed, compac
     rc = lib().spmm_plan_needed_rows_noalloc(
         _ptr(rowptr), _ptr(colidx), m, n, nnz, colblk.ctypes.data_as(ctypes.c_void_p), nb, _ptr(needed),
         needed.numel(), blk_off.ctypes.data_as(ctypes.c_void_p), _ptr(compact),
-        (PLAN_VALIDATE if validate else 0) | (PLAN_OBLIVIOUS if oblivious else 0), _stream())
+        _plan_flags(validate, oblivious, multipass), _stream())
     _check(rc, "spmm_plan_needed_rows_noalloc")
     N = int(blk_off[-1])
     return Plan(needed[:N], blk_off, compact[:nnz] if compact is not None else None)

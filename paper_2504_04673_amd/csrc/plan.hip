@@ -90,7 +90,7 @@ PlanWs carve(void* base, int64_t n, int32_t nb, int64_t nnz) {
   w.blocksum = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(w.nblk + 1)));
   w.colblk = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
   w.blkoff = reinterpret_cast<int64_t*>(take(sizeof(int64_t) * (size_t)(nb + 1)));
-  w.err = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * 4));
+  w.err = reinterpret_cast<int32_t*>(take(256));   // 4 counters; the small-block path keeps its result record here
   const bool bucketed = bucket_mark_eligible(n, nnz);
   w.part = lds_mark_eligible(n, nnz)
                ? reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)kLdsGroups * kLdsWords))
@@ -738,6 +738,125 @@ SAGNN_EXPORT int spmm_plan_workspace_bytes(int64_t m, int64_t n, int64_t nnz, in
 namespace sagnn {
 namespace {
 
+// ---------------------------------------------------------------------------------------------
+// Small blocks (the launch-latency regime: a few thousand rows and columns): the whole plan in one
+// workgroup and one launch.  Membership bits, their prefix counts and the validity flags live in
+// LDS; the block boundaries come in as a kernel argument and the block offsets and error flags go
+// out through one small record, so the call is one launch, one copy back and one wait instead of
+// ten launches and three copies.  Same results as the general path: needed[] ascending, remap -1
+// for a column outside [0, n), nothing written to needed[] / the remap when N exceeds the
+// capacity or the validation fails.
+constexpr int64_t kSmallMaxCols = 262144;   // 4096 membership words of 64 columns
+constexpr int64_t kSmallMaxNnz = 65536;
+constexpr int64_t kSmallMaxRows = 262144;
+constexpr int32_t kSmallMaxBlocks = 16;
+struct SmallColblk { int64_t v[kSmallMaxBlocks + 1]; };
+struct SmallOut {
+  int32_t err[4];
+  int64_t blkoff[kSmallMaxBlocks + 1];
+};
+static_assert(sizeof(SmallOut) <= 256, "the record shares the 256-byte slot of the error counters");
+
+__global__ __launch_bounds__(1024) void plan_small_kernel(const int32_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ colidx, int64_t m, int64_t n,
+                                                          int64_t nnz, const SmallColblk cb, int32_t nb,
+                                                          int32_t* __restrict__ needed, int64_t needed_cap,
+                                                          int32_t* __restrict__ compact, int32_t validate,
+                                                          SmallOut* __restrict__ out) {
+  __shared__ uint64_t bm[kSmallMaxCols / 64];
+  __shared__ int32_t pre[kSmallMaxCols / 64 + 1];
+  __shared__ int32_t wsum[16];
+  __shared__ int32_t bad[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int W = (int)((n + 63) >> 6);
+  for (int i = tid; i < W; i += 1024) bm[i] = 0ull;
+  if (tid < 2) bad[tid] = 0;
+  __syncthreads();
+  if (validate) {
+    for (int64_t r = tid; r < m; r += 1024)
+      if (rowptr[r] > rowptr[r + 1]) bad[0] = 1;
+    if (tid == 0 && (rowptr[0] != 0 || (int64_t)rowptr[m] != nnz)) bad[0] = 1;
+  }
+  uint32_t* bits = reinterpret_cast<uint32_t*>(bm);   // bit c of the 64-bit word c >> 6 = bit c & 31 of 32-bit word c >> 5
+  // (eight loads in flight per thread: one workgroup has to hide the memory latency by itself)
+  for (int64_t e0 = tid; e0 < nnz; e0 += 8 * 1024) {
+    int32_t c8[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c8[j] = e0 + j * 1024 < nnz ? colidx[e0 + j * 1024] : 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (e0 + j * 1024 >= nnz) continue;
+      const int32_t c = c8[j];
+      if (c < 0 || c >= n) {
+        bad[1] = 1;
+      } else {
+        const uint32_t bit = 1u << (c & 31);
+        if ((__hip_atomic_load(&bits[c >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) & bit) == 0)
+          __hip_atomic_fetch_or(&bits[c >> 5], bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+    }
+  }
+  __syncthreads();
+  // prefix counts: thread t owns words 4t .. 4t + 3
+  int cnt[4], sum = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int w = 4 * tid + k;
+    cnt[k] = w < W ? __popcll(bm[w]) : 0;
+    sum += cnt[k];
+  }
+  int inc = sum;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int before = 0, N = 0;
+  for (int j = 0; j < 16; ++j) {
+    if (j < wave) before += wsum[j];
+    N += wsum[j];
+  }
+  int run = before + inc - sum;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int w = 4 * tid + k;
+    if (w < W) pre[w] = run;
+    run += cnt[k];
+  }
+  if (tid == 0) pre[W] = N;
+  __syncthreads();
+  auto rank = [&](int64_t c) -> int32_t {
+    if (c >= n) return N;
+    const int w = (int)(c >> 6);
+    return pre[w] + __popcll(bm[w] & ((1ull << (c & 63)) - 1ull));
+  };
+  for (int q = tid; q <= nb; q += 1024) out->blkoff[q] = rank(cb.v[q]);
+  if (tid < 4) out->err[tid] = tid < 2 ? bad[tid] : 0;
+  if ((int64_t)N > needed_cap || (validate && (bad[0] || bad[1]))) return;   // (the same for every thread)
+  for (int w = wave; w < W; w += 16) {     // one wavefront per word: lane = column, slot from the lanes below
+    const uint64_t x = bm[w];
+    const bool set = (x >> lane) & 1ull;
+    const int slot = __popcll(x & ((1ull << lane) - 1ull));
+    if (set) needed[pre[w] + slot] = w * 64 + lane;
+  }
+  if (compact)
+    for (int64_t e0 = tid; e0 < nnz; e0 += 8 * 1024) {
+      int32_t c8[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c8[j] = e0 + j * 1024 < nnz ? colidx[e0 + j * 1024] : 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (e0 + j * 1024 < nnz) compact[e0 + j * 1024] = (c8[j] < 0 || c8[j] >= n) ? -1 : rank(c8[j]);
+    }
+}
+
+}  // namespace
+}  // namespace sagnn
+
+namespace sagnn {
+namespace {
+
 // host-side argument checks shared by the two planning entry points (no HIP call is made)
 int plan_check_args(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_t n,
                     int64_t nnz, const int64_t* h_colblk, int32_t nb, const int32_t* d_needed,
@@ -760,6 +879,23 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
              int64_t* h_blk_off, int32_t* d_colidx_compact, const PlanWs& w, uint32_t flags,
              hipStream_t s) {
 
+  if ((flags & (SAGNN_PLAN_OBLIVIOUS | SAGNN_PLAN_MULTIPASS)) == 0 && n <= kSmallMaxCols && nnz <= kSmallMaxNnz && m <= kSmallMaxRows &&
+      nb <= kSmallMaxBlocks) {
+    // one launch, one copy back, one wait (the record lies in the slot of the error counters)
+    SmallColblk cb{};
+    for (int32_t q = 0; q <= nb; ++q) cb.v[q] = h_colblk[q];
+    SmallOut* d_out = reinterpret_cast<SmallOut*>(w.err);
+    hipLaunchKernelGGL(plan_small_kernel, dim3(1), dim3(1024), 0, s, d_rowptr, d_colidx, m, n, nnz, cb, nb, d_needed,
+                       needed_cap, d_colidx_compact, (flags & SAGNN_PLAN_VALIDATE) ? 1 : 0, d_out);
+    SAGNN_LAUNCH_CHECK();
+    SmallOut h_out;
+    SAGNN_HIP(hipMemcpyAsync(&h_out, d_out, sizeof(SmallOut), hipMemcpyDeviceToHost, s));
+    SAGNN_HIP(hipStreamSynchronize(s));
+    for (int32_t q = 0; q <= nb; ++q) h_blk_off[q] = h_out.blkoff[q];
+    if ((flags & SAGNN_PLAN_VALIDATE) && (h_out.err[0] || h_out.err[1])) return SAGNN_EFORMAT;
+    if (h_blk_off[nb] > needed_cap) return SAGNN_ECAPACITY;
+    return SAGNN_OK;
+  }
   SAGNN_HIP(hipMemcpyAsync(w.colblk, h_colblk, sizeof(int64_t) * (size_t)(nb + 1),
                            hipMemcpyHostToDevice, s));
   // (the bucketed marking does not use the flag bytes: only the error counters are cleared then)

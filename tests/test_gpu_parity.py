@@ -81,15 +81,79 @@ def test_pack_rows_offsets_beyond_4gib():
 
 # ------------------------------------------------------------------------------------ plan
 
+def small_block(m, n, nnz, nb):
+    """the shapes the library plans with one workgroup in one launch"""
+    return n <= 262144 and m <= 262144 and nnz <= 65536 and nb <= 16
+
+
 def check_plan(rowptr, colidx, n, colblk):
-    plan = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), n, colblk)
-    torch.cuda.synchronize()
+    """Against the oracle; small blocks through both the one-launch and the general path."""
     needed, blk_off, compact = oracle.needed_rows(rowptr, colidx, n, colblk)
-    assert np.array_equal(plan.blk_off, blk_off)
-    assert np.array_equal(plan.needed.cpu().numpy(), needed)
-    if colidx.size:
-        assert np.array_equal(plan.colidx_compact.cpu().numpy(), compact)
+    modes = (False, True) if small_block(rowptr.size - 1, n, colidx.size, len(colblk) - 1) else (False,)
+    for multipass in modes:
+        plan = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), n, colblk, multipass=multipass)
+        torch.cuda.synchronize()
+        assert np.array_equal(plan.blk_off, blk_off), multipass
+        assert np.array_equal(plan.needed.cpu().numpy(), needed), multipass
+        if colidx.size:
+            assert np.array_equal(plan.colidx_compact.cpu().numpy(), compact), multipass
     return plan
+
+
+@pytest.mark.parametrize("m,n,nnz,nb,seed", [(4096, 262_144, 65_536, 16, 0), (262_144, 262_144, 65_536, 1, 1),
+                                             (4096, 262_145, 65_536, 16, 2), (4096, 262_144, 65_537, 16, 3),
+                                             (4096, 262_144, 65_536, 17, 4), (300, 129, 5000, 7, 5),
+                                             (10, 64, 64, 2, 6), (7, 1, 40, 1, 7), (2000, 200_000, 3, 16, 8)])
+def test_plan_small_blocks_one_launch_and_its_limits(m, n, nnz, nb, seed):
+    """Shapes at and just beyond the limits of the one-launch path (columns, entries, blocks), tiny
+    and nearly empty ones; unsorted columns with duplicates, columns on both sides of every 64-column
+    word edge in use and of the last column, block boundaries that coincide and that cut inside a word.
+    Capacity: exactly N succeeds; N - 1 is refused with the required size reported and nothing written."""
+    rng = np.random.default_rng(seed)
+    cols = rng.integers(0, n, size=nnz)
+    edge = [0, n - 1, 63, 64, 65, 127, 128, n // 2, (n - 1) // 64 * 64, max((n - 1) // 64 * 64 - 1, 0)]
+    k = min(len(edge), nnz)
+    cols[:k] = [min(max(c, 0), n - 1) for c in edge[:k]]
+    if nnz > 200:
+        cols[100:200] = cols[0]                                   # a run of duplicates
+    cuts = np.sort(rng.integers(0, nnz + 1, size=m - 1))
+    rowptr = np.array([0, *cuts, nnz], dtype=np.int32)
+    colidx = cols.astype(np.int32)
+    bc = np.sort(rng.integers(0, n + 1, size=nb - 1))
+    if nb > 3:
+        bc[1] = bc[0]                                             # an empty block
+    colblk = np.array([0, *bc, n], dtype=np.int64)
+    plan = check_plan(rowptr, colidx, n, colblk)
+    N = plan.N
+    for multipass in ((False, True) if small_block(m, n, nnz, nb) else (False,)):
+        exact = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), n, colblk, needed_cap=N, multipass=multipass)
+        assert exact.N == N and torch.equal(exact.needed, plan.needed)
+        if N > 0:
+            ws, needed, compact = sagnn.plan_buffers(m, n, nnz, nb, torch.device("cuda"), N - 1, True)
+            needed.fill_(-7)
+            compact.fill_(-7)
+            with pytest.raises(sagnn.SagnnError) as ei:
+                sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), n, colblk, needed_cap=N - 1,
+                                            bufs=(ws, needed, compact), multipass=multipass)
+            assert ei.value.code == -2
+            torch.cuda.synchronize()
+            assert bool((needed == -7).all()) and bool((compact == -7).all())
+        # validation: a negative column, a column equal to n, a row pointer that steps back
+        for bad_at, bad_val in ((0, -1), (nnz - 1, n)):
+            badc = colidx.copy()
+            badc[bad_at] = bad_val
+            with pytest.raises(sagnn.SagnnError) as ei:
+                sagnn.spmm_plan_needed_rows(dev(rowptr), dev(badc), n, colblk, validate=True, multipass=multipass)
+            assert ei.value.code == -3
+            lax = sagnn.spmm_plan_needed_rows(dev(rowptr), dev(badc), n, colblk, multipass=multipass)
+            assert int(lax.colidx_compact[bad_at]) == -1            # not validated: skipped and flagged
+        if m >= 3 and rowptr[1] < nnz:
+            badrp = rowptr.copy()
+            badrp[1] = badrp[2] + 1
+            with pytest.raises(sagnn.SagnnError) as ei:
+                sagnn.spmm_plan_needed_rows(dev(badrp), dev(colidx), n, colblk, validate=True, multipass=multipass)
+            assert ei.value.code == -3
+        sagnn.spmm_plan_needed_rows(dev(rowptr), dev(colidx), n, colblk, validate=True, multipass=multipass)
 
 
 def test_plan_cfg1_all_blocks(cfg1):
