@@ -14,6 +14,8 @@
 // so lane (row r, half h) takes the 16 (fp32) or 32 (bf16) contiguous bytes
 // X[r][8j+4h..] / X[r][16j+8h..] and the matching rows of W are picked from LDS.
 //   fp32: v_mfma_f32_32x32x2_f32;  bf16: operands rounded RNE, v_mfma_f32_32x32x16_bf16.
+//   fp32 operands as three bfloat16 terms: the same bfloat16 instruction six times per product, W kept in
+//   LDS as three packed planes, X split in registers (the accuracy of the fp32 instruction at 6/16 of its cost).
 // The epilogue applies the optional mask and activation and stores from the accumulator
 // layout (row = 8*(v/4) + 4*(lane/32) + v%4, col = lane%32 of each 32x32 tile).
 //
