@@ -69,9 +69,8 @@ enum {
                                    matrix cores with fp32 accumulation.  The dropped products are below
                                    2^-23 |x||w|: the accuracy of SAGNN_GEMM_FP32, results not bit-equal
                                    to it.  dense_gemm_act, gcn_layer_fwd (with d_T given, or through a
-                                   workspace whose sweep ends with the dense transform) and the
-                                   G-gradient of gcn_layer_bwd run it; the weight gradient then uses
-                                   SAGNN_GEMM_FP32; the row-range one-kernel layer
+                                   workspace whose sweep ends with the dense transform) and both
+                                   gradients of gcn_layer_bwd run it; the row-range one-kernel layer
                                    (gcn_layer_fwd_fused, gcn_layer_fwd without d_T and without such a
                                    workspace) returns SAGNN_EINVAL */
 

@@ -342,21 +342,22 @@ struct TnArgs {
   float* partial;  // [gridDim.x][fi][fo]
 };
 
-template <bool BF16>
+// PREC as in gemm_nn_kernel; PREC = 2 keeps three bfloat16 planes (one per term) of both staged operands
+template <int PREC>
 __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
-  using lds_t = typename std::conditional<BF16, __bf16, float>::type;
+  constexpr bool BF16 = PREC == SAGNN_GEMM_BF16;
+  constexpr bool X3 = PREC == SAGNN_GEMM_FP32_BF16X3;
+  using lds_t = typename std::conditional<PREC != SAGNN_GEMM_FP32, __bf16, float>::type;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   lds_t* Xs = reinterpret_cast<lds_t*>(smem);                    // [fi][KP]
   lds_t* Ss = Xs + (size_t)((g.fi + 31) / 32) * 32 * KP;         // [fo][KP], after the padded X part
+  const int plane = ((g.fi + 31) / 32 + (g.fo + 31) / 32) * 32 * KP;   // elements per term plane (X3)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i = lane & 31, h = lane >> 5;
   const int wa = wave >> 1, wb = wave & 1;  // wave tile: a-tiles {2wa,2wa+1}, b-tiles {4wb..4wb+3}
   const int TA = (g.fi + 31) / 32, TB = (g.fo + 31) / 32;
   // columns of the last tile that lie beyond fi / fo are never staged: keep them zero
-  for (int idx = tid; idx < (TA + TB) * 32 * KP; idx += kTnThreads) {
-    if (idx < TA * 32 * KP) Xs[idx] = (lds_t)0.f;
-    else (Xs + (size_t)TA * 32 * KP)[idx - TA * 32 * KP] = (lds_t)0.f;
-  }
+  for (int idx = tid; idx < (TA + TB) * 32 * KP * (X3 ? 3 : 1); idx += kTnThreads) Xs[idx] = (lds_t)0.f;
   __syncthreads();
 
   const int64_t r_begin = (int64_t)blockIdx.x * g.rows_per_wg;
@@ -399,13 +400,26 @@ __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int col = cg * 4 + c;
-        if (col < g.fi) {
-          Xs[col * KP + kk] = (lds_t)xa[c];
-          Xs[col * KP + kk + 1] = (lds_t)xb[c];
-        }
-        if (col < g.fo) {
-          Ss[col * KP + kk] = (lds_t)sa[c];
-          Ss[col * KP + kk + 1] = (lds_t)sb[c];
+        if constexpr (X3) {
+          __bf16* Xb = reinterpret_cast<__bf16*>(Xs);
+          __bf16* Sb = reinterpret_cast<__bf16*>(Ss);
+          if (col < g.fi) {
+            split3(xa[c], Xb[col * KP + kk], Xb[plane + col * KP + kk], Xb[2 * plane + col * KP + kk]);
+            split3(xb[c], Xb[col * KP + kk + 1], Xb[plane + col * KP + kk + 1], Xb[2 * plane + col * KP + kk + 1]);
+          }
+          if (col < g.fo) {
+            split3(sa[c], Sb[col * KP + kk], Sb[plane + col * KP + kk], Sb[2 * plane + col * KP + kk]);
+            split3(sb[c], Sb[col * KP + kk + 1], Sb[plane + col * KP + kk + 1], Sb[2 * plane + col * KP + kk + 1]);
+          }
+        } else {
+          if (col < g.fi) {
+            Xs[col * KP + kk] = (lds_t)xa[c];
+            Xs[col * KP + kk + 1] = (lds_t)xb[c];
+          }
+          if (col < g.fo) {
+            Ss[col * KP + kk] = (lds_t)sa[c];
+            Ss[col * KP + kk + 1] = (lds_t)sb[c];
+          }
         }
       }
     }
@@ -417,7 +431,39 @@ __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
     store_stage();
     __syncthreads();
     if (r0 + KB < r_end) load_stage(r0 + KB);  // prefetch the next stage into registers
-    if (BF16) {
+    if constexpr (X3) {
+      const __bf16* Xb = reinterpret_cast<const __bf16*>(Xs);
+      const __bf16* Sb = reinterpret_cast<const __bf16*>(Ss);
+#pragma unroll 1
+      for (int ks = 0; ks < KB / 16; ++ks) {
+        // (the terms of one operand pair at a time: 128 accumulator registers leave room for little else)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int tb = 4 * wb + b;
+          bf16x8 bv[3];
+#pragma unroll
+          for (int t = 0; t < 3; ++t)
+            bv[t] = *reinterpret_cast<const bf16x8*>(Sb + t * plane + ((tb < TB ? tb : 0) * 32 + i) * KP + ks * 16 + 8 * h);
+#pragma unroll
+          for (int a = 0; a < 2; ++a) {
+            const int ta = 2 * wa + a;
+            bf16x8 av[3];
+#pragma unroll
+            for (int t = 0; t < 3; ++t)
+              av[t] = *reinterpret_cast<const bf16x8*>(Xb + t * plane + ((ta < TA ? ta : 0) * 32 + i) * KP + ks * 16 + 8 * h);
+            if (ta < TA && tb < TB) {
+              // the six products down to 2^-16 of the leading one, smallest first
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[2], bv[0], acc[a][b], 0, 0, 0);
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0], bv[2], acc[a][b], 0, 0, 0);
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[1], bv[1], acc[a][b], 0, 0, 0);
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[1], bv[0], acc[a][b], 0, 0, 0);
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0], bv[1], acc[a][b], 0, 0, 0);
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0], bv[0], acc[a][b], 0, 0, 0);
+            }
+          }
+        }
+      }
+    } else if (BF16) {
 #pragma unroll
       for (int ks = 0; ks < KB / 16; ++ks) {
         bf16x8 av[2], bv[4];
@@ -524,17 +570,19 @@ int launch_gemm_tn(const float* X, int64_t ldx, const float* S, int64_t lds_, in
   g.X = X; g.ldx = ldx; g.S = S; g.lds_ = lds_; g.m = m; g.fi = fi; g.fo = fo;
   g.rows_per_wg = ceil_div(ceil_div(m > 0 ? m : 1, parts), KB) * KB;
   g.partial = reinterpret_cast<float*>(yws);
-  const bool bf16 = prec == SAGNN_GEMM_BF16;
-  const size_t lds = (size_t)(((fi + 31) / 32 + (fo + 31) / 32) * 32) * KP * (bf16 ? 2 : 4);
-  if (bf16) {
-    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_kernel<true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(gemm_tn_kernel<true>, dim3(parts), dim3(kTnThreads), lds, s, g);
-  } else {
-    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_kernel<false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(gemm_tn_kernel<false>, dim3(parts), dim3(kTnThreads), lds, s, g);
-  }
+  const size_t lds = (size_t)(((fi + 31) / 32 + (fo + 31) / 32) * 32) * KP *
+                     (prec == SAGNN_GEMM_BF16 ? 2 : (prec == SAGNN_GEMM_FP32_BF16X3 ? 6 : 4));
+  auto go = [&](auto kern) -> int {
+    SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds));
+    hipLaunchKernelGGL(kern, dim3(parts), dim3(kTnThreads), lds, s, g);
+    return SAGNN_OK;
+  };
+  int rc;
+  if (prec == SAGNN_GEMM_BF16) rc = go(gemm_tn_kernel<SAGNN_GEMM_BF16>);
+  else if (prec == SAGNN_GEMM_FP32_BF16X3) rc = go(gemm_tn_kernel<SAGNN_GEMM_FP32_BF16X3>);
+  else rc = go(gemm_tn_kernel<SAGNN_GEMM_FP32>);
+  if (rc != SAGNN_OK) return rc;
   SAGNN_LAUNCH_CHECK();
   const int64_t elems = (int64_t)fi * fo;
   hipLaunchKernelGGL(tn_reduce_kernel, dim3((unsigned)ceil_div(elems, 256)), dim3(256), 0, s,
