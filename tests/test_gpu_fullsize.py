@@ -140,7 +140,8 @@ def test_cfg3_width_sweep():
             Wf = np.ascontiguousarray(wl.W[:f, :f])
             rows = pick_rows(g, 1500, 4)
             sel = torch.from_numpy(rows).cuda()
-            for prec, rtol in ((sagnn.GEMM_FP32, RTOL_GEMM), (sagnn.GEMM_BF16, RTOL_BF16)):
+            for prec, rtol in ((sagnn.GEMM_FP32, RTOL_GEMM), (sagnn.GEMM_BF16, RTOL_BF16),
+                               (sagnn.GEMM_FP32_BF16X3, RTOL_GEMM)):
                 assert sagnn.gcn_layer_fwd_form(ws, f, f, prec) == 2
                 _, Zl, Hl = sagnn.gcn_layer_fwd(rp, plan.colidx_compact, v, Hn, dev(Wf), act=sagnn.ACT_RELU,
                                                 prec=prec, ws=ws, want_t=False)
