@@ -403,7 +403,7 @@ int gcn_layer_fwd(const int32_t* d_rowptr, const int32_t* d_colidx, const float*
                   size_t ws_bytes, void* stream);
 /* Host query: *h_form = 2 if gcn_layer_fwd(d_T = NULL) with this prepared workspace (may be NULL)
  * and these widths runs as the slab sweep with the dense transform as its epilogue, 1 if it
- * runs as the row-range kernel, 0 if neither supports the shape. */
+ * runs as the row-range kernel, 0 if neither supports the shape or the operand mode. */
 int gcn_layer_fwd_form(const void* d_ws, int32_t f_in, int32_t f_out, int32_t gemm_prec, int32_t* h_form);
 int gcn_layer_fwd_fused(const int32_t* d_rowptr, const int32_t* d_colidx, const float* d_val,
                         int64_t m, int64_t k, int64_t nnz, const float* d_H, int64_t ldh,
