@@ -27,6 +27,21 @@ def test_header_symbols_are_exported():
     assert sorted(binding.EXPORTS) == names
 
 
+def test_binding_constants_match_the_header():
+    """The binding repeats the header's flag and mode values; a change on one side only would
+    silently select another path."""
+    text = open(os.path.join(ROOT, "include", "sagnn.h")).read()
+    defs = {k: int(v.rstrip("u"), 0) for k, v in re.findall(r"#define\s+(SAGNN_[A-Z0-9_]+)\s+(-?\d+u?)\b", text)}
+    pairs = {"SAGNN_PLAN_VALIDATE": binding.PLAN_VALIDATE, "SAGNN_PLAN_OBLIVIOUS": binding.PLAN_OBLIVIOUS,
+             "SAGNN_PLAN_MULTIPASS": binding.PLAN_MULTIPASS, "SAGNN_GEMM_FP32": binding.GEMM_FP32,
+             "SAGNN_GEMM_BF16": binding.GEMM_BF16, "SAGNN_GEMM_FP32_BF16X3": binding.GEMM_FP32_BF16X3,
+             "SAGNN_ACT_IDENTITY": binding.ACT_IDENTITY, "SAGNN_ACT_RELU": binding.ACT_RELU}
+    for name, value in pairs.items():
+        assert defs[name] == value, name
+    assert len({binding.PLAN_VALIDATE, binding.PLAN_OBLIVIOUS, binding.PLAN_MULTIPASS}) == 3
+    assert binding.PLAN_VALIDATE & binding.PLAN_OBLIVIOUS == 0 and binding.PLAN_MULTIPASS & 3 == 0
+
+
 def test_version_and_strerror():
     L = sagnn.lib()
     assert L.sagnn_version() >= 100
