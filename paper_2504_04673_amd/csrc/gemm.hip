@@ -389,7 +389,17 @@ __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
                                          : make_float4(0.f, 0.f, 0.f, 0.f);
       }
   };
+  // Transposing stores: column col = 4 cg + c of the stage goes to LDS row col, k contiguous, so a
+  // lane's two rows (k, k + 1) of one column are one 4-byte (bfloat16) or 8-byte (fp32) store.  Row
+  // starts are 20 (40) words apart: lanes that store the same c fall on two banks only.  Lane cg
+  // therefore takes its four columns in the order c = (j + cg / 2) mod 4, which spreads a store over
+  // eight banks.
+  auto pick = [](const float (&a)[4], int c) { return c == 0 ? a[0] : (c == 1 ? a[1] : (c == 2 ? a[2] : a[3])); };
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   auto store_stage = [&]() {
+    // (rounded-bfloat16 mode: the stage is short and bound by the latency of its loads; the selects of
+    // the rotation would only lengthen the path from a load to its store)
+    const int rot = BF16 ? 0 : (cg >> 1) & 3;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
       const int kk = (kp + 8 * p) * 2;
@@ -398,28 +408,52 @@ __global__ __launch_bounds__(kTnThreads) void gemm_tn_kernel(const TnArgs g) {
       const float sa[4] = {sr[p][0].x, sr[p][0].y, sr[p][0].z, sr[p][0].w};
       const float sb[4] = {sr[p][1].x, sr[p][1].y, sr[p][1].z, sr[p][1].w};
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int j = 0; j < 4; ++j) {
+        const int c = BF16 ? j : (j + rot) & 3;
         const int col = cg * 4 + c;
+        const float x0 = BF16 ? xa[j] : pick(xa, c), x1 = BF16 ? xb[j] : pick(xb, c);
+        const float s0 = BF16 ? sa[j] : pick(sa, c), s1 = BF16 ? sb[j] : pick(sb, c);
         if constexpr (X3) {
           __bf16* Xb = reinterpret_cast<__bf16*>(Xs);
           __bf16* Sb = reinterpret_cast<__bf16*>(Ss);
+          __bf16 lo[3], hi[3];
           if (col < g.fi) {
-            split3(xa[c], Xb[col * KP + kk], Xb[plane + col * KP + kk], Xb[2 * plane + col * KP + kk]);
-            split3(xb[c], Xb[col * KP + kk + 1], Xb[plane + col * KP + kk + 1], Xb[2 * plane + col * KP + kk + 1]);
+            split3(x0, lo[0], lo[1], lo[2]);
+            split3(x1, hi[0], hi[1], hi[2]);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+              bf16x2 t;
+              t[0] = lo[q]; t[1] = hi[q];
+              *reinterpret_cast<bf16x2*>(Xb + q * plane + col * KP + kk) = t;
+            }
           }
           if (col < g.fo) {
-            split3(sa[c], Sb[col * KP + kk], Sb[plane + col * KP + kk], Sb[2 * plane + col * KP + kk]);
-            split3(sb[c], Sb[col * KP + kk + 1], Sb[plane + col * KP + kk + 1], Sb[2 * plane + col * KP + kk + 1]);
+            split3(s0, lo[0], lo[1], lo[2]);
+            split3(s1, hi[0], hi[1], hi[2]);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+              bf16x2 t;
+              t[0] = lo[q]; t[1] = hi[q];
+              *reinterpret_cast<bf16x2*>(Sb + q * plane + col * KP + kk) = t;
+            }
+          }
+        } else if constexpr (BF16) {
+          __bf16* Xb = reinterpret_cast<__bf16*>(Xs);
+          __bf16* Sb = reinterpret_cast<__bf16*>(Ss);
+          bf16x2 t;
+          if (col < g.fi) {
+            t[0] = (__bf16)x0; t[1] = (__bf16)x1;
+            *reinterpret_cast<bf16x2*>(Xb + col * KP + kk) = t;
+          }
+          if (col < g.fo) {
+            t[0] = (__bf16)s0; t[1] = (__bf16)s1;
+            *reinterpret_cast<bf16x2*>(Sb + col * KP + kk) = t;
           }
         } else {
-          if (col < g.fi) {
-            Xs[col * KP + kk] = (lds_t)xa[c];
-            Xs[col * KP + kk + 1] = (lds_t)xb[c];
-          }
-          if (col < g.fo) {
-            Ss[col * KP + kk] = (lds_t)sa[c];
-            Ss[col * KP + kk + 1] = (lds_t)sb[c];
-          }
+          float* Xf = reinterpret_cast<float*>(Xs);
+          float* Sf = reinterpret_cast<float*>(Ss);
+          if (col < g.fi) *reinterpret_cast<float2*>(Xf + col * KP + kk) = make_float2(x0, x1);
+          if (col < g.fo) *reinterpret_cast<float2*>(Sf + col * KP + kk) = make_float2(s0, s1);
         }
       }
     }
