@@ -585,29 +585,47 @@ __global__ __launch_bounds__(kThreads) void scan_blocks_kernel(int32_t* __restri
   if (threadIdx.x == 0) blocksum[nblk] = carry;
 }
 
+// A tile of kWordsPerBlock words goes through LDS so that both the loads of the words and the
+// stores of the prefix counts and rank records are coalesced (thread t of step i moves element
+// t + 256 i), while the scan still gives a thread eight consecutive words.
 __global__ __launch_bounds__(kThreads) void prefix_kernel(const uint64_t* __restrict__ bm,
                                                           int64_t W,
                                                           const int32_t* __restrict__ blocksum,
                                                           int64_t nblk, int32_t* __restrict__ prefix,
                                                           uint4* __restrict__ rank16) {
-  const int64_t w0 = (int64_t)blockIdx.x * kWordsPerBlock + (int64_t)threadIdx.x * 8;
+  __shared__ uint64_t words[kWordsPerBlock];
+  __shared__ int32_t pre[kWordsPerBlock];
+  const int64_t tile0 = (int64_t)blockIdx.x * kWordsPerBlock;
+#pragma unroll
+  for (int i = 0; i < kWordsPerBlock / kThreads; ++i) {
+    const int j = threadIdx.x + i * kThreads;
+    words[j] = tile0 + j < W ? bm[tile0 + j] : 0ull;
+  }
+  __syncthreads();
   int c[8];
   int s = 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    c[i] = (w0 + i < W) ? __popcll(bm[w0 + i]) : 0;
+    c[i] = __popcll(words[threadIdx.x * 8 + i]);
     s += c[i];
   }
   int total;
   int run = blocksum[blockIdx.x] + block_exclusive_scan(s, &total);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    if (w0 + i < W) {
-      prefix[w0 + i] = run;
-      const uint64_t word = bm[w0 + i];
-      rank16[w0 + i] = make_uint4((uint32_t)word, (uint32_t)(word >> 32), (uint32_t)run, 0u);
-    }
+    pre[threadIdx.x * 8 + i] = run;
     run += c[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kWordsPerBlock / kThreads; ++i) {
+    const int j = threadIdx.x + i * kThreads;
+    if (tile0 + j < W) {
+      const uint64_t word = words[j];
+      const int32_t p = pre[j];
+      prefix[tile0 + j] = p;
+      rank16[tile0 + j] = make_uint4((uint32_t)word, (uint32_t)(word >> 32), (uint32_t)p, 0u);
+    }
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) prefix[W] = blocksum[nblk];
 }
