@@ -364,34 +364,89 @@ __global__ __launch_bounds__(1024) void bucket_starts_kernel(int32_t* __restrict
   if (threadIdx.x == 1023) a[nbk] = before + inc;
 }
 
-// every workgroup places its entries behind its own offset of every range; a run of adjacent lanes
-// with one range takes its places with one atomic and writes them side by side
+// Every workgroup places its entries behind its own offset of every range.  A batch of 8192 entries
+// is first sorted by range inside LDS (count per range, scan, place; runs of adjacent lanes with one
+// range share one atomic) and then written out in that order, so that neighbouring lanes store to
+// neighbouring places of one range (about a dozen entries per range and batch on a wide block)
+// instead of to as many ranges as there are lanes.
+constexpr int kBktBatch = 8 * kBktThreads;
 __global__ __launch_bounds__(kBktThreads) void bucket_scatter_kernel(const int32_t* __restrict__ colidx, int64_t nnz,
                                                                   int64_t n, int32_t nbk,
                                                                   const int32_t* __restrict__ within,
                                                                   const int32_t* __restrict__ start,
                                                                   int32_t* __restrict__ cols) {
-  __shared__ int32_t off[kBktMaxRanges];
-  for (int b = threadIdx.x; b < nbk; b += kBktThreads) off[b] = start[b] + within[(int64_t)b * kBktGroups + blockIdx.x];
+  __shared__ int32_t off[kBktMaxRanges];   // this workgroup's next free place in every range
+  __shared__ int32_t cur[kBktMaxRanges];   // batch: entries per range
+  __shared__ int32_t cs[kBktMaxRanges];    // batch: first staged position of every range
+  __shared__ int32_t stage[kBktBatch];
+  __shared__ int32_t wsum[kBktThreads / 64];
+  static_assert(kBktMaxRanges == 2 * kBktThreads, "a thread scans two ranges");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b0 = 2 * tid, b1 = 2 * tid + 1;                      // the two ranges this thread keeps
+  off[b0] = b0 < nbk ? start[b0] + within[(int64_t)b0 * kBktGroups + blockIdx.x] : 0;
+  off[b1] = b1 < nbk ? start[b1] + within[(int64_t)b1 * kBktGroups + blockIdx.x] : 0;
+  cur[b0] = 0;
+  cur[b1] = 0;
   __syncthreads();
-  const int lane = threadIdx.x & 63;
   const int64_t per = ceil_div_dev(nnz, kBktGroups);
   const int64_t e0 = (int64_t)blockIdx.x * per, e1 = e0 + per < nnz ? e0 + per : nnz;
-  for (int64_t base = e0; base < e1; base += 8 * kBktThreads) {
-    const int64_t e = base + threadIdx.x;
+  for (int64_t base = e0; base < e1; base += kBktBatch) {
+    const int64_t e = base + tid;
     int32_t c[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) c[j] = e + j * kBktThreads < e1 ? colidx[e + j * kBktThreads] : -1;
+    // count per range; the value an atomic returns is the entry's place among its range's entries of
+    // this batch, so one pass of LDS atomics (about one lane per clock) serves both the counts and the order
+    int32_t b[8], rank[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int32_t b = (c[j] < 0 || c[j] >= n) ? -1 : (int32_t)((uint32_t)c[j] / (uint32_t)kBktCols);
-      const LaneRun r = lane_run(b, lane);
-      int32_t first_pos = 0;
-      if (r.first && b >= 0) first_pos = atomicAdd(&off[b], r.len);
-      const int32_t pos = __shfl(first_pos, r.head, 64) + (lane - r.head);
-      // (the order inside a bucket does not matter: the marks are a set)
-      if (b >= 0 && pos >= 0 && pos < nnz) cols[pos] = c[j];
+      b[j] = (c[j] < 0 || c[j] >= n) ? -1 : (int32_t)((uint32_t)c[j] / (uint32_t)kBktCols);
+      const LaneRun r = lane_run(b[j], lane);
+      int32_t first_rank = 0;
+      if (r.first && b[j] >= 0) first_rank = atomicAdd(&cur[b[j]], r.len);
+      rank[j] = __shfl(first_rank, r.head, 64) + (lane - r.head);
     }
+    __syncthreads();
+    // exclusive scan of the counts: cs = first staged position of a range
+    const int v0 = cur[b0], v1 = cur[b1];
+    int inc = v0 + v1;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kBktThreads / 64; ++w) {
+      if (w < wave) before += wsum[w];
+      total += wsum[w];
+    }
+    const int ex = before + inc - (v0 + v1);
+    cs[b0] = ex;
+    cs[b1] = ex + v0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      // (the order inside a range does not matter: the marks are a set)
+      if (b[j] >= 0) {
+        const int32_t pos = cs[b[j]] + rank[j];
+        if (pos >= 0 && pos < kBktBatch) stage[pos] = c[j];
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < total; i += kBktThreads) {
+      const int32_t col = stage[i];
+      const int32_t rb = (int32_t)((uint32_t)col / (uint32_t)kBktCols);
+      const int64_t place = (int64_t)off[rb] + (i - cs[rb]);
+      if (place >= 0 && place < nnz) cols[place] = col;
+    }
+    __syncthreads();
+    off[b0] += cur[b0];
+    off[b1] += cur[b1];
+    cur[b0] = 0;
+    cur[b1] = 0;
+    __syncthreads();
   }
 }
 
