@@ -115,7 +115,7 @@ int sagnn_version(void);
  *
  * Workspace: spmm_plan_workspace_bytes(); contents are scratch.  Its size is a few bytes per
  * column plus, for wide blocks with many entries (n above about 5 M columns and nnz >= 2^22),
- * 4*nnz bytes for the entries sorted into column ranges.
+ * 8*nnz bytes for the entries sorted into column ranges and the place every entry went to.
  */
 int spmm_plan_workspace_bytes(int64_t m, int64_t n, int64_t nnz, int32_t nb, size_t* bytes);
 int spmm_plan_needed_rows(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m,

@@ -67,6 +67,7 @@ struct PlanWs {
   int32_t* err;       // 4 counters
   uint32_t* part;     // LDS marking only: kLdsGroups private bitmaps of kLdsWords words
   int32_t* bkt_cols;  // bucketed marking only: the column ids partitioned by range (nnz)
+  int32_t* bkt_place; // bucketed marking only: where in bkt_cols every entry went (nnz; -1: column out of range)
   int32_t* bkt_cnt;   // bucketed marking only: [ranges][kBktGroups] counts, then offsets inside the range
   int32_t* bkt_start; // bucketed marking only: first entry of every range (+ total)
   int64_t W, nblk;
@@ -96,6 +97,7 @@ PlanWs carve(void* base, int64_t n, int32_t nb, int64_t nnz) {
                ? reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)kLdsGroups * kLdsWords))
                : nullptr;
   w.bkt_cols = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)nnz)) : nullptr;
+  w.bkt_place = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)nnz)) : nullptr;
   w.bkt_cnt = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(bucket_ranges(n) * kBktGroups)))
                        : nullptr;
   w.bkt_start = bucketed ? reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)(bucket_ranges(n) + 1))) : nullptr;
@@ -374,7 +376,8 @@ __global__ __launch_bounds__(kBktThreads) void bucket_scatter_kernel(const int32
                                                                   int64_t n, int32_t nbk,
                                                                   const int32_t* __restrict__ within,
                                                                   const int32_t* __restrict__ start,
-                                                                  int32_t* __restrict__ cols) {
+                                                                  int32_t* __restrict__ cols,
+                                                                  int32_t* __restrict__ place_e) {
   __shared__ int32_t off[kBktMaxRanges];   // this workgroup's next free place in every range
   __shared__ int32_t cur[kBktMaxRanges];   // batch: entries per range
   __shared__ int32_t cs[kBktMaxRanges];    // batch: first staged position of every range
@@ -433,6 +436,8 @@ __global__ __launch_bounds__(kBktThreads) void bucket_scatter_kernel(const int32
         const int32_t pos = cs[b[j]] + rank[j];
         if (pos >= 0 && pos < kBktBatch) stage[pos] = c[j];
       }
+      // where the entry ends up in the partitioned array (the remap finds its rank there)
+      if (place_e && e + j * kBktThreads < e1) place_e[e + j * kBktThreads] = b[j] >= 0 ? off[b[j]] + rank[j] : -1;
     }
     __syncthreads();
     for (int i = tid; i < total; i += kBktThreads) {
@@ -447,6 +452,64 @@ __global__ __launch_bounds__(kBktThreads) void bucket_scatter_kernel(const int32
     cur[b0] = 0;
     cur[b1] = 0;
     __syncthreads();
+  }
+}
+
+// The remap of a wide block from the partitioned entries.  Looked up in entry order, every rank
+// costs a line of a table that no L2 holds (27.7 MB of rank records for 111 M columns).  In range
+// order the records of one range (2432 x 16 bytes) sit in LDS: a workgroup per range replaces every
+// column id of its bucket by the column's rank, in place; the entries then fetch their rank from
+// the place the scatter noted for them.  That gather is local: a workgroup's share of the entries
+// went to its own segment of every range, a few lines per range that stay in L2 while the share
+// is walked.
+__global__ __launch_bounds__(kLdsThreads) void remap_bucket_kernel(int32_t* __restrict__ cols,
+                                                                   const int32_t* __restrict__ start, int64_t nnz,
+                                                                   int64_t n, int64_t W,
+                                                                   const uint4* __restrict__ rank16) {
+  __shared__ uint4 rec[kBktCols / 64];
+  const int range = blockIdx.x;
+  const int64_t w0 = (int64_t)range * (kBktCols / 64);
+  for (int i = threadIdx.x; i < (int)(kBktCols / 64); i += kLdsThreads)
+    rec[i] = w0 + i < W ? rank16[w0 + i] : make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();
+  const int64_t c0 = (int64_t)range * kBktCols;
+  int64_t e0 = start[range], e1 = start[range + 1];
+  e0 = e0 < 0 ? 0 : e0;
+  e1 = e1 > nnz ? nnz : e1;
+  for (int64_t e = e0 + threadIdx.x; e < e1; e += 8 * kLdsThreads) {
+    int32_t c[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = e + j * kLdsThreads < e1 ? cols[e + j * kLdsThreads] : -1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (e + j * kLdsThreads >= e1) continue;
+      const int64_t rel = (int64_t)c[j] - c0;
+      int32_t rk = -1;
+      if (rel >= 0 && rel < kBktCols && c[j] < n) {
+        const uint4 t = rec[rel >> 6];
+        const uint64_t word = (uint64_t)t.x | ((uint64_t)t.y << 32);
+        rk = (int32_t)t.z + __popcll(word & ((1ull << (rel & 63)) - 1ull));
+      }
+      cols[e + j * kLdsThreads] = rk;
+    }
+  }
+}
+
+// compact[e] = rank found at the entry's place (same shares of the entries as the scatter)
+__global__ __launch_bounds__(kBktThreads) void remap_gather_kernel(const int32_t* __restrict__ place_e,
+                                                                  const int32_t* __restrict__ ranks, int64_t nnz,
+                                                                  int32_t* __restrict__ compact) {
+  const int64_t per = ceil_div_dev(nnz, kBktGroups);
+  const int64_t e0 = (int64_t)blockIdx.x * per, e1 = e0 + per < nnz ? e0 + per : nnz;
+  for (int64_t e = e0 + threadIdx.x; e < e1; e += 8 * kBktThreads) {
+    int32_t p[8], r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) p[j] = e + j * kBktThreads < e1 ? __builtin_nontemporal_load(&place_e[e + j * kBktThreads]) : -1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = (p[j] >= 0 && p[j] < nnz) ? ranks[p[j]] : -1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (e + j * kBktThreads < e1) __builtin_nontemporal_store(r[j], &compact[e + j * kBktThreads]);
   }
 }
 
@@ -996,7 +1059,7 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
     hipLaunchKernelGGL(bucket_starts_kernel, dim3(1), dim3(1024), 0, s, w.bkt_start, nbk);
     SAGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(bucket_scatter_kernel, dim3(kBktGroups), dim3(kBktThreads), 0, s, d_colidx, nnz, n, nbk,
-                       w.bkt_cnt, w.bkt_start, w.bkt_cols);
+                       w.bkt_cnt, w.bkt_start, w.bkt_cols, d_colidx_compact ? w.bkt_place : (int32_t*)nullptr);
     SAGNN_LAUNCH_CHECK();
     SAGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(mark_bucket_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -1070,10 +1133,17 @@ int plan_run(const int32_t* d_rowptr, const int32_t* d_colidx, int64_t m, int64_
     const int al = (aligned16(d_colidx) && aligned16(d_colidx_compact)) ? 1 : 0;
     if (N == n && speculated)
       return SAGNN_OK;
-    if (N == n)
+    if (N == n) {
       hipLaunchKernelGGL(remap_identity_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx,
                          nnz, n, d_colidx_compact, al);
-    else
+    } else if (bucket_mark) {
+      // ranks inside the buckets (in place), then every entry fetches the rank at its place
+      hipLaunchKernelGGL(remap_bucket_kernel, dim3((unsigned)bucket_ranges(n)), dim3(kLdsThreads), 0, s, w.bkt_cols,
+                         w.bkt_start, nnz, n, w.W, w.rank16);
+      SAGNN_LAUNCH_CHECK();
+      hipLaunchKernelGGL(remap_gather_kernel, dim3(kBktGroups), dim3(kBktThreads), 0, s, w.bkt_place, w.bkt_cols, nnz,
+                         d_colidx_compact);
+    } else
       hipLaunchKernelGGL(remap_kernel, dim3(grid_for(nnz, 8)), dim3(kThreads), 0, s, d_colidx, nnz, n,
                          w.rank16, d_colidx_compact, al);
     SAGNN_LAUNCH_CHECK();
