@@ -457,7 +457,7 @@ __global__ __launch_bounds__(kBktThreads) void bucket_scatter_kernel(const int32
 
 // The remap of a wide block from the partitioned entries.  Looked up in entry order, every rank
 // costs a line of a table that no L2 holds (27.7 MB of rank records for 111 M columns).  In range
-// order the records of one range (2432 x 16 bytes) sit in LDS: a workgroup per range replaces every
+// order the records of one range (39 KB) sit in LDS: a workgroup per range replaces every
 // column id of its bucket by the column's rank, in place; the entries then fetch their rank from
 // the place the scatter noted for them.  That gather is local: a workgroup's share of the entries
 // went to its own segment of every range, a few lines per range that stay in L2 while the share
@@ -466,11 +466,15 @@ __global__ __launch_bounds__(kLdsThreads) void remap_bucket_kernel(int32_t* __re
                                                                    const int32_t* __restrict__ start, int64_t nnz,
                                                                    int64_t n, int64_t W,
                                                                    const uint4* __restrict__ rank16) {
-  __shared__ uint4 rec[kBktCols / 64];
+  // per 32 columns: {membership bits, needed columns before them}: a lookup is one 8-byte LDS read
+  __shared__ uint2 rec[kBktCols / 32];
   const int range = blockIdx.x;
   const int64_t w0 = (int64_t)range * (kBktCols / 64);
-  for (int i = threadIdx.x; i < (int)(kBktCols / 64); i += kLdsThreads)
-    rec[i] = w0 + i < W ? rank16[w0 + i] : make_uint4(0u, 0u, 0u, 0u);
+  for (int i = threadIdx.x; i < (int)(kBktCols / 64); i += kLdsThreads) {
+    const uint4 t = w0 + i < W ? rank16[w0 + i] : make_uint4(0u, 0u, 0u, 0u);
+    rec[2 * i] = make_uint2(t.x, t.z);
+    rec[2 * i + 1] = make_uint2(t.y, t.z + (uint32_t)__popc(t.x));
+  }
   __syncthreads();
   const int64_t c0 = (int64_t)range * kBktCols;
   int64_t e0 = start[range], e1 = start[range + 1];
@@ -486,9 +490,8 @@ __global__ __launch_bounds__(kLdsThreads) void remap_bucket_kernel(int32_t* __re
       const int64_t rel = (int64_t)c[j] - c0;
       int32_t rk = -1;
       if (rel >= 0 && rel < kBktCols && c[j] < n) {
-        const uint4 t = rec[rel >> 6];
-        const uint64_t word = (uint64_t)t.x | ((uint64_t)t.y << 32);
-        rk = (int32_t)t.z + __popcll(word & ((1ull << (rel & 63)) - 1ull));
+        const uint2 t = rec[rel >> 5];
+        rk = (int32_t)t.y + __popc(t.x & ((1u << (rel & 31)) - 1u));
       }
       cols[e + j * kLdsThreads] = rk;
     }
