@@ -526,20 +526,26 @@ __global__ __launch_bounds__(kLdsThreads) void mark_bucket_kernel(const int32_t*
   const int range = blockIdx.x;
   const int64_t c0 = (int64_t)range * kBktCols;
   uint4* b4 = reinterpret_cast<uint4*>(bits);
-  for (int i = threadIdx.x; i < (int)(kBktCols / 16); i += kLdsThreads) b4[i] = make_uint4(0u, 0u, 0u, 0u);
-  __syncthreads();
   int64_t e0 = start[range], e1 = start[range + 1];
   e0 = e0 < 0 ? 0 : e0;
   e1 = e1 > nnz ? nnz : e1;
-  for (int64_t e = e0 + threadIdx.x; e < e1; e += 8 * kLdsThreads) {
-    int32_t c[8];
+  // sixteen loads per thread in flight, the first batch requested before the flags are cleared (one
+  // workgroup per CU: nothing else hides the latency of the stream)
+  constexpr int U = 16;
+  int32_t c[U];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) c[j] = e + j * kLdsThreads < e1 ? cols[e + j * kLdsThreads] : -1;
+  for (int j = 0; j < U; ++j) c[j] = e0 + threadIdx.x + j * kLdsThreads < e1 ? cols[e0 + threadIdx.x + j * kLdsThreads] : -1;
+  for (int i = threadIdx.x; i < (int)(kBktCols / 16); i += kLdsThreads) b4[i] = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();
+  for (int64_t base = e0; base < e1; base += U * kLdsThreads) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < U; ++j) {
       const int64_t rel = (int64_t)c[j] - c0;
       if (c[j] >= 0 && rel >= 0 && rel < kBktCols) flag[rel] = 1;
     }
+    const int64_t en = base + U * kLdsThreads + threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < U; ++j) c[j] = en + j * kLdsThreads < e1 ? cols[en + j * kLdsThreads] : -1;
   }
   __syncthreads();
   // 64 flag bytes -> one word: a lane squeezes its 8 bytes into 8 bits, eight lanes make a word
